@@ -1,0 +1,169 @@
+/*
+ * streamtgn.h -- C ABI of the MI355X (gfx950) incremental TGN / TGAT inference step.
+ *
+ * The library keeps the whole serving state of a temporal graph network resident in
+ * device memory (paper Sec. 3.2: temporal adjacency list, per-node recent-neighbour
+ * lists, node memory, one embedding cache per attention layer) and exposes the calls of
+ * the paper's problem statement: create the state, ingest a batch of timestamped edges
+ * (Sec. 3.3 / Algorithm 1, in the order of the "global index refresh" of Sec. 4: apply
+ * edges, GRU memory update, dirty-flag propagation, recompute the affected set), read
+ * cached embeddings, and rebuild every embedding from scratch (Sec. 3.5, full rebuild).
+ *
+ * Conventions
+ *  - Every function returns STGN_OK (0) or a negative STGN_E_* code; nothing throws.
+ *  - All matrices are fp32, row-major, laid out [inputs x outputs] (y = x * W).
+ *  - Node ids and edge ids are uint32; timestamps are fp64; features and embeddings fp32.
+ *  - "host" / "device" in a comment says where a pointer must point.  The caller owns
+ *    every buffer it passes in.  Host inputs are consumed before the call returns.
+ *    Device inputs must stay valid until the stream has executed the call (stgn_sync).
+ *  - The device workspace is allocated by the caller (stgn_query_workspace tells the
+ *    size) and must outlive the context; the library itself allocates no device memory
+ *    after stgn_create has returned.
+ *  - Work is enqueued on the HIP stream given at creation.  stgn_ingest_batch and
+ *    stgn_full_rebuild are asynchronous unless a statistics struct is requested.
+ *  - A context is not thread-safe.
+ */
+#ifndef STREAMTGN_H
+#define STREAMTGN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define STGN_MAX_LAYERS 4
+#define STGN_MAX_BATCH  8192   /* edges per ingest call (the batch sort runs in one workgroup) */
+
+enum {
+  STGN_OK = 0,
+  STGN_E_INVALID_ARG       = -1,  /* NULL pointer, unsupported dimension, bad size             */
+  STGN_E_NODE_OUT_OF_RANGE = -2,  /* an endpoint id >= num_nodes                               */
+  STGN_E_TIME_ORDER        = -3,  /* a timestamp below its predecessor (Definition 1: the edge
+                                     stream is chronological) or not a number                  */
+  STGN_E_SELF_LOOP         = -4,  /* src == dst                                                */
+  STGN_E_BATCH_TOO_LARGE   = -5,  /* n > max_batch                                             */
+  STGN_E_EDGE_CAPACITY     = -6,  /* more than max_edges edges in total                        */
+  STGN_E_DEVICE            = -7,  /* a HIP call failed or no gfx950 device is present          */
+  STGN_E_WORKSPACE         = -8   /* workspace missing, misaligned or too small                */
+};
+
+typedef struct stgn_ctx stgn_ctx;
+
+/* Model and capacity description (paper Sec. 2.2 for the dimensions).
+ * d_mem = 0 selects a memoryless (TGAT-style) model: no message/GRU stage, layer-0 rows
+ * are the static node features.  Layer-0 width is d_mem + d_node and must be > 0.
+ * heads must divide d_emb; d_emb / heads <= 128; layers <= STGN_MAX_LAYERS;
+ * max_batch <= STGN_MAX_BATCH; max_edges < 2^31. */
+typedef struct {
+  uint32_t num_nodes;
+  uint64_t max_edges;
+  uint32_t max_batch;
+  uint32_t d_mem, d_node, d_edge, d_time, d_emb, d_msg;
+  uint32_t k;        /* most recent neighbours kept per node (Sec. 3.3.2)   */
+  uint32_t heads;    /* attention heads                                    */
+  uint32_t layers;   /* attention layers = hops of dirty-flag propagation   */
+} stgn_config;
+
+/* Parameters, host pointers, copied (and re-packed) by stgn_create.
+ *   time encoding (Sec. 2.2.1):  phi_i(x) = sqrt(1/d_time) * cos(omega_i * x + phase_i)
+ *   message (Eq. msg_linear):    m = [s_self | s_other | e | phi(t - t_self_last)] W_msg + b_msg
+ *   GRU (Eq. gru_detail):        W_*: [d_msg x d_mem], U_*: [d_mem x d_mem], b_*: [d_mem]
+ *   attention layer l (Eq. attn_detail), d_in = (l == 0 ? d_mem + d_node : d_emb):
+ *       W_Q[l]: [(d_in + d_time) x d_emb]           input [h_v | phi(0)]
+ *       W_K[l], W_V[l]: [(d_in + d_edge + d_time) x d_emb]   input [h_u | e | phi(dt)]
+ *       W_O[l]: [d_emb x d_emb], b_O[l]: [d_emb]    applied to the concatenated heads
+ * The message/GRU pointers are ignored when d_mem == 0. */
+typedef struct {
+  const float *omega, *phase;
+  const float *W_msg, *b_msg;
+  const float *W_z, *U_z, *b_z, *W_r, *U_r, *b_r, *W_h, *U_h, *b_h;
+  const float *const *W_Q, *const *W_K, *const *W_V, *const *W_O, *const *b_O; /* [layers] each */
+} stgn_weights;
+
+/* Per-batch report; requesting it makes stgn_ingest_batch synchronise the stream. */
+typedef struct {
+  uint32_t n_edges;
+  uint32_t n_direct;                       /* |V_direct|: distinct endpoints of the batch     */
+  uint32_t n_affected;                     /* |V_aff| (Eq. affected_set)                      */
+  uint32_t frontier[STGN_MAX_LAYERS + 1];  /* nodes first reached at hop h (frontier[0]=|D|)   */
+  uint64_t entries_scanned;                /* adjacency entries read by the propagation       */
+  float    us_stage[6];                    /* sort | memory update | apply | propagate+compact
+                                              | embed | total; microseconds from HIP events    */
+} stgn_batch_stats;
+
+/* Device bytes stgn_create needs for this configuration (host computation only). */
+int stgn_query_workspace(const stgn_config *cfg, size_t *device_bytes);
+
+/* Builds the state on the current device: zero memory (Sec. 2.2.4), empty adjacency, every
+ * cached row equal to the empty-neighbourhood embedding.  node_feat: host [num_nodes x d_node]
+ * or NULL (zeros).  workspace: device, 256-byte aligned, >= the queried size.  hip_stream: a
+ * hipStream_t (NULL = the default stream).  Synchronises before returning. */
+int stgn_create(const stgn_config *cfg, const stgn_weights *w, const float *node_feat,
+                void *device_workspace, size_t device_bytes, void *hip_stream, stgn_ctx **out);
+
+void stgn_destroy(stgn_ctx *ctx);
+
+/* One incremental step (Sec. 3.3, Algorithm 1; order of Sec. 4 "Global index refresh"):
+ * messages + Last aggregation + GRU on the batch endpoints from pre-batch state, append the
+ * edges, propagate dirty flags `layers` hops, recompute all layers for the affected set.
+ * src, dst: [n]; ts: [n] non-decreasing and >= the last ingested timestamp; efeat: [n x d_edge]
+ * (may be NULL when d_edge == 0).  All four live on the host (inputs_on_device = 0) or all on
+ * the device (1).  Errors found on the host are returned at once and leave the state untouched;
+ * with device inputs the check runs on the device, a failing batch is skipped as a whole and
+ * its code is returned by the next synchronising call (stgn_sync, stgn_get_*, or this call with
+ * stats != NULL). */
+int stgn_ingest_batch(stgn_ctx *ctx, uint32_t n, const uint32_t *src, const uint32_t *dst,
+                      const double *ts, const float *efeat, int inputs_on_device,
+                      stgn_batch_stats *stats /* host, nullable */);
+
+/* Cached final-layer rows (Sec. 3.2.3, O(1) lookup per node).  layer: 1..layers, or 0 for the
+ * last one.  nodes/out on host (on_device = 0, synchronises) or device (1, asynchronous).
+ * out: [n x d_emb]. */
+int stgn_get_embeddings(stgn_ctx *ctx, uint32_t layer, uint32_t n, const uint32_t *nodes,
+                        float *out, int on_device);
+
+/* Recompute every layer for every node from the current state (Sec. 3.5, full rebuild). */
+int stgn_full_rebuild(stgn_ctx *ctx);
+
+/* Waits for the stream; returns the code of the first skipped device-side batch (and clears it). */
+int stgn_sync(stgn_ctx *ctx);
+
+/* ---- inspection hooks used by the parity tests (all synchronise, host outputs) ---- */
+
+/* Affected set of the last ingested batch, ascending.  count receives |V_aff|; at most cap ids
+ * are written. */
+int stgn_get_affected(stgn_ctx *ctx, uint32_t *out, uint32_t cap, uint32_t *count);
+
+/* Most recent <= k neighbours of a node, most recent first (Sec. 3.3.2).  Arrays of length k. */
+int stgn_get_neighbors(stgn_ctx *ctx, uint32_t node, uint32_t *nbr, uint32_t *eid, double *ts,
+                       uint32_t *count);
+
+/* `count` entries of a node's full temporal adjacency starting at position `first` (arrival
+ * order; Sec. 3.2.2 GetNeighbors).  degree receives the node's total entry count. */
+int stgn_get_history(stgn_ctx *ctx, uint32_t node, uint32_t first, uint32_t count,
+                     uint32_t *nbr, uint32_t *eid, uint32_t *degree);
+
+/* Memory rows [n x d_mem] (nullable) and last-interaction times [n] (nullable). */
+int stgn_get_memory(stgn_ctx *ctx, uint32_t n, const uint32_t *nodes, float *mem, double *t_last);
+
+/* Totals since creation: edges ingested, sum of |V_direct|, sum of |V_aff|, adjacency entries
+ * scanned by the propagation.  Synchronises.  Any pointer may be NULL. */
+int stgn_get_totals(stgn_ctx *ctx, uint64_t *edges, uint64_t *direct, uint64_t *affected,
+                    uint64_t *scanned);
+
+/* Microseconds (HIP events on the context's stream) spent in each kernel class since the last
+ * call with reset != 0, and launch counts.  Collection is off until enabled; while it is on,
+ * every kernel launch is bracketed by two events.  names: static strings owned by the library.
+ * Returns the number of classes written (<= cap) or a negative code. */
+int stgn_kernel_times(stgn_ctx *ctx, int enable, int reset, uint32_t cap,
+                      const char **names, double *usec, uint64_t *launches);
+
+const char *stgn_last_error(const stgn_ctx *ctx);   /* NULL ctx: message of the last failed create */
+const char *stgn_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* STREAMTGN_H */

@@ -1,0 +1,687 @@
+// extern "C" boundary and host orchestration: argument checks, workspace layout, parameter
+// packing, launch order of one incremental step.  No arithmetic of the method runs here.
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "stgn_internal.h"
+
+using namespace stgn;
+
+namespace {
+
+const char* const kClassNames[KC_COUNT] = {"stage_sort", "memory_update", "apply", "plan", "expand", "compact",
+                                           "qproj", "attn", "oproj", "gather_rows"};
+
+std::string g_create_error;
+
+struct TimedLaunch { int cls; hipEvent_t a, b; };
+
+}  // namespace
+
+struct stgn_ctx {
+  stgn_config cfg;
+  Dev d;
+  hipStream_t stream = nullptr;
+  std::string err;
+  uint64_t host_edges = 0;          // upper bound of edges enqueued so far
+  bool host_t_known = true;         // host knows the last ingested timestamp
+  bool any_edges = false;
+  double host_t_last = 0.0;
+  // pinned staging for host inputs, double buffered
+  char* pin[2] = {nullptr, nullptr};
+  hipEvent_t pin_ev[2] = {nullptr, nullptr};
+  bool pin_used[2] = {false, false};
+  size_t pin_bytes = 0;
+  int pin_next = 0;
+  Ctrl* ctrl_host = nullptr;        // pinned read-back of the control block
+  hipEvent_t stage_ev[7] = {};
+  // optional per-kernel timing
+  bool timing = false;
+  std::vector<TimedLaunch> pending;
+  std::vector<hipEvent_t> free_events;
+  double k_usec[KC_COUNT] = {};
+  uint64_t k_launches[KC_COUNT] = {};
+};
+
+namespace {
+
+int fail(stgn_ctx* c, int code, const std::string& msg) {
+  if (c) c->err = msg; else g_create_error = msg;
+  return code;
+}
+
+#define HIPCHK(ctx, call)                                                                      \
+  do {                                                                                         \
+    hipError_t e_ = (call);                                                                    \
+    if (e_ != hipSuccess)                                                                      \
+      return fail(ctx, STGN_E_DEVICE, std::string(#call) + ": " + hipGetErrorString(e_));      \
+  } while (0)
+
+uint32_t np32(uint32_t x) { return round_up(x, 32); }
+uint32_t row_ld(uint32_t width) { return width ? round_up(width, 32) : 0; }   // 128-byte aligned rows
+
+struct Bump {
+  char* base;
+  size_t off = 0;
+  template <class T>
+  T* take(size_t count) {
+    off = (off + 255) & ~(size_t)255;
+    T* p = base ? reinterpret_cast<T*>(base + off) : nullptr;
+    off += count * sizeof(T);
+    return p;
+  }
+};
+
+int check_config(const stgn_config* c, std::string* why) {
+  auto bad = [&](const char* m) { *why = m; return STGN_E_INVALID_ARG; };
+  if (!c) return bad("config is NULL");
+  if (c->num_nodes == 0 || c->num_nodes > 0x7FFFFFFFu) return bad("num_nodes out of range");
+  if (c->max_edges == 0 || c->max_edges >= (1ull << 31)) return bad("max_edges out of range");
+  if (c->max_batch == 0 || c->max_batch > STGN_MAX_BATCH) return bad("max_batch out of range");
+  if (c->layers == 0 || c->layers > STGN_MAX_LAYERS) return bad("layers out of range");
+  if (c->k == 0 || c->k > 1024) return bad("k out of range");
+  if (c->d_emb == 0 || c->d_emb > 512 || c->d_time == 0 || c->d_time > 512 || c->d_edge > 1024) return bad("dimension out of range");
+  if (c->d_mem + c->d_node == 0 || c->d_mem + c->d_node > 512) return bad("layer-0 width (d_mem + d_node) out of range");
+  if (c->d_mem && (c->d_msg == 0 || c->d_msg > 512)) return bad("d_msg out of range");
+  if (c->heads == 0 || c->d_emb % c->heads != 0) return bad("heads must divide d_emb");
+  if (c->d_emb / c->heads > 128) return bad("d_emb / heads > 128");
+  for (uint32_t l = 0; l < c->layers; ++l) {
+    const uint32_t din = l == 0 ? c->d_mem + c->d_node : c->d_emb;
+    if (!attn_supported(din + c->d_edge + c->d_time, c->heads)) return bad("unsupported attention width or head count (heads in {1,2,4}, d_in+d_edge+d_time <= 512)");
+  }
+  return STGN_OK;
+}
+
+// Lays the whole device state out in one workspace; base == nullptr only measures.
+size_t layout(const stgn_config& c, char* base, Dev* d) {
+  Bump b{base};
+  const uint32_t N = c.num_nodes, B2 = 2 * c.max_batch;
+  d->N = N; d->k = c.k; d->heads = c.heads; d->layers = c.layers;
+  d->d_mem = c.d_mem; d->d_node = c.d_node; d->d0 = c.d_mem + c.d_node; d->d_edge = c.d_edge;
+  d->d_time = c.d_time; d->d_emb = c.d_emb; d->d_msg = c.d_msg; d->dk = c.d_emb / c.heads;
+  d->max_batch = c.max_batch; d->max_edges = c.max_edges;
+  // adjacency blocks of 8, 16, 32, ... entries: capacity after b blocks is 8 (2^b - 1)
+  uint32_t maxb = 1;
+  while (8ull * ((1ull << maxb) - 1) < 2 * c.max_edges) ++maxb;
+  d->maxb = maxb;
+  const uint64_t active = std::min<uint64_t>(N, 2 * c.max_edges);
+  d->pool_cap_units = active + (4 * c.max_edges + kMinBlock - 1) / kMinBlock + 1;   // sum(2 deg + 8) / 8
+
+  d->H[0].ld = row_ld(d->d0);
+  d->H[0].base = b.take<float>((size_t)N * d->H[0].ld);
+  for (uint32_t l = 1; l <= c.layers; ++l) {
+    d->H[l].ld = row_ld(c.d_emb);
+    d->H[l].base = b.take<float>((size_t)N * d->H[l].ld);
+  }
+  d->t_last = b.take<double>(N);
+  d->deg = b.take<uint32_t>(N);
+  d->ring = b.take<RingEntry>((size_t)N * c.k);
+  d->pool_nt = b.take<uint2>(d->pool_cap_units * kMinBlock);
+  d->pool_eid = b.take<uint32_t>(d->pool_cap_units * kMinBlock);
+  d->blk = b.take<uint32_t>((size_t)N * maxb);
+  d->efeat.ld = row_ld(c.d_edge);
+  d->efeat.base = b.take<float>((size_t)c.max_edges * d->efeat.ld);
+  d->ets = b.take<double>(c.max_edges);
+  d->ctrl = b.take<Ctrl>(1);
+  d->st_src = b.take<uint32_t>(c.max_batch);
+  d->st_dst = b.take<uint32_t>(c.max_batch);
+  d->st_ts = b.take<double>(c.max_batch);
+  d->st_ef = b.take<float>((size_t)c.max_batch * c.d_edge);
+  d->D = b.take<uint32_t>(B2);
+  d->seg_start = b.take<uint32_t>(B2 + 1);
+  d->last_slot = b.take<uint32_t>(B2);
+  d->deg_new = b.take<uint32_t>(B2);
+  d->slot_pos = b.take<uint32_t>(B2);
+  d->slot_d = b.take<uint32_t>(B2);
+  d->mem_new = b.take<float>((size_t)B2 * c.d_mem);
+  d->bitmap = b.take<uint32_t>(((size_t)N + 31) / 32);
+  d->front[0] = b.take<uint32_t>(N);
+  d->front[1] = b.take<uint32_t>(N);
+  d->items_cap = (uint64_t)N + 2 * c.max_edges / kLogChunk + 1024;
+  d->items = b.take<uint64_t>(d->items_cap);
+  d->blocksum = b.take<uint32_t>(((size_t)N + 31) / 32 / 1024 + 2);
+  d->A = b.take<uint32_t>(N);
+  uint32_t zp_max = 0;
+  for (uint32_t l = 0; l < c.layers; ++l) {
+    LayerDev& L = d->L[l];
+    L.d_in = l == 0 ? d->d0 : c.d_emb;
+    L.d_in2 = round_up(L.d_in, 2);
+    L.Zdim = L.d_in + c.d_edge + c.d_time;
+    L.Zp = np32(L.Zdim);
+    zp_max = std::max(zp_max, L.Zp);
+  }
+  d->QT = b.take<float>((size_t)N * c.heads * zp_max);
+  d->ZB = b.take<float>((size_t)N * c.heads * zp_max);
+  d->q_cap = 65536;
+  d->qnodes = b.take<uint32_t>(d->q_cap);
+  d->qout = b.take<float>((size_t)d->q_cap * std::max(d->d0, c.d_emb));
+  // parameters
+  d->om_rev = b.take<double>(c.d_time);
+  d->ph_rev = b.take<double>(c.d_time);
+  const uint32_t dk2 = round_up(d->dk, 2);
+  if (c.d_mem) {
+    d->Kmsg = 2 * c.d_mem + c.d_edge + c.d_time;
+    d->Kmsg2 = round_up(d->Kmsg, 2);
+    const uint32_t dg2 = round_up(c.d_msg, 2), dm2 = round_up(c.d_mem, 2);
+    d->Wmsg = b.take<float>((size_t)d->Kmsg2 * np32(c.d_msg));
+    d->bmsg = b.take<float>(c.d_msg);
+    d->Wzr = b.take<float>((size_t)dg2 * 2 * np32(c.d_mem));
+    d->Uzr = b.take<float>((size_t)dm2 * 2 * np32(c.d_mem));
+    d->Wh = b.take<float>((size_t)dg2 * np32(c.d_mem));
+    d->Uh = b.take<float>((size_t)dm2 * np32(c.d_mem));
+    d->bz = b.take<float>(c.d_mem);
+    d->br = b.take<float>(c.d_mem);
+    d->bh = b.take<float>(c.d_mem);
+  } else {
+    d->Kmsg = d->Kmsg2 = 0;
+    d->Wmsg = d->bmsg = d->Wzr = d->Uzr = d->Wh = d->Uh = d->bz = d->br = d->bh = nullptr;
+  }
+  for (uint32_t l = 0; l < c.layers; ++l) {
+    LayerDev& L = d->L[l];
+    L.WQn = b.take<float>((size_t)L.d_in2 * np32(c.d_emb));
+    L.cQ = b.take<float>(c.d_emb);
+    L.WKT = b.take<float>((size_t)c.heads * dk2 * L.Zp);
+    L.WV = b.take<float>((size_t)c.heads * round_up(L.Zdim, 2) * np32(d->dk));
+    L.WO = b.take<float>((size_t)round_up(c.d_emb, 2) * np32(c.d_emb));
+    L.bO = b.take<float>(c.d_emb);
+  }
+  return (b.off + 255) & ~(size_t)255;
+}
+
+template <class T>
+int upload(stgn_ctx* ctx, const T* dst, const std::vector<T>& v) {
+  if (v.empty()) return STGN_OK;
+  HIPCHK(ctx, hipMemcpy(const_cast<T*>(dst), v.data(), v.size() * sizeof(T), hipMemcpyHostToDevice));
+  return STGN_OK;
+}
+
+// copies src [rows x cols] into a zero-padded [rows_p x cols_p] matrix at column offset c0
+void put_block(std::vector<float>& dst, uint32_t cols_p, uint32_t c0, const float* src, uint32_t rows, uint32_t cols,
+               const std::vector<double>* row_scale = nullptr) {
+  for (uint32_t r = 0; r < rows; ++r)
+    for (uint32_t c = 0; c < cols; ++c) {
+      double v = src[(size_t)r * cols + c];
+      if (row_scale) v *= (*row_scale)[r];
+      dst[(size_t)r * cols_p + c0 + c] = (float)v;
+    }
+}
+
+int pack_parameters(stgn_ctx* ctx, const stgn_weights* w) {
+  const stgn_config& c = ctx->cfg;
+  const Dev& d = ctx->d;
+  const double two_pi = 6.283185307179586476925286766559;
+  const double tscale = std::sqrt(1.0 / (double)c.d_time);
+  std::vector<double> om(c.d_time), ph(c.d_time);
+  for (uint32_t i = 0; i < c.d_time; ++i) { om[i] = (double)w->omega[i] / two_pi; ph[i] = (double)w->phase[i] / two_pi; }
+  int rc;
+  if ((rc = upload(ctx, d.om_rev, om))) return rc;
+  if ((rc = upload(ctx, d.ph_rev, ph))) return rc;
+  auto vec = [](const float* p, uint32_t n) { return std::vector<float>(p, p + n); };
+  if (c.d_mem) {
+    const uint32_t npg = np32(c.d_msg), npm = np32(c.d_mem);
+    const uint32_t dg2 = round_up(c.d_msg, 2), dm2 = round_up(c.d_mem, 2);
+    std::vector<double> rs(d.Kmsg, 1.0);
+    for (uint32_t i = 0; i < c.d_time; ++i) rs[2 * c.d_mem + c.d_edge + i] = tscale;   // phi carries sqrt(1/d_t)
+    std::vector<float> Wm((size_t)d.Kmsg2 * npg, 0.0f);
+    put_block(Wm, npg, 0, w->W_msg, d.Kmsg, c.d_msg, &rs);
+    std::vector<float> Wzr((size_t)dg2 * 2 * npm, 0.0f), Uzr((size_t)dm2 * 2 * npm, 0.0f);
+    put_block(Wzr, 2 * npm, 0, w->W_z, c.d_msg, c.d_mem);
+    put_block(Wzr, 2 * npm, npm, w->W_r, c.d_msg, c.d_mem);
+    put_block(Uzr, 2 * npm, 0, w->U_z, c.d_mem, c.d_mem);
+    put_block(Uzr, 2 * npm, npm, w->U_r, c.d_mem, c.d_mem);
+    std::vector<float> Wh((size_t)dg2 * npm, 0.0f), Uh((size_t)dm2 * npm, 0.0f);
+    put_block(Wh, npm, 0, w->W_h, c.d_msg, c.d_mem);
+    put_block(Uh, npm, 0, w->U_h, c.d_mem, c.d_mem);
+    if ((rc = upload(ctx, d.Wmsg, Wm)) || (rc = upload(ctx, d.bmsg, vec(w->b_msg, c.d_msg))) ||
+        (rc = upload(ctx, d.Wzr, Wzr)) || (rc = upload(ctx, d.Uzr, Uzr)) || (rc = upload(ctx, d.Wh, Wh)) ||
+        (rc = upload(ctx, d.Uh, Uh)) || (rc = upload(ctx, d.bz, vec(w->b_z, c.d_mem))) ||
+        (rc = upload(ctx, d.br, vec(w->b_r, c.d_mem))) || (rc = upload(ctx, d.bh, vec(w->b_h, c.d_mem))))
+      return rc;
+  }
+  const uint32_t dk = d.dk, dk2 = round_up(dk, 2), npk = np32(dk), npd = np32(c.d_emb);
+  const double inv_sqrt_dk = 1.0 / std::sqrt((double)dk);
+  for (uint32_t l = 0; l < c.layers; ++l) {
+    const LayerDev& L = d.L[l];
+    const float *WQ = w->W_Q[l], *WK = w->W_K[l], *WV = w->W_V[l];
+    std::vector<float> WQn((size_t)L.d_in2 * npd, 0.0f);
+    put_block(WQn, npd, 0, WQ, L.d_in, c.d_emb);
+    std::vector<float> cQ(c.d_emb);
+    for (uint32_t col = 0; col < c.d_emb; ++col) {
+      double acc = 0.0;
+      for (uint32_t i = 0; i < c.d_time; ++i)
+        acc += tscale * std::cos((double)w->phase[i]) * (double)WQ[(size_t)(L.d_in + i) * c.d_emb + col];
+      cQ[col] = (float)acc;
+    }
+    std::vector<float> WKT((size_t)c.heads * dk2 * L.Zp, 0.0f);
+    std::vector<float> WVp((size_t)c.heads * round_up(L.Zdim, 2) * npk, 0.0f);
+    for (uint32_t h = 0; h < c.heads; ++h)
+      for (uint32_t z = 0; z < L.Zdim; ++z) {
+        const double rsz = z >= L.d_in + c.d_edge ? tscale : 1.0;
+        for (uint32_t cc = 0; cc < dk; ++cc) {
+          WKT[((size_t)h * dk2 + cc) * L.Zp + z] = (float)((double)WK[(size_t)z * c.d_emb + h * dk + cc] * inv_sqrt_dk * rsz);
+          WVp[((size_t)h * round_up(L.Zdim, 2) + z) * npk + cc] = (float)((double)WV[(size_t)z * c.d_emb + h * dk + cc] * rsz);
+        }
+      }
+    std::vector<float> WO((size_t)round_up(c.d_emb, 2) * npd, 0.0f);
+    put_block(WO, npd, 0, w->W_O[l], c.d_emb, c.d_emb);
+    if ((rc = upload(ctx, L.WQn, WQn)) || (rc = upload(ctx, L.cQ, cQ)) || (rc = upload(ctx, L.WKT, WKT)) ||
+        (rc = upload(ctx, L.WV, WVp)) || (rc = upload(ctx, L.WO, WO)) || (rc = upload(ctx, L.bO, vec(w->b_O[l], c.d_emb))))
+      return rc;
+  }
+  return STGN_OK;
+}
+
+// ---- optional per-kernel event timing
+hipEvent_t get_event(stgn_ctx* ctx) {
+  if (!ctx->free_events.empty()) { hipEvent_t e = ctx->free_events.back(); ctx->free_events.pop_back(); return e; }
+  hipEvent_t e = nullptr;
+  if (hipEventCreate(&e) != hipSuccess) return nullptr;
+  return e;
+}
+
+struct Scope {
+  stgn_ctx* ctx; int cls; hipEvent_t a = nullptr, b = nullptr;
+  Scope(stgn_ctx* c, int k) : ctx(c), cls(k) {
+    if (ctx->timing) { a = get_event(ctx); b = get_event(ctx); if (a) hipEventRecord(a, ctx->stream); }
+  }
+  ~Scope() {
+    if (ctx->timing && a && b) { hipEventRecord(b, ctx->stream); ctx->pending.push_back({cls, a, b}); }
+  }
+};
+
+void drain_timing(stgn_ctx* ctx) {
+  for (const TimedLaunch& t : ctx->pending) {
+    float ms = 0.0f;
+    if (hipEventElapsedTime(&ms, t.a, t.b) == hipSuccess) { ctx->k_usec[t.cls] += 1000.0 * ms; ctx->k_launches[t.cls] += 1; }
+    ctx->free_events.push_back(t.a);
+    ctx->free_events.push_back(t.b);
+  }
+  ctx->pending.clear();
+}
+
+void run_layers(stgn_ctx* ctx, const uint32_t* rows, const uint32_t* count_ptr, uint32_t count_max) {
+  const Dev& d = ctx->d;
+  for (uint32_t l = 0; l < d.layers; ++l) {
+    { Scope s(ctx, KC_QPROJ); launch_qproj(d, ctx->stream, l, rows, count_ptr, count_max); }
+    { Scope s(ctx, KC_ATTN);  launch_attn(d, ctx->stream, l, rows, count_ptr, count_max); }
+    { Scope s(ctx, KC_OPROJ); launch_oproj(d, ctx->stream, l, rows, count_ptr, count_max); }
+  }
+}
+
+int read_ctrl(stgn_ctx* ctx) {
+  HIPCHK(ctx, hipMemcpyAsync(ctx->ctrl_host, ctx->d.ctrl, sizeof(Ctrl), hipMemcpyDeviceToHost, ctx->stream));
+  HIPCHK(ctx, hipStreamSynchronize(ctx->stream));
+  return STGN_OK;
+}
+
+// synchronise, fetch the control block, report and clear a pending device-side error
+int sync_and_poll(stgn_ctx* ctx) {
+  int rc = read_ctrl(ctx);
+  if (rc) return rc;
+  if (ctx->timing) drain_timing(ctx);
+  const int code = ctx->ctrl_host->err_code;
+  if (code != 0) {
+    const int32_t zero = 0;
+    HIPCHK(ctx, hipMemcpy(&ctx->d.ctrl->err_code, &zero, sizeof(zero), hipMemcpyHostToDevice));
+    char buf[128];
+    snprintf(buf, sizeof buf, "batch %u rejected on the device with code %d; it was skipped as a whole",
+             ctx->ctrl_host->err_batch, code);
+    ctx->err = buf;
+    ctx->host_t_known = false;
+    return code;
+  }
+  return STGN_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* stgn_version(void) { return "streamtgn-gfx950 0.1"; }
+
+const char* stgn_last_error(const stgn_ctx* ctx) { return ctx ? ctx->err.c_str() : g_create_error.c_str(); }
+
+int stgn_query_workspace(const stgn_config* cfg, size_t* device_bytes) {
+  std::string why;
+  int rc = check_config(cfg, &why);
+  if (rc) return fail(nullptr, rc, why);
+  if (!device_bytes) return fail(nullptr, STGN_E_INVALID_ARG, "device_bytes is NULL");
+  Dev tmp;
+  memset(&tmp, 0, sizeof tmp);
+  *device_bytes = layout(*cfg, nullptr, &tmp);
+  return STGN_OK;
+}
+
+int stgn_create(const stgn_config* cfg, const stgn_weights* w, const float* node_feat, void* device_workspace,
+                size_t device_bytes, void* hip_stream, stgn_ctx** out) {
+  std::string why;
+  int rc = check_config(cfg, &why);
+  if (rc) return fail(nullptr, rc, why);
+  if (!w || !out) return fail(nullptr, STGN_E_INVALID_ARG, "weights or out pointer is NULL");
+  if (!w->omega || !w->phase || !w->W_Q || !w->W_K || !w->W_V || !w->W_O || !w->b_O)
+    return fail(nullptr, STGN_E_INVALID_ARG, "a time-encoding or attention parameter pointer is NULL");
+  for (uint32_t l = 0; l < cfg->layers; ++l)
+    if (!w->W_Q[l] || !w->W_K[l] || !w->W_V[l] || !w->W_O[l] || !w->b_O[l])
+      return fail(nullptr, STGN_E_INVALID_ARG, "an attention layer parameter pointer is NULL");
+  if (cfg->d_mem && (!w->W_msg || !w->b_msg || !w->W_z || !w->U_z || !w->b_z || !w->W_r || !w->U_r || !w->b_r ||
+                     !w->W_h || !w->U_h || !w->b_h))
+    return fail(nullptr, STGN_E_INVALID_ARG, "a message/GRU parameter pointer is NULL");
+  Dev tmp;
+  memset(&tmp, 0, sizeof tmp);
+  const size_t need = layout(*cfg, nullptr, &tmp);
+  if (!device_workspace || ((uintptr_t)device_workspace & 255) || device_bytes < need)
+    return fail(nullptr, STGN_E_WORKSPACE, "workspace is NULL, not 256-byte aligned or smaller than stgn_query_workspace reports");
+  int ndev = 0;
+  if (hipGetDeviceCount(&ndev) != hipSuccess || ndev == 0) return fail(nullptr, STGN_E_DEVICE, "no HIP device");
+  int dev = 0;
+  hipDeviceProp_t prop;
+  if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess)
+    return fail(nullptr, STGN_E_DEVICE, "cannot query the current device");
+  if (strncmp(prop.gcnArchName, "gfx950", 6) != 0)
+    return fail(nullptr, STGN_E_DEVICE, std::string("built for gfx950, current device is ") + prop.gcnArchName);
+
+  stgn_ctx* ctx = new stgn_ctx();
+  ctx->cfg = *cfg;
+  memset(&ctx->d, 0, sizeof(Dev));
+  layout(*cfg, (char*)device_workspace, &ctx->d);
+  ctx->stream = (hipStream_t)hip_stream;
+  auto bail = [&](int code) { g_create_error = ctx->err; stgn_destroy(ctx); return code; };
+
+  ctx->pin_bytes = (size_t)cfg->max_batch * (2 * sizeof(uint32_t) + sizeof(double) + (size_t)cfg->d_edge * sizeof(float));
+  for (int i = 0; i < 2; ++i) {
+    if (hipHostMalloc((void**)&ctx->pin[i], ctx->pin_bytes, hipHostMallocDefault) != hipSuccess ||
+        hipEventCreateWithFlags(&ctx->pin_ev[i], hipEventDisableTiming) != hipSuccess) {
+      ctx->err = "pinned staging allocation failed";
+      return bail(STGN_E_DEVICE);
+    }
+  }
+  if (hipHostMalloc((void**)&ctx->ctrl_host, sizeof(Ctrl), hipHostMallocDefault) != hipSuccess) {
+    ctx->err = "pinned control block allocation failed";
+    return bail(STGN_E_DEVICE);
+  }
+  for (auto& e : ctx->stage_ev)
+    if (hipEventCreate(&e) != hipSuccess) { ctx->err = "event creation failed"; return bail(STGN_E_DEVICE); }
+  if (setup_ingest_attributes(ctx->d) || setup_embed_attributes(ctx->d) || setup_memory_attributes(ctx->d)) {
+    ctx->err = "a kernel needs more LDS than one gfx950 workgroup has for these dimensions";
+    return bail(STGN_E_INVALID_ARG);
+  }
+  if ((rc = pack_parameters(ctx, w))) return bail(rc);
+  launch_init_state(ctx->d, ctx->stream);
+  if (hipStreamSynchronize(ctx->stream) != hipSuccess) { ctx->err = "state initialisation failed"; return bail(STGN_E_DEVICE); }
+  if (node_feat && cfg->d_node) {
+    hipError_t e = hipMemcpy2D(ctx->d.H[0].base + cfg->d_mem, (size_t)ctx->d.H[0].ld * sizeof(float), node_feat,
+                               (size_t)cfg->d_node * sizeof(float), (size_t)cfg->d_node * sizeof(float), cfg->num_nodes,
+                               hipMemcpyHostToDevice);
+    if (e != hipSuccess) { ctx->err = std::string("node feature upload: ") + hipGetErrorString(e); return bail(STGN_E_DEVICE); }
+  }
+  run_layers(ctx, nullptr, nullptr, cfg->num_nodes);    // every cache row = empty-neighbourhood embedding
+  hipError_t e = hipStreamSynchronize(ctx->stream);
+  if (e == hipSuccess) e = hipGetLastError();
+  if (e != hipSuccess) { ctx->err = std::string("initial rebuild: ") + hipGetErrorString(e); return bail(STGN_E_DEVICE); }
+  *out = ctx;
+  return STGN_OK;
+}
+
+void stgn_destroy(stgn_ctx* ctx) {
+  if (!ctx) return;
+  if (ctx->stream || ctx->ctrl_host) hipStreamSynchronize(ctx->stream);
+  for (int i = 0; i < 2; ++i) {
+    if (ctx->pin[i]) hipHostFree(ctx->pin[i]);
+    if (ctx->pin_ev[i]) hipEventDestroy(ctx->pin_ev[i]);
+  }
+  if (ctx->ctrl_host) hipHostFree(ctx->ctrl_host);
+  for (auto& e : ctx->stage_ev) if (e) hipEventDestroy(e);
+  for (const TimedLaunch& t : ctx->pending) { hipEventDestroy(t.a); hipEventDestroy(t.b); }
+  for (hipEvent_t e : ctx->free_events) hipEventDestroy(e);
+  delete ctx;
+}
+
+int stgn_ingest_batch(stgn_ctx* ctx, uint32_t n, const uint32_t* src, const uint32_t* dst, const double* ts,
+                      const float* efeat, int inputs_on_device, stgn_batch_stats* stats) {
+  if (!ctx) return STGN_E_INVALID_ARG;
+  const stgn_config& c = ctx->cfg;
+  const Dev& d = ctx->d;
+  if (n > c.max_batch) return fail(ctx, STGN_E_BATCH_TOO_LARGE, "batch larger than max_batch");
+  if (n && (!src || !dst || !ts || (c.d_edge && !efeat))) return fail(ctx, STGN_E_INVALID_ARG, "NULL batch array");
+  if (ctx->host_edges + n > c.max_edges) return fail(ctx, STGN_E_EDGE_CAPACITY, "max_edges exceeded");
+
+  const uint32_t *dsrc = src, *ddst = dst;
+  const double* dts = ts;
+  const float* def = efeat;
+  if (!inputs_on_device) {
+    // host-side validation: nothing is enqueued for a bad batch
+    double prev = (ctx->any_edges && ctx->host_t_known) ? ctx->host_t_last : -INFINITY;
+    for (uint32_t i = 0; i < n; ++i) {
+      if (src[i] >= c.num_nodes || dst[i] >= c.num_nodes) return fail(ctx, STGN_E_NODE_OUT_OF_RANGE, "endpoint id >= num_nodes");
+      if (src[i] == dst[i]) return fail(ctx, STGN_E_SELF_LOOP, "self loop");
+      if (!(ts[i] >= prev)) return fail(ctx, STGN_E_TIME_ORDER, "timestamps must be non-decreasing");
+      prev = ts[i];
+    }
+    if (n) {
+      const int pb = ctx->pin_next;
+      ctx->pin_next ^= 1;
+      if (ctx->pin_used[pb]) HIPCHK(ctx, hipEventSynchronize(ctx->pin_ev[pb]));
+      char* p = ctx->pin[pb];
+      const size_t o_dst = (size_t)c.max_batch * 4, o_ts = (size_t)c.max_batch * 8, o_ef = (size_t)c.max_batch * 16;
+      memcpy(p, src, (size_t)n * 4);
+      memcpy(p + o_dst, dst, (size_t)n * 4);
+      memcpy(p + o_ts, ts, (size_t)n * 8);
+      if (c.d_edge) memcpy(p + o_ef, efeat, (size_t)n * c.d_edge * 4);
+      HIPCHK(ctx, hipMemcpyAsync(d.st_src, p, (size_t)n * 4, hipMemcpyHostToDevice, ctx->stream));
+      HIPCHK(ctx, hipMemcpyAsync(d.st_dst, p + o_dst, (size_t)n * 4, hipMemcpyHostToDevice, ctx->stream));
+      HIPCHK(ctx, hipMemcpyAsync(d.st_ts, p + o_ts, (size_t)n * 8, hipMemcpyHostToDevice, ctx->stream));
+      if (c.d_edge)
+        HIPCHK(ctx, hipMemcpyAsync(d.st_ef, p + o_ef, (size_t)n * c.d_edge * 4, hipMemcpyHostToDevice, ctx->stream));
+      HIPCHK(ctx, hipEventRecord(ctx->pin_ev[pb], ctx->stream));
+      ctx->pin_used[pb] = true;
+      ctx->host_t_last = ts[n - 1];
+      ctx->host_t_known = true;
+      ctx->any_edges = true;
+    }
+    dsrc = d.st_src; ddst = d.st_dst; dts = d.st_ts; def = d.st_ef;
+  } else if (n) {
+    ctx->host_t_known = false;
+    ctx->any_edges = true;
+  }
+  ctx->host_edges += n;
+
+  hipStream_t s = ctx->stream;
+  hipEvent_t* ev = stats ? ctx->stage_ev : nullptr;
+  if (ev) hipEventRecord(ev[0], s);
+  { Scope t(ctx, KC_SORT); launch_stage_sort(d, s, n, dsrc, ddst, dts); }
+  if (ev) hipEventRecord(ev[1], s);
+  if (c.d_mem) { Scope t(ctx, KC_MEMORY); launch_memory_update(d, s, dsrc, ddst, dts, def); }
+  if (ev) hipEventRecord(ev[2], s);
+  { Scope t(ctx, KC_APPLY); launch_apply(d, s, dsrc, ddst, dts, def); }
+  if (ev) hipEventRecord(ev[3], s);
+  for (uint32_t hop = 0; hop < c.layers; ++hop) {
+    { Scope t(ctx, KC_PLAN); launch_plan(d, s, hop); }
+    { Scope t(ctx, KC_EXPAND); launch_expand(d, s, hop, hop + 1 == c.layers); }
+  }
+  { Scope t(ctx, KC_COMPACT); launch_compact(d, s, 0); }
+  { Scope t(ctx, KC_COMPACT); launch_compact(d, s, 1); }
+  if (ev) hipEventRecord(ev[4], s);
+  run_layers(ctx, d.A, &d.ctrl->nA, c.num_nodes);
+  if (ev) hipEventRecord(ev[5], s);
+  HIPCHK(ctx, hipGetLastError());
+
+  if (stats) {
+    int rc = sync_and_poll(ctx);
+    const Ctrl& h = *ctx->ctrl_host;
+    memset(stats, 0, sizeof *stats);
+    stats->n_edges = h.n_edges;
+    stats->n_direct = h.nD;
+    stats->n_affected = h.nA;
+    for (int i = 0; i <= STGN_MAX_LAYERS; ++i) stats->frontier[i] = h.n_front[i];
+    stats->entries_scanned = h.scanned;
+    for (int i = 0; i < 5; ++i) {
+      float ms = 0.0f;
+      hipEventElapsedTime(&ms, ev[i], ev[i + 1]);
+      stats->us_stage[i] = 1000.0f * ms;
+    }
+    float ms = 0.0f;
+    hipEventElapsedTime(&ms, ev[0], ev[5]);
+    stats->us_stage[5] = 1000.0f * ms;
+    return rc;
+  }
+  return STGN_OK;
+}
+
+int stgn_full_rebuild(stgn_ctx* ctx) {
+  if (!ctx) return STGN_E_INVALID_ARG;
+  run_layers(ctx, nullptr, nullptr, ctx->cfg.num_nodes);
+  HIPCHK(ctx, hipGetLastError());
+  return STGN_OK;
+}
+
+int stgn_sync(stgn_ctx* ctx) {
+  if (!ctx) return STGN_E_INVALID_ARG;
+  return sync_and_poll(ctx);
+}
+
+int stgn_get_embeddings(stgn_ctx* ctx, uint32_t layer, uint32_t n, const uint32_t* nodes, float* out, int on_device) {
+  if (!ctx) return STGN_E_INVALID_ARG;
+  const stgn_config& c = ctx->cfg;
+  const Dev& d = ctx->d;
+  if (layer == 0) layer = c.layers;
+  if (layer > c.layers) return fail(ctx, STGN_E_INVALID_ARG, "layer out of range");
+  if (n == 0) return on_device ? STGN_OK : sync_and_poll(ctx);
+  if (!nodes || !out) return fail(ctx, STGN_E_INVALID_ARG, "NULL nodes or out");
+  if (on_device) {
+    Scope t(ctx, KC_GATHER);
+    launch_gather_rows(d, ctx->stream, layer, n, nodes, out);
+    return STGN_OK;
+  }
+  for (uint32_t i = 0; i < n; ++i)
+    if (nodes[i] >= c.num_nodes) return fail(ctx, STGN_E_NODE_OUT_OF_RANGE, "node id >= num_nodes");
+  for (uint32_t lo = 0; lo < n; lo += d.q_cap) {
+    const uint32_t m = std::min(d.q_cap, n - lo);
+    HIPCHK(ctx, hipMemcpyAsync(d.qnodes, nodes + lo, (size_t)m * 4, hipMemcpyHostToDevice, ctx->stream));
+    launch_gather_rows(d, ctx->stream, layer, m, d.qnodes, d.qout);
+    HIPCHK(ctx, hipMemcpyAsync(out + (size_t)lo * c.d_emb, d.qout, (size_t)m * c.d_emb * 4, hipMemcpyDeviceToHost, ctx->stream));
+    HIPCHK(ctx, hipStreamSynchronize(ctx->stream));
+  }
+  return sync_and_poll(ctx);
+}
+
+int stgn_get_affected(stgn_ctx* ctx, uint32_t* out, uint32_t cap, uint32_t* count) {
+  if (!ctx || !count) return STGN_E_INVALID_ARG;
+  int rc = sync_and_poll(ctx);
+  const uint32_t nA = ctx->ctrl_host->nA;
+  *count = nA;
+  const uint32_t m = std::min(nA, cap);
+  if (m && out) HIPCHK(ctx, hipMemcpy(out, ctx->d.A, (size_t)m * 4, hipMemcpyDeviceToHost));
+  return rc;
+}
+
+int stgn_get_neighbors(stgn_ctx* ctx, uint32_t node, uint32_t* nbr, uint32_t* eid, double* ts, uint32_t* count) {
+  if (!ctx || !count) return STGN_E_INVALID_ARG;
+  if (node >= ctx->cfg.num_nodes) return fail(ctx, STGN_E_NODE_OUT_OF_RANGE, "node id >= num_nodes");
+  int rc = sync_and_poll(ctx);
+  const uint32_t k = ctx->cfg.k;
+  uint32_t dg = 0;
+  HIPCHK(ctx, hipMemcpy(&dg, ctx->d.deg + node, 4, hipMemcpyDeviceToHost));
+  std::vector<RingEntry> r(k);
+  HIPCHK(ctx, hipMemcpy(r.data(), ctx->d.ring + (size_t)node * k, (size_t)k * sizeof(RingEntry), hipMemcpyDeviceToHost));
+  const uint32_t cnt = std::min(dg, k);
+  for (uint32_t j = 0; j < cnt; ++j) {
+    const RingEntry& e = r[(dg - 1 - j) % k];
+    if (nbr) nbr[j] = e.nbr;
+    if (eid) eid[j] = e.eid;
+    if (ts) ts[j] = e.t;
+  }
+  *count = cnt;
+  return rc;
+}
+
+int stgn_get_history(stgn_ctx* ctx, uint32_t node, uint32_t first, uint32_t count, uint32_t* nbr, uint32_t* eid,
+                     uint32_t* degree) {
+  if (!ctx) return STGN_E_INVALID_ARG;
+  if (node >= ctx->cfg.num_nodes) return fail(ctx, STGN_E_NODE_OUT_OF_RANGE, "node id >= num_nodes");
+  int rc = sync_and_poll(ctx);
+  const Dev& d = ctx->d;
+  uint32_t dg = 0;
+  HIPCHK(ctx, hipMemcpy(&dg, d.deg + node, 4, hipMemcpyDeviceToHost));
+  if (degree) *degree = dg;
+  if (count == 0) return rc;
+  if ((uint64_t)first + count > dg) return fail(ctx, STGN_E_INVALID_ARG, "history range beyond the node's degree");
+  std::vector<uint32_t> blk(d.maxb);
+  HIPCHK(ctx, hipMemcpy(blk.data(), d.blk + (size_t)node * d.maxb, (size_t)d.maxb * 4, hipMemcpyDeviceToHost));
+  std::vector<uint2> tmp;
+  uint32_t p = first;
+  while (p < first + count) {
+    uint32_t b = 0;
+    while (kMinBlock * ((2u << b) - 1u) <= p) ++b;                 // block holding position p
+    const uint32_t bstart = kMinBlock * ((1u << b) - 1u), bend = kMinBlock * ((2u << b) - 1u);
+    const uint32_t m = std::min(bend, first + count) - p;
+    const uint64_t a = (uint64_t)blk[b] * kMinBlock + (p - bstart);
+    if (nbr) {
+      tmp.resize(m);
+      HIPCHK(ctx, hipMemcpy(tmp.data(), d.pool_nt + a, (size_t)m * sizeof(uint2), hipMemcpyDeviceToHost));
+      for (uint32_t i = 0; i < m; ++i) nbr[p - first + i] = tmp[i].x;
+    }
+    if (eid) HIPCHK(ctx, hipMemcpy(eid + (p - first), d.pool_eid + a, (size_t)m * 4, hipMemcpyDeviceToHost));
+    p += m;
+  }
+  return rc;
+}
+
+int stgn_get_memory(stgn_ctx* ctx, uint32_t n, const uint32_t* nodes, float* mem, double* t_last) {
+  if (!ctx || (n && !nodes)) return STGN_E_INVALID_ARG;
+  const stgn_config& c = ctx->cfg;
+  const Dev& d = ctx->d;
+  for (uint32_t i = 0; i < n; ++i)
+    if (nodes[i] >= c.num_nodes) return fail(ctx, STGN_E_NODE_OUT_OF_RANGE, "node id >= num_nodes");
+  int rc = sync_and_poll(ctx);
+  if (mem && c.d_mem) {
+    std::vector<float> rowbuf;
+    for (uint32_t lo = 0; lo < n; lo += d.q_cap) {
+      const uint32_t m = std::min(d.q_cap, n - lo);
+      rowbuf.resize((size_t)m * d.d0);
+      HIPCHK(ctx, hipMemcpyAsync(d.qnodes, nodes + lo, (size_t)m * 4, hipMemcpyHostToDevice, ctx->stream));
+      launch_gather_rows(d, ctx->stream, 0, m, d.qnodes, d.qout);
+      HIPCHK(ctx, hipMemcpyAsync(rowbuf.data(), d.qout, rowbuf.size() * 4, hipMemcpyDeviceToHost, ctx->stream));
+      HIPCHK(ctx, hipStreamSynchronize(ctx->stream));
+      for (uint32_t i = 0; i < m; ++i)
+        memcpy(mem + (size_t)(lo + i) * c.d_mem, rowbuf.data() + (size_t)i * d.d0, (size_t)c.d_mem * 4);
+    }
+  }
+  if (t_last) {
+    std::vector<double> all(c.num_nodes);
+    HIPCHK(ctx, hipMemcpy(all.data(), d.t_last, (size_t)c.num_nodes * 8, hipMemcpyDeviceToHost));
+    for (uint32_t i = 0; i < n; ++i) t_last[i] = all[nodes[i]];
+  }
+  return rc;
+}
+
+int stgn_get_totals(stgn_ctx* ctx, uint64_t* edges, uint64_t* direct, uint64_t* affected, uint64_t* scanned) {
+  if (!ctx) return STGN_E_INVALID_ARG;
+  int rc = sync_and_poll(ctx);
+  const Ctrl& h = *ctx->ctrl_host;
+  if (edges) *edges = h.E;
+  if (direct) *direct = h.tot_direct;
+  if (affected) *affected = h.tot_affected;
+  if (scanned) *scanned = h.tot_scanned;
+  return rc;
+}
+
+int stgn_kernel_times(stgn_ctx* ctx, int enable, int reset, uint32_t cap, const char** names, double* usec,
+                      uint64_t* launches) {
+  if (!ctx) return STGN_E_INVALID_ARG;
+  HIPCHK(ctx, hipStreamSynchronize(ctx->stream));
+  drain_timing(ctx);
+  const uint32_t m = std::min<uint32_t>(cap, KC_COUNT);
+  for (uint32_t i = 0; i < m; ++i) {
+    if (names) names[i] = kClassNames[i];
+    if (usec) usec[i] = ctx->k_usec[i];
+    if (launches) launches[i] = ctx->k_launches[i];
+  }
+  if (reset) for (int i = 0; i < KC_COUNT; ++i) { ctx->k_usec[i] = 0.0; ctx->k_launches[i] = 0; }
+  ctx->timing = enable != 0;
+  return (int)m;
+}
+
+}  // extern "C"

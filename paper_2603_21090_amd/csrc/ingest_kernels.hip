@@ -1,0 +1,286 @@
+// Batch staging (validate + endpoint sort + dedupe + adjacency block allocation) and the apply
+// step (append to the temporal adjacency, recent-neighbour rings, edge-feature table, memory
+// commit).  Paper Sec. 3.2.1 (edge queue), 3.2.2 (temporal adjacency list), 3.3.2 (neighbour
+// cache), 3.3.5 (adjacency append, in-place memory write-back).
+#include "stgn_internal.h"
+
+namespace stgn {
+
+namespace {
+
+constexpr int kSortThreads = 1024;
+
+// Exclusive block scan of one value per thread (blockDim.x == kSortThreads); returns the
+// exclusive prefix and writes the block total to *total.
+__device__ uint32_t block_excl_scan(uint32_t v, uint32_t* s_buf, uint32_t* total) {
+  const int t = threadIdx.x;
+  s_buf[t] = v;
+  __syncthreads();
+  for (int off = 1; off < kSortThreads; off <<= 1) {
+    uint32_t add = (t >= off) ? s_buf[t - off] : 0u;
+    __syncthreads();
+    s_buf[t] += add;
+    __syncthreads();
+  }
+  const uint32_t incl = s_buf[t];
+  if (total) *total = s_buf[kSortThreads - 1];
+  __syncthreads();
+  return incl - v;
+}
+
+// number of adjacency blocks (sizes 8, 16, 32, ...) needed to hold x entries
+__device__ inline uint32_t blocks_for(uint32_t x) {
+  const uint32_t units = (x + kMinBlock - 1) / kMinBlock;
+  return units ? 32u - (uint32_t)__clz((int)units) : 0u;
+}
+
+// One workgroup.  keys: (node << 32 | slot), slot = 2*i (source side) or 2*i + 1 (destination).
+__global__ __launch_bounds__(kSortThreads) void stage_sort_kernel(Dev d, uint32_t n, const uint32_t* __restrict__ src,
+                                                                  const uint32_t* __restrict__ dst,
+                                                                  const double* __restrict__ ts, uint32_t P) {
+  extern __shared__ uint64_t keys[];
+  __shared__ uint32_t s_buf[kSortThreads];
+  __shared__ uint32_t s_err, s_nD, s_units;
+  const uint32_t t = threadIdx.x;
+  Ctrl* c = d.ctrl;
+  if (t == 0) s_err = 0xFFFFFFFFu;
+  __syncthreads();
+
+  // ---- validation: first offending edge decides the code (ids, self loop, time order)
+  const double t_prev_stream = c->t_stream;
+  const bool have_prev = c->E > 0;
+  for (uint32_t i = t; i < n; i += kSortThreads) {
+    uint32_t code = 0;
+    const uint32_t u = src[i], v = dst[i];
+    const double ti = ts[i];
+    if (u >= d.N || v >= d.N) code = 2;                       // STGN_E_NODE_OUT_OF_RANGE
+    else if (u == v) code = 4;                                // STGN_E_SELF_LOOP
+    else {
+      bool ok;
+      if (i > 0) ok = ti >= ts[i - 1];
+      else ok = have_prev ? (ti >= t_prev_stream) : (ti == ti);
+      if (!ok) code = 3;                                      // STGN_E_TIME_ORDER
+    }
+    if (code) atomicMin(&s_err, (i << 4) | code);
+  }
+  if (t == 0 && c->E + n > d.max_edges) atomicMin(&s_err, 6u);   // STGN_E_EDGE_CAPACITY
+  __syncthreads();
+  if (s_err != 0xFFFFFFFFu) {
+    if (t == 0) {
+      c->skip = 1;
+      if (c->err_code == 0) { c->err_code = -(int32_t)(s_err & 15u); c->err_batch = c->batch_seq; }
+      c->batch_seq += 1;
+      c->n_edges = 0; c->nD = 0; c->scanned = 0;
+      for (int h = 0; h < STGN_MAX_LAYERS + 2; ++h) c->n_front[h] = 0;
+      for (int h = 0; h < STGN_MAX_LAYERS + 1; ++h) c->n_items[h] = 0;
+    }
+    return;
+  }
+
+  // ---- keys + bitonic sort in LDS
+  const uint32_t m = 2 * n;
+  for (uint32_t s = t; s < P; s += kSortThreads) {
+    uint64_t key = ~0ull;
+    if (s < m) {
+      const uint32_t node = (s & 1) ? dst[s >> 1] : src[s >> 1];
+      key = ((uint64_t)node << 32) | s;
+    }
+    keys[s] = key;
+  }
+  __syncthreads();
+  for (uint32_t k2 = 2; k2 <= P; k2 <<= 1) {
+    for (uint32_t j = k2 >> 1; j > 0; j >>= 1) {
+      for (uint32_t x = t; x < (P >> 1); x += kSortThreads) {
+        const uint32_t i = ((x & ~(j - 1)) << 1) | (x & (j - 1));
+        const uint32_t ij = i + j;
+        const bool up = (i & k2) == 0;
+        const uint64_t a = keys[i], b = keys[ij];
+        if ((a > b) == up) { keys[i] = b; keys[ij] = a; }
+      }
+      __syncthreads();
+    }
+  }
+
+  // ---- segment heads -> D, seg_start
+  const uint32_t ept = (P + kSortThreads - 1) / kSortThreads;   // contiguous elements per thread
+  const uint32_t lo = t * ept, hi = min(lo + ept, m);
+  uint32_t heads = 0;
+  for (uint32_t i = lo; i < hi; ++i) {
+    const uint32_t node = (uint32_t)(keys[i] >> 32);
+    heads += (i == 0 || node != (uint32_t)(keys[i - 1] >> 32)) ? 1u : 0u;
+  }
+  uint32_t* totp = &s_nD;
+  uint32_t excl = block_excl_scan(heads, s_buf, totp);
+  const uint32_t nD = s_nD;
+  {
+    uint32_t dcur = excl;          // number of heads before element lo
+    for (uint32_t i = lo; i < hi; ++i) {
+      const uint32_t node = (uint32_t)(keys[i] >> 32);
+      if (i == 0 || node != (uint32_t)(keys[i - 1] >> 32)) {
+        d.D[dcur] = node;
+        d.seg_start[dcur] = i;
+        ++dcur;
+      }
+    }
+    if (t == 0) d.seg_start[nD] = m;
+  }
+  __threadfence_block();
+  __syncthreads();
+  {
+    uint32_t dcur = excl;
+    for (uint32_t i = lo; i < hi; ++i) {
+      const uint64_t key = keys[i];
+      const uint32_t node = (uint32_t)(key >> 32), slot = (uint32_t)key;
+      if (i == 0 || node != (uint32_t)(keys[i - 1] >> 32)) ++dcur;
+      const uint32_t di = dcur - 1;
+      const uint32_t rank = i - d.seg_start[di];
+      d.slot_pos[slot] = d.deg[node] + rank;
+      d.slot_d[slot] = di;
+    }
+  }
+
+  // ---- per distinct endpoint: new degree, last slot, adjacency blocks to allocate
+  const uint32_t eptd = (2 * d.max_batch + kSortThreads - 1) / kSortThreads;
+  const uint32_t dlo = t * eptd, dhi = min(dlo + eptd, nD);
+  uint32_t units = 0;
+  for (uint32_t x = dlo; x < dhi; ++x) {
+    const uint32_t node = d.D[x];
+    const uint32_t s0 = d.seg_start[x], s1 = d.seg_start[x + 1];
+    const uint32_t dp = d.deg[node], dn = dp + (s1 - s0);
+    d.deg_new[x] = dn;
+    d.last_slot[x] = (uint32_t)keys[s1 - 1];
+    const uint32_t b0 = blocks_for(dp), b1 = blocks_for(dn);
+    units += (1u << b1) - (1u << b0);
+  }
+  uint32_t uexcl = block_excl_scan(units, s_buf, &s_units);
+  {
+    uint64_t base = c->pool_units + uexcl;
+    for (uint32_t x = dlo; x < dhi; ++x) {
+      const uint32_t node = d.D[x];
+      const uint32_t b0 = blocks_for(d.deg[node]), b1 = blocks_for(d.deg_new[x]);
+      for (uint32_t b = b0; b < b1; ++b) {
+        d.blk[(size_t)node * d.maxb + b] = (uint32_t)base;
+        base += 1u << b;
+      }
+    }
+  }
+  __syncthreads();
+  if (t == 0) {
+    c->skip = 0;
+    c->batch_seq += 1;
+    c->n_edges = n;
+    c->nD = nD;
+    c->scanned = 0;
+    for (int h = 0; h < STGN_MAX_LAYERS + 2; ++h) c->n_front[h] = 0;
+    for (int h = 0; h < STGN_MAX_LAYERS + 1; ++h) c->n_items[h] = 0;
+    c->n_front[0] = nD;
+    c->E_base = c->E;
+    c->E += n;
+    c->pool_units += s_units;
+    if (n) c->t_stream = ts[n - 1];
+  }
+}
+
+__device__ inline uint64_t log_addr(const Dev& d, uint32_t node, uint32_t pos) {
+  const uint32_t b = 31u - (uint32_t)__clz((int)((pos >> 3) + 1u));
+  const uint32_t off = pos - kMinBlock * ((1u << b) - 1u);
+  return (uint64_t)d.blk[(size_t)node * d.maxb + b] * kMinBlock + off;
+}
+
+__global__ __launch_bounds__(256) void apply_kernel(Dev d, const uint32_t* __restrict__ src,
+                                                    const uint32_t* __restrict__ dst,
+                                                    const double* __restrict__ ts, const float* __restrict__ ef) {
+  const Ctrl* c = d.ctrl;
+  if (c->skip) return;
+  const uint32_t n = c->n_edges, nD = c->nD;
+  const uint64_t E0 = c->E_base;
+  const uint32_t tid = blockIdx.x * blockDim.x + threadIdx.x, nth = gridDim.x * blockDim.x;
+
+  // adjacency entries and ring slots, one thread per (edge, side)
+  for (uint32_t s = tid; s < 2 * n; s += nth) {
+    const uint32_t i = s >> 1;
+    const uint32_t u = src[i], v = dst[i];
+    const uint32_t node = (s & 1) ? v : u, other = (s & 1) ? u : v;
+    const uint32_t pos = d.slot_pos[s], twin = d.slot_pos[s ^ 1];
+    const uint32_t eid = (uint32_t)(E0 + i);
+    const uint64_t a = log_addr(d, node, pos);
+    d.pool_nt[a] = make_uint2(other, twin);
+    d.pool_eid[a] = eid;
+    // only the last k entries a node receives in this batch reach its ring (no slot is written twice)
+    if ((uint64_t)pos + d.k >= d.deg_new[d.slot_d[s]]) {
+      RingEntry r; r.nbr = other; r.eid = eid; r.t = ts[i];
+      d.ring[(size_t)node * d.k + pos % d.k] = r;
+    }
+  }
+  // per distinct endpoint: degree, last interaction time, dirty seed
+  for (uint32_t x = tid; x < nD; x += nth) {
+    const uint32_t v = d.D[x];
+    d.deg[v] = d.deg_new[x];
+    d.t_last[v] = ts[d.last_slot[x] >> 1];
+    atomicOr(&d.bitmap[v >> 5], 1u << (v & 31));
+  }
+  // in-place memory write-back (all reads of the old rows happened in the previous kernel)
+  if (d.d_mem) {
+    const uint32_t tot = nD * d.d_mem;
+    for (uint32_t x = tid; x < tot; x += nth) {
+      const uint32_t dd = x / d.d_mem, col = x - dd * d.d_mem;
+      d.H[0].base[(size_t)d.D[dd] * d.H[0].ld + col] = d.mem_new[(size_t)dd * d.d_mem + col];
+    }
+  }
+  // edge-feature rows and timestamps
+  if (d.d_edge) {
+    const uint32_t tot = n * d.d_edge;
+    for (uint32_t x = tid; x < tot; x += nth) {
+      const uint32_t i = x / d.d_edge, col = x - i * d.d_edge;
+      d.efeat.base[(E0 + i) * d.efeat.ld + col] = ef[x];
+    }
+  }
+  for (uint32_t i = tid; i < n; i += nth) d.ets[E0 + i] = ts[i];
+}
+
+// initial state: zero memory, node features copied by the host afterwards, empty graph
+__global__ void init_state_kernel(Dev d) {
+  const size_t tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x, nth = (size_t)gridDim.x * blockDim.x;
+  for (size_t x = tid; x < (size_t)d.N; x += nth) { d.deg[x] = 0; d.t_last[x] = 0.0; }
+  const size_t h0 = (size_t)d.N * d.H[0].ld;
+  for (size_t x = tid; x < h0; x += nth) d.H[0].base[x] = 0.0f;
+  const size_t nw = ((size_t)d.N + 31) / 32;
+  for (size_t x = tid; x < nw; x += nth) d.bitmap[x] = 0;
+  const size_t nr = (size_t)d.N * d.k;
+  for (size_t x = tid; x < nr; x += nth) { RingEntry r; r.nbr = 0; r.eid = 0; r.t = 0.0; d.ring[x] = r; }
+  if (tid == 0) {
+    Ctrl z = {};
+    *d.ctrl = z;
+  }
+}
+
+}  // namespace
+
+void launch_stage_sort(const Dev& d, hipStream_t s, uint32_t n, const uint32_t* src, const uint32_t* dst,
+                       const double* ts) {
+  uint32_t P = 2;
+  while (P < 2 * n) P <<= 1;
+  hipLaunchKernelGGL(stage_sort_kernel, dim3(1), dim3(kSortThreads), P * sizeof(uint64_t), s, d, n, src, dst, ts, P);
+}
+
+void launch_apply(const Dev& d, hipStream_t s, const uint32_t* src, const uint32_t* dst, const double* ts,
+                  const float* ef) {
+  // sized for the largest section (feature rows of a full batch), grid-stride inside
+  const uint32_t work = d.max_batch * (d.d_edge > 2 ? d.d_edge : 2);
+  uint32_t blocks = (work + 255) / 256;
+  if (blocks > 2048) blocks = 2048;
+  if (blocks < 1) blocks = 1;
+  hipLaunchKernelGGL(apply_kernel, dim3(blocks), dim3(256), 0, s, d, src, dst, ts, ef);
+}
+
+void launch_init_state(const Dev& d, hipStream_t s) {
+  hipLaunchKernelGGL(init_state_kernel, dim3(2048), dim3(256), 0, s, d);
+}
+
+int setup_ingest_attributes(const Dev&) {
+  hipError_t e = hipFuncSetAttribute((const void*)stage_sort_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                     2 * STGN_MAX_BATCH * (int)sizeof(uint64_t));
+  return e == hipSuccess ? 0 : -1;
+}
+
+}  // namespace stgn

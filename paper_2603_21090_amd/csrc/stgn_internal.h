@@ -1,0 +1,145 @@
+// Internal declarations shared by the translation units of libstreamtgn (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "streamtgn.h"
+
+namespace stgn {
+
+constexpr uint32_t kLogChunk = 1024;   // adjacency entries per propagation work item
+constexpr uint32_t kMinBlock = 8;      // entries in the first adjacency block of a node
+
+// 16-byte recent-neighbour record (Sec. 3.3.2): slot (pos mod k) of node v at ring[v*k + slot]
+struct __align__(16) RingEntry {
+  uint32_t nbr;
+  uint32_t eid;
+  double   t;
+};
+
+// Device-resident control block: every size the kernels need lives here so that a whole batch
+// can be enqueued without reading anything back.
+struct Ctrl {
+  uint32_t skip;                 // 1: the current batch failed validation, all its kernels exit
+  int32_t  err_code;             // first device-side error (sticky until read by the host)
+  uint32_t err_batch;
+  uint32_t batch_seq;            // batches seen
+  uint32_t n_edges;              // edges of the current batch
+  uint32_t nD;                   // |V_direct| of the current batch
+  uint32_t nA;                   // |V_aff| of the current batch
+  uint32_t n_front[STGN_MAX_LAYERS + 2];  // frontier sizes per hop (n_front[0] = nD)
+  uint32_t n_items[STGN_MAX_LAYERS + 1];  // propagation work items per hop
+  uint32_t pad0;
+  uint64_t scanned;              // adjacency entries scanned in the current batch
+  uint64_t E_base;               // edges ingested before the current batch
+  uint64_t E;                    // edges ingested including the current batch
+  uint64_t pool_units;           // adjacency pool cursor, in units of kMinBlock entries
+  double   t_stream;             // last ingested timestamp
+  uint64_t tot_direct, tot_affected, tot_scanned;
+};
+
+// Row-table descriptor: row v starts at base + v * ld (floats)
+struct Table {
+  float*   base;
+  uint32_t ld;
+};
+
+// Packed parameters of one attention layer (device pointers)
+struct LayerDev {
+  uint32_t d_in, d_in2;          // input width, padded to even
+  uint32_t Zdim, Zp;             // d_in + d_edge + d_time, and its padded row stride
+  const float* WQn;              // [d_in2 x Np(d_emb)]            node block of W_Q
+  const float* cQ;               // [d_emb]                        phi(0) * (time block of W_Q)
+  const float* WKT;              // [heads][dk2 x Zp]              (W_K head block)^T / sqrt(dk); time rows * sqrt(1/d_t)
+  const float* WV;               // [heads][Zdim2 x Np(dk)]        W_V head block; time rows * sqrt(1/d_t)
+  const float* WO;               // [d_emb2 x Np(d_emb)]
+  const float* bO;               // [d_emb]
+};
+
+struct Dev {
+  // configuration
+  uint32_t N, k, heads, layers, d_mem, d_node, d0, d_edge, d_time, d_emb, d_msg, dk;
+  uint32_t max_batch, maxb;      // maxb: adjacency blocks per node in the block table
+  uint64_t max_edges, pool_cap_units;
+  // persistent state
+  Table    H[STGN_MAX_LAYERS + 1];   // H[0] = [memory | node features]; H[l] = layer-l cache
+  double*  t_last;                   // [N]
+  uint32_t* deg;                     // [N] adjacency entries per node
+  RingEntry* ring;                   // [N x k]
+  uint2*   pool_nt;                  // adjacency pool: (neighbour, position of the twin entry)
+  uint32_t* pool_eid;                // adjacency pool: edge id
+  uint32_t* blk;                     // [N x maxb] block bases in units of kMinBlock entries
+  Table    efeat;                    // [max_edges x ld]
+  double*  ets;                      // [max_edges] edge timestamps
+  // per-batch scratch
+  Ctrl*    ctrl;
+  uint32_t* st_src; uint32_t* st_dst; double* st_ts; float* st_ef;   // staging for host inputs
+  uint32_t* D;                       // [2*max_batch] sorted distinct endpoints
+  uint32_t* seg_start;               // [2*max_batch + 1]
+  uint32_t* last_slot;               // [2*max_batch] per D entry: slot (2*i + side) of its last edge
+  uint32_t* deg_new;                 // [2*max_batch] per D entry: degree after the batch
+  uint32_t* slot_pos;                // [2*max_batch] per slot: position in its node's adjacency
+  uint32_t* slot_d;                  // [2*max_batch] per slot: index into D
+  float*   mem_new;                  // [2*max_batch x d_mem]
+  uint32_t* bitmap;                  // [ceil(N/32)] dirty flags
+  uint32_t* front[2];                // [N] each: frontier lists (ping-pong)
+  uint64_t* items;                   // propagation work items (node, chunk)
+  uint64_t items_cap;
+  uint32_t* blocksum;                // compaction partial sums
+  uint32_t* A;                       // [N] affected set, ascending
+  float*   QT;                       // [N x heads x Zp_max] per-row transformed queries
+  float*   ZB;                       // [N x heads x Zp_max] per-row attention-weighted inputs
+  uint32_t* qnodes; float* qout;     // staging for host-side get_embeddings
+  uint32_t q_cap;
+  // parameters
+  const double* om_rev; const double* ph_rev;   // omega/(2 pi), phase/(2 pi)
+  uint32_t Kmsg, Kmsg2;
+  const float* Wmsg; const float* bmsg;         // [Kmsg2 x Np(d_msg)]
+  const float* Wzr;  const float* Uzr;          // [d_msg2 x 2*Np(d_mem)], [d_mem2 x 2*Np(d_mem)]
+  const float* Wh;   const float* Uh;           // [d_msg2 x Np(d_mem)],  [d_mem2 x Np(d_mem)]
+  const float* bz; const float* br; const float* bh;
+  LayerDev L[STGN_MAX_LAYERS];
+};
+
+inline __host__ __device__ uint32_t round_up(uint32_t x, uint32_t m) { return (x + m - 1) / m * m; }
+
+// Kernel classes for the optional event timing
+enum KernelClass { KC_SORT = 0, KC_MEMORY, KC_APPLY, KC_PLAN, KC_EXPAND, KC_COMPACT, KC_QPROJ, KC_ATTN, KC_OPROJ,
+                   KC_GATHER, KC_COUNT };
+
+struct Launcher {
+  hipStream_t stream;
+  bool timing;
+  // filled by api: begin/end bracket one launch of class c
+  void (*begin)(void* self, int c);
+  void (*end)(void* self, int c);
+  void* self;
+};
+
+// ---- launch wrappers (one per kernel family), defined in the .hip files ----
+void launch_stage_sort(const Dev& d, hipStream_t s, uint32_t n, const uint32_t* src, const uint32_t* dst,
+                       const double* ts);
+void launch_memory_update(const Dev& d, hipStream_t s, const uint32_t* src, const uint32_t* dst, const double* ts,
+                          const float* ef);
+void launch_apply(const Dev& d, hipStream_t s, const uint32_t* src, const uint32_t* dst, const double* ts,
+                  const float* ef);
+void launch_plan(const Dev& d, hipStream_t s, uint32_t hop);
+void launch_expand(const Dev& d, hipStream_t s, uint32_t hop, bool last);
+void launch_compact(const Dev& d, hipStream_t s, int phase);
+void launch_qproj(const Dev& d, hipStream_t s, uint32_t layer, const uint32_t* rows, const uint32_t* count_ptr,
+                  uint32_t count_max);
+void launch_attn(const Dev& d, hipStream_t s, uint32_t layer, const uint32_t* rows, const uint32_t* count_ptr,
+                 uint32_t count_max);
+void launch_oproj(const Dev& d, hipStream_t s, uint32_t layer, const uint32_t* rows, const uint32_t* count_ptr,
+                  uint32_t count_max);
+void launch_gather_rows(const Dev& d, hipStream_t s, uint32_t layer, uint32_t n, const uint32_t* nodes, float* out);
+void launch_init_state(const Dev& d, hipStream_t s);
+int  attn_supported(uint32_t Zdim, uint32_t heads);
+constexpr size_t kMaxLds = 160 * 1024;   // LDS per workgroup on gfx950
+int  setup_ingest_attributes(const Dev& d);
+int  setup_embed_attributes(const Dev& d);
+int  setup_memory_attributes(const Dev& d);
+
+}  // namespace stgn

@@ -1,0 +1,253 @@
+"""Parity of the HIP path (through the C ABI) against the CPU oracle.
+
+Integer results (batch endpoints, affected set, neighbour lists, degrees, adjacency history,
+last-interaction times) must be bit-exact.  Memory rows and embedding rows must satisfy, per
+row, ||g - r||_2 <= 1e-4 ||r||_2 + 1e-6 and the same in max-norm (r = oracle row, fp64
+arithmetic rounded once to fp32; g = fp32 arithmetic on the GPU)."""
+import numpy as np
+import pytest
+
+from oracle import oracle as orc
+from paper_2603_21090_amd import synth
+from tests.helpers import rows_close, tiny_workload
+
+pytestmark = pytest.mark.gpu
+
+REL = 1e-4
+
+
+@pytest.fixture(scope="module")
+def binding():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a device"
+    from paper_2603_21090_amd import binding as b
+    b.load_library()          # no fallback: a missing library fails here
+    return b
+
+
+def check_rows(got, ref, what):
+    ok = rows_close(got, ref, REL)
+    if not ok.all():
+        bad = np.nonzero(~ok)[0]
+        e = np.linalg.norm(got[bad].astype(np.float64) - ref[bad], axis=1) / (np.linalg.norm(ref[bad], axis=1) + 1e-30)
+        raise AssertionError(f"{what}: {len(bad)} rows out of tolerance, worst rel {e.max():.3e} (row {bad[e.argmax()]})")
+
+
+def check_neighbours(g, o, nodes):
+    for v in nodes:
+        gn, ge, gt = g.get_neighbors(v)
+        on, oe, ot = o.neighbors(v)
+        assert np.array_equal(gn, on) and np.array_equal(ge, oe) and np.array_equal(gt, ot), f"ring of node {v}"
+        assert g.get_degree(v) == o.degree(v)
+
+
+def run_stream(binding, w, *, batches=None, check_every=1, full_check_at=(), nodes_for_rings=None, node_feat=None,
+               device_inputs=False, weights=None):
+    import torch
+    st = synth.EdgeStream(w)
+    W = synth.make_weights(w) if weights is None else weights
+    o = orc.Oracle.from_workload(w, W, node_feat)
+    g = binding.StreamTGN.from_workload(w, W, node_feat)
+    nb = w.num_batches if batches is None else batches
+    allnodes = np.arange(w.num_nodes, dtype=np.uint32)
+    for b in range(nb):
+        s, d, t, ef = st.batch(b)
+        rc, D, A = o.ingest(s, d, t, ef)
+        assert rc == 0
+        if device_inputs:
+            args = (torch.from_numpy(s.astype(np.int32)).cuda(), torch.from_numpy(d.astype(np.int32)).cuda(),
+                    torch.from_numpy(t).cuda(), torch.from_numpy(ef).cuda())
+            stats = g.ingest_batch(*args, stats=True)
+        else:
+            stats = g.ingest_batch(s, d, t, ef, stats=True)
+        assert stats["n_direct"] == len(D), f"batch {b}: |D| {stats['n_direct']} != {len(D)}"
+        if b % check_every == 0 or b == nb - 1:
+            assert np.array_equal(g.get_affected(), A), f"batch {b}: affected set differs"
+        else:
+            assert stats["n_affected"] == len(A), f"batch {b}: |A|"
+        if b in full_check_at or b == nb - 1:
+            if w.d_mem:
+                gm, gt = g.get_memory(allnodes)
+                om, ot = o.memory(allnodes)
+                assert np.array_equal(gt, ot), f"batch {b}: t_last"
+                check_rows(gm, om, f"batch {b}: memory")
+            ref = o.embed_all()
+            for l in range(1, w.layers + 1):
+                check_rows(g.get_embeddings(allnodes, layer=l), ref[l - 1], f"batch {b}: layer {l}")
+            check_neighbours(g, o, allnodes if nodes_for_rings is None else nodes_for_rings)
+    return g, o, st
+
+
+def test_c1_full_stream(binding):
+    """Config 1 as specified: every batch's affected set, full state at ten checkpoints."""
+    w = synth.WORKLOADS["C1"]
+    g, o, st = run_stream(binding, w, full_check_at=set(range(0, 100, 10)))
+    tot = g.totals()
+    assert tot["edges"] == w.num_edges
+    # adjacency history of the busiest node, in arrival order
+    deg = np.bincount(np.concatenate([st.src, st.dst]), minlength=w.num_nodes)
+    hub = int(deg.argmax())
+    nbr, eid = g.get_history(hub)
+    inc = np.nonzero((st.src == hub) | (st.dst == hub))[0]
+    assert np.array_equal(eid, inc.astype(np.uint32))
+    assert np.array_equal(nbr, np.where(st.src[inc] == hub, st.dst[inc], st.src[inc]))
+    g.close()
+
+
+@pytest.mark.parametrize("kw", [
+    dict(layers=1, d_mem=8, d_edge=6, d_time=8, d_emb=8, d_msg=8, heads=2, k=3),
+    dict(layers=2, d_mem=10, d_edge=7, d_time=6, d_emb=12, d_msg=9, heads=4, k=3),          # odd widths
+    dict(layers=3, d_mem=33, d_edge=5, d_time=31, d_emb=66, d_msg=35, heads=2, k=4),          # ragged tiles
+    dict(layers=2, d_mem=16, d_edge=0, d_time=8, d_emb=16, d_msg=16, heads=1, k=2),           # no edge features
+    dict(layers=2, d_mem=0, d_node=12, d_edge=6, d_time=8, d_emb=16, heads=2, k=5),           # memoryless
+    dict(layers=2, d_mem=8, d_node=5, d_edge=6, d_time=8, d_emb=16, d_msg=8, heads=2, k=3),   # memory + features
+    dict(layers=2, d_mem=100, d_edge=172, d_time=100, d_emb=100, d_msg=100, heads=2, k=10),   # the paper's widths
+    dict(layers=2, d_mem=0, d_node=100, d_edge=64, d_time=100, d_emb=100, heads=2, k=20),     # config-5 widths
+])
+def test_small_graphs_all_shapes(binding, kw):
+    w = tiny_workload(num_nodes=150, num_edges=1500, batch=50, zipf_s=1.0, **kw)
+    nf = synth.node_features(w)
+    g, o, st = run_stream(binding, w, node_feat=nf, full_check_at=set(range(0, 30, 5)))
+    g.close()
+
+
+def test_device_inputs_match_host_inputs(binding):
+    w = tiny_workload(num_nodes=300, num_edges=3000, batch=100, d_mem=16, d_edge=12, d_time=16, d_emb=16, d_msg=16, k=4)
+    g, o, st = run_stream(binding, w, device_inputs=True, full_check_at={0, 7, 15})
+    g.close()
+
+
+def test_rows_outside_A_untouched_and_rebuild_is_bit_identical(binding):
+    """Theorem 'Equivalence of Incremental Computation': cached rows outside the affected set are
+    bit-identical before and after a batch; a full rebuild reproduces every cached row bit for bit
+    (same kernels, per-row results independent of which rows share a launch)."""
+    w = tiny_workload(num_nodes=400, num_edges=4000, batch=40, d_mem=32, d_edge=12, d_time=16, d_emb=32, d_msg=32,
+                      k=4, zipf_s=0.8)
+    st = synth.EdgeStream(w)
+    W = synth.make_weights(w)
+    g = binding.StreamTGN.from_workload(w, W)
+    allnodes = np.arange(w.num_nodes, dtype=np.uint32)
+    before = [g.get_embeddings(allnodes, layer=l) for l in (1, 2)]
+    seen_small = 0
+    for b in range(40):
+        g.ingest_batch(*st.batch(b))
+        A = g.get_affected()
+        outside = np.setdiff1d(allnodes, A)
+        after = [g.get_embeddings(allnodes, layer=l) for l in (1, 2)]
+        for l in range(2):
+            assert np.array_equal(after[l][outside], before[l][outside]), f"batch {b} layer {l + 1}"
+        seen_small += len(outside) > 0
+        before = after
+    assert seen_small > 0
+    g.full_rebuild()
+    for l in (1, 2):
+        assert np.array_equal(g.get_embeddings(allnodes, layer=l), before[l - 1])
+    g.close()
+
+
+def test_bad_batches_leave_the_state_unchanged(binding):
+    import torch
+    w = tiny_workload(num_nodes=100, num_edges=1000, batch=50, d_mem=8, d_edge=6, d_time=8, d_emb=8, d_msg=8)
+    st = synth.EdgeStream(w)
+    W = synth.make_weights(w)
+    g = binding.StreamTGN.from_workload(w, W)
+    allnodes = np.arange(w.num_nodes, dtype=np.uint32)
+    g.ingest_batch(*st.batch(0))
+    ref = g.get_embeddings(allnodes)
+    refm = g.get_memory(allnodes)
+    s, d, t, ef = [a.copy() for a in st.batch(1)]
+
+    def variants():
+        x = s.copy(); x[3] = w.num_nodes
+        yield (x, d, t, ef), -2
+        x = d.copy(); x[5] = s[5]
+        yield (s, x, t, ef), -4
+        x = t.copy(); x[7] = x[6] - 1.0
+        yield (s, d, x, ef), -3
+        x = t.copy(); x[0] = st.ts[w.batch - 1] - 0.5
+        yield (s, d, x, ef), -3
+        x = t.copy(); x[9] = np.nan
+        yield (s, d, x, ef), -3
+
+    for args, code in variants():        # host inputs: rejected at once
+        assert g.ingest_batch(*args, check=False) == code
+        assert np.array_equal(g.get_embeddings(allnodes), ref)
+    for args, code in variants():        # device inputs: skipped on the device, reported at the next sync
+        dev = (torch.from_numpy(args[0].astype(np.int32)).cuda(), torch.from_numpy(args[1].astype(np.int32)).cuda(),
+               torch.from_numpy(args[2]).cuda(), torch.from_numpy(args[3]).cuda())
+        assert g.ingest_batch(*dev, check=False) == 0
+        assert g.sync(check=False) == code
+        assert g.sync(check=False) == 0
+        assert np.array_equal(g.get_embeddings(allnodes), ref)
+        m = g.get_memory(allnodes)
+        assert np.array_equal(m[0], refm[0]) and np.array_equal(m[1], refm[1])
+    big = np.zeros(w.batch + 1, dtype=np.uint32)
+    assert g.ingest_batch(big, big + 1, np.zeros(w.batch + 1), np.zeros((w.batch + 1, w.d_edge), np.float32),
+                          check=False) == -5
+    # the stream continues normally afterwards
+    o = orc.Oracle.from_workload(w, W)
+    o.ingest(*st.batch(0))
+    rc, D, A = o.ingest(s, d, t, ef)
+    g.ingest_batch(s, d, t, ef)
+    assert np.array_equal(g.get_affected(), A)
+    check_rows(g.get_embeddings(allnodes), o.embed_all()[-1], "after recovery")
+    g.close()
+
+
+def test_empty_batch_and_ring_overflow_in_one_batch(binding):
+    w = tiny_workload(num_nodes=6, num_edges=7, batch=7, layers=1, k=3, d_mem=8, d_edge=6, d_time=8, d_emb=8, d_msg=8)
+    W = synth.make_weights(w)
+    g = binding.StreamTGN.from_workload(w, W, max_edges=64, max_batch=16)
+    o = orc.Oracle.from_workload(w, W)
+    e = np.zeros(0, dtype=np.uint32)
+    st0 = g.ingest_batch(e, e, np.zeros(0), np.zeros((0, w.d_edge), np.float32), stats=True)
+    assert st0["n_direct"] == 0 and st0["n_affected"] == 0 and len(g.get_affected()) == 0
+    src = np.array([0, 1, 0, 2, 0, 0, 3], dtype=np.uint32)
+    dst = np.array([1, 0, 1, 0, 4, 5, 0], dtype=np.uint32)
+    ts = np.arange(1, 8, dtype=np.float64)
+    ef = np.random.default_rng(3).standard_normal((7, w.d_edge)).astype(np.float32)
+    rc, D, A = o.ingest(src, dst, ts, ef)
+    g.ingest_batch(src, dst, ts, ef)
+    assert np.array_equal(g.get_affected(), A)
+    allnodes = np.arange(6, dtype=np.uint32)
+    check_neighbours(g, o, allnodes)
+    check_rows(g.get_embeddings(allnodes), o.embed_all()[-1], "overflow batch")
+    gm, _ = g.get_memory(allnodes)
+    check_rows(gm, o.memory(allnodes)[0], "memory")
+    g.close()
+
+
+def test_c2_stream_sampled(binding):
+    """Config 2 (the benchmark workload), first 300 batches with device-resident inputs as the
+    benchmark feeds them: exact affected set every batch; memory and sampled embeddings at
+    checkpoints; one full comparison of all rows at the end."""
+    import torch
+    w = synth.WORKLOADS["C2"]
+    st = synth.EdgeStream(w)
+    W = synth.make_weights(w)
+    o = orc.Oracle.from_workload(w, W)
+    g = binding.StreamTGN.from_workload(w, W)
+    rng = np.random.default_rng(5)
+    allnodes = np.arange(w.num_nodes, dtype=np.uint32)
+    nb = 300
+    for b in range(nb):
+        s, d, t, ef = st.batch(b)
+        rc, D, A = o.ingest(s, d, t, ef)
+        dev = (torch.from_numpy(s.astype(np.int32)).cuda(), torch.from_numpy(d.astype(np.int32)).cuda(),
+               torch.from_numpy(t).cuda(), torch.from_numpy(ef).cuda())
+        g.ingest_batch(*dev)
+        assert np.array_equal(g.get_affected(), A), f"batch {b}"
+        if b % 60 == 59:
+            gm, gt = g.get_memory(D)
+            om, ot = o.memory(D)
+            assert np.array_equal(gt, ot)
+            check_rows(gm, om, f"batch {b}: memory of D")
+            inA = rng.choice(A, size=60, replace=False)
+            out = rng.choice(np.setdiff1d(allnodes, A), size=20, replace=False)
+            S = np.concatenate([inA, out]).astype(np.uint32)
+            check_rows(g.get_embeddings(S), o.embed_nodes(S), f"batch {b}: sampled embeddings")
+            check_neighbours(g, o, S[:20])
+    ref = o.embed_all()
+    for l in (1, 2):
+        check_rows(g.get_embeddings(allnodes, layer=l), ref[l - 1], f"final layer {l}")
+    g.close()

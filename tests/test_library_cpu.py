@@ -1,0 +1,75 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every declared symbol, sizes a
+workspace and rejects bad arguments.  No kernel runs here."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2603_21090_amd import binding, synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2603_21090_amd import build
+        build.build_library()
+    return binding.load_library()
+
+
+def test_exports_every_declared_symbol(lib):
+    header = open(os.path.join(ROOT, "include", "streamtgn.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(stgn_[a-z_]+)\s*\(", header))
+    assert declared == set(binding.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert lib.stgn_version().decode().startswith("streamtgn")
+
+
+def cfg_of(w, **kw):
+    base = dict(num_nodes=w.num_nodes, max_edges=w.num_edges, max_batch=w.batch, d_mem=w.d_mem, d_node=w.d_node,
+                d_edge=w.d_edge, d_time=w.d_time, d_emb=w.d_emb, d_msg=w.d_msg, k=w.k, heads=w.heads, layers=w.layers)
+    base.update(kw)
+    return binding.make_config(**base)
+
+
+def test_workspace_sizes_scale_with_the_configuration():
+    sizes = {name: binding.query_workspace(cfg_of(w)) for name, w in synth.WORKLOADS.items()}
+    assert sizes["C1"] < sizes["C2"] < sizes["C3"] < sizes["C4"] < sizes["C5"]
+    assert sizes["C5"] < 200 * 2**30          # the largest workload fits one MI355X (288 GB)
+    # the edge-feature table (128-byte aligned rows) must be inside
+    w = synth.WORKLOADS["C4"]
+    assert sizes["C4"] > w.num_edges * 128 * 4
+
+
+@pytest.mark.parametrize("bad", [dict(num_nodes=0), dict(max_edges=0), dict(max_batch=0), dict(max_batch=8193),
+                                 dict(layers=0), dict(layers=5), dict(k=0), dict(heads=3), dict(heads=0),
+                                 dict(d_emb=0), dict(d_time=0), dict(d_mem=0, d_node=0), dict(max_edges=2**31)])
+def test_bad_configurations_are_rejected(lib, bad):
+    w = synth.WORKLOADS["C1"]
+    n = C.c_size_t(0)
+    assert lib.stgn_query_workspace(C.byref(cfg_of(w, **bad)), C.byref(n)) == -1
+    assert lib.stgn_last_error(None)
+
+
+def test_null_arguments(lib):
+    n = C.c_size_t(0)
+    assert lib.stgn_query_workspace(None, C.byref(n)) == -1
+    assert lib.stgn_query_workspace(C.byref(cfg_of(synth.WORKLOADS["C1"])), None) == -1
+    assert lib.stgn_sync(None) == -1
+    assert lib.stgn_full_rebuild(None) == -1
+    lib.stgn_destroy(None)
+
+
+def test_create_without_workspace_or_device_fails_cleanly(lib):
+    w = synth.WORKLOADS["C1"]
+    W = synth.make_weights(w)
+    cw, keep = binding._marshal_weights(W, w.layers, True)
+    h = C.c_void_p(None)
+    rc = lib.stgn_create(C.byref(cfg_of(w)), C.byref(cw), None, None, 0, None, C.byref(h))
+    assert rc == -8 and not h.value
+    rc = lib.stgn_create(C.byref(cfg_of(w)), None, None, None, 0, None, C.byref(h))
+    assert rc == -1
