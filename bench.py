@@ -1,0 +1,241 @@
+#!/usr/bin/env python3
+"""Benchmark of the per-batch incremental inference step on one MI355X.
+
+A step is one batch of the synthetic edge stream through the whole hot path
+(stage + sort, message/GRU, apply, dirty-flag propagation, compaction, all attention
+layers for the affected set).  Inputs are resident in device memory before the timed
+region starts.  The stream is replayed from the empty graph:
+
+  warmup   W batches, untimed                              (default: first 70 % of the stream)
+  timed    K batches enqueued back to back, one sync      -> `value` (edges/s), ms_per_step
+  latency  next batches, one sync per batch                -> p50 / p95 batch latency
+  kernels  next batches with one HIP event pair per launch -> per-kernel average duration,
+                                                              roofline of the dominant kernel
+  cpu      the CPU oracle (full recompute per batch) on a bounded sample, 1 core
+
+Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_F32_PEAK_TFLOPS = 157.3   # MI355X dense fp32 matrix, published
+
+
+def algorithmic_bytes_per_row(w, layer):
+    """Bytes the method must move for one (node, layer): own row, last-interaction time, the
+    ring, k neighbour rows, k edge-feature rows, and the output row (fp32 rows, 16-byte ring
+    records)."""
+    d_in = (w.d_mem + w.d_node) if layer == 0 else w.d_emb
+    return 4 * d_in + 8 + 16 * w.k + w.k * (4 * d_in + 4 * w.d_edge) + 4 * w.d_emb
+
+
+def projection_flops_per_row(w, layer):
+    """FLOPs the re-associated projections execute for one (node, layer), by kernel."""
+    d_in = (w.d_mem + w.d_node) if layer == 0 else w.d_emb
+    z = d_in + w.d_edge + w.d_time
+    q = 2 * (d_in * w.d_emb + w.d_emb * z)          # q, then q W_K^T per head (heads * dk = d_emb)
+    o = 2 * (z * w.d_emb + w.d_emb * w.d_emb)       # zb W_V per head, then W_O
+    return q, o
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--workload", default="C2")
+    ap.add_argument("--latency-steps", type=int, default=None)
+    ap.add_argument("--kernel-steps", type=int, default=None)
+    ap.add_argument("--cpu-steps", type=int, default=2)
+    ap.add_argument("--no-cpu", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
+              "(no collectives or sharding in this library)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2603_21090_amd import binding, synth
+
+    w = synth.WORKLOADS[args.workload]
+    nb = w.num_batches
+    W = int(0.70 * nb) if args.warmup is None else args.warmup
+    K = int(0.15 * nb) if args.steps is None else args.steps
+    rest = max(nb - W - K, 0)
+    LAT = min(rest * 2 // 3, 200) if args.latency_steps is None else args.latency_steps
+    KER = min(rest - LAT, 100) if args.kernel_steps is None else args.kernel_steps
+    if W + K + LAT + KER > nb or K <= 0:
+        print(f"bench.py: warmup {W} + steps {K} + latency {LAT} + kernel {KER} exceed the stream of {nb} batches",
+              file=sys.stderr)
+        sys.exit(2)
+
+    dev = torch.device("cuda:0")
+    st = synth.EdgeStream(w)
+    weights = synth.make_weights(w)
+    nf = synth.node_features(w)
+    g = binding.StreamTGN.from_workload(w, weights, nf)
+
+    # the whole stream segment that will be used, resident on the device
+    used = (W + K + LAT + KER) * w.batch
+    used = min(used, w.num_edges)
+    d_src = torch.from_numpy(st.src[:used].astype(np.int32)).to(dev)
+    d_dst = torch.from_numpy(st.dst[:used].astype(np.int32)).to(dev)
+    d_ts = torch.from_numpy(st.ts[:used]).to(dev)
+    d_ef = torch.empty((used, w.d_edge), dtype=torch.float32, device=dev)
+    CH = 1 << 18
+    for lo in range(0, used, CH):
+        hi = min(lo + CH, used)
+        d_ef[lo:hi] = torch.from_numpy(st.edge_features(lo, hi)).to(dev)
+    torch.cuda.synchronize()
+
+    def feed(b, stats=False):
+        lo, hi = b * w.batch, min((b + 1) * w.batch, used)
+        return g.ingest_batch(d_src[lo:hi], d_dst[lo:hi], d_ts[lo:hi], d_ef[lo:hi], stats=stats)
+
+    b = 0
+    for _ in range(W):
+        feed(b); b += 1
+    g.sync()
+    tot0 = g.totals()
+
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(K):
+        feed(b); b += 1
+    g.sync()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    tot1 = g.totals()
+    wall = t1 - t0
+    edges = tot1["edges"] - tot0["edges"]
+    aff = tot1["affected"] - tot0["affected"]
+    direct = tot1["direct"] - tot0["direct"]
+
+    # per-batch latency: enqueue + wait, one batch at a time
+    lat = []
+    stage_us = np.zeros(6)
+    for _ in range(LAT):
+        a = time.perf_counter()
+        feed(b); g.sync()
+        lat.append(time.perf_counter() - a)
+        b += 1
+    for _ in range(min(20, KER)):      # stage split from the library's own events (adds a sync per batch)
+        s = feed(b, stats=True); b += 1
+        stage_us += np.array([s["us_stage"][k] for k in ("sort", "memory", "apply", "propagate", "embed", "total")])
+    n_stage = min(20, KER)
+
+    # per-kernel durations from HIP events on the library's stream
+    g.kernel_times(enable=True, reset=True)
+    totk0 = g.totals()
+    n_ker = 0
+    for _ in range(KER - n_stage):
+        feed(b); b += 1; n_ker += 1
+    kt = g.kernel_times(enable=False, reset=False)
+    totk1 = g.totals()
+    rows_per_launch = (totk1["affected"] - totk0["affected"]) / max(n_ker, 1)   # |A| per layer launch
+
+    kernels = {}
+    for name, v in kt.items():
+        if v["launches"]:
+            kernels[name] = {"avg_us": v["usec"] / v["launches"], "launches": v["launches"], "total_us": v["usec"]}
+    roofline = None
+    if kernels:
+        dom = max(kernels, key=lambda k: kernels[k]["total_us"])
+        avg_s = kernels[dom]["avg_us"] * 1e-6
+        layer_avg_bytes = np.mean([algorithmic_bytes_per_row(w, l) for l in range(w.layers)])
+        qf = np.mean([projection_flops_per_row(w, l)[0] for l in range(w.layers)])
+        of = np.mean([projection_flops_per_row(w, l)[1] for l in range(w.layers)])
+        if dom in ("qproj", "oproj"):
+            fl = (qf if dom == "qproj" else of) * rows_per_launch
+            ach = fl / avg_s / 1e12
+            roofline = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": MFMA_F32_PEAK_TFLOPS,
+                        "unit": "TFLOP/s", "frac": ach / MFMA_F32_PEAK_TFLOPS, "traffic": None}
+        else:
+            by = layer_avg_bytes * rows_per_launch if dom == "attn" else None
+            ach = (by / avg_s / 1e9) if by else 0.0
+            roofline = {"kernel": dom, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                        "frac": ach / HBM_PEAK_GBS, "traffic": None}
+        roofline["rows_per_launch"] = rows_per_launch
+        roofline["avg_launch_us"] = kernels[dom]["avg_us"]
+        # the same figures for the three layer kernels, whichever dominates
+        for name, kind in (("attn", "hbm"), ("qproj", "mfma"), ("oproj", "mfma")):
+            if name in kernels:
+                s_ = kernels[name]["avg_us"] * 1e-6
+                if kind == "hbm":
+                    kernels[name]["algorithmic_GBs"] = layer_avg_bytes * rows_per_launch / s_ / 1e9
+                    kernels[name]["frac_hbm"] = kernels[name]["algorithmic_GBs"] / HBM_PEAK_GBS
+                else:
+                    f_ = (qf if name == "qproj" else of) * rows_per_launch / s_ / 1e12
+                    kernels[name]["TFLOPs"] = f_
+                    kernels[name]["frac_mfma_f32"] = f_ / MFMA_F32_PEAK_TFLOPS
+
+    cpu = None
+    if not args.no_cpu and args.cpu_steps > 0:
+        from oracle import oracle as orc
+        o = orc.Oracle.from_workload(w, weights, nf)
+        ob = 0
+        for _ in range(min(W, nb - args.cpu_steps)):      # state building, untimed
+            o.ingest(*st.batch(ob)); ob += 1
+        c0 = time.perf_counter()
+        ce = 0
+        for _ in range(args.cpu_steps):
+            s_, d_, t_, e_ = st.batch(ob); ob += 1
+            o.ingest(s_, d_, t_, e_)
+            o.embed_all()                                  # the oracle has no cache: full recompute
+            ce += len(s_)
+        cw = time.perf_counter() - c0
+        cpu = {"value": ce / cw, "unit": "edges/s", "cores": 1, "kind": "oracle",
+               "sample": f"{args.cpu_steps} batches of {w.batch} edges after {ob - args.cpu_steps} untimed "
+                         f"state-building batches; each = ingest + full recompute of all {w.num_nodes} nodes, "
+                         f"{w.layers} layers; host has {os.cpu_count()} logical cores, oracle uses 1",
+               "seconds_per_batch": cw / args.cpu_steps}
+
+    lat_ms = np.array(lat) * 1e3 if lat else np.array([float("nan")])
+    out = {
+        "metric": "streamed_edges_per_s",
+        "value": edges / wall,
+        "unit": "edges/s",
+        "n_gpus": 1,
+        "steps": K,
+        "warmup": W,
+        "ms_per_step": 1e3 * wall / K,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{w.name}: {w.num_nodes} nodes, {w.num_edges} edges, Zipf s={w.zipf_s}, "
+                               f"d_edge={w.d_edge}, d={w.d_emb}, k={w.k}, heads={w.heads}, layers={w.layers}, "
+                               f"batch={w.batch}, {'TGN' if w.d_mem else 'TGAT (memoryless)'}",
+                   "batch": w.batch, "layers": w.layers, "k": w.k, "timed_batches": [W, W + K]},
+        "p50_batch_latency_ms": float(np.percentile(lat_ms, 50)),
+        "p95_batch_latency_ms": float(np.percentile(lat_ms, 95)),
+        "affected_embeddings_per_s": aff / wall,
+        "mean_affected": aff / K,
+        "mean_direct": direct / K,
+        "affected_fraction": aff / K / w.num_nodes,
+        "paper_bound_2BLK": binding.paper_affected_bound(w.batch, w.k, w.layers),
+        "stage_us": dict(zip(("sort", "memory", "apply", "propagate", "embed", "total"),
+                             (stage_us / max(n_stage, 1)).round(2).tolist())),
+        "kernels": kernels,
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "workspace_GiB": g.workspace_bytes / 2**30,
+    }
+    g.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -90,7 +90,9 @@ int check_config(const stgn_config* c, std::string* why) {
   if (c->d_emb / c->heads > 128) return bad("d_emb / heads > 128");
   for (uint32_t l = 0; l < c->layers; ++l) {
     const uint32_t din = l == 0 ? c->d_mem + c->d_node : c->d_emb;
-    if (!attn_supported(din + c->d_edge + c->d_time, c->heads)) return bad("unsupported attention width or head count (heads in {1,2,4}, d_in+d_edge+d_time <= 512)");
+    if (!attn_supported(din, c->d_edge, c->d_time, c->heads))
+      return bad("unsupported attention shape: heads in {1,2,4}, d_time <= 128, and the three input segments "
+                 "(each rounded up to 64) must total <= 512 floats");
   }
   return STGN_OK;
 }
@@ -150,7 +152,21 @@ size_t layout(const stgn_config& c, char* base, Dev* d) {
     L.d_in = l == 0 ? d->d0 : c.d_emb;
     L.d_in2 = round_up(L.d_in, 2);
     L.Zdim = L.d_in + c.d_edge + c.d_time;
-    L.Zp = np32(L.Zdim);
+    L.ns = 0;
+    const uint32_t widths[3] = {L.d_in, c.d_edge, c.d_time};
+    for (uint32_t seg = 0; seg < 3; ++seg)
+      for (uint32_t o = 0; o < widths[seg]; o += kSlot) {
+        L.kind[L.ns] = (uint8_t)seg;
+        L.valid[L.ns] = (uint16_t)std::min(kSlot, widths[seg] - o);
+        L.segoff[L.ns] = (uint16_t)o;
+        ++L.ns;
+      }
+    L.nt = (c.d_time + kSlot - 1) / kSlot;
+    L.Zp = kSlot * L.ns;
+    L.nqt = 0;
+    for (uint32_t h = 0; h < c.heads; ++h)
+      for (uint32_t nt = 0; nt < L.Zp / 32; ++nt)
+        if ((nt & 1u) * 32u < L.valid[nt >> 1]) { L.qt_h[L.nqt] = (uint8_t)h; L.qt_nt[L.nqt] = (uint8_t)nt; ++L.nqt; }
     zp_max = std::max(zp_max, L.Zp);
   }
   d->QT = b.take<float>((size_t)N * c.heads * zp_max);
@@ -184,7 +200,7 @@ size_t layout(const stgn_config& c, char* base, Dev* d) {
     L.WQn = b.take<float>((size_t)L.d_in2 * np32(c.d_emb));
     L.cQ = b.take<float>(c.d_emb);
     L.WKT = b.take<float>((size_t)c.heads * dk2 * L.Zp);
-    L.WV = b.take<float>((size_t)c.heads * round_up(L.Zdim, 2) * np32(d->dk));
+    L.WV = b.take<float>((size_t)c.heads * L.Zp * np32(d->dk));
     L.WO = b.take<float>((size_t)round_up(c.d_emb, 2) * np32(c.d_emb));
     L.bO = b.take<float>(c.d_emb);
   }
@@ -256,13 +272,14 @@ int pack_parameters(stgn_ctx* ctx, const stgn_weights* w) {
       cQ[col] = (float)acc;
     }
     std::vector<float> WKT((size_t)c.heads * dk2 * L.Zp, 0.0f);
-    std::vector<float> WVp((size_t)c.heads * round_up(L.Zdim, 2) * npk, 0.0f);
+    std::vector<float> WVp((size_t)c.heads * L.Zp * npk, 0.0f);
     for (uint32_t h = 0; h < c.heads; ++h)
       for (uint32_t z = 0; z < L.Zdim; ++z) {
         const double rsz = z >= L.d_in + c.d_edge ? tscale : 1.0;
+        const uint32_t pz = slot_pos(z, L.d_in, c.d_edge);
         for (uint32_t cc = 0; cc < dk; ++cc) {
-          WKT[((size_t)h * dk2 + cc) * L.Zp + z] = (float)((double)WK[(size_t)z * c.d_emb + h * dk + cc] * inv_sqrt_dk * rsz);
-          WVp[((size_t)h * round_up(L.Zdim, 2) + z) * npk + cc] = (float)((double)WV[(size_t)z * c.d_emb + h * dk + cc] * rsz);
+          WKT[((size_t)h * dk2 + cc) * L.Zp + pz] = (float)((double)WK[(size_t)z * c.d_emb + h * dk + cc] * inv_sqrt_dk * rsz);
+          WVp[((size_t)h * L.Zp + pz) * npk + cc] = (float)((double)WV[(size_t)z * c.d_emb + h * dk + cc] * rsz);
         }
       }
     std::vector<float> WO((size_t)round_up(c.d_emb, 2) * npd, 0.0f);
@@ -277,8 +294,9 @@ int pack_parameters(stgn_ctx* ctx, const stgn_weights* w) {
 // ---- optional per-kernel event timing
 hipEvent_t get_event(stgn_ctx* ctx) {
   if (!ctx->free_events.empty()) { hipEvent_t e = ctx->free_events.back(); ctx->free_events.pop_back(); return e; }
+  // timing-only events: no system-scope cache write-back / invalidate around the measured kernel
   hipEvent_t e = nullptr;
-  if (hipEventCreate(&e) != hipSuccess) return nullptr;
+  if (hipEventCreateWithFlags(&e, hipEventDisableSystemFence) != hipSuccess) return nullptr;
   return e;
 }
 
@@ -410,6 +428,8 @@ int stgn_create(const stgn_config* cfg, const stgn_weights* w, const float* node
   }
   if ((rc = pack_parameters(ctx, w))) return bail(rc);
   launch_init_state(ctx->d, ctx->stream);
+  for (uint32_t l = 1; l <= cfg->layers; ++l)     // padding columns of the layer caches are read by 16-byte gathers
+    launch_zero(ctx->d.H[l].base, (size_t)cfg->num_nodes * ctx->d.H[l].ld, ctx->stream);
   if (hipStreamSynchronize(ctx->stream) != hipSuccess) { ctx->err = "state initialisation failed"; return bail(STGN_E_DEVICE); }
   if (node_feat && cfg->d_node) {
     hipError_t e = hipMemcpy2D(ctx->d.H[0].base + cfg->d_mem, (size_t)ctx->d.H[0].ld * sizeof(float), node_feat,

@@ -18,13 +18,19 @@ __global__ __launch_bounds__(256) void plan_kernel(Dev d, uint32_t hop) {
   const uint32_t nf = c->n_front[hop];
   const uint32_t* list = hop == 0 ? d.D : d.front[hop & 1];
   const uint32_t tid = blockIdx.x * blockDim.x + threadIdx.x, nth = gridDim.x * blockDim.x;
+  unsigned long long scanned = 0;
   for (uint32_t x = tid; x < nf; x += nth) {
     const uint32_t u = list[x];
-    const uint32_t nch = (d.deg[u] + kLogChunk - 1) / kLogChunk;
+    const uint32_t dg = d.deg[u];
+    const uint32_t nch = (dg + kLogChunk - 1) / kLogChunk;
     if (nch == 0) continue;
+    scanned += dg;
     const uint32_t base = atomicAdd(&c->n_items[hop], nch);
     for (uint32_t ch = 0; ch < nch; ++ch) d.items[base + ch] = ((uint64_t)u << 32) | ch;
   }
+  // entries the expansion of this hop will read: one atomic per wave
+  for (int off = 32; off > 0; off >>= 1) scanned += __shfl_xor(scanned, off);
+  if ((threadIdx.x & 63) == 0 && scanned) atomicAdd((unsigned long long*)&c->scanned, scanned);
 }
 
 __global__ __launch_bounds__(256) void expand_kernel(Dev d, uint32_t hop, int write_next) {
@@ -54,7 +60,10 @@ __global__ __launch_bounds__(256) void expand_kernel(Dev d, uint32_t hop, int wr
         if ((uint64_t)e.y + d.k >= d.deg[w]) {
           const uint32_t bit = 1u << (w & 31);
           uint32_t* word = d.bitmap + (w >> 5);
-          if (!(*word & bit)) isnew = !(atomicOr(word, bit) & bit);
+          // coherent (L2) read first: most flags are already set, and a stale L1 line would turn
+          // every one of those into an atomic on a handful of hot cache lines
+          const uint32_t cur = __hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          if (!(cur & bit)) isnew = !(atomicOr(word, bit) & bit);
         }
       }
       const uint64_t m = __ballot(isnew);
@@ -65,7 +74,6 @@ __global__ __launch_bounds__(256) void expand_kernel(Dev d, uint32_t hop, int wr
         if (isnew && write_next) next[base + (uint32_t)__popcll(m & lt_mask)] = w;
       }
     }
-    if (lane == 0) atomicAdd((unsigned long long*)&c->scanned, (unsigned long long)(hi - lo));
   }
 }
 

@@ -227,15 +227,19 @@ __global__ __launch_bounds__(256) void apply_kernel(Dev d, const uint32_t* __res
       d.H[0].base[(size_t)d.D[dd] * d.H[0].ld + col] = d.mem_new[(size_t)dd * d.d_mem + col];
     }
   }
-  // edge-feature rows and timestamps
+  // edge-feature rows (padding columns zeroed: rows are read with 16-byte gathers) and timestamps
   if (d.d_edge) {
-    const uint32_t tot = n * d.d_edge;
+    const uint32_t ld = d.efeat.ld, tot = n * ld;
     for (uint32_t x = tid; x < tot; x += nth) {
-      const uint32_t i = x / d.d_edge, col = x - i * d.d_edge;
-      d.efeat.base[(E0 + i) * d.efeat.ld + col] = ef[x];
+      const uint32_t i = x / ld, col = x - i * ld;
+      d.efeat.base[(E0 + i) * ld + col] = col < d.d_edge ? ef[(size_t)i * d.d_edge + col] : 0.0f;
     }
   }
   for (uint32_t i = tid; i < n; i += nth) d.ets[E0 + i] = ts[i];
+}
+
+__global__ void zero_kernel(float* p, size_t n) {
+  for (size_t x = (size_t)blockIdx.x * blockDim.x + threadIdx.x; x < n; x += (size_t)gridDim.x * blockDim.x) p[x] = 0.0f;
 }
 
 // initial state: zero memory, node features copied by the host afterwards, empty graph
@@ -266,7 +270,7 @@ void launch_stage_sort(const Dev& d, hipStream_t s, uint32_t n, const uint32_t* 
 void launch_apply(const Dev& d, hipStream_t s, const uint32_t* src, const uint32_t* dst, const double* ts,
                   const float* ef) {
   // sized for the largest section (feature rows of a full batch), grid-stride inside
-  const uint32_t work = d.max_batch * (d.d_edge > 2 ? d.d_edge : 2);
+  const uint32_t work = d.max_batch * (d.efeat.ld > 2 ? d.efeat.ld : 2);
   uint32_t blocks = (work + 255) / 256;
   if (blocks > 2048) blocks = 2048;
   if (blocks < 1) blocks = 1;
@@ -275,6 +279,10 @@ void launch_apply(const Dev& d, hipStream_t s, const uint32_t* src, const uint32
 
 void launch_init_state(const Dev& d, hipStream_t s) {
   hipLaunchKernelGGL(init_state_kernel, dim3(2048), dim3(256), 0, s, d);
+}
+
+void launch_zero(float* p, size_t n, hipStream_t s) {
+  hipLaunchKernelGGL(zero_kernel, dim3(2048), dim3(256), 0, s, p, n);
 }
 
 int setup_ingest_attributes(const Dev&) {

@@ -26,11 +26,13 @@ __global__ __launch_bounds__(256) void memory_update_kernel(Dev d, const uint32_
                                                             const double* __restrict__ ts,
                                                             const float* __restrict__ ef) {
   extern __shared__ float lds[];
+  __shared__ uint32_t s_self[kRows], s_oth[kRows], s_ef[kRows], s_live[kRows];
+  __shared__ double s_dt[kRows];
   const Ctrl* c = d.ctrl;
   if (c->skip) return;
   const uint32_t nD = c->nD;
   const uint32_t ntiles = (nD + kRows - 1) / kRows;
-  const uint32_t dm = d.d_mem, dg = d.d_msg, de = d.d_edge, dt = d.d_time;
+  const uint32_t dm = d.d_mem, dg = d.d_msg, de = d.d_edge;
   const uint32_t dm2 = round_up(dm, 2), dg2 = round_up(dg, 2);
   const uint32_t ldx = d.Kmsg2 + 1, ldm = dg2 + 1, ldg = dm2 + 1;
   float* Xs = lds;                       // [32 x Kmsg2]  message input rows; first dm columns = s
@@ -43,24 +45,56 @@ __global__ __launch_bounds__(256) void memory_update_kernel(Dev d, const uint32_
 
   for (uint32_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
     const uint32_t r0 = tile * kRows;
-    for (uint32_t x = threadIdx.x; x < kRows * d.Kmsg2; x += 256) {
-      const uint32_t r = x / d.Kmsg2, col = x - r * d.Kmsg2;
-      float v = 0.0f;
-      if (r0 + r < nD && col < d.Kmsg) {
+    // per-row metadata first (one thread per row: node, partner, edge, time gap), through LDS
+    if (threadIdx.x < kRows) {
+      const uint32_t r = threadIdx.x;
+      uint32_t so = 0, oo = 0, eo = 0, live = 0;
+      double dtv = 0.0;
+      if (r0 + r < nD) {
         const uint32_t node = d.D[r0 + r];
         const uint32_t slot = d.last_slot[r0 + r];
         const uint32_t i = slot >> 1;
-        if (col < dm) v = H0.base[(size_t)node * H0.ld + col];
-        else if (col < 2 * dm) {
-          const uint32_t other = (slot & 1) ? src[i] : dst[i];
-          v = H0.base[(size_t)other * H0.ld + (col - dm)];
-        } else if (col < 2 * dm + de) v = ef[(size_t)i * de + (col - 2 * dm)];
-        else {
-          const uint32_t q = col - 2 * dm - de;
-          v = cos_rev64(d.om_rev[q] * (ts[i] - d.t_last[node]) + d.ph_rev[q]);
+        const uint32_t other = (slot & 1) ? src[i] : dst[i];
+        so = node * H0.ld; oo = other * H0.ld; eo = i * de; live = 1;
+        dtv = ts[i] - d.t_last[node];
+      }
+      s_self[r] = so; s_oth[r] = oo; s_ef[r] = eo; s_live[r] = live; s_dt[r] = dtv;
+    }
+    __syncthreads();
+    // then every thread issues its loads in batches of four, unconditionally (dead elements read a
+    // valid dummy address and are zeroed afterwards), so the latencies overlap
+    {
+      const uint32_t total = kRows * d.Kmsg2;
+      const float* efp = ef ? ef : H0.base;
+      for (uint32_t x0 = threadIdx.x; x0 < total; x0 += 256u * 4u) {
+        float v[4];
+        uint32_t rr[4], cc[4];
+        bool ok[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          uint32_t x = x0 + 256u * e;
+          ok[e] = x < total;
+          x = ok[e] ? x : 0u;
+          const uint32_t r = x / d.Kmsg2, col = x - r * d.Kmsg2;
+          rr[e] = r; cc[e] = col;
+          const float* p = H0.base;
+          if (col < dm) p = H0.base + s_self[r] + col;
+          else if (col < 2 * dm) p = H0.base + s_oth[r] + (col - dm);
+          else if (col < 2 * dm + de) p = efp + s_ef[r] + (col - 2 * dm);
+          v[e] = *p;
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const uint32_t r = rr[e], col = cc[e];
+          float val = v[e];
+          if (col >= 2 * dm + de && col < d.Kmsg) {
+            const uint32_t q = col - 2 * dm - de;
+            val = cos_rev64(d.om_rev[q] * s_dt[r] + d.ph_rev[q]);
+          }
+          if (!s_live[r] || col >= d.Kmsg) val = 0.0f;
+          if (ok[e]) Xs[r * ldx + col] = val;
         }
       }
-      Xs[r * ldx + col] = v;
     }
     for (uint32_t x = threadIdx.x; x < kRows; x += 256) {
       Ms[x * ldm + dg2 - 1] = 0.0f;

@@ -9,7 +9,7 @@
 
 namespace stgn {
 
-constexpr uint32_t kLogChunk = 1024;   // adjacency entries per propagation work item
+constexpr uint32_t kLogChunk = 128;    // adjacency entries per propagation work item
 constexpr uint32_t kMinBlock = 8;      // entries in the first adjacency block of a node
 
 // 16-byte recent-neighbour record (Sec. 3.3.2): slot (pos mod k) of node v at ring[v*k + slot]
@@ -47,16 +47,34 @@ struct Table {
 };
 
 // Packed parameters of one attention layer (device pointers)
+// The attention input z = [h_u | e | phi(dt)] is kept in a slot layout: each of the three segments
+// is padded to a multiple of 64 floats (one slot = 16 lanes x float4), so a slot never mixes
+// segments.  Zp = 64 * ns floats per head.
+constexpr uint32_t kSlot = 64;
+constexpr uint32_t kMaxSlots = 8;
 struct LayerDev {
   uint32_t d_in, d_in2;          // input width, padded to even
-  uint32_t Zdim, Zp;             // d_in + d_edge + d_time, and its padded row stride
+  uint32_t Zdim, Zp;             // d_in + d_edge + d_time; padded (slot layout) width
+  uint32_t ns, nt;               // slots in total, time slots (the last nt of them)
+  uint8_t  kind[kMaxSlots];      // 0 node row, 1 edge-feature row, 2 time encoding
+  uint16_t valid[kMaxSlots];     // valid floats in the slot (1..64)
+  uint16_t segoff[kMaxSlots];    // offset of the slot inside its segment's source row
+  uint32_t nqt;                  // (head, 32-column tile) pairs of the qt row that hold valid columns
+  uint8_t  qt_h[64], qt_nt[64];
   const float* WQn;              // [d_in2 x Np(d_emb)]            node block of W_Q
   const float* cQ;               // [d_emb]                        phi(0) * (time block of W_Q)
   const float* WKT;              // [heads][dk2 x Zp]              (W_K head block)^T / sqrt(dk); time rows * sqrt(1/d_t)
-  const float* WV;               // [heads][Zdim2 x Np(dk)]        W_V head block; time rows * sqrt(1/d_t)
+  const float* WV;               // [heads][Zp x Np(dk)]           W_V head block; time rows * sqrt(1/d_t)
   const float* WO;               // [d_emb2 x Np(d_emb)]
   const float* bO;               // [d_emb]
 };
+
+// position of original column z of [h_u | e | phi] in the slot layout
+inline __host__ __device__ uint32_t slot_pos(uint32_t z, uint32_t d_in, uint32_t d_edge) {
+  const uint32_t e0 = (d_in + kSlot - 1) / kSlot * kSlot;
+  const uint32_t t0 = e0 + (d_edge + kSlot - 1) / kSlot * kSlot;
+  return z < d_in ? z : z < d_in + d_edge ? e0 + (z - d_in) : t0 + (z - d_in - d_edge);
+}
 
 struct Dev {
   // configuration
@@ -109,15 +127,6 @@ inline __host__ __device__ uint32_t round_up(uint32_t x, uint32_t m) { return (x
 enum KernelClass { KC_SORT = 0, KC_MEMORY, KC_APPLY, KC_PLAN, KC_EXPAND, KC_COMPACT, KC_QPROJ, KC_ATTN, KC_OPROJ,
                    KC_GATHER, KC_COUNT };
 
-struct Launcher {
-  hipStream_t stream;
-  bool timing;
-  // filled by api: begin/end bracket one launch of class c
-  void (*begin)(void* self, int c);
-  void (*end)(void* self, int c);
-  void* self;
-};
-
 // ---- launch wrappers (one per kernel family), defined in the .hip files ----
 void launch_stage_sort(const Dev& d, hipStream_t s, uint32_t n, const uint32_t* src, const uint32_t* dst,
                        const double* ts);
@@ -136,7 +145,8 @@ void launch_oproj(const Dev& d, hipStream_t s, uint32_t layer, const uint32_t* r
                   uint32_t count_max);
 void launch_gather_rows(const Dev& d, hipStream_t s, uint32_t layer, uint32_t n, const uint32_t* nodes, float* out);
 void launch_init_state(const Dev& d, hipStream_t s);
-int  attn_supported(uint32_t Zdim, uint32_t heads);
+void launch_zero(float* p, size_t n, hipStream_t s);
+int  attn_supported(uint32_t d_in, uint32_t d_edge, uint32_t d_time, uint32_t heads);
 constexpr size_t kMaxLds = 160 * 1024;   // LDS per workgroup on gfx950
 int  setup_ingest_attributes(const Dev& d);
 int  setup_embed_attributes(const Dev& d);
