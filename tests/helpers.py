@@ -53,3 +53,42 @@ def rows_close(got, ref, rel=1e-4, abs_=1e-6):
     ok2 = np.linalg.norm(d, axis=1) <= rel * np.linalg.norm(ref, axis=1) + abs_
     okm = np.abs(d).max(axis=1) <= rel * np.abs(ref).max(axis=1) + abs_
     return ok2 & okm
+
+
+def rings_matrix(src, dst, n_edges, num_nodes, k):
+    """Vectorised most-recent-k table from the raw edge list: nbr[N,k], eid[N,k] (most recent
+    first, -1 padded) and the per-node degree.  Pure bookkeeping on the inputs."""
+    s = np.asarray(src[:n_edges], dtype=np.int64)
+    d = np.asarray(dst[:n_edges], dtype=np.int64)
+    e = np.arange(n_edges, dtype=np.int64)
+    node = np.concatenate([s, d])
+    other = np.concatenate([d, s])
+    eid = np.concatenate([e, e])
+    side = np.concatenate([np.zeros(n_edges, np.int64), np.ones(n_edges, np.int64)])
+    order = np.lexsort((side, eid, node))            # by node, then arrival (source side first)
+    node, other, eid = node[order], other[order], eid[order]
+    deg = np.bincount(node, minlength=num_nodes)
+    end = np.cumsum(deg)                              # one past the last entry of each node
+    nbr_m = np.full((num_nodes, k), -1, dtype=np.int64)
+    eid_m = np.full((num_nodes, k), -1, dtype=np.int64)
+    for j in range(k):
+        has = deg > j
+        idx = end[has] - 1 - j
+        nbr_m[has, j] = other[idx]
+        eid_m[has, j] = eid[idx]
+    return nbr_m, eid_m, deg
+
+
+def affected_from_rings(nbr_m, direct, hops):
+    """Pull formulation on the ring table: w joins when a member of its ring joined one hop ago."""
+    N = nbr_m.shape[0]
+    inA = np.zeros(N, dtype=bool)
+    inA[np.asarray(direct, dtype=np.int64)] = True
+    front = inA.copy()
+    valid = nbr_m >= 0
+    safe = np.where(valid, nbr_m, 0)
+    for _ in range(hops):
+        hit = (front[safe] & valid).any(axis=1) & ~inA
+        inA |= hit
+        front = hit
+    return np.nonzero(inA)[0].astype(np.uint32)
