@@ -32,12 +32,14 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_F32_PEAK_TFLOPS = 157.3   # MI355X dense fp32 matrix, published
 
 
-def algorithmic_bytes_per_row(w, layer):
-    """Bytes the method must move for one (node, layer): own row, last-interaction time, the
-    ring, k neighbour rows, k edge-feature rows, and the output row (fp32 rows, 16-byte ring
-    records)."""
-    d_in = (w.d_mem + w.d_node) if layer == 0 else w.d_emb
-    return 4 * d_in + 8 + 16 * w.k + w.k * (4 * d_in + 4 * w.d_edge) + 4 * w.d_emb
+def algorithmic_bytes(w, rows, entries):
+    """Bytes one attention layer must move for `rows` target rows that hold `entries` recent-
+    neighbour records in total: per row the own layer-input row, the last-interaction time and the
+    output row; per record the 16-byte ring entry, one neighbour row and one edge-feature row
+    (fp32).  With full rings (entries = k * rows) this is the per-(node, layer) figure
+    4 d + 8 + 4 d + k (16 + 4 d + 4 d_edge)."""
+    d_in = np.mean([(w.d_mem + w.d_node) if l == 0 else w.d_emb for l in range(w.layers)])
+    return rows * (4 * d_in + 8 + 4 * w.d_emb) + entries * (16 + 4 * d_in + 4 * w.d_edge)
 
 
 def projection_flops_per_row(w, layer):
@@ -59,6 +61,9 @@ def main():
     ap.add_argument("--kernel-steps", type=int, default=None)
     ap.add_argument("--cpu-steps", type=int, default=2)
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy (5 times) so that hardware byte counters "
+                         "collected around this command can be scaled against a kernel of known traffic")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
@@ -143,42 +148,43 @@ def main():
         feed(b); b += 1; n_ker += 1
     kt = g.kernel_times(enable=False, reset=False)
     totk1 = g.totals()
-    rows_per_launch = (totk1["affected"] - totk0["affected"]) / max(n_ker, 1)   # |A| per layer launch
+    n_layer_launches = max(n_ker * w.layers, 1)
+    rows_per_launch = (totk1["affected"] - totk0["affected"]) / max(n_ker, 1)          # |A| per layer launch
+    entries_per_launch = (totk1["gathered"] - totk0["gathered"]) / n_layer_launches    # ring records per launch
 
+    # An event pair around an empty kernel measures what the bracketing itself costs (the command
+    # processor handles two marker packets and one dispatch); it is subtracted from every class.
+    overhead_us = kt["noop"]["usec"] / kt["noop"]["launches"] if kt.get("noop", {}).get("launches") else 0.0
     kernels = {}
     for name, v in kt.items():
-        if v["launches"]:
-            kernels[name] = {"avg_us": v["usec"] / v["launches"], "launches": v["launches"], "total_us": v["usec"]}
+        if v["launches"] and name != "noop":
+            raw = v["usec"] / v["launches"]
+            kernels[name] = {"avg_us": max(raw - overhead_us, 0.05), "avg_us_with_event_overhead": raw,
+                             "launches": v["launches"]}
+            kernels[name]["total_us"] = kernels[name]["avg_us"] * v["launches"]
     roofline = None
     if kernels:
-        dom = max(kernels, key=lambda k: kernels[k]["total_us"])
-        avg_s = kernels[dom]["avg_us"] * 1e-6
-        layer_avg_bytes = np.mean([algorithmic_bytes_per_row(w, l) for l in range(w.layers)])
         qf = np.mean([projection_flops_per_row(w, l)[0] for l in range(w.layers)])
         of = np.mean([projection_flops_per_row(w, l)[1] for l in range(w.layers)])
-        if dom in ("qproj", "oproj"):
-            fl = (qf if dom == "qproj" else of) * rows_per_launch
-            ach = fl / avg_s / 1e12
-            roofline = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": MFMA_F32_PEAK_TFLOPS,
-                        "unit": "TFLOP/s", "frac": ach / MFMA_F32_PEAK_TFLOPS, "traffic": None}
-        else:
-            by = layer_avg_bytes * rows_per_launch if dom == "attn" else None
-            ach = (by / avg_s / 1e9) if by else 0.0
-            roofline = {"kernel": dom, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                        "frac": ach / HBM_PEAK_GBS, "traffic": None}
+        layer_bytes = algorithmic_bytes(w, rows_per_launch, entries_per_launch)
+        if "layer" in kernels:
+            # the fused layer kernel gathers (HBM) and projects (fp32 MFMA); per row the gather is the
+            # larger of the two at the published peaks, so HBM is the bounding roof
+            s_ = kernels["layer"]["avg_us"] * 1e-6
+            kernels["layer"]["algorithmic_GBs"] = layer_bytes / s_ / 1e9
+            kernels["layer"]["frac_hbm"] = kernels["layer"]["algorithmic_GBs"] / HBM_PEAK_GBS
+            kernels["layer"]["projection_TFLOPs"] = (qf + of) * rows_per_launch / s_ / 1e12
+            kernels["layer"]["frac_mfma_f32"] = kernels["layer"]["projection_TFLOPs"] / MFMA_F32_PEAK_TFLOPS
+        dom = max(kernels, key=lambda k: kernels[k]["total_us"])
+        roofline = {"kernel": "layer", "bound": "hbm", "achieved": kernels["layer"]["algorithmic_GBs"],
+                    "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": kernels["layer"]["frac_hbm"], "traffic": None,
+                    "mfma_f32_frac": kernels["layer"]["frac_mfma_f32"]}
+        if dom != "layer":
+            roofline["note"] = f"largest total time is in {dom}, which moves too little data for a roofline"
         roofline["rows_per_launch"] = rows_per_launch
-        roofline["avg_launch_us"] = kernels[dom]["avg_us"]
-        # the same figures for the three layer kernels, whichever dominates
-        for name, kind in (("attn", "hbm"), ("qproj", "mfma"), ("oproj", "mfma")):
-            if name in kernels:
-                s_ = kernels[name]["avg_us"] * 1e-6
-                if kind == "hbm":
-                    kernels[name]["algorithmic_GBs"] = layer_avg_bytes * rows_per_launch / s_ / 1e9
-                    kernels[name]["frac_hbm"] = kernels[name]["algorithmic_GBs"] / HBM_PEAK_GBS
-                else:
-                    f_ = (qf if name == "qproj" else of) * rows_per_launch / s_ / 1e12
-                    kernels[name]["TFLOPs"] = f_
-                    kernels[name]["frac_mfma_f32"] = f_ / MFMA_F32_PEAK_TFLOPS
+        roofline["ring_entries_per_launch"] = entries_per_launch
+        roofline["avg_launch_us"] = kernels[roofline["kernel"]]["avg_us"]
+        roofline["event_overhead_us"] = overhead_us
 
     cpu = None
     if not args.no_cpu and args.cpu_steps > 0:
@@ -234,6 +240,12 @@ def main():
         "workspace_GiB": g.workspace_bytes / 2**30,
     }
     g.close()
+    if args.calibrate_copy:
+        a_ = torch.empty(1 << 28, dtype=torch.float32, device=dev)
+        b_ = torch.zeros(1 << 28, dtype=torch.float32, device=dev)
+        for _ in range(5):
+            a_.copy_(b_)
+        torch.cuda.synchronize()
     print(json.dumps(out))
 
 

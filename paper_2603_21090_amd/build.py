@@ -1,26 +1,47 @@
 """Compiles the HIP sources of libstreamtgn for gfx950 into the package directory."""
 from __future__ import annotations
 
+import concurrent.futures as cf
 import os
 import subprocess
+import tempfile
 
 PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libstreamtgn.so")
-SOURCES = ["api.hip", "ingest_kernels.hip", "memory_kernels.hip", "frontier_kernels.hip", "embed_kernels.hip"]
-FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-shared", "-Wall", "-Wno-unused-value", "-Wno-unused-result", "-Wno-pass-failed",
+SOURCES = ["api.hip", "ingest_kernels.hip", "memory_kernels.hip", "frontier_kernels.hip", "embed_kernels.hip"] + \
+          [f"layer_ns{ns}.hip" for ns in range(2, 9)]
+FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-value", "-Wno-unused-result",
+         "-Wno-pass-failed",
          # packed fp32 forms are kept out of the generated code on this target
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 
-def build_library(verbose: bool = False) -> str:
+def build_library(verbose: bool = False, jobs: int | None = None) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *FLAGS, "-I", os.path.join(ROOT, "include"), "-I", CSRC,
-           *[os.path.join(CSRC, s) for s in SOURCES], "-o", LIB]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.check_call(cmd)
+    jobs = jobs or min(8, os.cpu_count() or 1, int(os.environ.get("MAX_JOBS", "8")))
+    inc = ["-I", os.path.join(ROOT, "include"), "-I", CSRC]
+    with tempfile.TemporaryDirectory(prefix="stgn_build_") as tmp:
+        def compile_one(src):
+            obj = os.path.join(tmp, src.replace(".hip", ".o"))
+            cmd = [hipcc, *FLAGS, *inc, "-c", os.path.join(CSRC, src), "-o", obj]
+            if verbose:
+                print(" ".join(cmd), flush=True)
+            r = subprocess.run(cmd, capture_output=True, text=True)
+            out = "\n".join(l for l in (r.stdout + r.stderr).splitlines() if "is not a recognized feature" not in l)
+            if r.returncode != 0:
+                raise RuntimeError(f"compiling {src} failed:\n{out}")
+            if out.strip() and verbose:
+                print(out, flush=True)
+            return obj
+
+        with cf.ThreadPoolExecutor(max_workers=jobs) as pool:
+            objs = list(pool.map(compile_one, SOURCES))
+        cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.check_call(cmd)
     return LIB
 
 

@@ -7,13 +7,14 @@
 #include <vector>
 
 #include "stgn_internal.h"
+#include "mfma16.h"
 
 using namespace stgn;
 
 namespace {
 
 const char* const kClassNames[KC_COUNT] = {"stage_sort", "memory_update", "apply", "plan", "expand", "compact",
-                                           "qproj", "attn", "oproj", "gather_rows"};
+                                           "layer", "gather_rows", "noop"};
 
 std::string g_create_error;
 
@@ -97,6 +98,16 @@ int check_config(const stgn_config* c, std::string* why) {
   return STGN_OK;
 }
 
+// Tile-major packing of a [K x N] weight matrix for 16x16x4 matrix instructions: element (k, j)
+// lives at ((j / 16) * ceil(K / 4) + k / 4) * 64 + (k % 4) * 16 + j % 16; zero padded, plus a few
+// zero blocks at the end so that a reader may run past the last tile.
+size_t tiled_size(uint32_t K, uint32_t N) {
+  return ((size_t)((N + 15) / 16) * ((K + 3) / 4) + kPadBlocks) * kBlk16;
+}
+void put_tiled(std::vector<float>& dst, uint32_t K, uint32_t k, uint32_t j, double v) {
+  dst[((size_t)(j / 16) * ((K + 3) / 4) + k / 4) * kBlk16 + (k % 4) * 16 + j % 16] = (float)v;
+}
+
 // Lays the whole device state out in one workspace; base == nullptr only measures.
 size_t layout(const stgn_config& c, char* base, Dev* d) {
   Bump b{base};
@@ -146,7 +157,6 @@ size_t layout(const stgn_config& c, char* base, Dev* d) {
   d->items = b.take<uint64_t>(d->items_cap);
   d->blocksum = b.take<uint32_t>(((size_t)N + 31) / 32 / 1024 + 2);
   d->A = b.take<uint32_t>(N);
-  uint32_t zp_max = 0;
   for (uint32_t l = 0; l < c.layers; ++l) {
     LayerDev& L = d->L[l];
     L.d_in = l == 0 ? d->d0 : c.d_emb;
@@ -163,21 +173,13 @@ size_t layout(const stgn_config& c, char* base, Dev* d) {
       }
     L.nt = (c.d_time + kSlot - 1) / kSlot;
     L.Zp = kSlot * L.ns;
-    L.nqt = 0;
-    for (uint32_t h = 0; h < c.heads; ++h)
-      for (uint32_t nt = 0; nt < L.Zp / 32; ++nt)
-        if ((nt & 1u) * 32u < L.valid[nt >> 1]) { L.qt_h[L.nqt] = (uint8_t)h; L.qt_nt[L.nqt] = (uint8_t)nt; ++L.nqt; }
-    zp_max = std::max(zp_max, L.Zp);
   }
-  d->QT = b.take<float>((size_t)N * c.heads * zp_max);
-  d->ZB = b.take<float>((size_t)N * c.heads * zp_max);
   d->q_cap = 65536;
   d->qnodes = b.take<uint32_t>(d->q_cap);
   d->qout = b.take<float>((size_t)d->q_cap * std::max(d->d0, c.d_emb));
   // parameters
   d->om_rev = b.take<double>(c.d_time);
   d->ph_rev = b.take<double>(c.d_time);
-  const uint32_t dk2 = round_up(d->dk, 2);
   if (c.d_mem) {
     d->Kmsg = 2 * c.d_mem + c.d_edge + c.d_time;
     d->Kmsg2 = round_up(d->Kmsg, 2);
@@ -197,11 +199,11 @@ size_t layout(const stgn_config& c, char* base, Dev* d) {
   }
   for (uint32_t l = 0; l < c.layers; ++l) {
     LayerDev& L = d->L[l];
-    L.WQn = b.take<float>((size_t)L.d_in2 * np32(c.d_emb));
+    L.WQn = b.take<float>(tiled_size(L.d_in, c.d_emb));
     L.cQ = b.take<float>(c.d_emb);
-    L.WKT = b.take<float>((size_t)c.heads * dk2 * L.Zp);
-    L.WV = b.take<float>((size_t)c.heads * L.Zp * np32(d->dk));
-    L.WO = b.take<float>((size_t)round_up(c.d_emb, 2) * np32(c.d_emb));
+    L.WKT = b.take<float>(tiled_size(d->dk, c.heads * L.Zp));
+    L.WV = b.take<float>(tiled_size(L.Zp, c.heads * round_up(d->dk, 16)));
+    L.WO = b.take<float>(tiled_size(c.d_emb, c.d_emb));
     L.bO = b.take<float>(c.d_emb);
   }
   return (b.off + 255) & ~(size_t)255;
@@ -257,13 +259,15 @@ int pack_parameters(stgn_ctx* ctx, const stgn_weights* w) {
         (rc = upload(ctx, d.br, vec(w->b_r, c.d_mem))) || (rc = upload(ctx, d.bh, vec(w->b_h, c.d_mem))))
       return rc;
   }
-  const uint32_t dk = d.dk, dk2 = round_up(dk, 2), npk = np32(dk), npd = np32(c.d_emb);
+  // attention weights feed 16x16x4 matrix instructions: tile-major packing (see tiled_size)
+  const uint32_t dk = d.dk, npk = round_up(dk, 16);
   const double inv_sqrt_dk = 1.0 / std::sqrt((double)dk);
   for (uint32_t l = 0; l < c.layers; ++l) {
     const LayerDev& L = d.L[l];
-    const float *WQ = w->W_Q[l], *WK = w->W_K[l], *WV = w->W_V[l];
-    std::vector<float> WQn((size_t)L.d_in2 * npd, 0.0f);
-    put_block(WQn, npd, 0, WQ, L.d_in, c.d_emb);
+    const float *WQ = w->W_Q[l], *WK = w->W_K[l], *WV = w->W_V[l], *WOs = w->W_O[l];
+    std::vector<float> WQn(tiled_size(L.d_in, c.d_emb), 0.0f);
+    for (uint32_t i = 0; i < L.d_in; ++i)
+      for (uint32_t col = 0; col < c.d_emb; ++col) put_tiled(WQn, L.d_in, i, col, WQ[(size_t)i * c.d_emb + col]);
     std::vector<float> cQ(c.d_emb);
     for (uint32_t col = 0; col < c.d_emb; ++col) {
       double acc = 0.0;
@@ -271,19 +275,22 @@ int pack_parameters(stgn_ctx* ctx, const stgn_weights* w) {
         acc += tscale * std::cos((double)w->phase[i]) * (double)WQ[(size_t)(L.d_in + i) * c.d_emb + col];
       cQ[col] = (float)acc;
     }
-    std::vector<float> WKT((size_t)c.heads * dk2 * L.Zp, 0.0f);
-    std::vector<float> WVp((size_t)c.heads * L.Zp * npk, 0.0f);
+    // W_K head blocks transposed: K = dk, columns = (head, slot position); W_V head blocks: K = slot
+    // position, columns = (head, column inside the head padded to 16)
+    std::vector<float> WKT(tiled_size(dk, c.heads * L.Zp), 0.0f);
+    std::vector<float> WVp(tiled_size(L.Zp, c.heads * npk), 0.0f);
     for (uint32_t h = 0; h < c.heads; ++h)
       for (uint32_t z = 0; z < L.Zdim; ++z) {
         const double rsz = z >= L.d_in + c.d_edge ? tscale : 1.0;
         const uint32_t pz = slot_pos(z, L.d_in, c.d_edge);
         for (uint32_t cc = 0; cc < dk; ++cc) {
-          WKT[((size_t)h * dk2 + cc) * L.Zp + pz] = (float)((double)WK[(size_t)z * c.d_emb + h * dk + cc] * inv_sqrt_dk * rsz);
-          WVp[((size_t)h * L.Zp + pz) * npk + cc] = (float)((double)WV[(size_t)z * c.d_emb + h * dk + cc] * rsz);
+          put_tiled(WKT, dk, cc, h * L.Zp + pz, (double)WK[(size_t)z * c.d_emb + h * dk + cc] * inv_sqrt_dk * rsz);
+          put_tiled(WVp, L.Zp, pz, h * npk + cc, (double)WV[(size_t)z * c.d_emb + h * dk + cc] * rsz);
         }
       }
-    std::vector<float> WO((size_t)round_up(c.d_emb, 2) * npd, 0.0f);
-    put_block(WO, npd, 0, w->W_O[l], c.d_emb, c.d_emb);
+    std::vector<float> WO(tiled_size(c.d_emb, c.d_emb), 0.0f);
+    for (uint32_t i = 0; i < c.d_emb; ++i)
+      for (uint32_t col = 0; col < c.d_emb; ++col) put_tiled(WO, c.d_emb, i, col, WOs[(size_t)i * c.d_emb + col]);
     if ((rc = upload(ctx, L.WQn, WQn)) || (rc = upload(ctx, L.cQ, cQ)) || (rc = upload(ctx, L.WKT, WKT)) ||
         (rc = upload(ctx, L.WV, WVp)) || (rc = upload(ctx, L.WO, WO)) || (rc = upload(ctx, L.bO, vec(w->b_O[l], c.d_emb))))
       return rc;
@@ -323,9 +330,8 @@ void drain_timing(stgn_ctx* ctx) {
 void run_layers(stgn_ctx* ctx, const uint32_t* rows, const uint32_t* count_ptr, uint32_t count_max) {
   const Dev& d = ctx->d;
   for (uint32_t l = 0; l < d.layers; ++l) {
-    { Scope s(ctx, KC_QPROJ); launch_qproj(d, ctx->stream, l, rows, count_ptr, count_max); }
-    { Scope s(ctx, KC_ATTN);  launch_attn(d, ctx->stream, l, rows, count_ptr, count_max); }
-    { Scope s(ctx, KC_OPROJ); launch_oproj(d, ctx->stream, l, rows, count_ptr, count_max); }
+    Scope s(ctx, KC_LAYER);
+    launch_layer(d, ctx->stream, l, rows, count_ptr, count_max);
   }
 }
 
@@ -525,6 +531,7 @@ int stgn_ingest_batch(stgn_ctx* ctx, uint32_t n, const uint32_t* src, const uint
   { Scope t(ctx, KC_COMPACT); launch_compact(d, s, 1); }
   if (ev) hipEventRecord(ev[4], s);
   run_layers(ctx, d.A, &d.ctrl->nA, c.num_nodes);
+  if (ctx->timing) { Scope t(ctx, KC_NOOP); launch_noop(s); }   // event-pair overhead, for calibration
   if (ev) hipEventRecord(ev[5], s);
   HIPCHK(ctx, hipGetLastError());
 
@@ -677,7 +684,8 @@ int stgn_get_memory(stgn_ctx* ctx, uint32_t n, const uint32_t* nodes, float* mem
   return rc;
 }
 
-int stgn_get_totals(stgn_ctx* ctx, uint64_t* edges, uint64_t* direct, uint64_t* affected, uint64_t* scanned) {
+int stgn_get_totals(stgn_ctx* ctx, uint64_t* edges, uint64_t* direct, uint64_t* affected, uint64_t* scanned,
+                    uint64_t* gathered) {
   if (!ctx) return STGN_E_INVALID_ARG;
   int rc = sync_and_poll(ctx);
   const Ctrl& h = *ctx->ctrl_host;
@@ -685,6 +693,7 @@ int stgn_get_totals(stgn_ctx* ctx, uint64_t* edges, uint64_t* direct, uint64_t* 
   if (direct) *direct = h.tot_direct;
   if (affected) *affected = h.tot_affected;
   if (scanned) *scanned = h.tot_scanned;
+  if (gathered) *gathered = h.tot_gathered;
   return rc;
 }
 

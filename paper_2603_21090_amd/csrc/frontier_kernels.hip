@@ -39,7 +39,8 @@ __global__ __launch_bounds__(256) void expand_kernel(Dev d, uint32_t hop, int wr
   const uint32_t n_items = c->n_items[hop];
   uint32_t* next = d.front[(hop + 1) & 1];
   const uint32_t lane = threadIdx.x & 63;
-  const uint32_t wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+  // wave index, made provably uniform so that everything derived from it stays in scalar registers
+  const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)((blockIdx.x * blockDim.x + threadIdx.x) >> 6));
   const uint32_t nwaves = (gridDim.x * blockDim.x) >> 6;
   const uint64_t lt_mask = (1ull << lane) - 1ull;
   for (uint32_t it = wave; it < n_items; it += nwaves) {

@@ -281,6 +281,9 @@ void launch_init_state(const Dev& d, hipStream_t s) {
   hipLaunchKernelGGL(init_state_kernel, dim3(2048), dim3(256), 0, s, d);
 }
 
+__global__ void noop_kernel() {}
+void launch_noop(hipStream_t s) { hipLaunchKernelGGL(noop_kernel, dim3(1), dim3(64), 0, s); }
+
 void launch_zero(float* p, size_t n, hipStream_t s) {
   hipLaunchKernelGGL(zero_kernel, dim3(2048), dim3(256), 0, s, p, n);
 }

@@ -1,0 +1,6 @@
+// Instantiates the fused attention-layer kernel for inputs that occupy 8 slots of 64 floats.
+#include "layer_kernel.h"
+
+namespace stgn {
+template void layer_entry<8>(layer_impl::LaunchArgs&);
+}  // namespace stgn

@@ -40,7 +40,9 @@ __global__ __launch_bounds__(256) void memory_update_kernel(Dev d, const uint32_
   float* Zg = Ms + kRows * ldm;          // [32 x dm2]    update gate
   float* Rs = Zg + kRows * ldg;          // [32 x dm2]    r . s
   const uint32_t npg = round_up(dg, 32), npm = round_up(dm, 32);
-  const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+  const uint32_t lane = threadIdx.x & 63u;
+  // wave index, made provably uniform so that tile indices and weight addresses stay in scalar registers
+  const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
   const Table H0 = d.H[0];
 
   for (uint32_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {

@@ -38,6 +38,7 @@ struct Ctrl {
   uint64_t pool_units;           // adjacency pool cursor, in units of kMinBlock entries
   double   t_stream;             // last ingested timestamp
   uint64_t tot_direct, tot_affected, tot_scanned;
+  uint64_t tot_gathered;         // ring entries gathered by the attention kernels (all layers)
 };
 
 // Row-table descriptor: row v starts at base + v * ld (floats)
@@ -59,11 +60,9 @@ struct LayerDev {
   uint8_t  kind[kMaxSlots];      // 0 node row, 1 edge-feature row, 2 time encoding
   uint16_t valid[kMaxSlots];     // valid floats in the slot (1..64)
   uint16_t segoff[kMaxSlots];    // offset of the slot inside its segment's source row
-  uint32_t nqt;                  // (head, 32-column tile) pairs of the qt row that hold valid columns
-  uint8_t  qt_h[64], qt_nt[64];
-  const float* WQn;              // [d_in2 x Np(d_emb)]            node block of W_Q
+  const float* WQn;              // [d_in4 x Np(d_emb)]            node block of W_Q (K padded to 4, columns to 16)
   const float* cQ;               // [d_emb]                        phi(0) * (time block of W_Q)
-  const float* WKT;              // [heads][dk2 x Zp]              (W_K head block)^T / sqrt(dk); time rows * sqrt(1/d_t)
+  const float* WKT;              // [heads][dk4 x Zp]              (W_K head block)^T / sqrt(dk); time rows * sqrt(1/d_t)
   const float* WV;               // [heads][Zp x Np(dk)]           W_V head block; time rows * sqrt(1/d_t)
   const float* WO;               // [d_emb2 x Np(d_emb)]
   const float* bO;               // [d_emb]
@@ -107,8 +106,6 @@ struct Dev {
   uint64_t items_cap;
   uint32_t* blocksum;                // compaction partial sums
   uint32_t* A;                       // [N] affected set, ascending
-  float*   QT;                       // [N x heads x Zp_max] per-row transformed queries
-  float*   ZB;                       // [N x heads x Zp_max] per-row attention-weighted inputs
   uint32_t* qnodes; float* qout;     // staging for host-side get_embeddings
   uint32_t q_cap;
   // parameters
@@ -124,8 +121,8 @@ struct Dev {
 inline __host__ __device__ uint32_t round_up(uint32_t x, uint32_t m) { return (x + m - 1) / m * m; }
 
 // Kernel classes for the optional event timing
-enum KernelClass { KC_SORT = 0, KC_MEMORY, KC_APPLY, KC_PLAN, KC_EXPAND, KC_COMPACT, KC_QPROJ, KC_ATTN, KC_OPROJ,
-                   KC_GATHER, KC_COUNT };
+enum KernelClass { KC_SORT = 0, KC_MEMORY, KC_APPLY, KC_PLAN, KC_EXPAND, KC_COMPACT, KC_LAYER,
+                   KC_GATHER, KC_NOOP, KC_COUNT };
 
 // ---- launch wrappers (one per kernel family), defined in the .hip files ----
 void launch_stage_sort(const Dev& d, hipStream_t s, uint32_t n, const uint32_t* src, const uint32_t* dst,
@@ -137,15 +134,12 @@ void launch_apply(const Dev& d, hipStream_t s, const uint32_t* src, const uint32
 void launch_plan(const Dev& d, hipStream_t s, uint32_t hop);
 void launch_expand(const Dev& d, hipStream_t s, uint32_t hop, bool last);
 void launch_compact(const Dev& d, hipStream_t s, int phase);
-void launch_qproj(const Dev& d, hipStream_t s, uint32_t layer, const uint32_t* rows, const uint32_t* count_ptr,
-                  uint32_t count_max);
-void launch_attn(const Dev& d, hipStream_t s, uint32_t layer, const uint32_t* rows, const uint32_t* count_ptr,
-                 uint32_t count_max);
-void launch_oproj(const Dev& d, hipStream_t s, uint32_t layer, const uint32_t* rows, const uint32_t* count_ptr,
+void launch_layer(const Dev& d, hipStream_t s, uint32_t layer, const uint32_t* rows, const uint32_t* count_ptr,
                   uint32_t count_max);
 void launch_gather_rows(const Dev& d, hipStream_t s, uint32_t layer, uint32_t n, const uint32_t* nodes, float* out);
 void launch_init_state(const Dev& d, hipStream_t s);
 void launch_zero(float* p, size_t n, hipStream_t s);
+void launch_noop(hipStream_t s);
 int  attn_supported(uint32_t d_in, uint32_t d_edge, uint32_t d_time, uint32_t heads);
 constexpr size_t kMaxLds = 160 * 1024;   // LDS per workgroup on gfx950
 int  setup_ingest_attributes(const Dev& d);
