@@ -20,6 +20,7 @@ from __future__ import annotations
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -51,6 +52,22 @@ def projection_flops_per_row(w, layer):
     return q, o
 
 
+def stored_traffic(workload, batches):
+    """HBM bytes per layer-kernel launch from the hardware counters.  Counters cannot be read from
+    inside this process; the figure comes from the two counter runs of this same command whose
+    summary is kept as text under profiles/, and applies only to the same workload and batch range."""
+    path = os.path.join(ROOT, "profiles", f"layer_kernel_{workload}_hbm_traffic.txt")
+    try:
+        text = open(path).read()
+    except OSError:
+        return None
+    m = re.search(r"^traffic_bytes_per_launch\s*=\s*([0-9.eE+]+)", text, re.M)
+    r = re.search(r"^batches\s*=\s*\[(\d+),\s*(\d+)\]", text, re.M)
+    if not m or not r or [int(r.group(1)), int(r.group(2))] != list(batches):
+        return None
+    return float(m.group(1))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -59,6 +76,9 @@ def main():
     ap.add_argument("--workload", default="C2")
     ap.add_argument("--latency-steps", type=int, default=None)
     ap.add_argument("--kernel-steps", type=int, default=None)
+    ap.add_argument("--host-steps", type=int, default=None,
+                    help="batches fed from host (pageable numpy) buffers, for the PCIe-inclusive rate")
+    ap.add_argument("--rebuilds", type=int, default=3, help="timed full_rebuild() calls at the end")
     ap.add_argument("--cpu-steps", type=int, default=2)
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -78,11 +98,12 @@ def main():
     W = int(0.70 * nb) if args.warmup is None else args.warmup
     K = int(0.15 * nb) if args.steps is None else args.steps
     rest = max(nb - W - K, 0)
-    LAT = min(rest * 2 // 3, 200) if args.latency_steps is None else args.latency_steps
-    KER = min(rest - LAT, 100) if args.kernel_steps is None else args.kernel_steps
-    if W + K + LAT + KER > nb or K <= 0:
-        print(f"bench.py: warmup {W} + steps {K} + latency {LAT} + kernel {KER} exceed the stream of {nb} batches",
-              file=sys.stderr)
+    LAT = min(rest * 8 // 15, 160) if args.latency_steps is None else args.latency_steps
+    HOST = min(rest * 2 // 15, 40) if args.host_steps is None else args.host_steps
+    KER = min(rest - LAT - HOST, 100) if args.kernel_steps is None else args.kernel_steps
+    if W + K + LAT + HOST + KER > nb or K <= 0:
+        print(f"bench.py: warmup {W} + steps {K} + latency {LAT} + host {HOST} + kernel {KER} exceed the stream "
+              f"of {nb} batches", file=sys.stderr)
         sys.exit(2)
 
     dev = torch.device("cuda:0")
@@ -92,7 +113,7 @@ def main():
     g = binding.StreamTGN.from_workload(w, weights, nf)
 
     # the whole stream segment that will be used, resident on the device
-    used = (W + K + LAT + KER) * w.batch
+    used = (W + K + LAT + HOST + KER) * w.batch
     used = min(used, w.num_edges)
     d_src = torch.from_numpy(st.src[:used].astype(np.int32)).to(dev)
     d_dst = torch.from_numpy(st.dst[:used].astype(np.int32)).to(dev)
@@ -135,10 +156,23 @@ def main():
         feed(b); g.sync()
         lat.append(time.perf_counter() - a)
         b += 1
+    # the same call with host-resident inputs: pinned staging copy + H2D inside the call
+    host_edges, host_wall = 0, 0.0
+    if HOST:
+        hb = [st.batch(b + i) for i in range(HOST)]
+        g.sync()
+        a = time.perf_counter()
+        for s_, d_, t_, e_ in hb:
+            g.ingest_batch(s_, d_, t_, e_)
+            host_edges += len(s_)
+        g.sync()
+        host_wall = time.perf_counter() - a
+        b += HOST
     for _ in range(min(20, KER)):      # stage split from the library's own events (adds a sync per batch)
         s = feed(b, stats=True); b += 1
         stage_us += np.array([s["us_stage"][k] for k in ("sort", "memory", "apply", "propagate", "embed", "total")])
     n_stage = min(20, KER)
+    kernel_pass = [b, b + KER - n_stage]
 
     # per-kernel durations from HIP events on the library's stream
     g.kernel_times(enable=True, reset=True)
@@ -185,6 +219,25 @@ def main():
         roofline["ring_entries_per_launch"] = entries_per_launch
         roofline["avg_launch_us"] = kernels[roofline["kernel"]]["avg_us"]
         roofline["event_overhead_us"] = overhead_us
+        roofline["batches"] = kernel_pass
+        roofline["traffic"] = stored_traffic(w.name, kernel_pass)
+
+    # full_rebuild(): every layer over all N rows, the largest launches this path has
+    rebuild = None
+    if args.rebuilds > 0:
+        g.full_rebuild(); g.sync()
+        tr0 = g.totals()
+        a = time.perf_counter()
+        for _ in range(args.rebuilds):
+            g.full_rebuild()
+        g.sync()
+        rw = (time.perf_counter() - a) / args.rebuilds
+        tr1 = g.totals()
+        ent = (tr1["gathered"] - tr0["gathered"]) / args.rebuilds          # ring records over all layers
+        rb_bytes = w.layers * algorithmic_bytes(w, w.num_nodes, ent / w.layers)
+        rebuild = {"ms": rw * 1e3, "node_layers_per_s": w.num_nodes * w.layers / rw,
+                   "algorithmic_GBs": rb_bytes / rw / 1e9, "frac_hbm": rb_bytes / rw / 1e9 / HBM_PEAK_GBS,
+                   "ring_entries": ent / w.layers}
 
     cpu = None
     if not args.no_cpu and args.cpu_steps > 0:
@@ -232,6 +285,8 @@ def main():
         "mean_direct": direct / K,
         "affected_fraction": aff / K / w.num_nodes,
         "paper_bound_2BLK": binding.paper_affected_bound(w.batch, w.k, w.layers),
+        "host_input_edges_per_s": (host_edges / host_wall) if host_wall else None,
+        "full_rebuild": rebuild,
         "stage_us": dict(zip(("sort", "memory", "apply", "propagate", "embed", "total"),
                              (stage_us / max(n_stage, 1)).round(2).tolist())),
         "kernels": kernels,
@@ -244,7 +299,7 @@ def main():
         a_ = torch.empty(1 << 28, dtype=torch.float32, device=dev)
         b_ = torch.zeros(1 << 28, dtype=torch.float32, device=dev)
         for _ in range(5):
-            a_.copy_(b_)
+            torch.mul(b_, 1.0, out=a_)      # one elementwise kernel: reads 1 GiB, writes 1 GiB
         torch.cuda.synchronize()
     print(json.dumps(out))
 
