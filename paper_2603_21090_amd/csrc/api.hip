@@ -62,7 +62,7 @@ int fail(stgn_ctx* c, int code, const std::string& msg) {
   } while (0)
 
 uint32_t np32(uint32_t x) { return round_up(x, 32); }
-uint32_t row_ld(uint32_t width) { return width ? round_up(width, 32) : 0; }   // 128-byte aligned rows
+uint32_t row_ld(uint32_t width) { return width ? round_up(width, kSlot) : 0; }   // whole 64-float slots: gathers never need a mask
 
 struct Bump {
   char* base;
@@ -98,14 +98,16 @@ int check_config(const stgn_config* c, std::string* why) {
   return STGN_OK;
 }
 
-// Tile-major packing of a [K x N] weight matrix for 16x16x4 matrix instructions: element (k, j)
-// lives at ((j / 16) * ceil(K / 4) + k / 4) * 64 + (k % 4) * 16 + j % 16; zero padded, plus a few
-// zero blocks at the end so that a reader may run past the last tile.
+// Group-major packing of a [K x N] weight matrix for 16x16x4 matrix instructions (mfma16.h): for
+// column tile n = j / 16 and group g = k / 16 a block of 64 lanes x 4 floats, lane (i, col) =
+// ((k % 16) / 4, j % 16) holding the four k-steps u = k % 4 side by side; K zero padded to whole
+// chunks of four groups.
 size_t tiled_size(uint32_t K, uint32_t N) {
-  return ((size_t)((N + 15) / 16) * ((K + 3) / 4) + kPadBlocks) * kBlk16;
+  return (size_t)((N + 15) / 16) * groups_of(K) * kGrpFloats;
 }
 void put_tiled(std::vector<float>& dst, uint32_t K, uint32_t k, uint32_t j, double v) {
-  dst[((size_t)(j / 16) * ((K + 3) / 4) + k / 4) * kBlk16 + (k % 4) * 16 + j % 16] = (float)v;
+  const size_t block = (size_t)(j / 16) * groups_of(K) + k / kGrpK;
+  dst[block * kGrpFloats + (((k % kGrpK) / 4) * 16 + j % 16) * 4 + k % 4] = (float)v;
 }
 
 // Lays the whole device state out in one workspace; base == nullptr only measures.
@@ -259,7 +261,7 @@ int pack_parameters(stgn_ctx* ctx, const stgn_weights* w) {
         (rc = upload(ctx, d.br, vec(w->b_r, c.d_mem))) || (rc = upload(ctx, d.bh, vec(w->b_h, c.d_mem))))
       return rc;
   }
-  // attention weights feed 16x16x4 matrix instructions: tile-major packing (see tiled_size)
+  // attention weights feed 16x16x4 matrix instructions: group-major packing (see tiled_size)
   const uint32_t dk = d.dk, npk = round_up(dk, 16);
   const double inv_sqrt_dk = 1.0 / std::sqrt((double)dk);
   for (uint32_t l = 0; l < c.layers; ++l) {

@@ -13,7 +13,7 @@
 //      serves four rows, 16 lanes x float4 per 64-float slot; zb overwrites qt in LDS   (HBM bound)
 //   4. o_h = zb_h W_V,h                                                          (MFMA)
 //   5. h_v' = [o_1 | .. | o_H] W_O + b_O, written into the layer cache             (MFMA)
-// Weights stream from L2 (tile-major packing, see mfma16.h); two workgroups per CU overlap one's
+// Weights stream from L2 (group-major packing, see mfma16.h); two workgroups per CU overlap one's
 // gather with the other's products.
 #pragma once
 #include "stgn_internal.h"
@@ -53,19 +53,24 @@ __device__ inline float dot4(const float4 a, const float4 b, float acc) {
 }
 
 struct LayerLds {
-  uint32_t ldx, ldq, ldz;        // strides (floats) of the X, Q/O and qt/zb tiles
-  uint32_t off_q, off_z, off_o, total;
+  uint32_t ldx, ldq, ldz;        // strides (floats) of the X / O tile, the Q tile and the qt / zb tile
+  uint32_t dkp;                  // floats reserved per head in a Q row (dk rounded up to a group)
+  uint32_t off_q, off_z, off_r, total;
 };
 
-__host__ __device__ inline LayerLds layer_lds(uint32_t d_in, uint32_t d_emb, uint32_t heads, uint32_t Zp) {
+// Every stride is 4 (mod 8) floats: rows stay 16-byte aligned and the 16 rows of an operand read
+// fall into distinct banks.
+__host__ __device__ inline LayerLds layer_lds(uint32_t d_in, uint32_t d_emb, uint32_t heads, uint32_t Zp, uint32_t k) {
   LayerLds l;
-  l.ldx = round_up(d_in, 4) + 1;
-  l.ldq = (round_up(d_emb, 4) + 4) | 1u;          // room for the K padding of the last head
-  l.ldz = heads * Zp + 4;                         // 16-byte aligned rows, banks staggered by 4
+  const uint32_t wx = round_up(d_in, kGrpK), wo = round_up(d_emb, kGrpK);
+  l.ldx = (wx > wo ? wx : wo) + 4;                // the input tile and the head-output tile share storage
+  l.dkp = round_up(d_emb / heads, kGrpK);
+  l.ldq = heads * l.dkp + 4;
+  l.ldz = heads * Zp + 4;
   l.off_q = kTM * l.ldx;
-  l.off_z = round_up(l.off_q + kTM * l.ldq, 4);
-  l.off_o = l.off_z + kTM * l.ldz;
-  l.total = l.off_o + kTM * l.ldq;
+  l.off_z = l.off_q + kTM * l.ldq;
+  l.off_r = l.off_z + kTM * l.ldz + 4 * kGrpK;    // operand reads may run one chunk past the last row
+  l.total = l.off_r + kTM * k * 4;                // the ring records of the tile's rows, 16 bytes each
   return l;
 }
 
@@ -75,7 +80,7 @@ struct LayerArgs {
   const RingEntry* ring; const uint32_t* deg; const double* t_last;
   const double* om_rev; const double* ph_rev;
   Ctrl* ctrl;
-  const float *WQ, *cQ, *WKT, *WV, *WO, *bO;        // WQ, WKT, WV, WO tile-major (mfma16.h)
+  const float *WQ, *cQ, *WKT, *WV, *WO, *bO;        // WQ, WKT, WV, WO group-major (mfma16.h)
   uint32_t ld_in, ld_out, ld_ef;
   uint32_t k, heads, d_in, d_emb, dk, d_time, Zp;
   uint16_t valid[kMaxSlots];     // valid floats per slot
@@ -83,12 +88,20 @@ struct LayerArgs {
   uint8_t  kind[kMaxSlots];      // 0 node row, 1 edge-feature row, 2 time encoding
 };
 
+// gathered (node / edge) slots of one chunk of JC ring entries, one float4 per lane and slot
+template <int JC, int NG>
+struct GatherBuf {
+  float4 g[JC][NG];
+};
+
 // NS slots in total, the last NT of them time-encoding slots; JC ring entries fetched together.
 template <int NS, int NT, int H, int JC>
 __global__ __launch_bounds__(256, 2) void layer_kernel(LayerArgs a, const uint32_t* __restrict__ rows,
                                                        const uint32_t* count_ptr, uint32_t count_max) {
   extern __shared__ __align__(16) float lds[];
-  __shared__ uint32_t s_node[kTM];
+  __shared__ uint32_t s_node[kTM], s_cnt[kTM];
+  __shared__ double s_tq[kTM];
+  __shared__ uint32_t s_zt[4 * kMaxSlots];     // 16-column tiles of a qt row that hold valid columns
   __shared__ double s_om[2 * kSlot], s_ph[2 * kSlot];
   if (count_ptr && a.ctrl->skip) return;
   uint32_t n = count_max;
@@ -98,23 +111,36 @@ __global__ __launch_bounds__(256, 2) void layer_kernel(LayerArgs a, const uint32
   // wave index, made provably uniform so that tile indices and weight addresses stay in scalar registers
   const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
   const uint32_t Zp = a.Zp, k = a.k, dk = a.dk;
-  const uint32_t s_in = round_up(a.d_in, 4) >> 2, s_de = round_up(a.d_emb, 4) >> 2, s_dk = round_up(dk, 4) >> 2;  // k-steps
-  const uint32_t ntd = round_up(a.d_emb, 16) >> 4, ntk = round_up(dk, 16) >> 4, ntz = Zp >> 4;               // column tiles
-  const LayerLds ll = layer_lds(a.d_in, a.d_emb, a.heads, Zp);
-  float* Xs = lds;
+  const uint32_t c_in = chunks_of(a.d_in), c_de = chunks_of(a.d_emb), c_dk = chunks_of(dk);                    // chunks of K
+  const uint32_t g_in = kCG * c_in, g_de = kCG * c_de, g_dk = kCG * c_dk, g_z = Zp / kGrpK;                   // groups of K
+  const uint32_t ntd = round_up(a.d_emb, 16) >> 4, ntk = round_up(dk, 16) >> 4, ntz = Zp >> 4;                // column tiles
+  const LayerLds ll = layer_lds(a.d_in, a.d_emb, a.heads, Zp, k);
+  float* Xs = lds;                            // input rows (phases 0-1), then head outputs (phases 4-5)
   float* Qs = lds + ll.off_q;
   float* Zs = lds + ll.off_z;
-  float* Os = lds + ll.off_o;
+  RingEntry* Rs = reinterpret_cast<RingEntry*>(lds + ll.off_r);   // [row][j], j = 0 the most recent entry
   constexpr int NG = NS - NT;                 // gathered (node / edge) slots
+  using ZBuf = GatherBuf<JC, NG>;
 
   // ---- per-lane constants
-  bool lane_ok[NS];
-#pragma unroll
-  for (int s = 0; s < NS; ++s) lane_ok[s] = 4u * sub < a.valid[s];
   // time-encoding parameters (omega, phase in revolutions) live in LDS, zero past d_time
   for (uint32_t q = threadIdx.x; q < 2 * kSlot; q += 256) {
     s_om[q] = q < a.d_time ? a.om_rev[q] : 0.0;
     s_ph[q] = q < a.d_time ? a.ph_rev[q] : 0.0;
+  }
+  // operand padding (columns nobody writes) must be finite: clear the tiles once
+  for (uint32_t x = threadIdx.x; x < ll.off_r; x += 256) lds[x] = 0.0f;
+  // list of the qt column tiles that are not wholly slot padding
+  uint32_t nzt;
+  {
+    uint32_t vq = 0;
+#pragma unroll
+    for (int s = 0; s < NS; ++s)
+      if ((lane >> 2) == (uint32_t)s) vq = a.valid[s];
+    const bool tv = lane < ntz && (lane & 3u) * 16u < vq;
+    const uint64_t m = __ballot(tv);
+    nzt = (uint32_t)__popcll(m);
+    if (wave == 0 && tv) s_zt[__popcll(m & ((1ull << lane) - 1ull))] = lane;
   }
   bool tok[NT][4];
 #pragma unroll
@@ -123,47 +149,65 @@ __global__ __launch_bounds__(256, 2) void layer_kernel(LayerArgs a, const uint32
     for (int c = 0; c < 4; ++c) tok[t][c] = (uint32_t)t * kSlot + 4u * sub + c < a.d_time;
   uint32_t gathered = 0;
   const uint32_t a_x = a16_lane_off(ll.ldx), a_q = a16_lane_off(ll.ldq), a_z = a16_lane_off(ll.ldz);
-  const uint32_t c_off_q = m16_row(lane, 0) * ll.ldq + m16_col(lane);
+  const uint32_t c_off_x = m16_row(lane, 0) * ll.ldx + m16_col(lane);
   const uint32_t c_off_z = m16_row(lane, 0) * ll.ldz + m16_col(lane);
 
-  // ---- phase-2 tile cursor: (head, 16-column tile); this wave owns tiles wave, wave + 4, ... of
-  // every head; tiles that lie wholly in slot padding are skipped (nobody reads them)
-  struct Cur { uint32_t h, t; };
-  auto cur_skip = [&](Cur& c) {
-    while (c.h < a.heads) {
-      if (c.t >= ntz) { ++c.h; c.t = wave; continue; }
-      if ((c.t & 3u) * 16u < a.valid[c.t >> 2]) break;
-      c.t += 4;
+  // ---- phase-2 work units: (head, pair of valid qt column tiles); wave w owns units w, w + 4, ...
+  const uint32_t npr = (nzt + 1u) >> 1, nunits2 = a.heads * npr;
+  struct Unit2 { uint32_t h, t0, t1; bool two; };
+  auto decode2 = [&](uint32_t x) {
+    Unit2 u;
+    u.h = x / npr;
+    const uint32_t i0 = 2u * (x - u.h * npr);
+    u.two = i0 + 1u < nzt;
+    u.t0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)s_zt[i0]);
+    u.t1 = (uint32_t)__builtin_amdgcn_readfirstlane((int)s_zt[u.two ? i0 + 1u : i0]);
+    return u;
+  };
+  auto wkt = [&](uint32_t h, uint32_t t) { return a.WKT + (size_t)(h * ntz + t) * g_dk * kGrpFloats; };
+  auto store2 = [&](const Unit2& u, const floatx4 (&acc)[2]) {
+    float* zp = Zs + u.h * Zp + c_off_z;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) zp[u.t0 * 16 + r * ll.ldz] = acc[0][r];
+    if (u.two) {
+#pragma unroll
+      for (int r = 0; r < 4; ++r) zp[u.t1 * 16 + r * ll.ldz] = acc[1][r];
     }
   };
-  auto cur_next = [&](Cur c) { c.t += 4; cur_skip(c); return c; };
-  auto qt_weights = [&](const Cur& c) { return a.WKT + (size_t)(c.h * ntz + c.t) * s_dk * kBlk16; };
-  auto qt_tile = [&](const Cur& c, float (&b)[kU16]) {
-    floatx4 acc = {0.f, 0.f, 0.f, 0.f};
-    mfma16_tile_pre<kU16>(Qs + c.h * dk, a_q, s_dk, qt_weights(c), acc, b);
-    float* zp = Zs + c.h * Zp + c.t * 16 + c_off_z;
-#pragma unroll
-    for (int r = 0; r < 4; ++r) zp[r * ll.ldz] = acc[r];
-  };
+  // ---- phase-4 work units: (head, pair of head-output column tiles)
+  const uint32_t np4 = (ntk + 1u) >> 1, nunits4 = a.heads * np4;
+  // ---- phases 1 and 5: column tiles nt and nt + 4 of the d_emb outputs form a unit
+  __syncthreads();
 
   for (uint32_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
     const uint32_t r0 = tile * kTM;
     // ================================================================ phase 0: stage the tile
-    float b1[kU16];
-    const bool has1 = wave < ntd;
-    if (has1) load_b16<kU16>(a.WQ + (size_t)wave * s_in * kBlk16, 0, b1);
+    Ops16<2> oq;                                              // first weight chunk of this wave's first unit
+    const uint32_t w1 = wave < ntd ? wave : 0u;              // loads are unconditional (clamped), products are not
+    load_b16(a.WQ + (size_t)w1 * g_in * kGrpFloats, 0, oq.b[0]);
+    load_b16(a.WQ + (size_t)(w1 + 4 < ntd ? w1 + 4 : w1) * g_in * kGrpFloats, 0, oq.b[1]);
     if (threadIdx.x < kTM) {
       const uint32_t r = r0 + threadIdx.x;
       s_node[threadIdx.x] = r < n ? (rows ? rows[r] : r) : 0xFFFFFFFFu;
     }
-    for (uint32_t x = threadIdx.x; x < kTM * (ll.ldq - a.d_emb); x += 256) {
-      const uint32_t r = x / (ll.ldq - a.d_emb), c = a.d_emb + x % (ll.ldq - a.d_emb);
-      Qs[r * ll.ldq + c] = 0.0f;
-      Os[r * ll.ldq + c] = 0.0f;
-    }
     __syncthreads();
+    // the rows' ring records, most recent first; slots past the row's entry count name node 0 / edge 0
+    // (finite rows that later meet a zero weight)
+    for (uint32_t x = threadIdx.x; x < kTM * k; x += 256) {
+      const uint32_t r = x / k, j = x - r * k;
+      const uint32_t node = s_node[r];
+      const bool live = node != 0xFFFFFFFFu;
+      const uint32_t nn = live ? node : 0u;
+      const uint32_t dg = live ? a.deg[nn] : 0u;
+      const uint32_t cnt = dg < k ? dg : k;
+      RingEntry e;
+      e.nbr = 0u; e.eid = 0u; e.t = 0.0;
+      if (j < cnt) e = a.ring[(size_t)nn * k + (dg - 1u - j) % k];
+      Rs[x] = e;
+      if (j == 0) { s_cnt[r] = cnt; s_tq[r] = a.t_last[nn]; }
+    }
     {
-      const uint32_t qpr = s_in, total = kTM * qpr;            // 16-byte quads per row / per tile
+      const uint32_t qpr = round_up(a.d_in, kGrpK) >> 2, total = kTM * qpr;   // 16-byte quads per row / per tile
       for (uint32_t x0 = threadIdx.x; x0 < total; x0 += 512u) {
         float4 v[2];
         uint32_t rr[2], cc[2];
@@ -177,108 +221,131 @@ __global__ __launch_bounds__(256, 2) void layer_kernel(LayerArgs a, const uint32
           const uint32_t node = s_node[r];
           rr[e] = r; cc[e] = 4u * q;
           const bool live = node != 0xFFFFFFFFu;
+          // columns past d_in are row padding of the table (zero)
           v[e] = *reinterpret_cast<const float4*>(a.Hin + (size_t)(live ? node : 0u) * a.ld_in + 4u * q);
           if (!live) v[e] = make_float4(0.f, 0.f, 0.f, 0.f);
         }
 #pragma unroll
         for (int e = 0; e < 2; ++e)
-          if (ok[e]) {
-            float* p = Xs + rr[e] * ll.ldx + cc[e];
-            p[0] = v[e].x; p[1] = v[e].y; p[2] = v[e].z; p[3] = v[e].w;
-          }
+          if (ok[e]) *reinterpret_cast<float4*>(Xs + rr[e] * ll.ldx + cc[e]) = v[e];
       }
     }
     __syncthreads();
-    // ================================================================ phase 1: q = x W_Q + c_Q
-    float bA[kU16], bB[kU16];
-    Cur f{0u, wave};
-    cur_skip(f);
-    if (f.h < a.heads) load_b16<kU16>(qt_weights(f), 0, bA);
-    for (uint32_t nt = wave; nt < ntd; nt += 4) {
-      floatx4 acc = {0.f, 0.f, 0.f, 0.f};
-      const float* Wt = a.WQ + (size_t)nt * s_in * kBlk16;
-      if (nt == wave) mfma16_tile_pre<kU16>(Xs, a_x, s_in, Wt, acc, b1);
-      else mfma16_tile<kU16>(Xs, a_x, s_in, Wt, acc);
-      const uint32_t col = nt * 16 + m16_col(lane);
-      if (col < a.d_emb) {
-        const float cq = a.cQ[col];
-        float* qp = Qs + nt * 16 + c_off_q;
+    // ---- this lane group's row: entry count, query time, ring records; the first chunk of neighbour
+    // rows is requested now and arrives while the projections below run
+    const uint32_t local = wave * 4u + grp;
+    const uint32_t cnt = s_cnt[local];
+    const double tq = s_tq[local];
+    const RingEntry* rrow = Rs + local * k;
+    gathered += cnt;
+    uint32_t cmax = (uint32_t)__builtin_amdgcn_readlane((int)cnt, 0);
+    cmax = max(cmax, (uint32_t)__builtin_amdgcn_readlane((int)cnt, 16));
+    cmax = max(cmax, (uint32_t)__builtin_amdgcn_readlane((int)cnt, 32));
+    cmax = max(cmax, (uint32_t)__builtin_amdgcn_readlane((int)cnt, 48));
+    const uint32_t nchunk3 = (cmax + JC - 1) / JC;
+    auto gather = [&](uint32_t c, ZBuf& zb) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) qp[r * ll.ldq] = acc[r] + cq;
+      for (int jc = 0; jc < JC; ++jc) {
+        const uint32_t j = c * JC + jc;
+        const RingEntry e = rrow[j < k ? j : k - 1u];
+        const float* hrow = a.Hin + (size_t)e.nbr * a.ld_in + 4u * sub;
+        const float* erow = a.efeat + (size_t)e.eid * a.ld_ef + 4u * sub;
+#pragma unroll
+        for (int s = 0; s < NG; ++s)
+          zb.g[jc][s] = *reinterpret_cast<const float4*>((a.kind[s] == 0 ? hrow : erow) + a.segoff[s]);
+      }
+    };
+    ZBuf z0;
+    gather(0, z0);
+    // ================================================================ phase 1: q = x W_Q + c_Q
+    for (uint32_t nt = wave; nt < ntd; nt += 8) {
+      const bool two = nt + 4 < ntd;
+      const float* const Bt[2] = {a.WQ + (size_t)nt * g_in * kGrpFloats, a.WQ + (size_t)(two ? nt + 4 : nt) * g_in * kGrpFloats};
+      floatx4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+      if (nt != wave) { load_b16(Bt[0], 0, oq.b[0]); load_b16(Bt[1], 0, oq.b[1]); }
+      mfma16_gemm_pre<2>(Xs + a_x, c_in, Bt, acc, oq);
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        const uint32_t col = (nt + 4 * t) * 16 + m16_col(lane);
+        if ((t == 0 || two) && col < a.d_emb) {
+          const float cq = a.cQ[col];
+          const uint32_t h = col / dk;
+          float* qp = Qs + m16_row(lane, 0) * ll.ldq + h * ll.dkp + (col - h * dk);
+#pragma unroll
+          for (int r = 0; r < 4; ++r) qp[r * ll.ldq] = acc[t][r] + cq;
+        }
       }
     }
-    __syncthreads();
     // ================================================================ phase 2: qt_h = q_h W_K,h^T / sqrt(dk)
-    while (f.h < a.heads) {
-      const Cur g = cur_next(f);
-      if (g.h < a.heads) load_b16<kU16>(qt_weights(g), 0, bB);
-      qt_tile(f, bA);
-      if (g.h >= a.heads) break;
-      f = cur_next(g);
-      if (f.h < a.heads) load_b16<kU16>(qt_weights(f), 0, bA);
-      qt_tile(g, bB);
+    {
+      Ops16<2> o2;
+      uint32_t x = wave;
+      Unit2 ua = decode2(x < nunits2 ? x : nunits2 - 1u);     // weights of the first unit are requested
+      load_b16(wkt(ua.h, ua.t0), 0, o2.b[0]);                 // ahead of the barrier
+      load_b16(wkt(ua.h, ua.t1), 0, o2.b[1]);
+      __syncthreads();
+      if (c_dk == 1) {
+        // one chunk per unit: the operands of the next unit are in flight during this unit's products
+        load_a16(Qs + ua.h * ll.dkp + a_q, 0, o2.a);
+        const uint32_t nu = wave < nunits2 ? (nunits2 - wave + 3u) >> 2 : 0u;
+        pingpong<Ops16<2>>(
+            nu, o2,
+            [&](uint32_t i, Ops16<2>& o) {
+              const Unit2 u = decode2(wave + 4u * i);
+              load_a16(Qs + u.h * ll.dkp + a_q, 0, o.a);
+              load_b16(wkt(u.h, u.t0), 0, o.b[0]);
+              load_b16(wkt(u.h, u.t1), 0, o.b[1]);
+            },
+            [&](uint32_t i, const Ops16<2>& o) {
+              const Unit2 u = decode2(wave + 4u * i);
+              floatx4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+              mfma16_chunk<2>(o, acc);
+              store2(u, acc);
+            });
+      } else {
+        for (; x < nunits2; x += 4) {
+          ua = decode2(x);
+          const float* const Bt[2] = {wkt(ua.h, ua.t0), wkt(ua.h, ua.t1)};
+          floatx4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+          mfma16_gemm<2>(Qs + ua.h * ll.dkp + a_q, c_dk, Bt, acc);
+          store2(ua, acc);
+        }
+      }
     }
     __syncthreads();
     // ================================================================ phase 3: gather + attention
     {
-      const uint32_t local = wave * 4u + grp;
-      const uint32_t v = s_node[local];
-      const bool act = v != 0xFFFFFFFFu;
-      const uint32_t vv = act ? v : 0u;
-      const uint32_t dg = act ? a.deg[vv] : 0u;
-      const uint32_t cnt = dg < k ? dg : k;
-      gathered += cnt;
-      const double tq = a.t_last[vv];
-      float* zrow = Zs + local * ll.ldz + 4u * sub;          // this lane's float4 of slot s, head h: + h Zp + 64 s
       float4 acc[H][NS];
 #pragma unroll
       for (int h = 0; h < H; ++h)
 #pragma unroll
         for (int s = 0; s < NS; ++s) acc[h][s] = make_float4(0.f, 0.f, 0.f, 0.f);
-      float mrun[H], lrun[H];
+      float mref[H], lrun[H];
 #pragma unroll
-      for (int h = 0; h < H; ++h) { mrun[h] = -INFINITY; lrun[h] = 0.0f; }
-      uint32_t cmax = (uint32_t)__builtin_amdgcn_readlane((int)cnt, 0);
-      cmax = max(cmax, (uint32_t)__builtin_amdgcn_readlane((int)cnt, 16));
-      cmax = max(cmax, (uint32_t)__builtin_amdgcn_readlane((int)cnt, 32));
-      cmax = max(cmax, (uint32_t)__builtin_amdgcn_readlane((int)cnt, 48));
-      const RingEntry* ring = a.ring + (size_t)vv * k;
-      int slot = cnt ? (int)((dg - 1u) % k) : 0;            // ring slot of the most recent entry
-      for (uint32_t j0 = 0; j0 < cmax; j0 += JC) {
-        // ring records of the whole chunk first, then every row load of the chunk
-        RingEntry re[JC];
+      for (int h = 0; h < H; ++h) { mref[h] = -INFINITY; lrun[h] = 0.0f; }
+      const float* zq = Zs + local * ll.ldz + 4u * sub;       // this lane's float4 of slot s, head h: + h Zp + 64 s
+      auto attend = [&](uint32_t c, const ZBuf& zb) {
+        // time encodings of the chunk's entries
+        float4 zt[JC][NT];
         bool vj[JC];
 #pragma unroll
         for (int jc = 0; jc < JC; ++jc) {
-          vj[jc] = j0 + jc < cnt;
-          re[jc] = ring[vj[jc] ? slot : 0];
-          if (vj[jc]) slot = slot == 0 ? (int)k - 1 : slot - 1;
-        }
-        float4 z[JC][NS];
-#pragma unroll
-        for (int jc = 0; jc < JC; ++jc) {
-          const uint32_t nbr = vj[jc] ? re[jc].nbr : 0u, eid = vj[jc] ? re[jc].eid : 0u;
-          const double dt = tq - re[jc].t;
-          const float* hrow = a.Hin + (size_t)nbr * a.ld_in + 4u * sub;
-          const float* erow = a.efeat + (size_t)eid * a.ld_ef + 4u * sub;
-#pragma unroll
-          for (int s = 0; s < NG; ++s) {
-            float4 zz = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (vj[jc] && lane_ok[s]) zz = *reinterpret_cast<const float4*>((a.kind[s] == 0 ? hrow : erow) + a.segoff[s]);
-            z[jc][s] = zz;
-          }
+          const uint32_t j = c * JC + jc;
+          vj[jc] = j < cnt;
+          const double dt = tq - rrow[j < k ? j : k - 1u].t;
 #pragma unroll
           for (int t = 0; t < NT; ++t) {
-            float4 zz;
             const double* om = s_om + t * kSlot + 4u * sub;
             const double* ph = s_ph + t * kSlot + 4u * sub;
-            zz.x = (vj[jc] && tok[t][0]) ? cos_rev(om[0] * dt + ph[0]) : 0.0f;
-            zz.y = (vj[jc] && tok[t][1]) ? cos_rev(om[1] * dt + ph[1]) : 0.0f;
-            zz.z = (vj[jc] && tok[t][2]) ? cos_rev(om[2] * dt + ph[2]) : 0.0f;
-            zz.w = (vj[jc] && tok[t][3]) ? cos_rev(om[3] * dt + ph[3]) : 0.0f;
-            z[jc][NG + t] = zz;
+            float4 zz;
+            zz.x = tok[t][0] ? cos_rev(om[0] * dt + ph[0]) : 0.0f;
+            zz.y = tok[t][1] ? cos_rev(om[1] * dt + ph[1]) : 0.0f;
+            zz.z = tok[t][2] ? cos_rev(om[2] * dt + ph[2]) : 0.0f;
+            zz.w = tok[t][3] ? cos_rev(om[3] * dt + ph[3]) : 0.0f;
+            zt[jc][t] = zz;
           }
         }
+        // scores
         float sc[JC][H];
 #pragma unroll
         for (int h = 0; h < H; ++h) {
@@ -287,10 +354,9 @@ __global__ __launch_bounds__(256, 2) void layer_kernel(LayerArgs a, const uint32
           for (int jc = 0; jc < JC; ++jc) p[jc] = 0.0f;
 #pragma unroll
           for (int s = 0; s < NS; ++s) {
-            float4 qv = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (lane_ok[s]) qv = *reinterpret_cast<const float4*>(zrow + h * Zp + s * kSlot);
+            const float4 qv = *reinterpret_cast<const float4*>(zq + h * Zp + s * kSlot);
 #pragma unroll
-            for (int jc = 0; jc < JC; ++jc) p[jc] = dot4(qv, z[jc][s], p[jc]);
+            for (int jc = 0; jc < JC; ++jc) p[jc] = dot4(qv, s < NG ? zb.g[jc][s < NG ? s : 0] : zt[jc][s < NG ? 0 : s - NG], p[jc]);
           }
 #pragma unroll
           for (int jc = 0; jc < JC; ++jc) {
@@ -298,35 +364,51 @@ __global__ __launch_bounds__(256, 2) void layer_kernel(LayerArgs a, const uint32
             sc[jc][h] = vj[jc] ? t : -INFINITY;
           }
         }
+        // softmax against a reference score that only moves when a score exceeds it by a wide
+        // margin (any reference gives the same quotient; the margin keeps exp() in range)
+        bool need = false;
+        float smax[H];
 #pragma unroll
         for (int h = 0; h < H; ++h) {
-          float mnew = mrun[h];
+          smax[h] = sc[0][h];
 #pragma unroll
-          for (int jc = 0; jc < JC; ++jc) mnew = fmaxf(mnew, sc[jc][h]);
-          // rows with no entry in this chunk keep their state (mnew may still be -inf for them)
-          const float scale = (mnew == -INFINITY) ? 1.0f : __expf(mrun[h] - mnew);
-          float lsum = lrun[h] * scale;
+          for (int jc = 1; jc < JC; ++jc) smax[h] = fmaxf(smax[h], sc[jc][h]);
+          need = need || smax[h] > mref[h] + 30.0f;
+        }
+        if (__any(need)) {
 #pragma unroll
-          for (int s = 0; s < NS; ++s) {
-            acc[h][s].x *= scale; acc[h][s].y *= scale; acc[h][s].z *= scale; acc[h][s].w *= scale;
-          }
-#pragma unroll
-          for (int jc = 0; jc < JC; ++jc) {
-            const float p = vj[jc] ? __expf(sc[jc][h] - mnew) : 0.0f;
-            lsum += p;
+          for (int h = 0; h < H; ++h) {
+            const bool mv = smax[h] > mref[h] + 30.0f;
+            const float mnew = mv ? smax[h] : mref[h];
+            const float scale = mv ? __expf(mref[h] - mnew) : 1.0f;     // exp(-inf) = 0 on the first move
+            lrun[h] *= scale;
 #pragma unroll
             for (int s = 0; s < NS; ++s) {
-              acc[h][s].x = fmaf(p, z[jc][s].x, acc[h][s].x);
-              acc[h][s].y = fmaf(p, z[jc][s].y, acc[h][s].y);
-              acc[h][s].z = fmaf(p, z[jc][s].z, acc[h][s].z);
-              acc[h][s].w = fmaf(p, z[jc][s].w, acc[h][s].w);
+              acc[h][s].x *= scale; acc[h][s].y *= scale; acc[h][s].z *= scale; acc[h][s].w *= scale;
+            }
+            mref[h] = mnew;
+          }
+        }
+#pragma unroll
+        for (int h = 0; h < H; ++h) {
+#pragma unroll
+          for (int jc = 0; jc < JC; ++jc) {
+            const float p = vj[jc] ? __expf(sc[jc][h] - mref[h]) : 0.0f;
+            lrun[h] += p;
+#pragma unroll
+            for (int s = 0; s < NS; ++s) {
+              const float4 zv = s < NG ? zb.g[jc][s < NG ? s : 0] : zt[jc][s < NG ? 0 : s - NG];
+              acc[h][s].x = fmaf(p, zv.x, acc[h][s].x);
+              acc[h][s].y = fmaf(p, zv.y, acc[h][s].y);
+              acc[h][s].z = fmaf(p, zv.z, acc[h][s].z);
+              acc[h][s].w = fmaf(p, zv.w, acc[h][s].w);
             }
           }
-          mrun[h] = mnew;
-          lrun[h] = lsum;
         }
-      }
-      // zb overwrites qt (each lane owns its float4s; padding lanes write zeros)
+      };
+      pingpong<ZBuf>(nchunk3, z0, gather, attend);
+      // zb overwrites qt (each lane owns its float4s; padding lanes hold zeros)
+      float* zw = Zs + local * ll.ldz + 4u * sub;
 #pragma unroll
       for (int h = 0; h < H; ++h) {
         const float inv = cnt ? 1.0f / lrun[h] : 0.0f;
@@ -334,57 +416,85 @@ __global__ __launch_bounds__(256, 2) void layer_kernel(LayerArgs a, const uint32
         for (int s = 0; s < NS; ++s) {
           float4 o = acc[h][s];
           o.x *= inv; o.y *= inv; o.z *= inv; o.w *= inv;
-          *reinterpret_cast<float4*>(zrow + h * Zp + s * kSlot) = o;
+          *reinterpret_cast<float4*>(zw + h * Zp + s * kSlot) = o;
         }
       }
     }
-    __syncthreads();
     // ================================================================ phase 4: o_h = zb_h W_V,h
     {
-      // wave w owns the (head, 16-column tile) pairs w, w + 4, ...; K runs over the slots, one chunk
-      // of 16 k-steps per slot; the weights of the next slot are in flight during the current one
-      const uint32_t npairs = a.heads * ntk;
-      bool first = true;
-      for (uint32_t p = wave; p < npairs; p += 4) {
-        const uint32_t h = p / ntk, nt = p - h * ntk;
-        const float* Wt = a.WV + (size_t)p * (Zp >> 2) * kBlk16;          // column tile p = h * ntk + nt
-        const float* Ap = Zs + h * Zp;
-        floatx4 acc = {0.f, 0.f, 0.f, 0.f};
-        float bc[kU16], bn[kU16];
-        load_b16<kU16>(Wt, 0, bc);
+      // K runs over the slots, one chunk per slot; the operands of the next slot are in flight
+      // during the current one.  The weights of the first slot are requested ahead of the barrier.
+      Ops16<2> ov[2];
+      uint32_t x = wave;
+      auto wv = [&](uint32_t h, uint32_t nt) { return a.WV + (size_t)(h * ntk + nt) * g_z * kGrpFloats; };
+      uint32_t h4 = 0, n0 = 0, n1 = 0;
+      bool two4 = false;
+      auto decode4 = [&](uint32_t xx) {
+        h4 = xx / np4;
+        n0 = 2u * (xx - h4 * np4);
+        two4 = n0 + 1u < ntk;
+        n1 = two4 ? n0 + 1u : n0;
+      };
+      decode4(x < nunits4 ? x : nunits4 - 1u);
+      load_b16(wv(h4, n0), 0, ov[0].b[0]);
+      load_b16(wv(h4, n1), 0, ov[0].b[1]);
+      __syncthreads();
+      for (; x < nunits4; x += 4) {
+        if (x != wave) {
+          decode4(x);
+          load_b16(wv(h4, n0), 0, ov[0].b[0]);
+          load_b16(wv(h4, n1), 0, ov[0].b[1]);
+        }
+        const float* Ap = Zs + h4 * Zp + a_z;
+        const float* B0 = wv(h4, n0);
+        const float* B1 = wv(h4, n1);
+        load_a16(Ap, 0, ov[0].a);
+        floatx4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
         for (int c = 0; c < NS; ++c) {
-          if (c + 1 < NS) load_b16<kU16>(Wt, (c + 1) * kU16, bn);
-          mfma16_steps<kU16>(Ap + c * kSlot, a_z, 0, (uint32_t)(a.valid[c] + 3u) >> 2, bc, acc);
-#pragma unroll
-          for (int u = 0; u < kU16; ++u) bc[u] = bn[u];
+          if (c + 1 < NS) {
+            load_a16(Ap, (c + 1) * kCG, ov[(c + 1) & 1].a);
+            load_b16(B0, (c + 1) * kCG, ov[(c + 1) & 1].b[0]);
+            load_b16(B1, (c + 1) * kCG, ov[(c + 1) & 1].b[1]);
+          }
+          __builtin_amdgcn_sched_barrier(0);      // requests stay ahead of the products they overlap
+          mfma16_chunk<2>(ov[c & 1], acc);
+          __builtin_amdgcn_sched_barrier(0);
         }
-        // weights of the output projection are requested before the head outputs are exchanged
-        if (first && has1) load_b16<kU16>(a.WO + (size_t)wave * s_de * kBlk16, 0, b1);
-        first = false;
-        const uint32_t col = nt * 16 + m16_col(lane);
-        if (col < dk) {
-          float* op = Os + h * dk + nt * 16 + c_off_q;
 #pragma unroll
-          for (int r = 0; r < 4; ++r) op[r * ll.ldq] = acc[r];
+        for (int t = 0; t < 2; ++t) {
+          const uint32_t col = (t ? n1 : n0) * 16 + m16_col(lane);
+          if ((t == 0 || two4) && col < dk) {
+            float* op = Xs + c_off_x - m16_col(lane) + h4 * dk + col;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) op[r * ll.ldx] = acc[t][r];
+          }
         }
       }
-      if (first && has1) load_b16<kU16>(a.WO + (size_t)wave * s_de * kBlk16, 0, b1);
     }
-    __syncthreads();
     // ================================================================ phase 5: h' = o W_O + b_O
-    for (uint32_t nt = wave; nt < ntd; nt += 4) {
-      floatx4 acc = {0.f, 0.f, 0.f, 0.f};
-      const float* Wt = a.WO + (size_t)nt * s_de * kBlk16;
-      if (nt == wave) mfma16_tile_pre<kU16>(Os, a_q, s_de, Wt, acc, b1);
-      else mfma16_tile<kU16>(Os, a_q, s_de, Wt, acc);
-      const uint32_t col = nt * 16 + m16_col(lane);
-      if (col < a.d_emb) {
-        const float b = a.bO[col];
+    {
+      Ops16<2> oo;
+      load_b16(a.WO + (size_t)w1 * g_de * kGrpFloats, 0, oo.b[0]);
+      load_b16(a.WO + (size_t)(w1 + 4 < ntd ? w1 + 4 : w1) * g_de * kGrpFloats, 0, oo.b[1]);
+      __syncthreads();
+      for (uint32_t nt = wave; nt < ntd; nt += 8) {
+        const bool two = nt + 4 < ntd;
+        const float* const Bt[2] = {a.WO + (size_t)nt * g_de * kGrpFloats, a.WO + (size_t)(two ? nt + 4 : nt) * g_de * kGrpFloats};
+        floatx4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+        if (nt != wave) { load_b16(Bt[0], 0, oo.b[0]); load_b16(Bt[1], 0, oo.b[1]); }
+        mfma16_gemm_pre<2>(Xs + a_x, c_de, Bt, acc, oo);
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const uint32_t node = s_node[m16_row(lane, r)];
-          if (node != 0xFFFFFFFFu) a.Hout[(size_t)node * a.ld_out + col] = acc[r] + b;
+        for (int t = 0; t < 2; ++t) {
+          const uint32_t col = (nt + 4 * t) * 16 + m16_col(lane);
+          if ((t == 0 || two) && col < a.d_emb) {
+            const float b = a.bO[col];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              const uint32_t node = s_node[m16_row(lane, r)];
+              if (node != 0xFFFFFFFFu) a.Hout[(size_t)node * a.ld_out + col] = acc[t][r] + b;
+            }
+          }
         }
       }
     }
@@ -421,11 +531,12 @@ void go(LaunchArgs& a) {
 
 template <int NS, int NT>
 void go_h(LaunchArgs& a) {
-  // ring entries in flight per row are bounded by registers (JC * NS float4 per lane)
+  // ring entries per chunk are bounded by registers (two chunks of JC * NS float4 per lane in flight,
+  // beside H * NS float4 of accumulators)
   switch (a.k.heads) {
-    case 1: go<NS, NT, 1, (NS <= 4 ? 5 : NS == 5 ? 3 : 2)>(a); break;
-    case 2: go<NS, NT, 2, (NS <= 4 ? 5 : NS == 5 ? 3 : 2)>(a); break;
-    default: go<NS, NT, 4, (NS <= 4 ? 3 : 2)>(a); break;
+    case 1: go<NS, NT, 1, (NS <= 4 ? 4 : NS == 5 ? 3 : 2)>(a); break;
+    case 2: go<NS, NT, 2, (NS <= 4 ? 4 : NS == 5 ? 3 : 2)>(a); break;
+    default: go<NS, NT, 4, (NS <= 4 ? 2 : 1)>(a); break;
   }
 }
 
