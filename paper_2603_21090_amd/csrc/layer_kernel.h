@@ -102,7 +102,7 @@ __global__ __launch_bounds__(256, 2) void layer_kernel(LayerArgs a, const uint32
   __shared__ uint32_t s_node[kTM], s_cnt[kTM];
   __shared__ double s_tq[kTM];
   __shared__ uint32_t s_zt[4 * kMaxSlots];     // 16-column tiles of a qt row that hold valid columns
-  __shared__ double s_om[2 * kSlot], s_ph[2 * kSlot];
+  __shared__ __align__(16) double s_om[2 * kSlot], s_ph[2 * kSlot];
   if (count_ptr && a.ctrl->skip) return;
   uint32_t n = count_max;
   if (count_ptr) { const uint32_t c = *count_ptr; n = c < count_max ? c : count_max; }
@@ -323,11 +323,28 @@ __global__ __launch_bounds__(256, 2) void layer_kernel(LayerArgs a, const uint32
       float mref[H], lrun[H];
 #pragma unroll
       for (int h = 0; h < H; ++h) { mref[h] = -INFINITY; lrun[h] = 0.0f; }
-      const float* zq = Zs + local * ll.ldz + 4u * sub;       // this lane's float4 of slot s, head h: + h Zp + 64 s
+      // this lane's share of the row's qt vectors stays in registers for the whole phase
+      const float* zq = Zs + local * ll.ldz + 4u * sub;       // float4 of slot s, head h: + h Zp + 64 s
+      constexpr bool QREG = H * NS <= 16;                     // otherwise the registers go to the accumulators
+      float4 qt[QREG ? H : 1][QREG ? NS : 1];
+      if constexpr (QREG) {
+#pragma unroll
+        for (int h = 0; h < H; ++h)
+#pragma unroll
+          for (int s = 0; s < NS; ++s) qt[h][s] = *reinterpret_cast<const float4*>(zq + h * Zp + s * kSlot);
+      }
       auto attend = [&](uint32_t c, const ZBuf& zb) {
-        // time encodings of the chunk's entries
+        // time encodings of the chunk's entries (computed for every lane, then masked: no branches)
         float4 zt[JC][NT];
         bool vj[JC];
+        double2 om[NT][2], ph[NT][2];
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+#pragma unroll
+          for (int q = 0; q < 2; ++q) {
+            om[t][q] = *reinterpret_cast<const double2*>(s_om + t * kSlot + 4u * sub + 2 * q);
+            ph[t][q] = *reinterpret_cast<const double2*>(s_ph + t * kSlot + 4u * sub + 2 * q);
+          }
 #pragma unroll
         for (int jc = 0; jc < JC; ++jc) {
           const uint32_t j = c * JC + jc;
@@ -335,13 +352,13 @@ __global__ __launch_bounds__(256, 2) void layer_kernel(LayerArgs a, const uint32
           const double dt = tq - rrow[j < k ? j : k - 1u].t;
 #pragma unroll
           for (int t = 0; t < NT; ++t) {
-            const double* om = s_om + t * kSlot + 4u * sub;
-            const double* ph = s_ph + t * kSlot + 4u * sub;
+            const float c0 = cos_rev(om[t][0].x * dt + ph[t][0].x), c1 = cos_rev(om[t][0].y * dt + ph[t][0].y);
+            const float c2 = cos_rev(om[t][1].x * dt + ph[t][1].x), c3 = cos_rev(om[t][1].y * dt + ph[t][1].y);
             float4 zz;
-            zz.x = tok[t][0] ? cos_rev(om[0] * dt + ph[0]) : 0.0f;
-            zz.y = tok[t][1] ? cos_rev(om[1] * dt + ph[1]) : 0.0f;
-            zz.z = tok[t][2] ? cos_rev(om[2] * dt + ph[2]) : 0.0f;
-            zz.w = tok[t][3] ? cos_rev(om[3] * dt + ph[3]) : 0.0f;
+            zz.x = tok[t][0] ? c0 : 0.0f;
+            zz.y = tok[t][1] ? c1 : 0.0f;
+            zz.z = tok[t][2] ? c2 : 0.0f;
+            zz.w = tok[t][3] ? c3 : 0.0f;
             zt[jc][t] = zz;
           }
         }
@@ -354,9 +371,12 @@ __global__ __launch_bounds__(256, 2) void layer_kernel(LayerArgs a, const uint32
           for (int jc = 0; jc < JC; ++jc) p[jc] = 0.0f;
 #pragma unroll
           for (int s = 0; s < NS; ++s) {
-            const float4 qv = *reinterpret_cast<const float4*>(zq + h * Zp + s * kSlot);
+            float4 qv;
+            if constexpr (QREG) qv = qt[h][s];
+            else qv = *reinterpret_cast<const float4*>(zq + h * Zp + s * kSlot);
 #pragma unroll
-            for (int jc = 0; jc < JC; ++jc) p[jc] = dot4(qv, s < NG ? zb.g[jc][s < NG ? s : 0] : zt[jc][s < NG ? 0 : s - NG], p[jc]);
+            for (int jc = 0; jc < JC; ++jc)
+              p[jc] = dot4(qv, s < NG ? zb.g[jc][s < NG ? s : 0] : zt[jc][s < NG ? 0 : s - NG], p[jc]);
           }
 #pragma unroll
           for (int jc = 0; jc < JC; ++jc) {
@@ -532,11 +552,11 @@ void go(LaunchArgs& a) {
 template <int NS, int NT>
 void go_h(LaunchArgs& a) {
   // ring entries per chunk are bounded by registers (two chunks of JC * NS float4 per lane in flight,
-  // beside H * NS float4 of accumulators)
+  // beside 2 * H * NS float4 of accumulators and qt values)
   switch (a.k.heads) {
-    case 1: go<NS, NT, 1, (NS <= 4 ? 4 : NS == 5 ? 3 : 2)>(a); break;
-    case 2: go<NS, NT, 2, (NS <= 4 ? 4 : NS == 5 ? 3 : 2)>(a); break;
-    default: go<NS, NT, 4, (NS <= 4 ? 2 : 1)>(a); break;
+    case 1: go<NS, NT, 1, (NS <= 4 ? 4 : NS == 5 ? 2 : 1)>(a); break;
+    case 2: go<NS, NT, 2, (NS <= 4 ? 2 : 1)>(a); break;
+    default: go<NS, NT, 4, 1>(a); break;
   }
 }
 

@@ -98,30 +98,20 @@ __device__ inline void mfma16_chunk(const Ops16<NTL>& o, floatx4 (&acc)[NTL]) { 
 
 // Runs compute(i, ops) for i = 0 .. n - 1 with two operand buffers: the operands of item i + 1 are
 // requested (load(i + 1, ops)) before the products of item i are issued, so every load has one whole
-// item of matrix work to arrive.  P already holds item 0.  Written as a loop over pairs plus a tail
-// so that each buffer is filled and consumed in straight-line code (no copies, no merged paths).
+// item of matrix work to arrive.  P already holds item 0.
 template <class Buf, class LoadF, class ComputeF>
 __device__ __forceinline__ void pingpong(uint32_t n, Buf& P, LoadF load, ComputeF compute) {
   Buf Q;
-  uint32_t i = 0;
   // the scheduling fences keep the requests ahead of the products they are meant to overlap
-  for (; i + 2 < n; i += 2) {
-    load(i + 1, Q);
+  for (uint32_t i = 0; i < n; i += 2) {
+    if (i + 1 < n) load(i + 1, Q);
     __builtin_amdgcn_sched_barrier(0);
     compute(i, P);
     __builtin_amdgcn_sched_barrier(0);
-    load(i + 2, P);
+    if (i + 2 < n) load(i + 2, P);
     __builtin_amdgcn_sched_barrier(0);
-    compute(i + 1, Q);
+    if (i + 1 < n) compute(i + 1, Q);
     __builtin_amdgcn_sched_barrier(0);
-  }
-  if (i + 1 < n) {
-    load(i + 1, Q);
-    __builtin_amdgcn_sched_barrier(0);
-    compute(i, P);
-    compute(i + 1, Q);
-  } else if (i < n) {
-    compute(i, P);
   }
 }
 
