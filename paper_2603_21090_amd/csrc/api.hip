@@ -152,12 +152,10 @@ size_t layout(const stgn_config& c, char* base, Dev* d) {
   d->slot_pos = b.take<uint32_t>(B2);
   d->slot_d = b.take<uint32_t>(B2);
   d->mem_new = b.take<float>((size_t)B2 * c.d_mem);
-  d->bitmap = b.take<uint32_t>(((size_t)N + 31) / 32);
-  d->front[0] = b.take<uint32_t>(N);
-  d->front[1] = b.take<uint32_t>(N);
+  d->mark = b.take<uint8_t>(mark_bytes(N));
   d->items_cap = (uint64_t)N + 2 * c.max_edges / kLogChunk + 1024;
   d->items = b.take<uint64_t>(d->items_cap);
-  d->blocksum = b.take<uint32_t>(((size_t)N + 31) / 32 / 1024 + 2);
+  d->blocksum = b.take<uint32_t>(mark_bytes(N) / kMarkPad + 2);
   d->A = b.take<uint32_t>(N);
   for (uint32_t l = 0; l < c.layers; ++l) {
     LayerDev& L = d->L[l];
@@ -527,7 +525,7 @@ int stgn_ingest_batch(stgn_ctx* ctx, uint32_t n, const uint32_t* src, const uint
   if (ev) hipEventRecord(ev[3], s);
   for (uint32_t hop = 0; hop < c.layers; ++hop) {
     { Scope t(ctx, KC_PLAN); launch_plan(d, s, hop); }
-    { Scope t(ctx, KC_EXPAND); launch_expand(d, s, hop, hop + 1 == c.layers); }
+    { Scope t(ctx, KC_EXPAND); launch_expand(d, s, hop); }
   }
   { Scope t(ctx, KC_COMPACT); launch_compact(d, s, 0); }
   { Scope t(ctx, KC_COMPACT); launch_compact(d, s, 1); }

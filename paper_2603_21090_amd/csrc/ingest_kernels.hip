@@ -217,7 +217,7 @@ __global__ __launch_bounds__(256) void apply_kernel(Dev d, const uint32_t* __res
     const uint32_t v = d.D[x];
     d.deg[v] = d.deg_new[x];
     d.t_last[v] = ts[d.last_slot[x] >> 1];
-    atomicOr(&d.bitmap[v >> 5], 1u << (v & 31));
+    d.mark[v] = 1;
   }
   // in-place memory write-back (all reads of the old rows happened in the previous kernel)
   if (d.d_mem) {
@@ -248,8 +248,8 @@ __global__ void init_state_kernel(Dev d) {
   for (size_t x = tid; x < (size_t)d.N; x += nth) { d.deg[x] = 0; d.t_last[x] = 0.0; }
   const size_t h0 = (size_t)d.N * d.H[0].ld;
   for (size_t x = tid; x < h0; x += nth) d.H[0].base[x] = 0.0f;
-  const size_t nw = ((size_t)d.N + 31) / 32;
-  for (size_t x = tid; x < nw; x += nth) d.bitmap[x] = 0;
+  const size_t nw = mark_bytes(d.N) / 4;
+  for (size_t x = tid; x < nw; x += nth) reinterpret_cast<uint32_t*>(d.mark)[x] = 0;
   const size_t nr = (size_t)d.N * d.k;
   for (size_t x = tid; x < nr; x += nth) { RingEntry r; r.nbr = 0; r.eid = 0; r.t = 0.0; d.ring[x] = r; }
   if (tid == 0) {

@@ -11,6 +11,8 @@ namespace stgn {
 
 constexpr uint32_t kLogChunk = 128;    // adjacency entries per propagation work item
 constexpr uint32_t kMinBlock = 8;      // entries in the first adjacency block of a node
+constexpr uint32_t kMarkPad = 4096;    // the dirty-flag array is padded to whole compaction blocks
+inline __host__ __device__ size_t mark_bytes(uint32_t N) { return ((size_t)N + kMarkPad - 1) / kMarkPad * kMarkPad; }
 
 // 16-byte recent-neighbour record (Sec. 3.3.2): slot (pos mod k) of node v at ring[v*k + slot]
 struct __align__(16) RingEntry {
@@ -100,8 +102,7 @@ struct Dev {
   uint32_t* slot_pos;                // [2*max_batch] per slot: position in its node's adjacency
   uint32_t* slot_d;                  // [2*max_batch] per slot: index into D
   float*   mem_new;                  // [2*max_batch x d_mem]
-  uint32_t* bitmap;                  // [ceil(N/32)] dirty flags
-  uint32_t* front[2];                // [N] each: frontier lists (ping-pong)
+  uint8_t* mark;                     // [mark_bytes(N)] dirty flags, one byte per node
   uint64_t* items;                   // propagation work items (node, chunk)
   uint64_t items_cap;
   uint32_t* blocksum;                // compaction partial sums
@@ -132,7 +133,7 @@ void launch_memory_update(const Dev& d, hipStream_t s, const uint32_t* src, cons
 void launch_apply(const Dev& d, hipStream_t s, const uint32_t* src, const uint32_t* dst, const double* ts,
                   const float* ef);
 void launch_plan(const Dev& d, hipStream_t s, uint32_t hop);
-void launch_expand(const Dev& d, hipStream_t s, uint32_t hop, bool last);
+void launch_expand(const Dev& d, hipStream_t s, uint32_t hop);
 void launch_compact(const Dev& d, hipStream_t s, int phase);
 void launch_layer(const Dev& d, hipStream_t s, uint32_t layer, const uint32_t* rows, const uint32_t* count_ptr,
                   uint32_t count_max);
