@@ -61,7 +61,6 @@ int fail(stgn_ctx* c, int code, const std::string& msg) {
       return fail(ctx, STGN_E_DEVICE, std::string(#call) + ": " + hipGetErrorString(e_));      \
   } while (0)
 
-uint32_t np32(uint32_t x) { return round_up(x, 32); }
 uint32_t row_ld(uint32_t width) { return width ? round_up(width, kSlot) : 0; }   // whole 64-float slots: gathers never need a mask
 
 struct Bump {
@@ -182,19 +181,17 @@ size_t layout(const stgn_config& c, char* base, Dev* d) {
   d->ph_rev = b.take<double>(c.d_time);
   if (c.d_mem) {
     d->Kmsg = 2 * c.d_mem + c.d_edge + c.d_time;
-    d->Kmsg2 = round_up(d->Kmsg, 2);
-    const uint32_t dg2 = round_up(c.d_msg, 2), dm2 = round_up(c.d_mem, 2);
-    d->Wmsg = b.take<float>((size_t)d->Kmsg2 * np32(c.d_msg));
+    d->Wmsg = b.take<float>(tiled_size(d->Kmsg, c.d_msg));
     d->bmsg = b.take<float>(c.d_msg);
-    d->Wzr = b.take<float>((size_t)dg2 * 2 * np32(c.d_mem));
-    d->Uzr = b.take<float>((size_t)dm2 * 2 * np32(c.d_mem));
-    d->Wh = b.take<float>((size_t)dg2 * np32(c.d_mem));
-    d->Uh = b.take<float>((size_t)dm2 * np32(c.d_mem));
+    d->Wzr = b.take<float>(tiled_size(c.d_msg, 2 * round_up(c.d_mem, 16)));
+    d->Uzr = b.take<float>(tiled_size(c.d_mem, 2 * round_up(c.d_mem, 16)));
+    d->Wh = b.take<float>(tiled_size(c.d_msg, c.d_mem));
+    d->Uh = b.take<float>(tiled_size(c.d_mem, c.d_mem));
     d->bz = b.take<float>(c.d_mem);
     d->br = b.take<float>(c.d_mem);
     d->bh = b.take<float>(c.d_mem);
   } else {
-    d->Kmsg = d->Kmsg2 = 0;
+    d->Kmsg = 0;
     d->Wmsg = d->bmsg = d->Wzr = d->Uzr = d->Wh = d->Uh = d->bz = d->br = d->bh = nullptr;
   }
   for (uint32_t l = 0; l < c.layers; ++l) {
@@ -216,17 +213,6 @@ int upload(stgn_ctx* ctx, const T* dst, const std::vector<T>& v) {
   return STGN_OK;
 }
 
-// copies src [rows x cols] into a zero-padded [rows_p x cols_p] matrix at column offset c0
-void put_block(std::vector<float>& dst, uint32_t cols_p, uint32_t c0, const float* src, uint32_t rows, uint32_t cols,
-               const std::vector<double>* row_scale = nullptr) {
-  for (uint32_t r = 0; r < rows; ++r)
-    for (uint32_t c = 0; c < cols; ++c) {
-      double v = src[(size_t)r * cols + c];
-      if (row_scale) v *= (*row_scale)[r];
-      dst[(size_t)r * cols_p + c0 + c] = (float)v;
-    }
-}
-
 int pack_parameters(stgn_ctx* ctx, const stgn_weights* w) {
   const stgn_config& c = ctx->cfg;
   const Dev& d = ctx->d;
@@ -239,20 +225,28 @@ int pack_parameters(stgn_ctx* ctx, const stgn_weights* w) {
   if ((rc = upload(ctx, d.ph_rev, ph))) return rc;
   auto vec = [](const float* p, uint32_t n) { return std::vector<float>(p, p + n); };
   if (c.d_mem) {
-    const uint32_t npg = np32(c.d_msg), npm = np32(c.d_mem);
-    const uint32_t dg2 = round_up(c.d_msg, 2), dm2 = round_up(c.d_mem, 2);
-    std::vector<double> rs(d.Kmsg, 1.0);
-    for (uint32_t i = 0; i < c.d_time; ++i) rs[2 * c.d_mem + c.d_edge + i] = tscale;   // phi carries sqrt(1/d_t)
-    std::vector<float> Wm((size_t)d.Kmsg2 * npg, 0.0f);
-    put_block(Wm, npg, 0, w->W_msg, d.Kmsg, c.d_msg, &rs);
-    std::vector<float> Wzr((size_t)dg2 * 2 * npm, 0.0f), Uzr((size_t)dm2 * 2 * npm, 0.0f);
-    put_block(Wzr, 2 * npm, 0, w->W_z, c.d_msg, c.d_mem);
-    put_block(Wzr, 2 * npm, npm, w->W_r, c.d_msg, c.d_mem);
-    put_block(Uzr, 2 * npm, 0, w->U_z, c.d_mem, c.d_mem);
-    put_block(Uzr, 2 * npm, npm, w->U_r, c.d_mem, c.d_mem);
-    std::vector<float> Wh((size_t)dg2 * npm, 0.0f), Uh((size_t)dm2 * npm, 0.0f);
-    put_block(Wh, npm, 0, w->W_h, c.d_msg, c.d_mem);
-    put_block(Uh, npm, 0, w->U_h, c.d_mem, c.d_mem);
+    // memory weights feed 16x16x4 matrix instructions: group-major packing (see tiled_size); the
+    // update and reset gates share one matrix, the reset gate's column tiles behind the update gate's
+    const uint32_t npm = round_up(c.d_mem, 16);
+    std::vector<float> Wm(tiled_size(d.Kmsg, c.d_msg), 0.0f);
+    for (uint32_t i = 0; i < d.Kmsg; ++i) {
+      const double rs = i >= 2 * c.d_mem + c.d_edge ? tscale : 1.0;             // phi carries sqrt(1/d_t)
+      for (uint32_t col = 0; col < c.d_msg; ++col) put_tiled(Wm, d.Kmsg, i, col, (double)w->W_msg[(size_t)i * c.d_msg + col] * rs);
+    }
+    std::vector<float> Wzr(tiled_size(c.d_msg, 2 * npm), 0.0f), Uzr(tiled_size(c.d_mem, 2 * npm), 0.0f);
+    std::vector<float> Wh(tiled_size(c.d_msg, c.d_mem), 0.0f), Uh(tiled_size(c.d_mem, c.d_mem), 0.0f);
+    for (uint32_t col = 0; col < c.d_mem; ++col) {
+      for (uint32_t i = 0; i < c.d_msg; ++i) {
+        put_tiled(Wzr, c.d_msg, i, col, w->W_z[(size_t)i * c.d_mem + col]);
+        put_tiled(Wzr, c.d_msg, i, npm + col, w->W_r[(size_t)i * c.d_mem + col]);
+        put_tiled(Wh, c.d_msg, i, col, w->W_h[(size_t)i * c.d_mem + col]);
+      }
+      for (uint32_t i = 0; i < c.d_mem; ++i) {
+        put_tiled(Uzr, c.d_mem, i, col, w->U_z[(size_t)i * c.d_mem + col]);
+        put_tiled(Uzr, c.d_mem, i, npm + col, w->U_r[(size_t)i * c.d_mem + col]);
+        put_tiled(Uh, c.d_mem, i, col, w->U_h[(size_t)i * c.d_mem + col]);
+      }
+    }
     if ((rc = upload(ctx, d.Wmsg, Wm)) || (rc = upload(ctx, d.bmsg, vec(w->b_msg, c.d_msg))) ||
         (rc = upload(ctx, d.Wzr, Wzr)) || (rc = upload(ctx, d.Uzr, Uzr)) || (rc = upload(ctx, d.Wh, Wh)) ||
         (rc = upload(ctx, d.Uh, Uh)) || (rc = upload(ctx, d.bz, vec(w->b_z, c.d_mem))) ||

@@ -1,18 +1,22 @@
 // Message + "Last" aggregation + GRU memory update on the distinct endpoints of a batch
 // (paper Eq. msg_linear, Eq. agg_functions "Last", Eq. gru_detail; Sec. 3.6.2: every read sees the
-// pre-batch state and each node makes one transition per batch).  One workgroup handles 32 rows:
-// the message input rows are gathered into LDS (two memory rows, the edge-feature row of the
-// node's last edge in the batch, the time encoding of t_edge - t_last), then four chained
-// matrix-core products run without leaving the CU.  New rows go to a scratch table; the apply
-// kernel commits them once every read of the old rows is done.
+// pre-batch state and each node makes one transition per batch).  One workgroup of eight waves
+// handles 16 rows: the message input rows are gathered into LDS (two memory rows, the edge-feature
+// row of the node's last edge in the batch, the time encoding of t_edge - t_last), then three
+// chained stages of 16x16x4 matrix-core products run without leaving the CU, each wave owning one
+// 16-column tile of the stage's output.  A batch has few rows (at most two per edge), so the work is
+// spread over columns rather than rows.  New rows go to a scratch table; the apply kernel commits
+// them once every read of the old rows is done.
 #include "stgn_internal.h"
-#include "mfma_gemm.h"
+#include "mfma16.h"
 
 namespace stgn {
 
 namespace {
 
-constexpr uint32_t kRows = 32;
+constexpr uint32_t kRows = 16;
+constexpr uint32_t kThreads = 512;
+constexpr uint32_t kWaves = kThreads / 64;
 
 __device__ inline float sigmoidf_(float x) { return 1.0f / (1.0f + expf(-x)); }
 
@@ -21,29 +25,50 @@ __device__ inline float cos_rev64(double x) {
   return __builtin_amdgcn_cosf((float)f);
 }
 
-__global__ __launch_bounds__(256) void memory_update_kernel(Dev d, const uint32_t* __restrict__ src,
-                                                            const uint32_t* __restrict__ dst,
-                                                            const double* __restrict__ ts,
-                                                            const float* __restrict__ ef) {
-  extern __shared__ float lds[];
+struct MemLds {
+  uint32_t ldx, ldm, ldr;      // strides of the input, message and (z | r.s) tiles, all 4 (mod 8)
+  uint32_t off_m, off_z, off_r, total;
+};
+
+__host__ __device__ inline MemLds memory_lds_layout(uint32_t Kmsg, uint32_t d_msg, uint32_t d_mem) {
+  MemLds l;
+  l.ldx = round_up(Kmsg, kGrpK) + 4;
+  l.ldm = round_up(d_msg, kGrpK) + 4;
+  l.ldr = round_up(d_mem, kGrpK) + 4;
+  l.off_m = kRows * l.ldx;
+  l.off_z = l.off_m + kRows * l.ldm;
+  l.off_r = l.off_z + kRows * l.ldr;
+  l.total = l.off_r + kRows * l.ldr + 4 * kGrpK;      // operand reads may run one chunk past the last row
+  return l;
+}
+
+__global__ __launch_bounds__(kThreads) void memory_update_kernel(Dev d, const uint32_t* __restrict__ src,
+                                                                 const uint32_t* __restrict__ dst,
+                                                                 const double* __restrict__ ts,
+                                                                 const float* __restrict__ ef) {
+  extern __shared__ __align__(16) float lds[];
   __shared__ uint32_t s_self[kRows], s_oth[kRows], s_ef[kRows], s_live[kRows];
   __shared__ double s_dt[kRows];
   const Ctrl* c = d.ctrl;
   if (c->skip) return;
   const uint32_t nD = c->nD;
   const uint32_t ntiles = (nD + kRows - 1) / kRows;
-  const uint32_t dm = d.d_mem, dg = d.d_msg, de = d.d_edge;
-  const uint32_t dm2 = round_up(dm, 2), dg2 = round_up(dg, 2);
-  const uint32_t ldx = d.Kmsg2 + 1, ldm = dg2 + 1, ldg = dm2 + 1;
-  float* Xs = lds;                       // [32 x Kmsg2]  message input rows; first dm columns = s
-  float* Ms = Xs + kRows * ldx;          // [32 x dg2]    messages
-  float* Zg = Ms + kRows * ldm;          // [32 x dm2]    update gate
-  float* Rs = Zg + kRows * ldg;          // [32 x dm2]    r . s
-  const uint32_t npg = round_up(dg, 32), npm = round_up(dm, 32);
+  const uint32_t dm = d.d_mem, dg = d.d_msg, de = d.d_edge, Kmsg = d.Kmsg;
+  const MemLds ll = memory_lds_layout(Kmsg, dg, dm);
+  float* Xs = lds;                       // [16 x Kmsg]  message input rows; first dm columns = s
+  float* Ms = lds + ll.off_m;            // [16 x dg]    messages
+  float* Zs = lds + ll.off_z;            // [16 x dm]    update gate
+  float* Rs = lds + ll.off_r;            // [16 x dm]    r . s
   const uint32_t lane = threadIdx.x & 63u;
   // wave index, made provably uniform so that tile indices and weight addresses stay in scalar registers
   const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  const uint32_t c_x = chunks_of(Kmsg), c_g = chunks_of(dg), c_m = chunks_of(dm);
+  const uint32_t ntg = round_up(dg, 16) >> 4, ntm = round_up(dm, 16) >> 4;
+  const uint32_t a_x = a16_lane_off(ll.ldx), a_m = a16_lane_off(ll.ldm), a_r = a16_lane_off(ll.ldr);
+  const uint32_t row0 = m16_row(lane, 0), colL = m16_col(lane);
   const Table H0 = d.H[0];
+  // operand padding (columns nobody writes) must be finite: clear the tiles once
+  for (uint32_t x = threadIdx.x; x < ll.total; x += kThreads) lds[x] = 0.0f;
 
   for (uint32_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
     const uint32_t r0 = tile * kRows;
@@ -66,18 +91,18 @@ __global__ __launch_bounds__(256) void memory_update_kernel(Dev d, const uint32_
     // then every thread issues its loads in batches of four, unconditionally (dead elements read a
     // valid dummy address and are zeroed afterwards), so the latencies overlap
     {
-      const uint32_t total = kRows * d.Kmsg2;
+      const uint32_t total = kRows * Kmsg;
       const float* efp = ef ? ef : H0.base;
-      for (uint32_t x0 = threadIdx.x; x0 < total; x0 += 256u * 4u) {
+      for (uint32_t x0 = threadIdx.x; x0 < total; x0 += kThreads * 4u) {
         float v[4];
         uint32_t rr[4], cc[4];
         bool ok[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          uint32_t x = x0 + 256u * e;
+          uint32_t x = x0 + kThreads * e;
           ok[e] = x < total;
           x = ok[e] ? x : 0u;
-          const uint32_t r = x / d.Kmsg2, col = x - r * d.Kmsg2;
+          const uint32_t r = x / Kmsg, col = x - r * Kmsg;
           rr[e] = r; cc[e] = col;
           const float* p = H0.base;
           if (col < dm) p = H0.base + s_self[r] + col;
@@ -89,75 +114,65 @@ __global__ __launch_bounds__(256) void memory_update_kernel(Dev d, const uint32_
         for (int e = 0; e < 4; ++e) {
           const uint32_t r = rr[e], col = cc[e];
           float val = v[e];
-          if (col >= 2 * dm + de && col < d.Kmsg) {
+          if (col >= 2 * dm + de) {
             const uint32_t q = col - 2 * dm - de;
             val = cos_rev64(d.om_rev[q] * s_dt[r] + d.ph_rev[q]);
           }
-          if (!s_live[r] || col >= d.Kmsg) val = 0.0f;
-          if (ok[e]) Xs[r * ldx + col] = val;
+          if (!s_live[r]) val = 0.0f;
+          if (ok[e]) Xs[r * ll.ldx + col] = val;
         }
       }
     }
-    for (uint32_t x = threadIdx.x; x < kRows; x += 256) {
-      Ms[x * ldm + dg2 - 1] = 0.0f;
-      Rs[x * ldg + dm2 - 1] = 0.0f;
-    }
     __syncthreads();
-    // m = x W_msg + b_msg
-    for (uint32_t nt = wave; nt < npg / 32; nt += 4) {
-      floatx16 acc[1];
-      zero_acc(acc);
-      mfma_tile<1>(Xs, ldx, d.Kmsg2, d.Wmsg, npg, nt * 32, acc);
-      const uint32_t col = nt * 32 + mfma_col(lane);
+    // ---- m = x W_msg + b_msg
+    for (uint32_t nt = wave; nt < ntg; nt += kWaves) {
+      const float* const Bt[1] = {d.Wmsg + (size_t)nt * kCG * c_x * kGrpFloats};
+      floatx4 acc[1] = {{0.f, 0.f, 0.f, 0.f}};
+      mfma16_gemm<1>(Xs + a_x, c_x, Bt, acc);
+      const uint32_t col = nt * 16 + colL;
       if (col < dg) {
         const float b = d.bmsg[col];
 #pragma unroll
-        for (int j = 0; j < 16; ++j) Ms[mfma_row(lane, j) * ldm + col] = acc[0][j] + b;
+        for (int r = 0; r < 4; ++r) Ms[(row0 + r) * ll.ldm + col] = acc[0][r] + b;
       }
     }
     __syncthreads();
-    // z = sigma(m W_z + s U_z + b_z) | r = sigma(m W_r + s U_r + b_r)
-    for (uint32_t nt = wave; nt < 2 * npm / 32; nt += 4) {
-      floatx16 acc[1];
-      zero_acc(acc);
-      mfma_tile<1>(Ms, ldm, dg2, d.Wzr, 2 * npm, nt * 32, acc);
-      mfma_tile<1>(Xs, ldx, dm2, d.Uzr, 2 * npm, nt * 32, acc);
-      const uint32_t gcol = nt * 32 + mfma_col(lane);
-      if (gcol < npm) {
-        if (gcol < dm) {
-          const float b = d.bz[gcol];
+    // ---- z = sigma(m W_z + s U_z + b_z), r = sigma(m W_r + s U_r + b_r): one wave, one column tile of both
+    for (uint32_t nt = wave; nt < ntm; nt += kWaves) {
+      const float* const Bw[2] = {d.Wzr + (size_t)nt * kCG * c_g * kGrpFloats, d.Wzr + (size_t)(ntm + nt) * kCG * c_g * kGrpFloats};
+      const float* const Bu[2] = {d.Uzr + (size_t)nt * kCG * c_m * kGrpFloats, d.Uzr + (size_t)(ntm + nt) * kCG * c_m * kGrpFloats};
+      floatx4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+      mfma16_gemm<2>(Ms + a_m, c_g, Bw, acc);
+      mfma16_gemm<2>(Xs + a_x, c_m, Bu, acc);
+      const uint32_t col = nt * 16 + colL;
+      if (col < dm) {
+        const float bz = d.bz[col], br = d.br[col];
 #pragma unroll
-          for (int j = 0; j < 16; ++j) Zg[mfma_row(lane, j) * ldg + gcol] = sigmoidf_(acc[0][j] + b);
-        }
-      } else {
-        const uint32_t col = gcol - npm;
-        if (col < dm) {
-          const float b = d.br[col];
-#pragma unroll
-          for (int j = 0; j < 16; ++j) {
-            const uint32_t r = mfma_row(lane, j);
-            Rs[r * ldg + col] = sigmoidf_(acc[0][j] + b) * Xs[r * ldx + col];
-          }
+        for (int r = 0; r < 4; ++r) {
+          const uint32_t row = row0 + r;
+          Zs[row * ll.ldr + col] = sigmoidf_(acc[0][r] + bz);
+          Rs[row * ll.ldr + col] = sigmoidf_(acc[1][r] + br) * Xs[row * ll.ldx + col];
         }
       }
     }
     __syncthreads();
-    // candidate = tanh(m W_h + (r . s) U_h + b_h);  s' = (1 - z) candidate + z s
-    for (uint32_t nt = wave; nt < npm / 32; nt += 4) {
-      floatx16 acc[1];
-      zero_acc(acc);
-      mfma_tile<1>(Ms, ldm, dg2, d.Wh, npm, nt * 32, acc);
-      mfma_tile<1>(Rs, ldg, dm2, d.Uh, npm, nt * 32, acc);
-      const uint32_t col = nt * 32 + mfma_col(lane);
+    // ---- candidate = tanh(m W_h + (r . s) U_h + b_h);  s' = (1 - z) candidate + z s
+    for (uint32_t nt = wave; nt < ntm; nt += kWaves) {
+      const float* const Bw[1] = {d.Wh + (size_t)nt * kCG * c_g * kGrpFloats};
+      const float* const Bu[1] = {d.Uh + (size_t)nt * kCG * c_m * kGrpFloats};
+      floatx4 acc[1] = {{0.f, 0.f, 0.f, 0.f}};
+      mfma16_gemm<1>(Ms + a_m, c_g, Bw, acc);
+      mfma16_gemm<1>(Rs + a_r, c_m, Bu, acc);
+      const uint32_t col = nt * 16 + colL;
       if (col < dm) {
         const float b = d.bh[col];
 #pragma unroll
-        for (int j = 0; j < 16; ++j) {
-          const uint32_t r = mfma_row(lane, j);
-          if (r0 + r < nD) {
-            const float cand = tanhf(acc[0][j] + b);
-            const float z = Zg[r * ldg + col], s = Xs[r * ldx + col];
-            d.mem_new[(size_t)(r0 + r) * dm + col] = (1.0f - z) * cand + z * s;
+        for (int r = 0; r < 4; ++r) {
+          const uint32_t row = row0 + r;
+          if (r0 + row < nD) {
+            const float cand = tanhf(acc[0][r] + b);
+            const float z = Zs[row * ll.ldr + col], s = Xs[row * ll.ldx + col];
+            d.mem_new[(size_t)(r0 + row) * dm + col] = (1.0f - z) * cand + z * s;
           }
         }
       }
@@ -166,10 +181,7 @@ __global__ __launch_bounds__(256) void memory_update_kernel(Dev d, const uint32_
   }
 }
 
-size_t memory_lds(const Dev& d) {
-  const uint32_t dm2 = round_up(d.d_mem, 2), dg2 = round_up(d.d_msg, 2);
-  return (size_t)kRows * ((d.Kmsg2 + 1) + (dg2 + 1) + 2 * (dm2 + 1)) * sizeof(float);
-}
+size_t memory_lds(const Dev& d) { return (size_t)memory_lds_layout(d.Kmsg, d.d_msg, d.d_mem).total * sizeof(float); }
 
 }  // namespace
 
@@ -177,13 +189,13 @@ void launch_memory_update(const Dev& d, hipStream_t s, const uint32_t* src, cons
                           const float* ef) {
   uint32_t blocks = (2 * d.max_batch + kRows - 1) / kRows;
   if (blocks > 1024) blocks = 1024;
-  hipLaunchKernelGGL(memory_update_kernel, dim3(blocks), dim3(256), memory_lds(d), s, d, src, dst, ts, ef);
+  hipLaunchKernelGGL(memory_update_kernel, dim3(blocks), dim3(kThreads), memory_lds(d), s, d, src, dst, ts, ef);
 }
 
 int setup_memory_attributes(const Dev& d) {
   if (d.d_mem == 0) return 0;
   const size_t need = memory_lds(d);
-  if (need > kMaxLds) return -1;
+  if (need + 1024 > kMaxLds) return -1;
   return hipFuncSetAttribute((const void*)memory_update_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                              (int)need) == hipSuccess ? 0 : -1;
 }

@@ -111,10 +111,10 @@ struct Dev {
   uint32_t q_cap;
   // parameters
   const double* om_rev; const double* ph_rev;   // omega/(2 pi), phase/(2 pi)
-  uint32_t Kmsg, Kmsg2;
-  const float* Wmsg; const float* bmsg;         // [Kmsg2 x Np(d_msg)]
-  const float* Wzr;  const float* Uzr;          // [d_msg2 x 2*Np(d_mem)], [d_mem2 x 2*Np(d_mem)]
-  const float* Wh;   const float* Uh;           // [d_msg2 x Np(d_mem)],  [d_mem2 x Np(d_mem)]
+  uint32_t Kmsg;                                // message input width 2 d_mem + d_edge + d_time
+  const float* Wmsg; const float* bmsg;         // matrices in the group-major packing of mfma16.h
+  const float* Wzr;  const float* Uzr;          // [d_msg x 2 R16(d_mem)], [d_mem x 2 R16(d_mem)]: update | reset gate
+  const float* Wh;   const float* Uh;           // [d_msg x d_mem], [d_mem x d_mem]
   const float* bz; const float* br; const float* bh;
   LayerDev L[STGN_MAX_LAYERS];
 };
