@@ -288,7 +288,7 @@ __global__ __launch_bounds__(256, 2) void layer_kernel(LayerArgs a, const uint32
         // one chunk per unit: the operands of the next unit are in flight during this unit's products
         load_a16(Qs + ua.h * ll.dkp + a_q, 0, o2.a);
         const uint32_t nu = wave < nunits2 ? (nunits2 - wave + 3u) >> 2 : 0u;
-        pingpong<Ops16<2>>(
+        if (nu) pingpong_peeled<Ops16<2>>(
             nu, o2,
             [&](uint32_t i, Ops16<2>& o) {
               const Unit2 u = decode2(wave + 4u * i);
@@ -426,7 +426,7 @@ __global__ __launch_bounds__(256, 2) void layer_kernel(LayerArgs a, const uint32
           }
         }
       };
-      pingpong<ZBuf>(nchunk3, z0, gather, attend);
+      if (nchunk3) pingpong_clamped<ZBuf>(nchunk3, z0, gather, attend);
       // zb overwrites qt (each lane owns its float4s; padding lanes hold zeros)
       float* zw = Zs + local * ll.ldz + 4u * sub;
 #pragma unroll

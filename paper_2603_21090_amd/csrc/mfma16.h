@@ -96,19 +96,52 @@ struct Ops16 {
 template <int NTL>
 __device__ inline void mfma16_chunk(const Ops16<NTL>& o, floatx4 (&acc)[NTL]) { mfma16_chunk<NTL>(o.a, o.b, acc); }
 
-// Runs compute(i, ops) for i = 0 .. n - 1 with two operand buffers: the operands of item i + 1 are
-// requested (load(i + 1, ops)) before the products of item i are issued, so every load has one whole
-// item of matrix work to arrive.  P already holds item 0.
+// Runs compute(i, buf) for i = 0 .. n - 1 (n >= 1) with two operand buffers: the operands of item
+// i + 1 are requested (load(i + 1, buf)) before the work on item i is issued, so every load has one
+// whole item of work to arrive.  P already holds item 0.  Scheduling fences keep the requests ahead
+// of the work they are meant to overlap.
+//
+// Loads inside the steady-state loop are never conditional: the memory counter a wave waits on
+// counts requests in issue order, and after a branch that may or may not have issued requests the
+// compiler must wait for the youngest of them -- which would drain the prefetch it was meant to hide.
+//
+// Peeled form: the tail is written out, so no request is wasted (three more copies of `compute`).
 template <class Buf, class LoadF, class ComputeF>
-__device__ __forceinline__ void pingpong(uint32_t n, Buf& P, LoadF load, ComputeF compute) {
+__device__ __forceinline__ void pingpong_peeled(uint32_t n, Buf& P, LoadF load, ComputeF compute) {
   Buf Q;
-  // the scheduling fences keep the requests ahead of the products they are meant to overlap
-  for (uint32_t i = 0; i < n; i += 2) {
-    if (i + 1 < n) load(i + 1, Q);
+  uint32_t i = 0;
+  for (; i + 2 < n; i += 2) {
+    load(i + 1, Q);
     __builtin_amdgcn_sched_barrier(0);
     compute(i, P);
     __builtin_amdgcn_sched_barrier(0);
-    if (i + 2 < n) load(i + 2, P);
+    load(i + 2, P);
+    __builtin_amdgcn_sched_barrier(0);
+    compute(i + 1, Q);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  if (i + 1 < n) {
+    load(i + 1, Q);
+    __builtin_amdgcn_sched_barrier(0);
+    compute(i, P);
+    __builtin_amdgcn_sched_barrier(0);
+    compute(i + 1, Q);
+  } else {
+    compute(i, P);
+  }
+}
+
+// Clamped form: two copies of `compute` only; past the end the last item is requested again (a
+// cache hit) and ignored.
+template <class Buf, class LoadF, class ComputeF>
+__device__ __forceinline__ void pingpong_clamped(uint32_t n, Buf& P, LoadF load, ComputeF compute) {
+  Buf Q;
+  for (uint32_t i = 0; i < n; i += 2) {
+    load(i + 1 < n ? i + 1 : n - 1, Q);
+    __builtin_amdgcn_sched_barrier(0);
+    compute(i, P);
+    __builtin_amdgcn_sched_barrier(0);
+    load(i + 2 < n ? i + 2 : n - 1, P);
     __builtin_amdgcn_sched_barrier(0);
     if (i + 1 < n) compute(i + 1, Q);
     __builtin_amdgcn_sched_barrier(0);
@@ -121,7 +154,7 @@ template <int NTL>
 __device__ __forceinline__ void mfma16_gemm_pre(const float* Ap, uint32_t nchunks, const float* const (&Bt)[NTL],
                                                 floatx4 (&acc)[NTL], Ops16<NTL>& P) {
   load_a16(Ap, 0, P.a);
-  pingpong<Ops16<NTL>>(
+  pingpong_peeled<Ops16<NTL>>(
       nchunks, P,
       [&](uint32_t ch, Ops16<NTL>& o) {
         load_a16(Ap, ch * kCG, o.a);
