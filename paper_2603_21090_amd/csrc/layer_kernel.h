@@ -153,15 +153,22 @@ __global__ __launch_bounds__(256, 2) void layer_kernel(LayerArgs a, const uint32
   const uint32_t c_off_z = m16_row(lane, 0) * ll.ldz + m16_col(lane);
 
   // ---- phase-2 work units: (head, pair of valid qt column tiles); wave w owns units w, w + 4, ...
+  // Lane i of `udesc` holds the description of the wave's i-th unit (head, the two tiles, whether the
+  // second tile is real), worked out once; inside the tile loop a unit costs one cross-lane read.
   const uint32_t npr = (nzt + 1u) >> 1, nunits2 = a.heads * npr;
+  const uint32_t nu2 = wave < nunits2 ? (nunits2 - wave + 3u) >> 2 : 0u;     // units of this wave
   struct Unit2 { uint32_t h, t0, t1; bool two; };
-  auto decode2 = [&](uint32_t x) {
+  __syncthreads();                                                           // s_zt is complete
+  uint32_t udesc = 0;
+  if (lane < nu2) {
+    const uint32_t x = wave + 4u * lane, h = x / npr, i0 = 2u * (x - h * npr);
+    const uint32_t two = i0 + 1u < nzt ? 1u : 0u;
+    udesc = h | (s_zt[i0] << 8) | (s_zt[i0 + two] << 16) | (two << 24);
+  }
+  auto decode2 = [&](uint32_t i) {
+    const uint32_t dsc = (uint32_t)__builtin_amdgcn_readlane((int)udesc, (int)i);
     Unit2 u;
-    u.h = x / npr;
-    const uint32_t i0 = 2u * (x - u.h * npr);
-    u.two = i0 + 1u < nzt;
-    u.t0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)s_zt[i0]);
-    u.t1 = (uint32_t)__builtin_amdgcn_readfirstlane((int)s_zt[u.two ? i0 + 1u : i0]);
+    u.h = dsc & 0xFFu; u.t0 = (dsc >> 8) & 0xFFu; u.t1 = (dsc >> 16) & 0xFFu; u.two = (dsc >> 24) != 0u;
     return u;
   };
   auto wkt = [&](uint32_t h, uint32_t t) { return a.WKT + (size_t)(h * ntz + t) * g_dk * kGrpFloats; };
@@ -191,20 +198,24 @@ __global__ __launch_bounds__(256, 2) void layer_kernel(LayerArgs a, const uint32
       s_node[threadIdx.x] = r < n ? (rows ? rows[r] : r) : 0xFFFFFFFFu;
     }
     __syncthreads();
-    // the rows' ring records, most recent first; slots past the row's entry count name node 0 / edge 0
-    // (finite rows that later meet a zero weight)
+    // the rows' ring records, most recent first; places past the row's entry count name node 0 / edge 0
+    // (finite rows that later meet a zero weight).  Thread (row, slot) fetches its slot without
+    // waiting for the row's degree (both loads leave together) and the degree then tells which place
+    // j the slot's record takes: the record of adjacency position p sits in slot p mod k.
     for (uint32_t x = threadIdx.x; x < kTM * k; x += 256) {
-      const uint32_t r = x / k, j = x - r * k;
+      const uint32_t r = x / k, sl = x - r * k;
       const uint32_t node = s_node[r];
       const bool live = node != 0xFFFFFFFFu;
       const uint32_t nn = live ? node : 0u;
+      RingEntry e = a.ring[(size_t)nn * k + sl];
       const uint32_t dg = live ? a.deg[nn] : 0u;
+      const double tl = a.t_last[nn];
       const uint32_t cnt = dg < k ? dg : k;
-      RingEntry e;
-      e.nbr = 0u; e.eid = 0u; e.t = 0.0;
-      if (j < cnt) e = a.ring[(size_t)nn * k + (dg - 1u - j) % k];
-      Rs[x] = e;
-      if (j == 0) { s_cnt[r] = cnt; s_tq[r] = a.t_last[nn]; }
+      const uint32_t newest = dg ? (dg - 1u) % k : 0u;
+      const uint32_t j = newest >= sl ? newest - sl : newest + k - sl;
+      if (j >= cnt) { e.nbr = 0u; e.eid = 0u; e.t = 0.0; }
+      Rs[r * k + j] = e;
+      if (sl == 0) { s_cnt[r] = cnt; s_tq[r] = tl; }
     }
     {
       const uint32_t qpr = round_up(a.d_in, kGrpK) >> 2, total = kTM * qpr;   // 16-byte quads per row / per tile
@@ -279,32 +290,30 @@ __global__ __launch_bounds__(256, 2) void layer_kernel(LayerArgs a, const uint32
     // ================================================================ phase 2: qt_h = q_h W_K,h^T / sqrt(dk)
     {
       Ops16<2> o2;
-      uint32_t x = wave;
-      Unit2 ua = decode2(x < nunits2 ? x : nunits2 - 1u);     // weights of the first unit are requested
-      load_b16(wkt(ua.h, ua.t0), 0, o2.b[0]);                 // ahead of the barrier
+      Unit2 ua = decode2(0);                                  // weights of the first unit are requested
+      load_b16(wkt(ua.h, ua.t0), 0, o2.b[0]);                 // ahead of the barrier (unit 0 of an idle wave: head 0, tile 0)
       load_b16(wkt(ua.h, ua.t1), 0, o2.b[1]);
       __syncthreads();
       if (c_dk == 1) {
         // one chunk per unit: the operands of the next unit are in flight during this unit's products
         load_a16(Qs + ua.h * ll.dkp + a_q, 0, o2.a);
-        const uint32_t nu = wave < nunits2 ? (nunits2 - wave + 3u) >> 2 : 0u;
-        if (nu) pingpong_peeled<Ops16<2>>(
-            nu, o2,
+        if (nu2) pingpong_peeled<Ops16<2>>(
+            nu2, o2,
             [&](uint32_t i, Ops16<2>& o) {
-              const Unit2 u = decode2(wave + 4u * i);
+              const Unit2 u = decode2(i);
               load_a16(Qs + u.h * ll.dkp + a_q, 0, o.a);
               load_b16(wkt(u.h, u.t0), 0, o.b[0]);
               load_b16(wkt(u.h, u.t1), 0, o.b[1]);
             },
             [&](uint32_t i, const Ops16<2>& o) {
-              const Unit2 u = decode2(wave + 4u * i);
+              const Unit2 u = decode2(i);
               floatx4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
               mfma16_chunk<2>(o, acc);
               store2(u, acc);
             });
       } else {
-        for (; x < nunits2; x += 4) {
-          ua = decode2(x);
+        for (uint32_t i = 0; i < nu2; ++i) {
+          ua = decode2(i);
           const float* const Bt[2] = {wkt(ua.h, ua.t0), wkt(ua.h, ua.t1)};
           floatx4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
           mfma16_gemm<2>(Qs + ua.h * ll.dkp + a_q, c_dk, Bt, acc);
