@@ -106,7 +106,17 @@ def main():
               f"of {nb} batches", file=sys.stderr)
         sys.exit(2)
 
+    last_note = [time.perf_counter()]
+
+    def note(msg, force=False):
+        """progress on stderr, at most every 20 s (long workloads are otherwise silent for minutes)"""
+        now = time.perf_counter()
+        if force or now - last_note[0] > 20.0:
+            print(f"[bench {w.name}] {msg}", file=sys.stderr, flush=True)
+            last_note[0] = now
+
     dev = torch.device("cuda:0")
+    note("generating the edge stream", force=True)
     st = synth.EdgeStream(w)
     weights = synth.make_weights(w)
     nf = synth.node_features(w)
@@ -123,7 +133,9 @@ def main():
     for lo in range(0, used, CH):
         hi = min(lo + CH, used)
         d_ef[lo:hi] = torch.from_numpy(st.edge_features(lo, hi)).to(dev)
+        note(f"edge features resident: {hi}/{used}")
     torch.cuda.synchronize()
+    note("warm-up", force=True)
 
     def feed(b, stats=False):
         lo, hi = b * w.batch, min((b + 1) * w.batch, used)
@@ -132,8 +144,12 @@ def main():
     b = 0
     for _ in range(W):
         feed(b); b += 1
+        if b % 256 == 0:
+            g.sync()
+            note(f"warm-up batch {b}/{W}")
     g.sync()
     tot0 = g.totals()
+    note("timed region", force=True)
 
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -148,6 +164,7 @@ def main():
     aff = tot1["affected"] - tot0["affected"]
     direct = tot1["direct"] - tot0["direct"]
 
+    note("latency / host-input / kernel passes", force=True)
     # per-batch latency: enqueue + wait, one batch at a time
     lat = []
     stage_us = np.zeros(6)
