@@ -200,7 +200,7 @@ def main():
     kt = g.kernel_times(enable=False, reset=False)
     totk1 = g.totals()
     n_layer_launches = max(n_ker * w.layers, 1)
-    rows_per_launch = (totk1["affected"] - totk0["affected"]) / max(n_ker, 1)          # |A| per layer launch
+    rows_per_launch = (totk1["rows"] - totk0["rows"]) / n_layer_launches              # rows a layer launch recomputes
     entries_per_launch = (totk1["gathered"] - totk0["gathered"]) / n_layer_launches    # ring records per launch
 
     # An event pair around an empty kernel measures what the bracketing itself costs (the command
@@ -251,7 +251,7 @@ def main():
         rw = (time.perf_counter() - a) / args.rebuilds
         tr1 = g.totals()
         ent = (tr1["gathered"] - tr0["gathered"]) / args.rebuilds          # ring records over all layers
-        rb_bytes = w.layers * algorithmic_bytes(w, w.num_nodes, ent / w.layers)
+        rb_bytes = w.layers * algorithmic_bytes(w, w.num_nodes, ent / w.layers)        # every row, every layer
         rebuild = {"ms": rw * 1e3, "node_layers_per_s": w.num_nodes * w.layers / rw,
                    "algorithmic_GBs": rb_bytes / rw / 1e9, "frac_hbm": rb_bytes / rw / 1e9 / HBM_PEAK_GBS,
                    "ring_entries": ent / w.layers}
@@ -299,6 +299,7 @@ def main():
         "p95_batch_latency_ms": float(np.percentile(lat_ms, 95)),
         "affected_embeddings_per_s": aff / wall,
         "mean_affected": aff / K,
+        "mean_rows_recomputed_per_layer": (tot1["rows"] - tot0["rows"]) / K / w.layers,
         "mean_direct": direct / K,
         "affected_fraction": aff / K / w.num_nodes,
         "paper_bound_2BLK": binding.paper_affected_bound(w.batch, w.k, w.layers),

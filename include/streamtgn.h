@@ -149,10 +149,13 @@ int stgn_get_history(stgn_ctx *ctx, uint32_t node, uint32_t first, uint32_t coun
 int stgn_get_memory(stgn_ctx *ctx, uint32_t n, const uint32_t *nodes, float *mem, double *t_last);
 
 /* Totals since creation: edges ingested, sum of |V_direct|, sum of |V_aff|, adjacency entries
- * scanned by the propagation, recent-neighbour entries gathered by the attention kernels (summed
- * over layers; includes full rebuilds).  Synchronises.  Any pointer may be NULL. */
+ * scanned by the propagation, recent-neighbour entries gathered and rows recomputed by the
+ * attention kernels (both summed over layers; both include full rebuilds).  Layer l of a batch
+ * recomputes only the affected nodes whose layer-l inputs changed (the endpoints and the first l
+ * hops; one hop less for a memoryless model, whose layer-0 rows never change), so `rows` can be
+ * smaller than layers * sum of |V_aff|.  Synchronises.  Any pointer may be NULL. */
 int stgn_get_totals(stgn_ctx *ctx, uint64_t *edges, uint64_t *direct, uint64_t *affected,
-                    uint64_t *scanned, uint64_t *gathered);
+                    uint64_t *scanned, uint64_t *gathered, uint64_t *rows);
 
 /* Microseconds (HIP events on the context's stream) spent in each kernel class since the last
  * call with reset != 0, and launch counts.  Collection is off until enabled; while it is on,

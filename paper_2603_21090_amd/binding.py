@@ -82,7 +82,7 @@ def load_library():
     L.stgn_get_neighbors.argtypes = [vp, C.c_uint32, vp, vp, vp, _u32p]
     L.stgn_get_history.argtypes = [vp, C.c_uint32, C.c_uint32, C.c_uint32, vp, vp, _u32p]
     L.stgn_get_memory.argtypes = [vp, C.c_uint32, vp, vp, vp]
-    L.stgn_get_totals.argtypes = [vp] + [C.POINTER(C.c_uint64)] * 5
+    L.stgn_get_totals.argtypes = [vp] + [C.POINTER(C.c_uint64)] * 6
     L.stgn_kernel_times.argtypes = [vp, C.c_int, C.c_int, C.c_uint32, C.POINTER(C.c_char_p), _f64p,
                                     C.POINTER(C.c_uint64)]
     L.stgn_last_error.argtypes = [vp]
@@ -265,9 +265,9 @@ class StreamTGN:
         return mem, tl
 
     def totals(self):
-        v = [C.c_uint64(0) for _ in range(5)]
+        v = [C.c_uint64(0) for _ in range(6)]
         self._check(self._L.stgn_get_totals(self._h, *[C.byref(x) for x in v]))
-        return dict(zip(("edges", "direct", "affected", "scanned", "gathered"), [x.value for x in v]))
+        return dict(zip(("edges", "direct", "affected", "scanned", "gathered", "rows"), [x.value for x in v]))
 
     def kernel_times(self, enable=True, reset=False):
         cap = 16

@@ -154,8 +154,14 @@ size_t layout(const stgn_config& c, char* base, Dev* d) {
   d->mark = b.take<uint8_t>(mark_bytes(N));
   d->items_cap = (uint64_t)N + 2 * c.max_edges / kLogChunk + 1024;
   d->items = b.take<uint64_t>(d->items_cap);
-  d->blocksum = b.take<uint32_t>(mark_bytes(N) / kMarkPad + 2);
+  d->blocksum = b.take<uint32_t>((size_t)(c.layers + 1) * (mark_bytes(N) / kMarkPad + 2));
   d->A = b.take<uint32_t>(N);
+  d->n_lists = 0;
+  for (uint32_t l = 0; l < c.layers; ++l) {
+    d->thr[l] = c.d_mem ? l + 2 : l + 1;                      // flags are 1 (endpoint) and h + 2 (hop h)
+    if (d->thr[l] >= c.layers + 1) { d->R[l] = d->A; d->thr[l] = 0xFFu; }
+    else { d->R[l] = b.take<uint32_t>(N); ++d->n_lists; }
+  }
   for (uint32_t l = 0; l < c.layers; ++l) {
     LayerDev& L = d->L[l];
     L.d_in = l == 0 ? d->d0 : c.d_emb;
@@ -321,11 +327,13 @@ void drain_timing(stgn_ctx* ctx) {
   ctx->pending.clear();
 }
 
-void run_layers(stgn_ctx* ctx, const uint32_t* rows, const uint32_t* count_ptr, uint32_t count_max) {
+// every layer over all rows (initial state, full rebuild) or over the per-layer lists of the last batch
+void run_layers(stgn_ctx* ctx, bool all_rows) {
   const Dev& d = ctx->d;
   for (uint32_t l = 0; l < d.layers; ++l) {
     Scope s(ctx, KC_LAYER);
-    launch_layer(d, ctx->stream, l, rows, count_ptr, count_max);
+    if (all_rows) launch_layer(d, ctx->stream, l, nullptr, nullptr, d.N);
+    else launch_layer(d, ctx->stream, l, d.R[l], &d.ctrl->nR[l], d.N);
   }
 }
 
@@ -437,7 +445,7 @@ int stgn_create(const stgn_config* cfg, const stgn_weights* w, const float* node
                                hipMemcpyHostToDevice);
     if (e != hipSuccess) { ctx->err = std::string("node feature upload: ") + hipGetErrorString(e); return bail(STGN_E_DEVICE); }
   }
-  run_layers(ctx, nullptr, nullptr, cfg->num_nodes);    // every cache row = empty-neighbourhood embedding
+  run_layers(ctx, true);    // every cache row = empty-neighbourhood embedding
   hipError_t e = hipStreamSynchronize(ctx->stream);
   if (e == hipSuccess) e = hipGetLastError();
   if (e != hipSuccess) { ctx->err = std::string("initial rebuild: ") + hipGetErrorString(e); return bail(STGN_E_DEVICE); }
@@ -524,7 +532,7 @@ int stgn_ingest_batch(stgn_ctx* ctx, uint32_t n, const uint32_t* src, const uint
   { Scope t(ctx, KC_COMPACT); launch_compact(d, s, 0); }
   { Scope t(ctx, KC_COMPACT); launch_compact(d, s, 1); }
   if (ev) hipEventRecord(ev[4], s);
-  run_layers(ctx, d.A, &d.ctrl->nA, c.num_nodes);
+  run_layers(ctx, false);
   if (ctx->timing) { Scope t(ctx, KC_NOOP); launch_noop(s); }   // event-pair overhead, for calibration
   if (ev) hipEventRecord(ev[5], s);
   HIPCHK(ctx, hipGetLastError());
@@ -553,7 +561,7 @@ int stgn_ingest_batch(stgn_ctx* ctx, uint32_t n, const uint32_t* src, const uint
 
 int stgn_full_rebuild(stgn_ctx* ctx) {
   if (!ctx) return STGN_E_INVALID_ARG;
-  run_layers(ctx, nullptr, nullptr, ctx->cfg.num_nodes);
+  run_layers(ctx, true);
   HIPCHK(ctx, hipGetLastError());
   return STGN_OK;
 }
@@ -679,7 +687,7 @@ int stgn_get_memory(stgn_ctx* ctx, uint32_t n, const uint32_t* nodes, float* mem
 }
 
 int stgn_get_totals(stgn_ctx* ctx, uint64_t* edges, uint64_t* direct, uint64_t* affected, uint64_t* scanned,
-                    uint64_t* gathered) {
+                    uint64_t* gathered, uint64_t* rows) {
   if (!ctx) return STGN_E_INVALID_ARG;
   int rc = sync_and_poll(ctx);
   const Ctrl& h = *ctx->ctrl_host;
@@ -688,6 +696,7 @@ int stgn_get_totals(stgn_ctx* ctx, uint64_t* edges, uint64_t* direct, uint64_t* 
   if (affected) *affected = h.tot_affected;
   if (scanned) *scanned = h.tot_scanned;
   if (gathered) *gathered = h.tot_gathered;
+  if (rows) *rows = h.tot_rows;
   return rc;
 }
 

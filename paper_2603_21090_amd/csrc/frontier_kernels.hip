@@ -126,13 +126,15 @@ __global__ __launch_bounds__(256) void expand_kernel(Dev d, uint32_t hop) {
 constexpr uint32_t kFlagsPerThread = 16;
 constexpr uint32_t kFlagsPerBlock = 256 * kFlagsPerThread;
 
-// bit j set iff byte j of the 16 flags is non-zero
-__device__ inline uint32_t nonzero_bytes(const uint4 m) {
+// bit j set iff byte j of the 16 flags lies in [1, thr]
+__device__ inline uint32_t bytes_upto(const uint4 m, uint32_t thr) {
   uint32_t bits = 0;
   const uint32_t w[4] = {m.x, m.y, m.z, m.w};
   for (int q = 0; q < 4; ++q)
-    for (int j = 0; j < 4; ++j)
-      if ((w[q] >> (8 * j)) & 0xFFu) bits |= 1u << (4 * q + j);
+    for (int j = 0; j < 4; ++j) {
+      const uint32_t f = (w[q] >> (8 * j)) & 0xFFu;
+      if (f != 0u && f <= thr) bits |= 1u << (4 * q + j);
+    }
   return bits;
 }
 __device__ inline uint32_t bytes_equal(const uint4 m, uint32_t value) {
@@ -143,51 +145,69 @@ __device__ inline uint32_t bytes_equal(const uint4 m, uint32_t value) {
   return n;
 }
 
+// list 0 is A (every non-zero flag); list 1 + l is R[l] for the layers that need their own list.
+// Block sums are stored list-major: blocksum[list * nblocks + block].
+__device__ inline uint32_t list_threshold(const Dev& d, uint32_t list) {
+  if (list == 0) return 0xFFu;
+  uint32_t seen = 0;
+  for (uint32_t l = 0; l < d.layers; ++l)
+    if (d.R[l] != d.A && ++seen == list) return d.thr[l];
+  return 0xFFu;
+}
+__device__ inline uint32_t* list_base(const Dev& d, uint32_t list) {
+  if (list == 0) return d.A;
+  uint32_t seen = 0;
+  for (uint32_t l = 0; l < d.layers; ++l)
+    if (d.R[l] != d.A && ++seen == list) return d.R[l];
+  return d.A;
+}
+
 __global__ __launch_bounds__(256) void compact_count_kernel(Dev d, uint32_t last_value) {
   __shared__ uint32_t s[256];
   const uint32_t v0 = blockIdx.x * kFlagsPerBlock + threadIdx.x * kFlagsPerThread;
-  uint32_t cnt = 0, reached = 0;
-  if (v0 < d.N) {                                            // the flag array is padded to whole blocks
-    const uint4 m = *reinterpret_cast<const uint4*>(d.mark + v0);
-    cnt = (uint32_t)__popc(nonzero_bytes(m));
-    reached = bytes_equal(m, last_value);
-  }
+  uint4 m = make_uint4(0u, 0u, 0u, 0u);
+  if (v0 < d.N) m = *reinterpret_cast<const uint4*>(d.mark + v0);     // the flag array is padded to whole blocks
   uint32_t excl;
-  const uint32_t tot = block_scan_256(cnt, s, &excl);
-  const uint32_t tot_reached = block_scan_256(reached, s, &excl);
-  if (threadIdx.x == 0) {
-    d.blocksum[blockIdx.x] = tot;
-    if (tot_reached) atomicAdd(&d.ctrl->n_front[last_value - 1u], tot_reached);   // first reached by the last hop
+  for (uint32_t list = 0; list <= d.n_lists; ++list) {
+    const uint32_t cnt = (uint32_t)__popc(bytes_upto(m, list_threshold(d, list)));
+    const uint32_t tot = block_scan_256(cnt, s, &excl);
+    if (threadIdx.x == 0) d.blocksum[list * gridDim.x + blockIdx.x] = tot;
   }
+  const uint32_t tot_reached = block_scan_256(bytes_equal(m, last_value), s, &excl);
+  if (threadIdx.x == 0 && tot_reached) atomicAdd(&d.ctrl->n_front[last_value - 1u], tot_reached);   // first reached by the last hop
 }
 
 __global__ __launch_bounds__(256) void compact_write_kernel(Dev d) {
   __shared__ uint32_t s[256];
   const uint32_t t = threadIdx.x;
-  // ids before this block
-  uint32_t part = 0;
-  for (uint32_t b = t; b < blockIdx.x; b += 256) part += d.blocksum[b];
-  uint32_t excl;
-  const uint32_t before = block_scan_256(part, s, &excl);
-  // scan inside the block
   const uint32_t v0 = blockIdx.x * kFlagsPerBlock + t * kFlagsPerThread;
-  uint32_t bits = 0;
-  if (v0 < d.N) bits = nonzero_bytes(*reinterpret_cast<const uint4*>(d.mark + v0));
-  const uint32_t cnt = (uint32_t)__popc(bits);
-  const uint32_t block_total = block_scan_256(cnt, s, &excl);
-  uint32_t out = before + excl;
-  uint32_t wv = bits;
-  while (wv) {
-    const uint32_t bit = (uint32_t)__ffs((int)wv) - 1u;
-    d.A[out++] = v0 + bit;
-    wv &= wv - 1u;
+  uint4 m = make_uint4(0u, 0u, 0u, 0u);
+  if (v0 < d.N) m = *reinterpret_cast<const uint4*>(d.mark + v0);
+  uint32_t excl, total[STGN_MAX_LAYERS + 1];
+  for (uint32_t list = 0; list <= d.n_lists; ++list) {
+    // ids before this block
+    uint32_t part = 0;
+    for (uint32_t b = t; b < blockIdx.x; b += 256) part += d.blocksum[list * gridDim.x + b];
+    const uint32_t before = block_scan_256(part, s, &excl);
+    // scan inside the block
+    uint32_t bits = bytes_upto(m, list_threshold(d, list));
+    const uint32_t cnt = (uint32_t)__popc(bits);
+    const uint32_t block_total = block_scan_256(cnt, s, &excl);
+    uint32_t* out = list_base(d, list) + before + excl;
+    while (bits) {
+      const uint32_t bit = (uint32_t)__ffs((int)bits) - 1u;
+      *out++ = v0 + bit;
+      bits &= bits - 1u;
+    }
+    total[list] = before + block_total;
   }
-  if (bits) *reinterpret_cast<uint4*>(d.mark + v0) = make_uint4(0u, 0u, 0u, 0u);   // ready for the next batch
+  if (m.x | m.y | m.z | m.w) *reinterpret_cast<uint4*>(d.mark + v0) = make_uint4(0u, 0u, 0u, 0u);   // ready for the next batch
   if (blockIdx.x == gridDim.x - 1 && t == 0) {
     Ctrl* c = d.ctrl;
-    const uint32_t nA = before + block_total;
-    c->nA = nA;
-    c->tot_affected += nA;
+    c->nA = total[0];
+    uint32_t seen = 0;
+    for (uint32_t l = 0; l < d.layers; ++l) c->nR[l] = d.R[l] != d.A ? total[++seen] : total[0];
+    c->tot_affected += total[0];
     c->tot_direct += c->nD;
     c->tot_scanned += c->scanned;
   }

@@ -535,6 +535,7 @@ __global__ __launch_bounds__(256, 2) void layer_kernel(LayerArgs a, const uint32
                         (uint32_t)__builtin_amdgcn_readlane((int)gathered, 32) +
                         (uint32_t)__builtin_amdgcn_readlane((int)gathered, 48);
   if (lane == 0 && gsum) atomicAdd((unsigned long long*)&a.ctrl->tot_gathered, (unsigned long long)gsum);
+  if (blockIdx.x == 0 && threadIdx.x == 0 && n) atomicAdd((unsigned long long*)&a.ctrl->tot_rows, (unsigned long long)n);
 }
 
 // ---- dispatch over (slots, time slots, heads, chunk)

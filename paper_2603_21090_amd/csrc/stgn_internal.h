@@ -41,6 +41,8 @@ struct Ctrl {
   double   t_stream;             // last ingested timestamp
   uint64_t tot_direct, tot_affected, tot_scanned;
   uint64_t tot_gathered;         // ring entries gathered by the attention kernels (all layers)
+  uint64_t tot_rows;             // rows the attention kernels recomputed (all layers)
+  uint32_t nR[STGN_MAX_LAYERS];  // rows layer l recomputes in the current batch
 };
 
 // Row-table descriptor: row v starts at base + v * ld (floats)
@@ -107,6 +109,12 @@ struct Dev {
   uint64_t items_cap;
   uint32_t* blocksum;                // compaction partial sums
   uint32_t* A;                       // [N] affected set, ascending
+  // Layer l only has to recompute the nodes whose inputs changed: flag <= thr[l] (the endpoints plus
+  // the first l hops with a memory, one hop less without one, where layer-0 inputs never change).
+  // R[l] is that ascending sub-list of A (A itself where the threshold covers every flag).
+  uint32_t* R[STGN_MAX_LAYERS];
+  uint32_t thr[STGN_MAX_LAYERS];
+  uint32_t n_lists;                  // separate lists (layers whose threshold does not cover every flag)
   uint32_t* qnodes; float* qout;     // staging for host-side get_embeddings
   uint32_t q_cap;
   // parameters

@@ -111,6 +111,26 @@ def test_small_graphs_all_shapes(binding, kw):
     g.close()
 
 
+@pytest.mark.parametrize("d_mem,d_node", [(16, 0), (0, 12)])
+def test_layers_recompute_only_rows_whose_inputs_changed(binding, d_mem, d_node):
+    """Layer l of a batch recomputes the endpoints plus the first l hops (one hop less without a
+    memory, whose layer-0 rows never change); the skipped rows of A are exactly those a recomputation
+    would leave bit-identical, so every layer cache must still equal the oracle's full recompute."""
+    w = tiny_workload(num_nodes=600, num_edges=2400, batch=30, layers=3, d_mem=d_mem, d_node=d_node, d_edge=6,
+                      d_time=8, d_emb=16, d_msg=16, heads=2, k=3, zipf_s=0.6)
+    nf = synth.node_features(w)
+    g, o, st = run_stream(binding, w, node_feat=nf, full_check_at=set(range(0, 80, 8)))
+    t = g.totals()
+    assert t["affected"] > 0 and t["direct"] > 0
+    initial = w.layers * w.num_nodes                         # the rebuild at creation
+    rows = t["rows"] - initial
+    assert rows < w.layers * t["affected"]                  # some layer skipped part of A
+    if d_mem == 0:
+        assert rows >= t["direct"]                           # layer 1 of a memoryless model: the endpoints only
+        assert rows <= t["direct"] + (w.layers - 1) * t["affected"]
+    g.close()
+
+
 def test_device_inputs_match_host_inputs(binding):
     w = tiny_workload(num_nodes=300, num_edges=3000, batch=100, d_mem=16, d_edge=12, d_time=16, d_emb=16, d_msg=16, k=4)
     g, o, st = run_stream(binding, w, device_inputs=True, full_check_at={0, 7, 15})
