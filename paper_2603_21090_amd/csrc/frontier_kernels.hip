@@ -18,81 +18,125 @@ namespace stgn {
 namespace {
 
 constexpr uint32_t kPlanThreads = 256;
-constexpr uint32_t kPlanNodes = 1024;      // candidate nodes per workgroup (4 flags per thread)
+constexpr uint32_t kPlanWaves = kPlanThreads / 64;
+constexpr uint32_t kRoundFlags = 256;      // flags one wave looks at per round (hop >= 1): 4 per lane
+constexpr uint32_t kRoundList = 64;        // entries of D one wave looks at per round (hop 0)
+constexpr uint32_t kMaxRounds = 16;        // rounds per chunk: a chunk costs one update of the item counter
+constexpr uint32_t kPlanWavesWanted = 2048;
 
-// exclusive scan of one value per thread of a 256-thread workgroup; returns the total
-__device__ inline uint32_t block_scan_256(uint32_t v, uint32_t* s, uint32_t* excl) {
-  const uint32_t t = threadIdx.x;
-  s[t] = v;
-  __syncthreads();
-  for (uint32_t off = 1; off < 256; off <<= 1) {
-    const uint32_t add = t >= off ? s[t - off] : 0u;
-    __syncthreads();
-    s[t] += add;
-    __syncthreads();
+// inclusive scan over the 64 lanes of a wave
+__device__ inline uint32_t wave_incl_scan(uint32_t v) {
+  const uint32_t lane = threadIdx.x & 63u;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const uint32_t o = __shfl_up(v, off);
+    if (lane >= (uint32_t)off) v += o;
   }
-  *excl = s[t] - v;
-  const uint32_t total = s[255];
-  __syncthreads();
-  return total;
+  return v;
 }
 
-// Work items of hop `hop`: from the list D (hop 0) or from the flags that equal hop + 1.
-__global__ __launch_bounds__(kPlanThreads) void plan_kernel(Dev d, uint32_t hop) {
-  __shared__ uint32_t s_scan[256], s_list[kPlanNodes], s_off[256], s_v[256];
-  __shared__ uint32_t s_base;
+// exclusive scan of one value per thread of a 256-thread workgroup (s: at least 4 words of LDS);
+// returns the total.  Lane shuffles inside each wave, one exchange of the four wave totals.
+__device__ inline uint32_t block_scan_256(uint32_t v, uint32_t* s, uint32_t* excl) {
+  const uint32_t lane = threadIdx.x & 63u, w = threadIdx.x >> 6;
+  const uint32_t incl = wave_incl_scan(v);
+  if (lane == 63) s[w] = incl;
+  __syncthreads();
+  const uint32_t t0 = s[0], t1 = s[1], t2 = s[2], t3 = s[3];
+  __syncthreads();
+  const uint32_t before = w == 0 ? 0u : w == 1 ? t0 : w == 2 ? t0 + t1 : t0 + t1 + t2;
+  *excl = before + incl - v;
+  return t0 + t1 + t2 + t3;
+}
+
+// Work items of hop `hop`: from the list D (hop 0) or from the flags that equal hop + 1.  Every wave
+// plans whole chunks on its own -- no workgroup barrier anywhere: a first pass over the chunk counts
+// its items (one counter update per chunk), a second pass writes them, the 64 lanes filling the
+// items of up to 64 frontier nodes together so that a hub's thousands of items do not land on one lane.
+__global__ __launch_bounds__(kPlanThreads) void plan_kernel(Dev d, uint32_t hop, uint32_t rounds) {
+  __shared__ uint32_t s_off[kPlanWaves][64], s_v[kPlanWaves][64];
   Ctrl* c = d.ctrl;
   if (c->skip) return;
-  const uint32_t t = threadIdx.x;
-  // ---- candidates of this workgroup, compacted into s_list
-  uint32_t cand[4], nc = 0;
-  if (hop == 0) {
-    const uint32_t nD = c->nD;
-    for (uint32_t j = 0; j < 4; ++j) {
-      const uint32_t x = blockIdx.x * kPlanNodes + 4 * t + j;
-      if (x < nD) cand[nc++] = d.D[x];
-    }
-  } else {
-    const uint32_t v0 = blockIdx.x * kPlanNodes + 4 * t;
-    if (v0 < d.N) {                                          // the flag array is padded to whole words
-      const uint32_t m = *reinterpret_cast<const uint32_t*>(d.mark + v0);
-      for (uint32_t j = 0; j < 4; ++j)
-        if (((m >> (8 * j)) & 0xFFu) == hop + 1u) cand[nc++] = v0 + j;
-    }
-  }
-  uint32_t excl;
-  const uint32_t ncand = block_scan_256(nc, s_scan, &excl);
-  if (ncand == 0) return;
-  for (uint32_t j = 0; j < nc; ++j) s_list[excl + j] = cand[j];
-  __syncthreads();
-  // ---- rounds of 256 candidates: chunk counts, one counter update per round, cooperative fill
-  unsigned long long scanned = 0;
-  for (uint32_t r0 = 0; r0 < ncand; r0 += 256) {
-    const uint32_t v = r0 + t < ncand ? s_list[r0 + t] : 0u;
-    const uint32_t dg = r0 + t < ncand ? d.deg[v] : 0u;
-    const uint32_t nch = (dg + kLogChunk - 1) / kLogChunk;
-    scanned += dg;
-    uint32_t off;
-    const uint32_t total = block_scan_256(nch, s_scan, &off);
-    s_off[t] = off;
-    s_v[t] = v;
-    if (t == 0) s_base = total ? atomicAdd(&c->n_items[hop], total) : 0u;
-    __syncthreads();
-    const uint32_t base = s_base;
-    for (uint32_t i = t; i < total; i += 256) {
-      uint32_t lo = 0, hi = 255;                             // last thread whose offset is <= i
-      while (lo < hi) {
-        const uint32_t mid = (lo + hi + 1) >> 1;
-        if (s_off[mid] <= i) lo = mid; else hi = mid - 1;
+  const uint32_t lane = threadIdx.x & 63u;
+  const uint32_t wib = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  const uint32_t gw = blockIdx.x * kPlanWaves + wib, nw = gridDim.x * kPlanWaves;
+  const uint32_t span = hop == 0 ? c->nD : d.N;
+  const uint32_t per_round = hop == 0 ? kRoundList : kRoundFlags;
+  const uint32_t chunk = rounds * per_round;
+  const uint32_t want = hop + 1u;
+  uint32_t* my_off = s_off[wib];
+  uint32_t* my_v = s_v[wib];
+  for (uint32_t base0 = gw * chunk; base0 < span; base0 += nw * chunk) {
+    // candidates of round r held by this lane: up to 4 (flags) or 1 (list)
+    auto candidates = [&](uint32_t r, uint32_t (&v)[4]) {
+      uint32_t n = 0;
+      const uint32_t x0 = base0 + r * per_round;
+      if (hop == 0) {
+        if (x0 + lane < span) v[n++] = d.D[x0 + lane];
+      } else {
+        const uint32_t f0 = x0 + 4u * lane;
+        if (f0 < d.N) {                                        // the flag array is padded to whole words
+          const uint32_t m = *reinterpret_cast<const uint32_t*>(d.mark + f0);
+#pragma unroll
+          for (uint32_t j = 0; j < 4; ++j)
+            if (((m >> (8 * j)) & 0xFFu) == want) v[n++] = f0 + j;
+        }
       }
-      d.items[base + i] = ((uint64_t)s_v[lo] << 32) | (i - s_off[lo]);
+      return n;
+    };
+    // ---- pass 1: items and scanned entries of the chunk
+    uint32_t items = 0;
+    unsigned long long scanned = 0;
+    for (uint32_t r = 0; r < rounds; ++r) {
+      uint32_t v[4] = {0u, 0u, 0u, 0u};
+      const uint32_t n = candidates(r, v);
+      uint32_t dg[4];
+#pragma unroll
+      for (uint32_t j = 0; j < 4; ++j) dg[j] = d.deg[v[j]];     // independent loads (dummy node 0 past n)
+#pragma unroll
+      for (uint32_t j = 0; j < 4; ++j)
+        if (j < n) { items += (dg[j] + kLogChunk - 1) / kLogChunk; scanned += dg[j]; }
     }
-    __syncthreads();
+    for (int off = 32; off > 0; off >>= 1) { items += __shfl_xor(items, off); scanned += __shfl_xor(scanned, off); }
+    if (items == 0) continue;                                  // wave-uniform
+    uint32_t out = 0;
+    if (lane == 0) {
+      out = atomicAdd(&c->n_items[hop], items);
+      atomicAdd((unsigned long long*)&c->scanned, scanned);
+    }
+    out = (uint32_t)__builtin_amdgcn_readfirstlane((int)out);
+    // ---- pass 2: write the items, up to 64 frontier nodes per step
+    for (uint32_t r = 0; r < rounds; ++r) {
+      uint32_t v[4] = {0u, 0u, 0u, 0u};
+      const uint32_t n = candidates(r, v);
+      uint32_t dg[4];
+#pragma unroll
+      for (uint32_t j = 0; j < 4; ++j) dg[j] = d.deg[v[j]];
+      const uint32_t nmax = hop == 0 ? 1u : 4u;
+#pragma unroll
+      for (uint32_t j = 0; j < 4; ++j) {
+        if (j >= nmax) break;
+        const bool have = j < n;
+        if (!__any(have)) break;                               // lanes fill v[] from the front
+        const uint32_t node = have ? v[j] : 0u;
+        const uint32_t nch = have ? (dg[j] + kLogChunk - 1) / kLogChunk : 0u;
+        const uint32_t incl = wave_incl_scan(nch);
+        const uint32_t total = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+        if (total == 0) continue;
+        my_off[lane] = incl - nch;
+        my_v[lane] = node;
+        for (uint32_t i = lane; i < total; i += 64) {
+          uint32_t lo = 0, hi = 63;                            // last lane whose offset is <= i
+          while (lo < hi) {
+            const uint32_t mid = (lo + hi + 1) >> 1;
+            if (my_off[mid] <= i) lo = mid; else hi = mid - 1;
+          }
+          d.items[out + i] = ((uint64_t)my_v[lo] << 32) | (i - my_off[lo]);
+        }
+        out += total;
+      }
+    }
   }
-  // statistics: frontier size and entries the expansion of this hop will read
-  for (int off = 32; off > 0; off >>= 1) scanned += __shfl_xor(scanned, off);
-  if ((t & 63) == 0 && scanned) atomicAdd((unsigned long long*)&c->scanned, scanned);
-  if (t == 0 && hop > 0) atomicAdd(&c->n_front[hop], ncand);
 }
 
 __global__ __launch_bounds__(256) void expand_kernel(Dev d, uint32_t hop) {
@@ -173,8 +217,11 @@ __global__ __launch_bounds__(256) void compact_count_kernel(Dev d, uint32_t last
     const uint32_t tot = block_scan_256(cnt, s, &excl);
     if (threadIdx.x == 0) d.blocksum[list * gridDim.x + blockIdx.x] = tot;
   }
-  const uint32_t tot_reached = block_scan_256(bytes_equal(m, last_value), s, &excl);
-  if (threadIdx.x == 0 && tot_reached) atomicAdd(&d.ctrl->n_front[last_value - 1u], tot_reached);   // first reached by the last hop
+  // statistics: nodes first reached by hop h carry the flag h + 2
+  for (uint32_t value = 2; value <= last_value; ++value) {
+    const uint32_t reached = block_scan_256(bytes_equal(m, value), s, &excl);
+    if (threadIdx.x == 0 && reached) atomicAdd(&d.ctrl->n_front[value - 1u], reached);
+  }
 }
 
 __global__ __launch_bounds__(256) void compact_write_kernel(Dev d) {
@@ -217,8 +264,15 @@ __global__ __launch_bounds__(256) void compact_write_kernel(Dev d) {
 
 void launch_plan(const Dev& d, hipStream_t s, uint32_t hop) {
   const uint32_t span = hop == 0 ? 2 * d.max_batch : d.N;
-  const uint32_t blocks = (span + kPlanNodes - 1) / kPlanNodes;
-  hipLaunchKernelGGL(plan_kernel, dim3(blocks), dim3(kPlanThreads), 0, s, d, hop);
+  const uint32_t per_round = hop == 0 ? kRoundList : kRoundFlags;
+  // as many waves as the span allows, up to kPlanWavesWanted; beyond that, more rounds per chunk
+  uint32_t rounds = (span + per_round * kPlanWavesWanted - 1) / (per_round * kPlanWavesWanted);
+  rounds = rounds < 1 ? 1 : rounds > kMaxRounds ? kMaxRounds : rounds;
+  const uint32_t chunk = rounds * per_round;
+  uint32_t blocks = ((span + chunk - 1) / chunk + kPlanWaves - 1) / kPlanWaves;
+  if (blocks > 2048) blocks = 2048;
+  if (blocks < 1) blocks = 1;
+  hipLaunchKernelGGL(plan_kernel, dim3(blocks), dim3(kPlanThreads), 0, s, d, hop, rounds);
 }
 
 void launch_expand(const Dev& d, hipStream_t s, uint32_t hop) {
