@@ -237,6 +237,72 @@ def test_empty_batch_and_ring_overflow_in_one_batch(binding):
     g.close()
 
 
+def test_equal_timestamps_and_repeated_pairs(binding):
+    """Ties: many edges share one timestamp and the same pair repeats inside a batch; arrival order
+    (batch index, source side first) is the only order, multi-edges are separate ring entries."""
+    w = tiny_workload(num_nodes=12, num_edges=96, batch=24, layers=2, k=4, d_mem=8, d_edge=6, d_time=8, d_emb=8,
+                      d_msg=8)
+    W = synth.make_weights(w)
+    g = binding.StreamTGN.from_workload(w, W)
+    o = orc.Oracle.from_workload(w, W)
+    rng = np.random.default_rng(11)
+    allnodes = np.arange(w.num_nodes, dtype=np.uint32)
+    t0 = 0.0
+    for b in range(4):
+        src = rng.integers(0, 4, size=24).astype(np.uint32)               # few nodes: many repeated pairs
+        dst = (src + 1 + rng.integers(0, 3, size=24)).astype(np.uint32) % 12
+        dst = np.where(dst == src, (src + 1) % 12, dst).astype(np.uint32)
+        ts = np.full(24, t0 + 1.0) if b % 2 == 0 else t0 + np.repeat(np.arange(1, 7, dtype=np.float64), 4)
+        t0 = float(ts[-1])
+        ef = rng.standard_normal((24, w.d_edge)).astype(np.float32)
+        rc, D, A = o.ingest(src, dst, ts, ef)
+        assert rc == 0
+        g.ingest_batch(src, dst, ts, ef)
+        assert np.array_equal(g.get_affected(), A)
+        check_neighbours(g, o, allnodes)
+        ref = o.embed_all()
+        for l in (1, 2):
+            check_rows(g.get_embeddings(allnodes, layer=l), ref[l - 1], f"batch {b} layer {l}")
+    g.close()
+
+
+def test_largest_batch_and_four_layers(binding):
+    """One batch of STGN_MAX_BATCH edges (the sort runs at its largest size) on a graph deep enough
+    for four layers; affected set exact, sampled embeddings against the oracle's recursion."""
+    w = tiny_workload(num_nodes=5000, num_edges=2 * 8192, batch=8192, layers=4, k=5, d_mem=16, d_edge=8, d_time=8,
+                      d_emb=16, d_msg=16, heads=2, zipf_s=0.9)
+    st = synth.EdgeStream(w)
+    W = synth.make_weights(w)
+    g = binding.StreamTGN.from_workload(w, W)
+    o = orc.Oracle.from_workload(w, W)
+    rng = np.random.default_rng(5)
+    for b in range(2):
+        s, d, t, ef = st.batch(b)
+        assert len(s) == 8192
+        rc, D, A = o.ingest(s, d, t, ef)
+        assert rc == 0
+        stats = g.ingest_batch(s, d, t, ef, stats=True)
+        assert stats["n_direct"] == len(D)
+        assert np.array_equal(g.get_affected(), A)
+        S = np.unique(np.concatenate([rng.choice(A, size=150), rng.integers(0, w.num_nodes, size=50)])).astype(np.uint32)
+        check_neighbours(g, o, S)
+        check_rows(g.get_embeddings(S), o.embed_nodes(S), f"batch {b}: sampled embeddings")
+    g.close()
+
+
+def test_edge_capacity_is_enforced(binding):
+    w = tiny_workload(num_nodes=50, num_edges=200, batch=40, d_mem=8, d_edge=6, d_time=8, d_emb=8, d_msg=8)
+    st = synth.EdgeStream(w)
+    g = binding.StreamTGN.from_workload(w, synth.make_weights(w), max_edges=100)
+    allnodes = np.arange(w.num_nodes, dtype=np.uint32)
+    assert g.ingest_batch(*st.batch(0), check=False) == 0
+    assert g.ingest_batch(*st.batch(1), check=False) == 0
+    ref = g.get_embeddings(allnodes)
+    assert g.ingest_batch(*st.batch(2), check=False) == -6          # 120 > 100: refused, nothing changes
+    assert np.array_equal(g.get_embeddings(allnodes), ref)
+    g.close()
+
+
 def test_c2_stream_sampled(binding):
     """Config 2 (the benchmark workload), first 300 batches with device-resident inputs as the
     benchmark feeds them: exact affected set every batch; memory and sampled embeddings at
