@@ -2,10 +2,14 @@
 
     python -m paper_2603_21090_amd.profile_summary trace  <dir> <bench.json>
     python -m paper_2603_21090_amd.profile_summary traffic <fetch dir> <write dir> <bench.json>
+    python -m paper_2603_21090_amd.profile_summary counters <pmc dir> <kernel name part> <last n dispatches>
 
 `trace` reads `*_kernel_stats.csv` and `*_kernel_trace.csv` of a `--kernel-trace --stats` run and
 prints the per-kernel table plus, for the layer kernel, the average duration over the launches of
 the batch range in which bench.py took its own event timings (`roofline.batches`).
+
+`counters` prints, for the last n dispatches of the kernels whose name contains the given text, the
+average of every counter in a `--pmc` run's `*_counter_collection.csv` and the average duration.
 
 `traffic` reads the `*_counter_collection.csv` of one `--pmc FETCH_SIZE` and one `--pmc WRITE_SIZE`
 run (both of `bench.py --calibrate-copy`), scales each counter by what it reads for the 1 GiB
@@ -95,9 +99,28 @@ def traffic(fetch_dir, write_dir, bench_json):
     print(f"traffic_bytes_per_launch = {total:.0f}")
 
 
+def counters(dirname, name_part, last_n):
+    rows = [r for r in csv.DictReader(open(_one(dirname, "*counter_collection.csv"))) if name_part in r["Kernel_Name"]]
+    ids = sorted({int(r["Dispatch_Id"]) for r in rows})[-int(last_n):]
+    keep = set(ids)
+    agg, dur = collections.defaultdict(float), {}
+    for r in rows:
+        d = int(r["Dispatch_Id"])
+        if d in keep:
+            agg[r["Counter_Name"]] += float(r["Counter_Value"])
+            dur[d] = int(r["End_Timestamp"]) - int(r["Start_Timestamp"])
+    print(f"kernel: {_short(rows[0]['Kernel_Name']) if rows else name_part}; last {len(ids)} dispatches; "
+          f"average duration {sum(dur.values()) / max(len(dur), 1) / 1e3:.1f} us (kernels run one at a time under --pmc)")
+    for k in sorted(agg):
+        print(f"  {k:<34}{agg[k] / len(ids):>18.1f}  per dispatch")
+    return {k: v / len(ids) for k, v in agg.items()}, sum(dur.values()) / max(len(dur), 1) / 1e3
+
+
 if __name__ == "__main__":
     if len(sys.argv) >= 4 and sys.argv[1] == "trace":
         trace(sys.argv[2], sys.argv[3])
+    elif len(sys.argv) >= 5 and sys.argv[1] == "counters":
+        counters(sys.argv[2], sys.argv[3], sys.argv[4])
     elif len(sys.argv) >= 5 and sys.argv[1] == "traffic":
         traffic(sys.argv[2], sys.argv[3], sys.argv[4])
     else:
