@@ -88,7 +88,12 @@ typedef struct {
   uint32_t n_direct;                       /* |V_direct|: distinct endpoints of the batch     */
   uint32_t n_affected;                     /* |V_aff| (Eq. affected_set)                      */
   uint32_t frontier[STGN_MAX_LAYERS + 1];  /* nodes first reached at hop h (frontier[0]=|D|)   */
-  uint64_t entries_scanned;                /* adjacency entries read by the propagation       */
+  uint64_t entries_scanned;                /* adjacency entries (push hops) and ring slots    */
+                                           /* (pull hops) read by the propagation             */
+  uint32_t pull_hops;                      /* bit h set: hop h pulled through the rings of the
+                                              clean nodes instead of pushing along the logs of
+                                              the frontier (chosen on the device, same flags) */
+  uint32_t reserved;
   float    us_stage[6];                    /* sort | memory update | apply | propagate+compact
                                               | embed | total; microseconds from HIP events    */
 } stgn_batch_stats;

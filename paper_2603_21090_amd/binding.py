@@ -39,11 +39,11 @@ class Weights(C.Structure):
 class BatchStats(C.Structure):
     _fields_ = [("n_edges", C.c_uint32), ("n_direct", C.c_uint32), ("n_affected", C.c_uint32),
                 ("frontier", C.c_uint32 * (STGN_MAX_LAYERS + 1)), ("entries_scanned", C.c_uint64),
-                ("us_stage", C.c_float * 6)]
+                ("pull_hops", C.c_uint32), ("reserved", C.c_uint32), ("us_stage", C.c_float * 6)]
 
     def as_dict(self):
         return dict(n_edges=self.n_edges, n_direct=self.n_direct, n_affected=self.n_affected,
-                    frontier=list(self.frontier), entries_scanned=self.entries_scanned,
+                    frontier=list(self.frontier), entries_scanned=self.entries_scanned, pull_hops=self.pull_hops,
                     us_stage=dict(zip(("sort", "memory", "apply", "propagate", "embed", "total"), self.us_stage)))
 
 

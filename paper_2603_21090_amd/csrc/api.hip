@@ -133,6 +133,7 @@ size_t layout(const stgn_config& c, char* base, Dev* d) {
   d->t_last = b.take<double>(N);
   d->deg = b.take<uint32_t>(N);
   d->ring = b.take<RingEntry>((size_t)N * c.k);
+  d->ring_nbr = b.take<uint32_t>((size_t)N * c.k);
   d->pool_nt = b.take<uint2>(d->pool_cap_units * kMinBlock);
   d->pool_eid = b.take<uint32_t>(d->pool_cap_units * kMinBlock);
   d->blk = b.take<uint32_t>((size_t)N * maxb);
@@ -546,6 +547,9 @@ int stgn_ingest_batch(stgn_ctx* ctx, uint32_t n, const uint32_t* src, const uint
     stats->n_affected = h.nA;
     for (int i = 0; i <= STGN_MAX_LAYERS; ++i) stats->frontier[i] = h.n_front[i];
     stats->entries_scanned = h.scanned;
+    stats->pull_hops = 0;
+    stats->reserved = 0;
+    for (uint32_t i = 0; i < ctx->cfg.layers; ++i) stats->pull_hops |= (h.pulled[i] ? 1u : 0u) << i;
     for (int i = 0; i < 5; ++i) {
       float ms = 0.0f;
       hipEventElapsedTime(&ms, ev[i], ev[i + 1]);

@@ -11,6 +11,14 @@
 // atomic operation at all.  The frontier of the next hop is simply "all nodes whose flag equals
 // h + 2", found by a scan of the flag array that also cuts the nodes' logs into work items of
 // kLogChunk entries (one wavefront each), so that a hub's log is spread over the whole chip.
+//
+// Direction.  Pushing costs one coalesced 8-byte read per entry of the frontier's logs plus a random
+// 4-byte degree lookup each (a 64-byte sector from L2 or HBM).  When the frontier owns more log
+// entries than half the node count -- every batch that touches a hub -- it is cheaper to PULL: every
+// clean node with at least one edge walks the neighbour ids of its own ring (k sequential 4-byte
+// reads) and asks whether any of them carries the frontier's flag (byte reads that hit L2).  Both
+// give the same flags: u is in w's ring exactly when w's ring holds u.  The choice is made on the
+// device from a running count of the frontier's log entries, identically by every workgroup.
 #include "stgn_internal.h"
 
 namespace stgn {
@@ -53,10 +61,12 @@ __device__ inline uint32_t block_scan_256(uint32_t v, uint32_t* s, uint32_t* exc
 // plans whole chunks on its own -- no workgroup barrier anywhere: a first pass over the chunk counts
 // its items (one counter update per chunk), a second pass writes them, the 64 lanes filling the
 // items of up to 64 frontier nodes together so that a hub's thousands of items do not land on one lane.
+__device__ inline bool pull_hop(const Dev& d, const Ctrl* c, uint32_t hop) { return c->front_deg[hop] >= (uint64_t)(d.N / 2u); }
+
 __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Dev d, uint32_t hop, uint32_t rounds) {
   __shared__ uint32_t s_off[kPlanWaves][64], s_v[kPlanWaves][64];
   Ctrl* c = d.ctrl;
-  if (c->skip) return;
+  if (c->skip || pull_hop(d, c, hop)) return;               // a pull hop needs no work items
   const uint32_t lane = threadIdx.x & 63u;
   const uint32_t wib = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
   const uint32_t gw = blockIdx.x * kPlanWaves + wib, nw = gridDim.x * kPlanWaves;
@@ -140,30 +150,71 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Dev d, uint32_t hop,
 }
 
 __global__ __launch_bounds__(256) void expand_kernel(Dev d, uint32_t hop) {
-  const Ctrl* c = d.ctrl;
+  __shared__ unsigned long long s_deg[4], s_scan[4];
+  Ctrl* c = d.ctrl;
   if (c->skip) return;
-  const uint32_t n_items = c->n_items[hop];
   const uint32_t lane = threadIdx.x & 63;
   const uint8_t value = (uint8_t)(hop + 2u);
-  // wave index, made provably uniform so that everything derived from it stays in scalar registers
-  const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)((blockIdx.x * blockDim.x + threadIdx.x) >> 6));
-  const uint32_t nwaves = (gridDim.x * blockDim.x) >> 6;
-  for (uint32_t it = wave; it < n_items; it += nwaves) {
-    const uint64_t item = d.items[it];
-    const uint32_t u = (uint32_t)(item >> 32), ch = (uint32_t)item;
-    const uint32_t dg = d.deg[u];
-    const uint32_t lo = ch * kLogChunk, hi = min(dg, lo + kLogChunk);
-    const uint32_t* blk = d.blk + (size_t)u * d.maxb;
-    for (uint32_t p0 = lo; p0 < hi; p0 += 64) {
-      const uint32_t p = p0 + lane;
-      if (p < hi) {
-        const uint32_t b = 31u - (uint32_t)__clz((int)((p >> 3) + 1u));
-        const uint32_t off = p - kMinBlock * ((1u << b) - 1u);
-        const uint2 e = d.pool_nt[(uint64_t)blk[b] * kMinBlock + off];
-        const uint32_t w = e.x;
-        if ((uint64_t)e.y + d.k >= d.deg[w] && d.mark[w] == 0) d.mark[w] = value;
+  unsigned long long newdeg = 0;                 // log entries owned by the nodes this thread flags
+  unsigned long long looked = 0;                 // ring slots a pull hop examined
+  if (pull_hop(d, c, hop)) {
+    // ---- pull: one clean node per lane
+    const uint8_t want = (uint8_t)(hop + 1u);
+    const uint32_t k = d.k;
+    for (uint32_t w = blockIdx.x * blockDim.x + threadIdx.x; w < d.N; w += gridDim.x * blockDim.x) {
+      if (d.mark[w] != 0) continue;
+      const uint32_t dg = d.deg[w];
+      if (dg == 0) continue;
+      const uint32_t cnt = dg < k ? dg : k;      // a ring that is not full yet fills slots 0 .. deg - 1
+      const uint32_t* nb = d.ring_nbr + (size_t)w * k;
+      bool hit = false;
+      for (uint32_t j0 = 0; j0 < cnt && !hit; j0 += 4) {
+        uint32_t u[4];
+#pragma unroll
+        for (uint32_t j = 0; j < 4; ++j) u[j] = nb[j0 + j < cnt ? j0 + j : j0];
+        uint8_t f[4];
+#pragma unroll
+        for (uint32_t j = 0; j < 4; ++j) f[j] = d.mark[u[j]];
+        hit = f[0] == want || f[1] == want || f[2] == want || f[3] == want;
+        looked += cnt - j0 < 4u ? cnt - j0 : 4u;
+      }
+      if (hit) { d.mark[w] = value; newdeg += dg; }
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) c->pulled[hop] = 1;
+  } else {
+    // ---- push: one wavefront per work item of the frontier's logs
+    const uint32_t n_items = c->n_items[hop];
+    // wave index, made provably uniform so that everything derived from it stays in scalar registers
+    const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)((blockIdx.x * blockDim.x + threadIdx.x) >> 6));
+    const uint32_t nwaves = (gridDim.x * blockDim.x) >> 6;
+    for (uint32_t it = wave; it < n_items; it += nwaves) {
+      const uint64_t item = d.items[it];
+      const uint32_t u = (uint32_t)(item >> 32), ch = (uint32_t)item;
+      const uint32_t dg = d.deg[u];
+      const uint32_t lo = ch * kLogChunk, hi = min(dg, lo + kLogChunk);
+      const uint32_t* blk = d.blk + (size_t)u * d.maxb;
+      for (uint32_t p0 = lo; p0 < hi; p0 += 64) {
+        const uint32_t p = p0 + lane;
+        if (p < hi) {
+          const uint32_t b = 31u - (uint32_t)__clz((int)((p >> 3) + 1u));
+          const uint32_t off = p - kMinBlock * ((1u << b) - 1u);
+          const uint2 e = d.pool_nt[(uint64_t)blk[b] * kMinBlock + off];
+          const uint32_t w = e.x;
+          const uint32_t dw = d.deg[w];
+          if ((uint64_t)e.y + d.k >= dw && d.mark[w] == 0) { d.mark[w] = value; newdeg += dw; }   // may count a node twice
+        }
       }
     }
+  }
+  // the next hop's frontier owns this many log entries: one counter update per workgroup
+  for (int off = 32; off > 0; off >>= 1) { newdeg += __shfl_xor(newdeg, off); looked += __shfl_xor(looked, off); }
+  if (lane == 0) { s_deg[threadIdx.x >> 6] = newdeg; s_scan[threadIdx.x >> 6] = looked; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const unsigned long long tot = s_deg[0] + s_deg[1] + s_deg[2] + s_deg[3];
+    if (tot) atomicAdd((unsigned long long*)&c->front_deg[hop + 1], tot);
+    const unsigned long long sc = s_scan[0] + s_scan[1] + s_scan[2] + s_scan[3];
+    if (sc) atomicAdd((unsigned long long*)&c->scanned, sc);
   }
 }
 

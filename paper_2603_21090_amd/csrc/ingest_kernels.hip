@@ -72,7 +72,7 @@ __global__ __launch_bounds__(kSortThreads) void stage_sort_kernel(Dev d, uint32_
       c->batch_seq += 1;
       c->n_edges = 0; c->nD = 0; c->scanned = 0;
       for (int h = 0; h < STGN_MAX_LAYERS + 2; ++h) c->n_front[h] = 0;
-      for (int h = 0; h < STGN_MAX_LAYERS + 1; ++h) c->n_items[h] = 0;
+      for (int h = 0; h < STGN_MAX_LAYERS + 1; ++h) { c->n_items[h] = 0; c->front_deg[h] = 0; c->pulled[h] = 0; }
     }
     return;
   }
@@ -143,11 +143,13 @@ __global__ __launch_bounds__(kSortThreads) void stage_sort_kernel(Dev d, uint32_
   const uint32_t eptd = (2 * d.max_batch + kSortThreads - 1) / kSortThreads;
   const uint32_t dlo = t * eptd, dhi = min(dlo + eptd, nD);
   uint32_t units = 0;
+  unsigned long long fdeg = 0;              // adjacency entries the endpoints own after this batch
   for (uint32_t x = dlo; x < dhi; ++x) {
     const uint32_t node = d.D[x];
     const uint32_t s0 = d.seg_start[x], s1 = d.seg_start[x + 1];
     const uint32_t dp = d.deg[node], dn = dp + (s1 - s0);
     d.deg_new[x] = dn;
+    fdeg += dn;
     d.last_slot[x] = (uint32_t)keys[s1 - 1];
     const uint32_t b0 = blocks_for(dp), b1 = blocks_for(dn);
     units += (1u << b1) - (1u << b0);
@@ -164,6 +166,10 @@ __global__ __launch_bounds__(kSortThreads) void stage_sort_kernel(Dev d, uint32_
       }
     }
   }
+  if (t == 0) { for (int h = 0; h < STGN_MAX_LAYERS + 1; ++h) { c->front_deg[h] = 0; c->pulled[h] = 0; } }
+  __syncthreads();
+  for (int off = 32; off > 0; off >>= 1) fdeg += __shfl_xor(fdeg, off);
+  if ((t & 63) == 0 && fdeg) atomicAdd((unsigned long long*)&c->front_deg[0], fdeg);
   __syncthreads();
   if (t == 0) {
     c->skip = 0;
@@ -210,6 +216,7 @@ __global__ __launch_bounds__(256) void apply_kernel(Dev d, const uint32_t* __res
     if ((uint64_t)pos + d.k >= d.deg_new[d.slot_d[s]]) {
       RingEntry r; r.nbr = other; r.eid = eid; r.t = ts[i];
       d.ring[(size_t)node * d.k + pos % d.k] = r;
+      d.ring_nbr[(size_t)node * d.k + pos % d.k] = other;
     }
   }
   // per distinct endpoint: degree, last interaction time, dirty seed
@@ -251,7 +258,7 @@ __global__ void init_state_kernel(Dev d) {
   const size_t nw = mark_bytes(d.N) / 4;
   for (size_t x = tid; x < nw; x += nth) reinterpret_cast<uint32_t*>(d.mark)[x] = 0;
   const size_t nr = (size_t)d.N * d.k;
-  for (size_t x = tid; x < nr; x += nth) { RingEntry r; r.nbr = 0; r.eid = 0; r.t = 0.0; d.ring[x] = r; }
+  for (size_t x = tid; x < nr; x += nth) { RingEntry r; r.nbr = 0; r.eid = 0; r.t = 0.0; d.ring[x] = r; d.ring_nbr[x] = 0; }
   if (tid == 0) {
     Ctrl z = {};
     *d.ctrl = z;

@@ -43,6 +43,11 @@ struct Ctrl {
   uint64_t tot_gathered;         // ring entries gathered by the attention kernels (all layers)
   uint64_t tot_rows;             // rows the attention kernels recomputed (all layers)
   uint32_t nR[STGN_MAX_LAYERS];  // rows layer l recomputes in the current batch
+  // adjacency entries the frontier of hop h owns (exact for hop 0 and after a pull hop, an upper
+  // estimate after a push hop): decides between pushing along the frontier's logs and pulling
+  // through the rings of the clean nodes
+  uint64_t front_deg[STGN_MAX_LAYERS + 1];
+  uint32_t pulled[STGN_MAX_LAYERS + 1];   // 1: hop h ran in pull mode (statistics)
 };
 
 // Row-table descriptor: row v starts at base + v * ld (floats)
@@ -88,6 +93,7 @@ struct Dev {
   Table    H[STGN_MAX_LAYERS + 1];   // H[0] = [memory | node features]; H[l] = layer-l cache
   double*  t_last;                   // [N]
   uint32_t* deg;                     // [N] adjacency entries per node
+  uint32_t* ring_nbr;                // [N x k] neighbour ids of the ring slots alone (4 B per slot, for the pull hop)
   RingEntry* ring;                   // [N x k]
   uint2*   pool_nt;                  // adjacency pool: (neighbour, position of the twin entry)
   uint32_t* pool_eid;                // adjacency pool: edge id

@@ -131,6 +131,31 @@ def test_layers_recompute_only_rows_whose_inputs_changed(binding, d_mem, d_node)
     g.close()
 
 
+def test_push_and_pull_hops_give_the_same_affected_set(binding):
+    """The expansion pushes along the frontier's logs while the frontier owns few adjacency entries
+    and pulls through the clean nodes' rings once it owns more than half the node count; the flags
+    must come out the same.  A large sparse graph with small batches starts in push mode and turns
+    to pull mode as degrees grow; the affected set is compared with the oracle on every batch."""
+    w = tiny_workload(num_nodes=3000, num_edges=6000, batch=25, layers=2, k=3, d_mem=8, d_edge=4, d_time=8, d_emb=8,
+                      d_msg=8, zipf_s=1.1)
+    st = synth.EdgeStream(w)
+    W = synth.make_weights(w)
+    o = orc.Oracle.from_workload(w, W)
+    g = binding.StreamTGN.from_workload(w, W)
+    seen = set()
+    for b in range(w.num_batches):
+        s, d, t, ef = st.batch(b)
+        rc, D, A = o.ingest(s, d, t, ef)
+        stats = g.ingest_batch(s, d, t, ef, stats=True)
+        assert np.array_equal(g.get_affected(), A), f"batch {b} (pull hops {stats['pull_hops']:b})"
+        seen.add(stats["pull_hops"] & 1)
+        seen.add(2 + ((stats["pull_hops"] >> 1) & 1))
+    assert {0, 1} <= seen, "hop 0 never ran in both directions"
+    allnodes = np.arange(w.num_nodes, dtype=np.uint32)
+    check_rows(g.get_embeddings(allnodes), o.embed_all()[-1], "final embeddings")
+    g.close()
+
+
 def test_device_inputs_match_host_inputs(binding):
     w = tiny_workload(num_nodes=300, num_edges=3000, batch=100, d_mem=16, d_edge=12, d_time=16, d_emb=16, d_msg=16, k=4)
     g, o, st = run_stream(binding, w, device_inputs=True, full_check_at={0, 7, 15})
