@@ -117,6 +117,7 @@ size_t layout(const stgn_config& c, char* base, Dev* d) {
   d->d_mem = c.d_mem; d->d_node = c.d_node; d->d0 = c.d_mem + c.d_node; d->d_edge = c.d_edge;
   d->d_time = c.d_time; d->d_emb = c.d_emb; d->d_msg = c.d_msg; d->dk = c.d_emb / c.heads;
   d->max_batch = c.max_batch; d->max_edges = c.max_edges;
+  d->num_cu = 0;
   // adjacency blocks of 8, 16, 32, ... entries: capacity after b blocks is 8 (2^b - 1)
   uint32_t maxb = 1;
   while (8ull * ((1ull << maxb) - 1) < 2 * c.max_edges) ++maxb;
@@ -431,6 +432,12 @@ int stgn_create(const stgn_config* cfg, const stgn_weights* w, const float* node
   }
   for (auto& e : ctx->stage_ev)
     if (hipEventCreate(&e) != hipSuccess) { ctx->err = "event creation failed"; return bail(STGN_E_DEVICE); }
+  {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
+      ctx->d.num_cu = (uint32_t)cus;
+  }
   if (setup_ingest_attributes(ctx->d) || setup_embed_attributes(ctx->d) || setup_memory_attributes(ctx->d)) {
     ctx->err = "a kernel needs more LDS than one gfx950 workgroup has for these dimensions";
     return bail(STGN_E_INVALID_ARG);

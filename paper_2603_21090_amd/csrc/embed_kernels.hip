@@ -39,6 +39,7 @@ LaunchArgs make_args(const Dev& d, uint32_t layer) {
     k.kind[s] = s < L.ns ? L.kind[s] : 3;
   }
   a.nt = L.nt;
+  a.grid_cap = 2u * (d.num_cu ? d.num_cu : 256u);
   a.lds = (size_t)layer_impl::layer_lds(L.d_in, d.d_emb, d.heads, L.Zp, d.k).total * sizeof(float);
   a.err = hipSuccess;
   return a;

@@ -99,7 +99,7 @@ template <int NS, int NT, int H, int JC>
 __global__ __launch_bounds__(256, 2) void layer_kernel(LayerArgs a, const uint32_t* __restrict__ rows,
                                                        const uint32_t* count_ptr, uint32_t count_max) {
   extern __shared__ __align__(16) float lds[];
-  __shared__ uint32_t s_node[kTM], s_cnt[kTM];
+  __shared__ uint32_t s_node[kTM], s_cnt[kTM], s_next[kTM];
   __shared__ double s_tq[kTM];
   __shared__ uint32_t s_zt[4 * kMaxSlots];     // 16-column tiles of a qt row that hold valid columns
   __shared__ __align__(16) double s_om[2 * kSlot], s_ph[2 * kSlot];
@@ -186,39 +186,103 @@ __global__ __launch_bounds__(256, 2) void layer_kernel(LayerArgs a, const uint32
   // ---- phases 1 and 5: column tiles nt and nt + 4 of the d_emb outputs form a unit
   __syncthreads();
 
+  // ---- staging of a tile, one tile ahead.  Stage A reads the tile's row ids into s_next; stage B
+  // (issued while the previous tile's last products run) fetches, into registers, this thread's
+  // share of the rows' ring slots, degrees, query times and own input rows; the tile's phase 0 then
+  // only moves registers into LDS.  A workgroup strides over many tiles, so all but its first tile
+  // start without waiting for memory.  Shapes whose share does not fit two items per thread stage
+  // inside phase 0 instead.
+  const uint32_t qpr = round_up(a.d_in, kGrpK) >> 2;          // 16-byte quads per staged input row
+  const bool pf_ok = kTM * k <= 512u && kTM * qpr <= 512u;
+  RingEntry p_ring[2];
+  uint32_t p_deg[2];
+  double p_tl[2];
+  float4 p_x[2];
+  auto stage_a = [&](uint32_t t) {
+    if (threadIdx.x < kTM) {
+      const uint32_t r = t * kTM + threadIdx.x;
+      s_next[threadIdx.x] = (t < ntiles && r < n) ? (rows ? rows[r] : r) : 0xFFFFFFFFu;
+    }
+  };
+  auto stage_b = [&]() {
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+      const uint32_t x = threadIdx.x + 256u * e;
+      {
+        const uint32_t xc = x < kTM * k ? x : 0u;
+        const uint32_t r = xc / k, sl = xc - r * k;
+        const uint32_t node = s_next[r];
+        const uint32_t nn = node != 0xFFFFFFFFu ? node : 0u;
+        p_ring[e] = a.ring[(size_t)nn * k + sl];
+        p_deg[e] = a.deg[nn];
+        p_tl[e] = a.t_last[nn];
+      }
+      {
+        const uint32_t xc = x < kTM * qpr ? x : 0u;
+        const uint32_t r = xc / qpr, q = xc - r * qpr;
+        const uint32_t node = s_next[r];
+        // columns past d_in are row padding of the table (zero)
+        p_x[e] = *reinterpret_cast<const float4*>(a.Hin + (size_t)(node != 0xFFFFFFFFu ? node : 0u) * a.ld_in + 4u * q);
+      }
+    }
+  };
+  // the record of adjacency position p sits in ring slot p mod k; with the row's degree known, slot
+  // sl holds the j-th most recent entry, j = (newest - sl) mod k; places past the row's entry count
+  // name node 0 / edge 0 (finite rows that later meet a zero weight)
+  auto place_ring = [&](uint32_t r, uint32_t sl, bool live, RingEntry e, uint32_t dg_in, double tl) {
+    const uint32_t dg = live ? dg_in : 0u;
+    const uint32_t cnt = dg < k ? dg : k;
+    const uint32_t newest = dg ? (dg - 1u) % k : 0u;
+    const uint32_t j = newest >= sl ? newest - sl : newest + k - sl;
+    if (j >= cnt) { e.nbr = 0u; e.eid = 0u; e.t = 0.0; }
+    Rs[r * k + j] = e;
+    if (sl == 0) { s_cnt[r] = cnt; s_tq[r] = tl; }
+  };
+  stage_a(blockIdx.x);
+  __syncthreads();
+  auto stage_none = [&]() {                                   // keeps the registers defined on every path
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+      p_ring[e].nbr = 0u; p_ring[e].eid = 0u; p_ring[e].t = 0.0; p_deg[e] = 0u; p_tl[e] = 0.0;
+      p_x[e] = make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+  };
+  if (pf_ok) stage_b(); else stage_none();
+
   for (uint32_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
-    const uint32_t r0 = tile * kTM;
     // ================================================================ phase 0: stage the tile
     Ops16<2> oq;                                              // first weight chunk of this wave's first unit
     const uint32_t w1 = wave < ntd ? wave : 0u;              // loads are unconditional (clamped), products are not
     load_b16(a.WQ + (size_t)w1 * g_in * kGrpFloats, 0, oq.b[0]);
     load_b16(a.WQ + (size_t)(w1 + 4 < ntd ? w1 + 4 : w1) * g_in * kGrpFloats, 0, oq.b[1]);
-    if (threadIdx.x < kTM) {
-      const uint32_t r = r0 + threadIdx.x;
-      s_node[threadIdx.x] = r < n ? (rows ? rows[r] : r) : 0xFFFFFFFFu;
+    if (threadIdx.x < kTM) s_node[threadIdx.x] = s_next[threadIdx.x];
+    if (pf_ok) {
+      // everything was fetched a tile ago: registers -> LDS
+#pragma unroll
+      for (int e = 0; e < 2; ++e) {
+        const uint32_t x = threadIdx.x + 256u * e;
+        if (x < kTM * k) {
+          const uint32_t r = x / k, sl = x - r * k;
+          place_ring(r, sl, s_next[r] != 0xFFFFFFFFu, p_ring[e], p_deg[e], p_tl[e]);
+        }
+        if (x < kTM * qpr) {
+          const uint32_t r = x / qpr, q = x - r * qpr;
+          const float4 v = s_next[r] != 0xFFFFFFFFu ? p_x[e] : make_float4(0.f, 0.f, 0.f, 0.f);
+          *reinterpret_cast<float4*>(Xs + r * ll.ldx + 4u * q) = v;
+        }
+      }
     }
     __syncthreads();
-    // the rows' ring records, most recent first; places past the row's entry count name node 0 / edge 0
-    // (finite rows that later meet a zero weight).  Thread (row, slot) fetches its slot without
-    // waiting for the row's degree (both loads leave together) and the degree then tells which place
-    // j the slot's record takes: the record of adjacency position p sits in slot p mod k.
-    for (uint32_t x = threadIdx.x; x < kTM * k; x += 256) {
-      const uint32_t r = x / k, sl = x - r * k;
-      const uint32_t node = s_node[r];
-      const bool live = node != 0xFFFFFFFFu;
-      const uint32_t nn = live ? node : 0u;
-      RingEntry e = a.ring[(size_t)nn * k + sl];
-      const uint32_t dg = live ? a.deg[nn] : 0u;
-      const double tl = a.t_last[nn];
-      const uint32_t cnt = dg < k ? dg : k;
-      const uint32_t newest = dg ? (dg - 1u) % k : 0u;
-      const uint32_t j = newest >= sl ? newest - sl : newest + k - sl;
-      if (j >= cnt) { e.nbr = 0u; e.eid = 0u; e.t = 0.0; }
-      Rs[r * k + j] = e;
-      if (sl == 0) { s_cnt[r] = cnt; s_tq[r] = tl; }
-    }
-    {
-      const uint32_t qpr = round_up(a.d_in, kGrpK) >> 2, total = kTM * qpr;   // 16-byte quads per row / per tile
+    if (!pf_ok) {
+      // thread (row, slot) fetches its slot without waiting for the row's degree (both loads leave together)
+      for (uint32_t x = threadIdx.x; x < kTM * k; x += 256) {
+        const uint32_t r = x / k, sl = x - r * k;
+        const uint32_t node = s_node[r];
+        const bool live = node != 0xFFFFFFFFu;
+        const uint32_t nn = live ? node : 0u;
+        place_ring(r, sl, live, a.ring[(size_t)nn * k + sl], a.deg[nn], a.t_last[nn]);
+      }
+      const uint32_t total = kTM * qpr;
       for (uint32_t x0 = threadIdx.x; x0 < total; x0 += 512u) {
         float4 v[2];
         uint32_t rr[2], cc[2];
@@ -240,8 +304,9 @@ __global__ __launch_bounds__(256, 2) void layer_kernel(LayerArgs a, const uint32
         for (int e = 0; e < 2; ++e)
           if (ok[e]) *reinterpret_cast<float4*>(Xs + rr[e] * ll.ldx + cc[e]) = v[e];
       }
+      __syncthreads();
     }
-    __syncthreads();
+    stage_a(tile + gridDim.x);                               // row ids of this workgroup's next tile
     // ---- this lane group's row: entry count, query time, ring records; the first chunk of neighbour
     // rows is requested now and arrives while the projections below run
     const uint32_t local = wave * 4u + grp;
@@ -468,6 +533,7 @@ __global__ __launch_bounds__(256, 2) void layer_kernel(LayerArgs a, const uint32
       load_b16(wv(h4, n0), 0, ov[0].b[0]);
       load_b16(wv(h4, n1), 0, ov[0].b[1]);
       __syncthreads();
+      if (pf_ok) stage_b(); else stage_none();                // next tile's rows, in flight during phases 4 and 5
       for (; x < nunits4; x += 4) {
         if (x != wave) {
           decode4(x);
@@ -543,6 +609,7 @@ struct LaunchArgs {
   LayerArgs k;
   hipStream_t s; const uint32_t* rows; const uint32_t* cp; uint32_t cm;
   uint32_t nt;                      // time slots of this layer
+  uint32_t grid_cap;                // workgroups that are resident at once (two per CU)
   bool set_attr; size_t lds; hipError_t err;
 };
 
@@ -554,7 +621,7 @@ void go(LaunchArgs& a) {
     return;
   }
   uint64_t blocks = ((uint64_t)a.cm + kTM - 1) / kTM;
-  if (blocks > 4096) blocks = 4096;          // persistent: each workgroup strides over the tiles
+  if (blocks > a.grid_cap) blocks = a.grid_cap;   // persistent: each workgroup strides over the tiles, staging one tile ahead
   if (blocks < 1) blocks = 1;
   hipLaunchKernelGGL(kern, dim3((uint32_t)blocks), dim3(256), a.lds, a.s, a.k, a.rows, a.cp, a.cm);
 }
