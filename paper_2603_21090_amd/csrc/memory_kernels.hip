@@ -42,6 +42,7 @@ __host__ __device__ inline MemLds memory_lds_layout(uint32_t Kmsg, uint32_t d_ms
   return l;
 }
 
+template <bool UP>
 __global__ __launch_bounds__(kThreads) void memory_update_kernel(Dev d, const uint32_t* __restrict__ src,
                                                                  const uint32_t* __restrict__ dst,
                                                                  const double* __restrict__ ts,
@@ -72,6 +73,11 @@ __global__ __launch_bounds__(kThreads) void memory_update_kernel(Dev d, const ui
 
   for (uint32_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
     const uint32_t r0 = tile * kRows;
+    Upfront16<1, 8> um;      // message weights: requested before anything else of the tile
+    if constexpr (UP) {
+      const float* const B0[1] = {d.Wmsg + (size_t)(wave < ntg ? wave : 0u) * kCG * c_x * kGrpFloats};
+      um.request(B0, c_x);
+    }
     // per-row metadata first (one thread per row: node, partner, edge, time gap), through LDS
     if (threadIdx.x < kRows) {
       const uint32_t r = threadIdx.x;
@@ -88,17 +94,18 @@ __global__ __launch_bounds__(kThreads) void memory_update_kernel(Dev d, const ui
       s_self[r] = so; s_oth[r] = oo; s_ef[r] = eo; s_live[r] = live; s_dt[r] = dtv;
     }
     __syncthreads();
-    // then every thread issues its loads in batches of four, unconditionally (dead elements read a
+    // then every thread issues its loads in batches of sixteen, unconditionally (dead elements read a
     // valid dummy address and are zeroed afterwards), so the latencies overlap
     {
       const uint32_t total = kRows * Kmsg;
       const float* efp = ef ? ef : H0.base;
-      for (uint32_t x0 = threadIdx.x; x0 < total; x0 += kThreads * 4u) {
-        float v[4];
-        uint32_t rr[4], cc[4];
-        bool ok[4];
+      constexpr int kInFlight = UP ? 8 : 16;
+      for (uint32_t x0 = threadIdx.x; x0 < total; x0 += kThreads * kInFlight) {
+        float v[kInFlight];
+        uint32_t rr[kInFlight], cc[kInFlight];
+        bool ok[kInFlight];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
+        for (int e = 0; e < kInFlight; ++e) {
           uint32_t x = x0 + kThreads * e;
           ok[e] = x < total;
           x = ok[e] ? x : 0u;
@@ -111,7 +118,7 @@ __global__ __launch_bounds__(kThreads) void memory_update_kernel(Dev d, const ui
           v[e] = *p;
         }
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
+        for (int e = 0; e < kInFlight; ++e) {
           const uint32_t r = rr[e], col = cc[e];
           float val = v[e];
           if (col >= 2 * dm + de) {
@@ -123,62 +130,107 @@ __global__ __launch_bounds__(kThreads) void memory_update_kernel(Dev d, const ui
         }
       }
     }
-    __syncthreads();
+    // A workgroup of this kernel has a CU to itself and nothing to overlap a memory latency with, so
+    // each stage requests ALL its weights at once, ahead of the barrier that completes its input
+    // (kernel variant UP, for short products only: up to 8 chunks of K for the message, 2 for the gates,
+    // one column tile per wave; other shapes run the chunk-by-chunk pipeline).
+    constexpr bool up_ok = UP;
+    const uint32_t wt = wave < ntm ? wave : 0u;
     // ---- m = x W_msg + b_msg
-    for (uint32_t nt = wave; nt < ntg; nt += kWaves) {
-      const float* const Bt[1] = {d.Wmsg + (size_t)nt * kCG * c_x * kGrpFloats};
-      floatx4 acc[1] = {{0.f, 0.f, 0.f, 0.f}};
-      mfma16_gemm<1>(Xs + a_x, c_x, Bt, acc);
-      const uint32_t col = nt * 16 + colL;
-      if (col < dg) {
-        const float b = d.bmsg[col];
+    {
+      __syncthreads();
+      for (uint32_t nt = wave, it = 0; nt < ntg && !(UP && it); nt += kWaves, ++it) {
+        const float* const Bt[1] = {d.Wmsg + (size_t)nt * kCG * c_x * kGrpFloats};
+        floatx4 acc[1] = {{0.f, 0.f, 0.f, 0.f}};
+        if constexpr (up_ok) {
+          um.multiply(Xs + a_x, c_x, acc);
+        } else {
+          mfma16_gemm<1>(Xs + a_x, c_x, Bt, acc);
+        }
+        const uint32_t col = nt * 16 + colL;
+        if (col < dg) {
+          const float b = d.bmsg[col];
 #pragma unroll
-        for (int r = 0; r < 4; ++r) Ms[(row0 + r) * ll.ldm + col] = acc[0][r] + b;
-      }
-    }
-    __syncthreads();
-    // ---- z = sigma(m W_z + s U_z + b_z), r = sigma(m W_r + s U_r + b_r): one wave, one column tile of both
-    for (uint32_t nt = wave; nt < ntm; nt += kWaves) {
-      const float* const Bw[2] = {d.Wzr + (size_t)nt * kCG * c_g * kGrpFloats, d.Wzr + (size_t)(ntm + nt) * kCG * c_g * kGrpFloats};
-      const float* const Bu[2] = {d.Uzr + (size_t)nt * kCG * c_m * kGrpFloats, d.Uzr + (size_t)(ntm + nt) * kCG * c_m * kGrpFloats};
-      floatx4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
-      mfma16_gemm<2>(Ms + a_m, c_g, Bw, acc);
-      mfma16_gemm<2>(Xs + a_x, c_m, Bu, acc);
-      const uint32_t col = nt * 16 + colL;
-      if (col < dm) {
-        const float bz = d.bz[col], br = d.br[col];
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const uint32_t row = row0 + r;
-          Zs[row * ll.ldr + col] = sigmoidf_(acc[0][r] + bz);
-          Rs[row * ll.ldr + col] = sigmoidf_(acc[1][r] + br) * Xs[row * ll.ldx + col];
+          for (int r = 0; r < 4; ++r) Ms[(row0 + r) * ll.ldm + col] = acc[0][r] + b;
         }
       }
     }
-    __syncthreads();
-    // ---- candidate = tanh(m W_h + (r . s) U_h + b_h);  s' = (1 - z) candidate + z s
-    for (uint32_t nt = wave; nt < ntm; nt += kWaves) {
-      const float* const Bw[1] = {d.Wh + (size_t)nt * kCG * c_g * kGrpFloats};
-      const float* const Bu[1] = {d.Uh + (size_t)nt * kCG * c_m * kGrpFloats};
-      floatx4 acc[1] = {{0.f, 0.f, 0.f, 0.f}};
-      mfma16_gemm<1>(Ms + a_m, c_g, Bw, acc);
-      mfma16_gemm<1>(Rs + a_r, c_m, Bu, acc);
-      const uint32_t col = nt * 16 + colL;
-      if (col < dm) {
-        const float b = d.bh[col];
+    // ---- z = sigma(m W_z + s U_z + b_z), r = sigma(m W_r + s U_r + b_r): one wave, one column tile of both
+    {
+      Upfront16<2, 2> uw, uu;
+      {
+        const float* const Bw[2] = {d.Wzr + (size_t)wt * kCG * c_g * kGrpFloats, d.Wzr + (size_t)(ntm + wt) * kCG * c_g * kGrpFloats};
+        const float* const Bu[2] = {d.Uzr + (size_t)wt * kCG * c_m * kGrpFloats, d.Uzr + (size_t)(ntm + wt) * kCG * c_m * kGrpFloats};
+        if constexpr (up_ok) { uw.request(Bw, c_g); uu.request(Bu, c_m); }
+      }
+      __syncthreads();
+      for (uint32_t nt = wave, it = 0; nt < ntm && !(UP && it); nt += kWaves, ++it) {
+        const float* const Bw[2] = {d.Wzr + (size_t)nt * kCG * c_g * kGrpFloats, d.Wzr + (size_t)(ntm + nt) * kCG * c_g * kGrpFloats};
+        const float* const Bu[2] = {d.Uzr + (size_t)nt * kCG * c_m * kGrpFloats, d.Uzr + (size_t)(ntm + nt) * kCG * c_m * kGrpFloats};
+        floatx4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+        if constexpr (up_ok) {
+          uw.multiply(Ms + a_m, c_g, acc);
+          uu.multiply(Xs + a_x, c_m, acc);
+        } else {
+          mfma16_gemm<2>(Ms + a_m, c_g, Bw, acc);
+          mfma16_gemm<2>(Xs + a_x, c_m, Bu, acc);
+        }
+        const uint32_t col = nt * 16 + colL;
+        if (col < dm) {
+          const float bz = d.bz[col], br = d.br[col];
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const uint32_t row = row0 + r;
-          if (r0 + row < nD) {
-            const float cand = tanhf(acc[0][r] + b);
-            const float z = Zs[row * ll.ldr + col], s = Xs[row * ll.ldx + col];
-            d.mem_new[(size_t)(r0 + row) * dm + col] = (1.0f - z) * cand + z * s;
+          for (int r = 0; r < 4; ++r) {
+            const uint32_t row = row0 + r;
+            Zs[row * ll.ldr + col] = sigmoidf_(acc[0][r] + bz);
+            Rs[row * ll.ldr + col] = sigmoidf_(acc[1][r] + br) * Xs[row * ll.ldx + col];
+          }
+        }
+      }
+    }
+    // ---- candidate = tanh(m W_h + (r . s) U_h + b_h);  s' = (1 - z) candidate + z s
+    {
+      Upfront16<1, 2> uw, uu;
+      {
+        const float* const Bw[1] = {d.Wh + (size_t)wt * kCG * c_g * kGrpFloats};
+        const float* const Bu[1] = {d.Uh + (size_t)wt * kCG * c_m * kGrpFloats};
+        if constexpr (up_ok) { uw.request(Bw, c_g); uu.request(Bu, c_m); }
+      }
+      __syncthreads();
+      for (uint32_t nt = wave, it = 0; nt < ntm && !(UP && it); nt += kWaves, ++it) {
+        const float* const Bw[1] = {d.Wh + (size_t)nt * kCG * c_g * kGrpFloats};
+        const float* const Bu[1] = {d.Uh + (size_t)nt * kCG * c_m * kGrpFloats};
+        floatx4 acc[1] = {{0.f, 0.f, 0.f, 0.f}};
+        if constexpr (up_ok) {
+          uw.multiply(Ms + a_m, c_g, acc);
+          uu.multiply(Rs + a_r, c_m, acc);
+        } else {
+          mfma16_gemm<1>(Ms + a_m, c_g, Bw, acc);
+          mfma16_gemm<1>(Rs + a_r, c_m, Bu, acc);
+        }
+        const uint32_t col = nt * 16 + colL;
+        if (col < dm) {
+          const float b = d.bh[col];
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const uint32_t row = row0 + r;
+            if (r0 + row < nD) {
+              const float cand = tanhf(acc[0][r] + b);
+              const float z = Zs[row * ll.ldr + col], s = Xs[row * ll.ldx + col];
+              d.mem_new[(size_t)(r0 + row) * dm + col] = (1.0f - z) * cand + z * s;
+            }
           }
         }
       }
     }
     __syncthreads();
   }
+}
+
+// shapes the all-weights-up-front variant covers: every stage one column tile per wave, the products
+// short enough for their whole B operand to sit in registers
+bool memory_upfront(const Dev& d) {
+  return chunks_of(d.Kmsg) <= 8u && chunks_of(d.d_msg) <= 2u && chunks_of(d.d_mem) <= 2u &&
+         round_up(d.d_msg, 16) / 16 <= kWaves && round_up(d.d_mem, 16) / 16 <= kWaves;
 }
 
 size_t memory_lds(const Dev& d) { return (size_t)memory_lds_layout(d.Kmsg, d.d_msg, d.d_mem).total * sizeof(float); }
@@ -189,15 +241,18 @@ void launch_memory_update(const Dev& d, hipStream_t s, const uint32_t* src, cons
                           const float* ef) {
   uint32_t blocks = (2 * d.max_batch + kRows - 1) / kRows;
   if (blocks > 1024) blocks = 1024;
-  hipLaunchKernelGGL(memory_update_kernel, dim3(blocks), dim3(kThreads), memory_lds(d), s, d, src, dst, ts, ef);
+  if (memory_upfront(d))
+    hipLaunchKernelGGL(memory_update_kernel<true>, dim3(blocks), dim3(kThreads), memory_lds(d), s, d, src, dst, ts, ef);
+  else
+    hipLaunchKernelGGL(memory_update_kernel<false>, dim3(blocks), dim3(kThreads), memory_lds(d), s, d, src, dst, ts, ef);
 }
 
 int setup_memory_attributes(const Dev& d) {
   if (d.d_mem == 0) return 0;
   const size_t need = memory_lds(d);
   if (need + 1024 > kMaxLds) return -1;
-  return hipFuncSetAttribute((const void*)memory_update_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                             (int)need) == hipSuccess ? 0 : -1;
+  const void* f = memory_upfront(d) ? (const void*)memory_update_kernel<true> : (const void*)memory_update_kernel<false>;
+  return hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)need) == hipSuccess ? 0 : -1;
 }
 
 }  // namespace stgn

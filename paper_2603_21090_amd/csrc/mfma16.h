@@ -173,4 +173,32 @@ __device__ __forceinline__ void mfma16_gemm(const float* Ap, uint32_t nchunks, c
   mfma16_gemm_pre<NTL>(Ap, nchunks, Bt, acc, P);
 }
 
+// All weight chunks of a short product at once: for K of at most MAXC chunks the whole B operand of
+// NTL column tiles is requested in one go (MAXC * NTL * 16 registers), typically ahead of the barrier
+// that completes A, and the products then run as the chunks arrive -- one memory latency per product
+// instead of one per chunk.  For workgroups that run alone on a CU and cannot hide latencies.
+template <int NTL, int MAXC>
+struct Upfront16 {
+  float4 b[MAXC][NTL][kCG];
+  // requests are unconditional: chunks past the end repeat the last one and are never multiplied
+  __device__ __forceinline__ void request(const float* const (&Bt)[NTL], uint32_t nchunks) {
+#pragma unroll
+    for (int ch = 0; ch < MAXC; ++ch) {
+      const uint32_t c = (uint32_t)ch < nchunks ? (uint32_t)ch : nchunks - 1u;
+#pragma unroll
+      for (int t = 0; t < NTL; ++t) load_b16(Bt[t], c * kCG, b[ch][t]);
+    }
+  }
+  __device__ __forceinline__ void multiply(const float* Ap, uint32_t nchunks, floatx4 (&acc)[NTL]) {
+#pragma unroll
+    for (int ch = 0; ch < MAXC; ++ch) {
+      if ((uint32_t)ch < nchunks) {                  // wave-uniform; only LDS reads and products inside
+        float4 a[kCG];
+        load_a16(Ap, ch * kCG, a);
+        mfma16_chunk<NTL>(a, b[ch], acc);
+      }
+    }
+  }
+};
+
 }  // namespace stgn

@@ -103,6 +103,7 @@ def test_c1_full_stream(binding):
     dict(layers=2, d_mem=8, d_node=5, d_edge=6, d_time=8, d_emb=16, d_msg=8, heads=2, k=3),   # memory + features
     dict(layers=2, d_mem=100, d_edge=172, d_time=100, d_emb=100, d_msg=100, heads=2, k=10),   # the paper's widths
     dict(layers=2, d_mem=0, d_node=100, d_edge=64, d_time=100, d_emb=100, heads=2, k=20),     # config-5 widths
+    dict(layers=1, d_mem=136, d_edge=20, d_time=24, d_emb=32, d_msg=140, heads=2, k=3),       # wide memory: chunked GRU path
 ])
 def test_small_graphs_all_shapes(binding, kw):
     w = tiny_workload(num_nodes=150, num_edges=1500, batch=50, zipf_s=1.0, **kw)
