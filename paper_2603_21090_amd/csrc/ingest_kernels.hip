@@ -8,24 +8,37 @@ namespace stgn {
 
 namespace {
 
-constexpr int kSortThreads = 1024;
+constexpr int kSortThreads = 1024;   // largest workgroup of the staging kernel; small batches launch fewer waves
 
-// Exclusive block scan of one value per thread (blockDim.x == kSortThreads); returns the
-// exclusive prefix and writes the block total to *total.
+// Exclusive scan of one value per thread of the (whole-wave multiple, at most 1024 threads) workgroup:
+// lane shuffles inside each wave, one exchange of the wave totals through s_buf (16 words).  Returns
+// the exclusive prefix and writes the workgroup total to *total.
 __device__ uint32_t block_excl_scan(uint32_t v, uint32_t* s_buf, uint32_t* total) {
-  const int t = threadIdx.x;
-  s_buf[t] = v;
-  __syncthreads();
-  for (int off = 1; off < kSortThreads; off <<= 1) {
-    uint32_t add = (t >= off) ? s_buf[t - off] : 0u;
-    __syncthreads();
-    s_buf[t] += add;
-    __syncthreads();
+  const uint32_t lane = threadIdx.x & 63u, w = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  uint32_t incl = v;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const uint32_t o = __shfl_up(incl, off);
+    if (lane >= (uint32_t)off) incl += o;
   }
-  const uint32_t incl = s_buf[t];
-  if (total) *total = s_buf[kSortThreads - 1];
+  if (lane == 63) s_buf[w] = incl;
   __syncthreads();
-  return incl - v;
+  uint32_t before = 0, all = 0;
+  for (uint32_t i = 0; i < nw; ++i) {
+    const uint32_t ti = s_buf[i];
+    before += i < w ? ti : 0u;
+    all += ti;
+  }
+  if (total && threadIdx.x == 0) *total = all;
+  __syncthreads();
+  return before + incl - v;
+}
+
+// orders the LDS traffic of one wave: what its lanes stored before is visible to its lanes after
+__device__ inline void wave_sync_lds() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
 // number of adjacency blocks (sizes 8, 16, 32, ...) needed to hold x entries
@@ -39,7 +52,7 @@ __global__ __launch_bounds__(kSortThreads) void stage_sort_kernel(Dev d, uint32_
                                                                   const uint32_t* __restrict__ dst,
                                                                   const double* __restrict__ ts, uint32_t P) {
   extern __shared__ uint64_t keys[];
-  __shared__ uint32_t s_buf[kSortThreads];
+  __shared__ uint32_t s_buf[kSortThreads / 64];
   __shared__ uint32_t s_err, s_nD, s_units;
   const uint32_t t = threadIdx.x;
   Ctrl* c = d.ctrl;
@@ -49,7 +62,7 @@ __global__ __launch_bounds__(kSortThreads) void stage_sort_kernel(Dev d, uint32_
   // ---- validation: first offending edge decides the code (ids, self loop, time order)
   const double t_prev_stream = c->t_stream;
   const bool have_prev = c->E > 0;
-  for (uint32_t i = t; i < n; i += kSortThreads) {
+  for (uint32_t i = t; i < n; i += blockDim.x) {
     uint32_t code = 0;
     const uint32_t u = src[i], v = dst[i];
     const double ti = ts[i];
@@ -79,7 +92,7 @@ __global__ __launch_bounds__(kSortThreads) void stage_sort_kernel(Dev d, uint32_
 
   // ---- keys + bitonic sort in LDS
   const uint32_t m = 2 * n;
-  for (uint32_t s = t; s < P; s += kSortThreads) {
+  for (uint32_t s = t; s < P; s += blockDim.x) {
     uint64_t key = ~0ull;
     if (s < m) {
       const uint32_t node = (s & 1) ? dst[s >> 1] : src[s >> 1];
@@ -88,21 +101,30 @@ __global__ __launch_bounds__(kSortThreads) void stage_sort_kernel(Dev d, uint32_
     keys[s] = key;
   }
   __syncthreads();
+  // Compare-exchange stage (k2, j): thread x owns the pair whose lower index is x with a zero bit
+  // inserted at position log2 j.  For j <= 64 the 64 pairs of a wave lie in one aligned block of 128
+  // keys, so those stages only need the wave's own LDS traffic ordered; a workgroup barrier is needed
+  // only around the wider strides.
+  const uint32_t nth = blockDim.x;
   for (uint32_t k2 = 2; k2 <= P; k2 <<= 1) {
     for (uint32_t j = k2 >> 1; j > 0; j >>= 1) {
-      for (uint32_t x = t; x < (P >> 1); x += kSortThreads) {
+      for (uint32_t x = t; x < (P >> 1); x += nth) {
         const uint32_t i = ((x & ~(j - 1)) << 1) | (x & (j - 1));
         const uint32_t ij = i + j;
         const bool up = (i & k2) == 0;
         const uint64_t a = keys[i], b = keys[ij];
         if ((a > b) == up) { keys[i] = b; keys[ij] = a; }
       }
-      __syncthreads();
+      // the next stage (j / 2, or the first of the next k2, j' = k2) is wave-local iff its stride is <= 64
+      // and so was this one
+      const uint32_t jn = j > 1 ? (j >> 1) : k2;
+      if (j <= 64 && jn <= 64) wave_sync_lds(); else __syncthreads();
     }
   }
+  __syncthreads();
 
   // ---- segment heads -> D, seg_start
-  const uint32_t ept = (P + kSortThreads - 1) / kSortThreads;   // contiguous elements per thread
+  const uint32_t ept = (P + nth - 1) / nth;   // contiguous elements per thread
   const uint32_t lo = t * ept, hi = min(lo + ept, m);
   uint32_t heads = 0;
   for (uint32_t i = lo; i < hi; ++i) {
@@ -140,7 +162,7 @@ __global__ __launch_bounds__(kSortThreads) void stage_sort_kernel(Dev d, uint32_
   }
 
   // ---- per distinct endpoint: new degree, last slot, adjacency blocks to allocate
-  const uint32_t eptd = (2 * d.max_batch + kSortThreads - 1) / kSortThreads;
+  const uint32_t eptd = (m + nth - 1) / nth;
   const uint32_t dlo = t * eptd, dhi = min(dlo + eptd, nD);
   uint32_t units = 0;
   unsigned long long fdeg = 0;              // adjacency entries the endpoints own after this batch
@@ -271,7 +293,10 @@ void launch_stage_sort(const Dev& d, hipStream_t s, uint32_t n, const uint32_t* 
                        const double* ts) {
   uint32_t P = 2;
   while (P < 2 * n) P <<= 1;
-  hipLaunchKernelGGL(stage_sort_kernel, dim3(1), dim3(kSortThreads), P * sizeof(uint64_t), s, d, n, src, dst, ts, P);
+  // one thread per compared pair, within 256 .. 1024: idle waves would only lengthen the barriers
+  uint32_t threads = P / 2;
+  threads = threads < 256 ? 256 : threads > (uint32_t)kSortThreads ? (uint32_t)kSortThreads : threads;
+  hipLaunchKernelGGL(stage_sort_kernel, dim3(1), dim3(threads), P * sizeof(uint64_t), s, d, n, src, dst, ts, P);
 }
 
 void launch_apply(const Dev& d, hipStream_t s, const uint32_t* src, const uint32_t* dst, const double* ts,
