@@ -10,8 +10,8 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libstreamtgn.so")
-SOURCES = ["api.hip", "ingest_kernels.hip", "memory_kernels.hip", "frontier_kernels.hip", "embed_kernels.hip"] + \
-          [f"layer_ns{ns}.hip" for ns in range(2, 9)]
+SOURCES = ["api.hip", "ingest_kernels.hip", "memory_kernels.hip", "frontier_kernels.hip", "embed_kernels.hip",
+           "layer_h1.hip", "layer_h2.hip", "layer_h4.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-value", "-Wno-unused-result",
          "-Wno-pass-failed",
          # packed fp32 forms are kept out of the generated code on this target

@@ -14,7 +14,7 @@ using namespace stgn;
 namespace {
 
 const char* const kClassNames[KC_COUNT] = {"stage_sort", "memory_update", "apply", "plan", "expand", "compact",
-                                           "layer", "gather_rows", "noop"};
+                                           "layer", "gather_rows", "noop", "project"};
 
 std::string g_create_error;
 
@@ -87,13 +87,9 @@ int check_config(const stgn_config* c, std::string* why) {
   if (c->d_mem + c->d_node == 0 || c->d_mem + c->d_node > 512) return bad("layer-0 width (d_mem + d_node) out of range");
   if (c->d_mem && (c->d_msg == 0 || c->d_msg > 512)) return bad("d_msg out of range");
   if (c->heads == 0 || c->d_emb % c->heads != 0) return bad("heads must divide d_emb");
-  if (c->d_emb / c->heads > 128) return bad("d_emb / heads > 128");
-  for (uint32_t l = 0; l < c->layers; ++l) {
-    const uint32_t din = l == 0 ? c->d_mem + c->d_node : c->d_emb;
-    if (!attn_supported(din, c->d_edge, c->d_time, c->heads))
-      return bad("unsupported attention shape: heads in {1,2,4}, d_time <= 128, and the three input segments "
-                 "(each rounded up to 64) must total <= 512 floats");
-  }
+  if (!attn_supported(c->d_emb, c->d_time, c->heads))
+    return bad("unsupported attention shape: heads in {1,2,4}, d_time <= 128, and heads * ceil(d_emb / heads / 64) <= 4 "
+               "(every head takes whole 64-float slots of a cached key row)");
   return STGN_OK;
 }
 
@@ -141,6 +137,16 @@ size_t layout(const stgn_config& c, char* base, Dev* d) {
   d->efeat.ld = row_ld(c.d_edge);
   d->efeat.base = b.take<float>((size_t)c.max_edges * d->efeat.ld);
   d->ets = b.take<double>(c.max_edges);
+  d->sh = (d->dk + kSlot - 1) / kSlot;
+  d->ks = c.heads * d->sh;
+  d->nt = (c.d_time + kSlot - 1) / kSlot;
+  d->ld_kv = 2 * kSlot * d->ks;
+  for (uint32_t l = 0; l < c.layers; ++l) {
+    d->KV[l].ld = d->ld_kv;
+    d->KV[l].base = b.take<float>((size_t)N * d->ld_kv);
+    d->KVE[l].ld = c.d_edge ? d->ld_kv : 0;                   // without edge features every edge reads one zero row
+    d->KVE[l].base = b.take<float>((size_t)(c.d_edge ? c.max_edges : 1) * d->ld_kv);
+  }
   d->ctrl = b.take<Ctrl>(1);
   d->st_src = b.take<uint32_t>(c.max_batch);
   d->st_dst = b.take<uint32_t>(c.max_batch);
@@ -164,23 +170,7 @@ size_t layout(const stgn_config& c, char* base, Dev* d) {
     if (d->thr[l] >= c.layers + 1) { d->R[l] = d->A; d->thr[l] = 0xFFu; }
     else { d->R[l] = b.take<uint32_t>(N); ++d->n_lists; }
   }
-  for (uint32_t l = 0; l < c.layers; ++l) {
-    LayerDev& L = d->L[l];
-    L.d_in = l == 0 ? d->d0 : c.d_emb;
-    L.d_in2 = round_up(L.d_in, 2);
-    L.Zdim = L.d_in + c.d_edge + c.d_time;
-    L.ns = 0;
-    const uint32_t widths[3] = {L.d_in, c.d_edge, c.d_time};
-    for (uint32_t seg = 0; seg < 3; ++seg)
-      for (uint32_t o = 0; o < widths[seg]; o += kSlot) {
-        L.kind[L.ns] = (uint8_t)seg;
-        L.valid[L.ns] = (uint16_t)std::min(kSlot, widths[seg] - o);
-        L.segoff[L.ns] = (uint16_t)o;
-        ++L.ns;
-      }
-    L.nt = (c.d_time + kSlot - 1) / kSlot;
-    L.Zp = kSlot * L.ns;
-  }
+  for (uint32_t l = 0; l < c.layers; ++l) d->L[l].d_in = l == 0 ? d->d0 : c.d_emb;
   d->q_cap = 65536;
   d->qnodes = b.take<uint32_t>(d->q_cap);
   d->qout = b.take<float>((size_t)d->q_cap * std::max(d->d0, c.d_emb));
@@ -206,10 +196,12 @@ size_t layout(const stgn_config& c, char* base, Dev* d) {
     LayerDev& L = d->L[l];
     L.WQn = b.take<float>(tiled_size(L.d_in, c.d_emb));
     L.cQ = b.take<float>(c.d_emb);
-    L.WKT = b.take<float>(tiled_size(d->dk, c.heads * L.Zp));
-    L.WV = b.take<float>(tiled_size(L.Zp, c.heads * round_up(d->dk, 16)));
-    L.WO = b.take<float>(tiled_size(c.d_emb, c.d_emb));
+    L.WKT = b.take<float>(tiled_size(kSlot * d->sh, c.heads * kSlot * d->nt));
+    L.WV = b.take<float>(tiled_size(kSlot * d->nt, c.heads * round_up(d->dk, 16)));
+    L.WO = b.take<float>(tiled_size(kSlot * d->ks, c.d_emb));
     L.bO = b.take<float>(c.d_emb);
+    L.WKVn = b.take<float>(tiled_size(L.d_in, d->ld_kv));
+    L.WKVe = c.d_edge ? b.take<float>(tiled_size(c.d_edge, d->ld_kv)) : nullptr;
   }
   return (b.off + 255) & ~(size_t)255;
 }
@@ -261,40 +253,63 @@ int pack_parameters(stgn_ctx* ctx, const stgn_weights* w) {
         (rc = upload(ctx, d.br, vec(w->b_r, c.d_mem))) || (rc = upload(ctx, d.bh, vec(w->b_h, c.d_mem))))
       return rc;
   }
-  // attention weights feed 16x16x4 matrix instructions: group-major packing (see tiled_size)
-  const uint32_t dk = d.dk, npk = round_up(dk, 16);
+  // attention weights feed 16x16x4 matrix instructions: group-major packing (see tiled_size).
+  // Row z of W_K / W_V belongs to the node block (z < d_in), the edge block or the time block of the
+  // attention input; column h dk + cc to head h.  In a cached row and in the head-output tile head h
+  // starts at float 64 sh h (padded-head layout).
+  const uint32_t dk = d.dk, npk = round_up(dk, 16), hp = kSlot * d.sh, Ztp = kSlot * d.nt;
   const double inv_sqrt_dk = 1.0 / std::sqrt((double)dk);
   for (uint32_t l = 0; l < c.layers; ++l) {
     const LayerDev& L = d.L[l];
     const float *WQ = w->W_Q[l], *WK = w->W_K[l], *WV = w->W_V[l], *WOs = w->W_O[l];
+    const uint32_t e0 = L.d_in, t0 = L.d_in + c.d_edge;       // first edge row, first time row
+    // the query carries the 1 / sqrt(dk) of the scores
     std::vector<float> WQn(tiled_size(L.d_in, c.d_emb), 0.0f);
     for (uint32_t i = 0; i < L.d_in; ++i)
-      for (uint32_t col = 0; col < c.d_emb; ++col) put_tiled(WQn, L.d_in, i, col, WQ[(size_t)i * c.d_emb + col]);
+      for (uint32_t col = 0; col < c.d_emb; ++col)
+        put_tiled(WQn, L.d_in, i, col, (double)WQ[(size_t)i * c.d_emb + col] * inv_sqrt_dk);
     std::vector<float> cQ(c.d_emb);
     for (uint32_t col = 0; col < c.d_emb; ++col) {
       double acc = 0.0;
       for (uint32_t i = 0; i < c.d_time; ++i)
         acc += tscale * std::cos((double)w->phase[i]) * (double)WQ[(size_t)(L.d_in + i) * c.d_emb + col];
-      cQ[col] = (float)acc;
+      cQ[col] = (float)(acc * inv_sqrt_dk);
     }
-    // W_K head blocks transposed: K = dk, columns = (head, slot position); W_V head blocks: K = slot
-    // position, columns = (head, column inside the head padded to 16)
-    std::vector<float> WKT(tiled_size(dk, c.heads * L.Zp), 0.0f);
-    std::vector<float> WVp(tiled_size(L.Zp, c.heads * npk), 0.0f);
+    // time rows of W_K, head blocks transposed: K = column inside the head, columns = (head, time index);
+    // time rows of W_V, head blocks: K = time index, columns = (head, column inside the head padded to 16)
+    std::vector<float> WKT(tiled_size(hp, c.heads * Ztp), 0.0f);
+    std::vector<float> WVp(tiled_size(Ztp, c.heads * npk), 0.0f);
     for (uint32_t h = 0; h < c.heads; ++h)
-      for (uint32_t z = 0; z < L.Zdim; ++z) {
-        const double rsz = z >= L.d_in + c.d_edge ? tscale : 1.0;
-        const uint32_t pz = slot_pos(z, L.d_in, c.d_edge);
+      for (uint32_t i = 0; i < c.d_time; ++i)
         for (uint32_t cc = 0; cc < dk; ++cc) {
-          put_tiled(WKT, dk, cc, h * L.Zp + pz, (double)WK[(size_t)z * c.d_emb + h * dk + cc] * inv_sqrt_dk * rsz);
-          put_tiled(WVp, L.Zp, pz, h * npk + cc, (double)WV[(size_t)z * c.d_emb + h * dk + cc] * rsz);
+          put_tiled(WKT, hp, cc, h * Ztp + i, (double)WK[(size_t)(t0 + i) * c.d_emb + h * dk + cc] * tscale);
+          put_tiled(WVp, Ztp, i, h * npk + cc, (double)WV[(size_t)(t0 + i) * c.d_emb + h * dk + cc] * tscale);
+        }
+    // W_O with its rows moved to the padded-head layout of the head outputs
+    std::vector<float> WO(tiled_size(kSlot * d.ks, c.d_emb), 0.0f);
+    for (uint32_t h = 0; h < c.heads; ++h)
+      for (uint32_t cc = 0; cc < dk; ++cc)
+        for (uint32_t col = 0; col < c.d_emb; ++col)
+          put_tiled(WO, kSlot * d.ks, h * hp + cc, col, WOs[(size_t)(h * dk + cc) * c.d_emb + col]);
+    // node and edge rows of [W_K | W_V] in the cached-row layout: keys in floats [0, 64 ks), values behind
+    std::vector<float> WKVn(tiled_size(L.d_in, d.ld_kv), 0.0f);
+    std::vector<float> WKVe(c.d_edge ? tiled_size(c.d_edge, d.ld_kv) : 0, 0.0f);
+    for (uint32_t h = 0; h < c.heads; ++h)
+      for (uint32_t cc = 0; cc < dk; ++cc) {
+        const uint32_t kc = h * hp + cc, vc = kSlot * d.ks + h * hp + cc;
+        const size_t wc = (size_t)h * dk + cc;
+        for (uint32_t i = 0; i < L.d_in; ++i) {
+          put_tiled(WKVn, L.d_in, i, kc, WK[(size_t)i * c.d_emb + wc]);
+          put_tiled(WKVn, L.d_in, i, vc, WV[(size_t)i * c.d_emb + wc]);
+        }
+        for (uint32_t i = 0; i < c.d_edge; ++i) {
+          put_tiled(WKVe, c.d_edge, i, kc, WK[(size_t)(e0 + i) * c.d_emb + wc]);
+          put_tiled(WKVe, c.d_edge, i, vc, WV[(size_t)(e0 + i) * c.d_emb + wc]);
         }
       }
-    std::vector<float> WO(tiled_size(c.d_emb, c.d_emb), 0.0f);
-    for (uint32_t i = 0; i < c.d_emb; ++i)
-      for (uint32_t col = 0; col < c.d_emb; ++col) put_tiled(WO, c.d_emb, i, col, WOs[(size_t)i * c.d_emb + col]);
     if ((rc = upload(ctx, L.WQn, WQn)) || (rc = upload(ctx, L.cQ, cQ)) || (rc = upload(ctx, L.WKT, WKT)) ||
-        (rc = upload(ctx, L.WV, WVp)) || (rc = upload(ctx, L.WO, WO)) || (rc = upload(ctx, L.bO, vec(w->b_O[l], c.d_emb))))
+        (rc = upload(ctx, L.WV, WVp)) || (rc = upload(ctx, L.WO, WO)) || (rc = upload(ctx, L.bO, vec(w->b_O[l], c.d_emb))) ||
+        (rc = upload(ctx, L.WKVn, WKVn)) || (rc = upload(ctx, L.WKVe, WKVe)))
       return rc;
   }
   return STGN_OK;
@@ -332,6 +347,7 @@ void drain_timing(stgn_ctx* ctx) {
 // every layer over all rows (initial state, full rebuild) or over the per-layer lists of the last batch
 void run_layers(stgn_ctx* ctx, bool all_rows) {
   const Dev& d = ctx->d;
+  if (all_rows) { Scope s(ctx, KC_PROJECT); launch_project_nodes(d, ctx->stream); }   // cached keys|values of the layer-0 rows
   for (uint32_t l = 0; l < d.layers; ++l) {
     Scope s(ctx, KC_LAYER);
     if (all_rows) launch_layer(d, ctx->stream, l, nullptr, nullptr, d.N);
@@ -453,6 +469,8 @@ int stgn_create(const stgn_config* cfg, const stgn_weights* w, const float* node
                                hipMemcpyHostToDevice);
     if (e != hipSuccess) { ctx->err = std::string("node feature upload: ") + hipGetErrorString(e); return bail(STGN_E_DEVICE); }
   }
+  // ring places past a row's entry count read edge 0: its rows must be finite before the first edge arrives
+  for (uint32_t l = 0; l < cfg->layers; ++l) launch_zero(ctx->d.KVE[l].base, ctx->d.ld_kv, ctx->stream);
   run_layers(ctx, true);    // every cache row = empty-neighbourhood embedding
   hipError_t e = hipStreamSynchronize(ctx->stream);
   if (e == hipSuccess) e = hipGetLastError();
@@ -532,6 +550,7 @@ int stgn_ingest_batch(stgn_ctx* ctx, uint32_t n, const uint32_t* src, const uint
   if (c.d_mem) { Scope t(ctx, KC_MEMORY); launch_memory_update(d, s, dsrc, ddst, dts, def); }
   if (ev) hipEventRecord(ev[2], s);
   { Scope t(ctx, KC_APPLY); launch_apply(d, s, dsrc, ddst, dts, def); }
+  { Scope t(ctx, KC_PROJECT); launch_project_batch(d, s, def); }
   if (ev) hipEventRecord(ev[3], s);
   for (uint32_t hop = 0; hop < c.layers; ++hop) {
     { Scope t(ctx, KC_PLAN); launch_plan(d, s, hop); }

@@ -1,4 +1,4 @@
-// Instantiates the fused attention-layer kernel for inputs that occupy 4 slots of 64 floats.
+// Instantiates the fused attention-layer kernel for 4 attention head(s).
 #include "layer_kernel.h"
 
 namespace stgn {

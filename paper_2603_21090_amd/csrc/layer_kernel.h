@@ -1,20 +1,22 @@
 // Temporal-attention layer for a list of target rows (paper Eq. attn_detail, Sec. 3.3.4 exact
 // mode, Sec. 3.6.2 "single batched kernel" over the affected set), one fused kernel per layer.
 //
-// The layer is evaluated in an algebraically re-associated form so that every dense product runs
-// over |rows| instead of |rows| * k:
-//     score_{h,j} = q_h . (z_j W_K,h) / sqrt(dk)      =  (W_K,h q_h / sqrt(dk)) . z_j  =  qt_h . z_j
-//     o_h         = sum_j alpha_{h,j} (z_j W_V,h)     =  (sum_j alpha_{h,j} z_j) W_V,h =  zb_h W_V,h
-// with z_j = [h_{u_j} | e_j | phi(t_v - t_j)] the raw gathered neighbour row.  A workgroup of four
-// waves owns 16 target rows and runs five phases without leaving the CU:
-//   1. q  = h_v W_Q(node block) + phi(0) W_Q(time block)                         (MFMA 16x16x4)
-//   2. qt_h = q_h W_K,h^T / sqrt(dk), kept in LDS in the slot layout               (MFMA)
-//   3. gather z_j (node row, edge-feature row, time encoding), scores, softmax, zb_h; one wave
-//      serves four rows, 16 lanes x float4 per 64-float slot; zb overwrites qt in LDS   (HBM bound)
-//   4. o_h = zb_h W_V,h                                                          (MFMA)
-//   5. h_v' = [o_1 | .. | o_H] W_O + b_O, written into the layer cache             (MFMA)
-// Weights stream from L2 (group-major packing, see mfma16.h); two workgroups per CU overlap one's
-// gather with the other's products.
+// Keys and values are linear in z_j = [h_{u_j} | e_j | phi(t_v - t_j)].  Their node and edge terms are
+// cached rows (per node / per edge, [keys | values], see LayerDev); the time term is re-associated so
+// that its dense products run over rows instead of (row, neighbour) pairs:
+//     score_{h,j} = q_h . (kn_{u_j} + ke_j)_h + qt_h . phi_j ,     qt_h = W_K,h[time] q_h      (q carries 1/sqrt(dk))
+//     o_h         = sum_j a_{h,j} (vn_{u_j} + ve_j)_h + pb_h W_V,h[time] ,   pb_h = sum_j a_{h,j} phi_j
+// A workgroup of four waves owns 16 target rows and runs its phases without leaving the CU:
+//   1. q  = h_v W_Q(node block) + phi(0) W_Q(time block)                           (MFMA 16x16x4)
+//   2. qt_h = q_h W_K,h[time]^T, kept in LDS                                        (MFMA)
+//   3. gather the cached rows of the ring entries, time encodings, scores, softmax, weighted sums;
+//      one wave serves four rows, 16 lanes x float4 per 64-float slot                (HBM / vector ALU)
+//   4. o_h += pb_h W_V,h[time]                                                       (MFMA)
+//   5. h_v' = [o_1 | .. | o_H] W_O + b_O, written into the layer cache               (MFMA)
+//   6. unless this is the last layer: the row's own cached keys|values for the next layer,
+//      h_v' [W_K | W_V](node rows of layer l + 1)                                     (MFMA)
+// Weights stream from L2 (group-major packing, see mfma16.h); several workgroups per CU overlap one's
+// gather with another's products.
 #pragma once
 #include "stgn_internal.h"
 #include "mfma16.h"
@@ -53,20 +55,18 @@ __device__ inline float dot4(const float4 a, const float4 b, float acc) {
 }
 
 struct LayerLds {
-  uint32_t ldx, ldq, ldz;        // strides (floats) of the X / O tile, the Q tile and the qt / zb tile
-  uint32_t dkp;                  // floats reserved per head in a Q row (dk rounded up to a group)
+  uint32_t ldx, ldq, ldz;        // strides (floats) of the X / O tile, the Q / H' tile and the qt / pb tile
   uint32_t off_q, off_z, off_r, total;
 };
 
 // Every stride is 4 (mod 8) floats: rows stay 16-byte aligned and the 16 rows of an operand read
-// fall into distinct banks.
-__host__ __device__ inline LayerLds layer_lds(uint32_t d_in, uint32_t d_emb, uint32_t heads, uint32_t Zp, uint32_t k) {
+// fall into distinct banks.  ks = key slots (heads * slots per head), nt = time slots.
+__host__ __device__ inline LayerLds layer_lds(uint32_t d_in, uint32_t heads, uint32_t ks, uint32_t nt, uint32_t k) {
   LayerLds l;
-  const uint32_t wx = round_up(d_in, kGrpK), wo = round_up(d_emb, kGrpK);
+  const uint32_t wx = round_up(d_in, kGrpK), wo = kSlot * ks;
   l.ldx = (wx > wo ? wx : wo) + 4;                // the input tile and the head-output tile share storage
-  l.dkp = round_up(d_emb / heads, kGrpK);
-  l.ldq = heads * l.dkp + 4;
-  l.ldz = heads * Zp + 4;
+  l.ldq = wo + 4;                                 // q in the padded-head layout, later the output rows h'
+  l.ldz = heads * kSlot * nt + 4;
   l.off_q = kTM * l.ldx;
   l.off_z = l.off_q + kTM * l.ldq;
   l.off_r = l.off_z + kTM * l.ldz + 4 * kGrpK;    // operand reads may run one chunk past the last row
@@ -76,33 +76,35 @@ __host__ __device__ inline LayerLds layer_lds(uint32_t d_in, uint32_t d_emb, uin
 
 // Everything the kernel needs, and nothing else (keeps the scalar register file uncrowded).
 struct LayerArgs {
-  const float* Hin; float* Hout; const float* efeat;
+  const float* Hin; float* Hout;
+  const float* KVn; const float* KVe;              // cached key|value rows of the input table's nodes / of the edges
+  float* KVout;                                    // the next layer's node table (null for the last layer)
   const RingEntry* ring; const uint32_t* deg; const double* t_last;
   const double* om_rev; const double* ph_rev;
   Ctrl* ctrl;
-  const float *WQ, *cQ, *WKT, *WV, *WO, *bO;        // WQ, WKT, WV, WO group-major (mfma16.h)
-  uint32_t ld_in, ld_out, ld_ef;
-  uint32_t k, heads, d_in, d_emb, dk, d_time, Zp;
-  uint16_t valid[kMaxSlots];     // valid floats per slot
-  uint16_t segoff[kMaxSlots];    // offset of the slot inside its source row
-  uint8_t  kind[kMaxSlots];      // 0 node row, 1 edge-feature row, 2 time encoding
+  const float *WQ, *cQ, *WKT, *WV, *WO, *bO, *WKVnext;   // matrices group-major (mfma16.h)
+  uint32_t ld_in, ld_out, ld_kv, ld_kve;           // ld_kve = 0 without edge features (every edge reads one zero row)
+  uint32_t k, d_in, d_emb, dk, d_time;
 };
 
-// gathered (node / edge) slots of one chunk of JC ring entries, one float4 per lane and slot
-template <int JC, int NG>
+// cached rows (node and edge, keys and values) of one chunk of JC ring entries, one float4 per lane and slot
+template <int JC, int KS>
 struct GatherBuf {
-  float4 g[JC][NG];
+  float4 n[JC][2 * KS];
+  float4 e[JC][2 * KS];
 };
 
-// NS slots in total, the last NT of them time-encoding slots; JC ring entries fetched together.
-template <int NS, int NT, int H, int JC>
-__global__ __launch_bounds__(256, 2) void layer_kernel(LayerArgs a, const uint32_t* __restrict__ rows,
-                                                       const uint32_t* count_ptr, uint32_t count_max) {
+// KS key slots in total (heads x slots per head), NT time slots; JC ring entries fetched together.
+template <int KS, int NT, int H, int JC, int WGS>
+__global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint32_t* __restrict__ rows,
+                                                         const uint32_t* count_ptr, uint32_t count_max) {
   extern __shared__ __align__(16) float lds[];
   __shared__ uint32_t s_node[kTM], s_cnt[kTM], s_next[kTM];
   __shared__ double s_tq[kTM];
-  __shared__ uint32_t s_zt[4 * kMaxSlots];     // 16-column tiles of a qt row that hold valid columns
-  __shared__ __align__(16) double s_om[2 * kSlot], s_ph[2 * kSlot];
+  __shared__ __align__(16) double s_om[NT * kSlot], s_ph[NT * kSlot];
+  static_assert(KS % H == 0, "whole slots per head");
+  constexpr int SH = KS / H;                  // slots per head
+  constexpr uint32_t Ztp = NT * kSlot;        // floats of one head's qt / pb vector
   if (count_ptr && a.ctrl->skip) return;
   uint32_t n = count_max;
   if (count_ptr) { const uint32_t c = *count_ptr; n = c < count_max ? c : count_max; }
@@ -110,38 +112,27 @@ __global__ __launch_bounds__(256, 2) void layer_kernel(LayerArgs a, const uint32
   const uint32_t lane = threadIdx.x & 63u, sub = lane & 15u, grp = lane >> 4;
   // wave index, made provably uniform so that tile indices and weight addresses stay in scalar registers
   const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-  const uint32_t Zp = a.Zp, k = a.k, dk = a.dk;
-  const uint32_t c_in = chunks_of(a.d_in), c_de = chunks_of(a.d_emb), c_dk = chunks_of(dk);                    // chunks of K
-  const uint32_t g_in = kCG * c_in, g_de = kCG * c_de, g_dk = kCG * c_dk, g_z = Zp / kGrpK;                   // groups of K
-  const uint32_t ntd = round_up(a.d_emb, 16) >> 4, ntk = round_up(dk, 16) >> 4, ntz = Zp >> 4;                // column tiles
-  const LayerLds ll = layer_lds(a.d_in, a.d_emb, a.heads, Zp, k);
-  float* Xs = lds;                            // input rows (phases 0-1), then head outputs (phases 4-5)
-  float* Qs = lds + ll.off_q;
-  float* Zs = lds + ll.off_z;
+  const uint32_t k = a.k, dk = a.dk;
+  const uint32_t c_in = chunks_of(a.d_in), c_de = chunks_of(a.d_emb);                                     // chunks of K
+  const uint32_t g_in = kCG * c_in, g_de = kCG * c_de, g_dk = kCG * SH, g_zt = kCG * NT, g_o = kCG * KS;  // groups of K
+  const uint32_t ntd = round_up(a.d_emb, 16) >> 4, ntk = round_up(dk, 16) >> 4;                           // column tiles
+  constexpr uint32_t ntz = Ztp >> 4;                                                                       // tiles of a qt vector
+  const uint32_t nzt = (a.d_time + 15u) >> 4;                                                              // ... that hold valid columns
+  const LayerLds ll = layer_lds(a.d_in, H, KS, NT, k);
+  float* Xs = lds;                            // input rows (phases 0-1), then head outputs (phases 3-5)
+  float* Qs = lds + ll.off_q;                 // q (phases 1-3), then the output rows (phases 5-6)
+  float* Zs = lds + ll.off_z;                 // qt (phases 2-3), then pb (phases 3-4)
   RingEntry* Rs = reinterpret_cast<RingEntry*>(lds + ll.off_r);   // [row][j], j = 0 the most recent entry
-  constexpr int NG = NS - NT;                 // gathered (node / edge) slots
-  using ZBuf = GatherBuf<JC, NG>;
+  using ZBuf = GatherBuf<JC, KS>;
 
   // ---- per-lane constants
   // time-encoding parameters (omega, phase in revolutions) live in LDS, zero past d_time
-  for (uint32_t q = threadIdx.x; q < 2 * kSlot; q += 256) {
+  for (uint32_t q = threadIdx.x; q < NT * kSlot; q += 256) {
     s_om[q] = q < a.d_time ? a.om_rev[q] : 0.0;
     s_ph[q] = q < a.d_time ? a.ph_rev[q] : 0.0;
   }
   // operand padding (columns nobody writes) must be finite: clear the tiles once
   for (uint32_t x = threadIdx.x; x < ll.off_r; x += 256) lds[x] = 0.0f;
-  // list of the qt column tiles that are not wholly slot padding
-  uint32_t nzt;
-  {
-    uint32_t vq = 0;
-#pragma unroll
-    for (int s = 0; s < NS; ++s)
-      if ((lane >> 2) == (uint32_t)s) vq = a.valid[s];
-    const bool tv = lane < ntz && (lane & 3u) * 16u < vq;
-    const uint64_t m = __ballot(tv);
-    nzt = (uint32_t)__popcll(m);
-    if (wave == 0 && tv) s_zt[__popcll(m & ((1ull << lane) - 1ull))] = lane;
-  }
   bool tok[NT][4];
 #pragma unroll
   for (int t = 0; t < NT; ++t)
@@ -150,30 +141,30 @@ __global__ __launch_bounds__(256, 2) void layer_kernel(LayerArgs a, const uint32
   uint32_t gathered = 0;
   const uint32_t a_x = a16_lane_off(ll.ldx), a_q = a16_lane_off(ll.ldq), a_z = a16_lane_off(ll.ldz);
   const uint32_t c_off_x = m16_row(lane, 0) * ll.ldx + m16_col(lane);
+  const uint32_t c_off_q = m16_row(lane, 0) * ll.ldq + m16_col(lane);
   const uint32_t c_off_z = m16_row(lane, 0) * ll.ldz + m16_col(lane);
 
   // ---- phase-2 work units: (head, pair of valid qt column tiles); wave w owns units w, w + 4, ...
-  // Lane i of `udesc` holds the description of the wave's i-th unit (head, the two tiles, whether the
-  // second tile is real), worked out once; inside the tile loop a unit costs one cross-lane read.
-  const uint32_t npr = (nzt + 1u) >> 1, nunits2 = a.heads * npr;
+  // Lane i of `udesc` holds the description of the wave's i-th unit (head, first tile, whether a
+  // second tile follows), worked out once; inside the tile loop a unit costs one cross-lane read.
+  const uint32_t npr = (nzt + 1u) >> 1, nunits2 = H * npr;
   const uint32_t nu2 = wave < nunits2 ? (nunits2 - wave + 3u) >> 2 : 0u;     // units of this wave
   struct Unit2 { uint32_t h, t0, t1; bool two; };
-  __syncthreads();                                                           // s_zt is complete
   uint32_t udesc = 0;
   if (lane < nu2) {
     const uint32_t x = wave + 4u * lane, h = x / npr, i0 = 2u * (x - h * npr);
     const uint32_t two = i0 + 1u < nzt ? 1u : 0u;
-    udesc = h | (s_zt[i0] << 8) | (s_zt[i0 + two] << 16) | (two << 24);
+    udesc = h | (i0 << 8) | (two << 24);
   }
   auto decode2 = [&](uint32_t i) {
     const uint32_t dsc = (uint32_t)__builtin_amdgcn_readlane((int)udesc, (int)i);
     Unit2 u;
-    u.h = dsc & 0xFFu; u.t0 = (dsc >> 8) & 0xFFu; u.t1 = (dsc >> 16) & 0xFFu; u.two = (dsc >> 24) != 0u;
+    u.h = dsc & 0xFFu; u.t0 = (dsc >> 8) & 0xFFu; u.two = (dsc >> 24) != 0u; u.t1 = u.t0 + (u.two ? 1u : 0u);
     return u;
   };
   auto wkt = [&](uint32_t h, uint32_t t) { return a.WKT + (size_t)(h * ntz + t) * g_dk * kGrpFloats; };
   auto store2 = [&](const Unit2& u, const floatx4 (&acc)[2]) {
-    float* zp = Zs + u.h * Zp + c_off_z;
+    float* zp = Zs + u.h * Ztp + c_off_z;
 #pragma unroll
     for (int r = 0; r < 4; ++r) zp[u.t0 * 16 + r * ll.ldz] = acc[0][r];
     if (u.two) {
@@ -182,7 +173,7 @@ __global__ __launch_bounds__(256, 2) void layer_kernel(LayerArgs a, const uint32
     }
   };
   // ---- phase-4 work units: (head, pair of head-output column tiles)
-  const uint32_t np4 = (ntk + 1u) >> 1, nunits4 = a.heads * np4;
+  const uint32_t np4 = (ntk + 1u) >> 1, nunits4 = H * np4;
   // ---- phases 1 and 5: column tiles nt and nt + 4 of the d_emb outputs form a unit
   __syncthreads();
 
@@ -228,7 +219,7 @@ __global__ __launch_bounds__(256, 2) void layer_kernel(LayerArgs a, const uint32
   };
   // the record of adjacency position p sits in ring slot p mod k; with the row's degree known, slot
   // sl holds the j-th most recent entry, j = (newest - sl) mod k; places past the row's entry count
-  // name node 0 / edge 0 (finite rows that later meet a zero weight)
+  // name node 0 / edge 0 (finite cached rows whose weight in every sum is zero)
   auto place_ring = [&](uint32_t r, uint32_t sl, bool live, RingEntry e, uint32_t dg_in, double tl) {
     const uint32_t dg = live ? dg_in : 0u;
     const uint32_t cnt = dg < k ? dg : k;
@@ -307,7 +298,7 @@ __global__ __launch_bounds__(256, 2) void layer_kernel(LayerArgs a, const uint32
       __syncthreads();
     }
     stage_a(tile + gridDim.x);                               // row ids of this workgroup's next tile
-    // ---- this lane group's row: entry count, query time, ring records; the first chunk of neighbour
+    // ---- this lane group's row: entry count, query time, ring records; the first chunk of cached
     // rows is requested now and arrives while the projections below run
     const uint32_t local = wave * 4u + grp;
     const uint32_t cnt = s_cnt[local];
@@ -324,11 +315,13 @@ __global__ __launch_bounds__(256, 2) void layer_kernel(LayerArgs a, const uint32
       for (int jc = 0; jc < JC; ++jc) {
         const uint32_t j = c * JC + jc;
         const RingEntry e = rrow[j < k ? j : k - 1u];
-        const float* hrow = a.Hin + (size_t)e.nbr * a.ld_in + 4u * sub;
-        const float* erow = a.efeat + (size_t)e.eid * a.ld_ef + 4u * sub;
+        const float* nrow = a.KVn + (size_t)e.nbr * a.ld_kv + 4u * sub;
+        const float* erow = a.KVe + (size_t)e.eid * a.ld_kve + 4u * sub;
 #pragma unroll
-        for (int s = 0; s < NG; ++s)
-          zb.g[jc][s] = *reinterpret_cast<const float4*>((a.kind[s] == 0 ? hrow : erow) + a.segoff[s]);
+        for (int s = 0; s < 2 * KS; ++s) {
+          zb.n[jc][s] = *reinterpret_cast<const float4*>(nrow + s * kSlot);
+          zb.e[jc][s] = *reinterpret_cast<const float4*>(erow + s * kSlot);
+        }
       }
     };
     ZBuf z0;
@@ -346,27 +339,27 @@ __global__ __launch_bounds__(256, 2) void layer_kernel(LayerArgs a, const uint32
         if ((t == 0 || two) && col < a.d_emb) {
           const float cq = a.cQ[col];
           const uint32_t h = col / dk;
-          float* qp = Qs + m16_row(lane, 0) * ll.ldq + h * ll.dkp + (col - h * dk);
+          float* qp = Qs + m16_row(lane, 0) * ll.ldq + h * (SH * kSlot) + (col - h * dk);
 #pragma unroll
           for (int r = 0; r < 4; ++r) qp[r * ll.ldq] = acc[t][r] + cq;
         }
       }
     }
-    // ================================================================ phase 2: qt_h = q_h W_K,h^T / sqrt(dk)
+    // ================================================================ phase 2: qt_h = q_h W_K,h[time]^T
     {
       Ops16<2> o2;
       Unit2 ua = decode2(0);                                  // weights of the first unit are requested
       load_b16(wkt(ua.h, ua.t0), 0, o2.b[0]);                 // ahead of the barrier (unit 0 of an idle wave: head 0, tile 0)
       load_b16(wkt(ua.h, ua.t1), 0, o2.b[1]);
       __syncthreads();
-      if (c_dk == 1) {
+      if constexpr (SH == 1) {
         // one chunk per unit: the operands of the next unit are in flight during this unit's products
-        load_a16(Qs + ua.h * ll.dkp + a_q, 0, o2.a);
+        load_a16(Qs + ua.h * kSlot + a_q, 0, o2.a);
         if (nu2) pingpong_peeled<Ops16<2>>(
             nu2, o2,
             [&](uint32_t i, Ops16<2>& o) {
               const Unit2 u = decode2(i);
-              load_a16(Qs + u.h * ll.dkp + a_q, 0, o.a);
+              load_a16(Qs + u.h * kSlot + a_q, 0, o.a);
               load_b16(wkt(u.h, u.t0), 0, o.b[0]);
               load_b16(wkt(u.h, u.t1), 0, o.b[1]);
             },
@@ -381,7 +374,8 @@ __global__ __launch_bounds__(256, 2) void layer_kernel(LayerArgs a, const uint32
           ua = decode2(i);
           const float* const Bt[2] = {wkt(ua.h, ua.t0), wkt(ua.h, ua.t1)};
           floatx4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
-          mfma16_gemm<2>(Qs + ua.h * ll.dkp + a_q, c_dk, Bt, acc);
+          if (i) { load_b16(Bt[0], 0, o2.b[0]); load_b16(Bt[1], 0, o2.b[1]); }
+          mfma16_gemm_pre<2>(Qs + ua.h * (SH * kSlot) + a_q, SH, Bt, acc, o2);
           store2(ua, acc);
         }
       }
@@ -389,24 +383,25 @@ __global__ __launch_bounds__(256, 2) void layer_kernel(LayerArgs a, const uint32
     __syncthreads();
     // ================================================================ phase 3: gather + attention
     {
-      float4 acc[H][NS];
+      float4 accv[KS], accp[H][NT];
+#pragma unroll
+      for (int s = 0; s < KS; ++s) accv[s] = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
       for (int h = 0; h < H; ++h)
 #pragma unroll
-        for (int s = 0; s < NS; ++s) acc[h][s] = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int t = 0; t < NT; ++t) accp[h][t] = make_float4(0.f, 0.f, 0.f, 0.f);
       float mref[H], lrun[H];
 #pragma unroll
       for (int h = 0; h < H; ++h) { mref[h] = -INFINITY; lrun[h] = 0.0f; }
-      // this lane's share of the row's qt vectors stays in registers for the whole phase
-      const float* zq = Zs + local * ll.ldz + 4u * sub;       // float4 of slot s, head h: + h Zp + 64 s
-      constexpr bool QREG = H * NS <= 16;                     // otherwise the registers go to the accumulators
-      float4 qt[QREG ? H : 1][QREG ? NS : 1];
-      if constexpr (QREG) {
+      // this lane's share of the row's q and qt vectors stays in registers for the whole phase
+      float4 qk[KS], qt[H][NT];
 #pragma unroll
-        for (int h = 0; h < H; ++h)
+      for (int s = 0; s < KS; ++s) qk[s] = *reinterpret_cast<const float4*>(Qs + local * ll.ldq + s * kSlot + 4u * sub);
 #pragma unroll
-          for (int s = 0; s < NS; ++s) qt[h][s] = *reinterpret_cast<const float4*>(zq + h * Zp + s * kSlot);
-      }
+      for (int h = 0; h < H; ++h)
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+          qt[h][t] = *reinterpret_cast<const float4*>(Zs + local * ll.ldz + h * Ztp + t * kSlot + 4u * sub);
       auto attend = [&](uint32_t c, const ZBuf& zb) {
         // time encodings of the chunk's entries (computed for every lane, then masked: no branches)
         float4 zt[JC][NT];
@@ -436,26 +431,24 @@ __global__ __launch_bounds__(256, 2) void layer_kernel(LayerArgs a, const uint32
             zt[jc][t] = zz;
           }
         }
-        // scores
+        // scores: q . (cached node keys + cached edge keys) + qt . phi
         float sc[JC][H];
 #pragma unroll
         for (int h = 0; h < H; ++h) {
-          float p[JC];
-#pragma unroll
-          for (int jc = 0; jc < JC; ++jc) p[jc] = 0.0f;
-#pragma unroll
-          for (int s = 0; s < NS; ++s) {
-            float4 qv;
-            if constexpr (QREG) qv = qt[h][s];
-            else qv = *reinterpret_cast<const float4*>(zq + h * Zp + s * kSlot);
-#pragma unroll
-            for (int jc = 0; jc < JC; ++jc)
-              p[jc] = dot4(qv, s < NG ? zb.g[jc][s < NG ? s : 0] : zt[jc][s < NG ? 0 : s - NG], p[jc]);
-          }
 #pragma unroll
           for (int jc = 0; jc < JC; ++jc) {
-            const float t = row16_sum(p[jc]);
-            sc[jc][h] = vj[jc] ? t : -INFINITY;
+            float p = 0.0f;
+#pragma unroll
+            for (int s = h * SH; s < (h + 1) * SH; ++s) {
+              float4 kk;
+              kk.x = zb.n[jc][s].x + zb.e[jc][s].x; kk.y = zb.n[jc][s].y + zb.e[jc][s].y;
+              kk.z = zb.n[jc][s].z + zb.e[jc][s].z; kk.w = zb.n[jc][s].w + zb.e[jc][s].w;
+              p = dot4(qk[s], kk, p);
+            }
+#pragma unroll
+            for (int t = 0; t < NT; ++t) p = dot4(qt[h][t], zt[jc][t], p);
+            const float tsum = row16_sum(p);
+            sc[jc][h] = vj[jc] ? tsum : -INFINITY;
           }
         }
         // softmax against a reference score that only moves when a score exceeds it by a wide
@@ -477,8 +470,12 @@ __global__ __launch_bounds__(256, 2) void layer_kernel(LayerArgs a, const uint32
             const float scale = mv ? __expf(mref[h] - mnew) : 1.0f;     // exp(-inf) = 0 on the first move
             lrun[h] *= scale;
 #pragma unroll
-            for (int s = 0; s < NS; ++s) {
-              acc[h][s].x *= scale; acc[h][s].y *= scale; acc[h][s].z *= scale; acc[h][s].w *= scale;
+            for (int s = h * SH; s < (h + 1) * SH; ++s) {
+              accv[s].x *= scale; accv[s].y *= scale; accv[s].z *= scale; accv[s].w *= scale;
+            }
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+              accp[h][t].x *= scale; accp[h][t].y *= scale; accp[h][t].z *= scale; accp[h][t].w *= scale;
             }
             mref[h] = mnew;
           }
@@ -490,37 +487,51 @@ __global__ __launch_bounds__(256, 2) void layer_kernel(LayerArgs a, const uint32
             const float p = vj[jc] ? __expf(sc[jc][h] - mref[h]) : 0.0f;
             lrun[h] += p;
 #pragma unroll
-            for (int s = 0; s < NS; ++s) {
-              const float4 zv = s < NG ? zb.g[jc][s < NG ? s : 0] : zt[jc][s < NG ? 0 : s - NG];
-              acc[h][s].x = fmaf(p, zv.x, acc[h][s].x);
-              acc[h][s].y = fmaf(p, zv.y, acc[h][s].y);
-              acc[h][s].z = fmaf(p, zv.z, acc[h][s].z);
-              acc[h][s].w = fmaf(p, zv.w, acc[h][s].w);
+            for (int s = h * SH; s < (h + 1) * SH; ++s) {
+              const float4 vn = zb.n[jc][KS + s], ve = zb.e[jc][KS + s];
+              accv[s].x = fmaf(p, vn.x + ve.x, accv[s].x);
+              accv[s].y = fmaf(p, vn.y + ve.y, accv[s].y);
+              accv[s].z = fmaf(p, vn.z + ve.z, accv[s].z);
+              accv[s].w = fmaf(p, vn.w + ve.w, accv[s].w);
+            }
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+              const float4 zv = zt[jc][t];
+              accp[h][t].x = fmaf(p, zv.x, accp[h][t].x);
+              accp[h][t].y = fmaf(p, zv.y, accp[h][t].y);
+              accp[h][t].z = fmaf(p, zv.z, accp[h][t].z);
+              accp[h][t].w = fmaf(p, zv.w, accp[h][t].w);
             }
           }
         }
       };
       if (nchunk3) pingpong_clamped<ZBuf>(nchunk3, z0, gather, attend);
-      // zb overwrites qt (each lane owns its float4s; padding lanes hold zeros)
-      float* zw = Zs + local * ll.ldz + 4u * sub;
+      // the cached-value part of the head outputs goes into the O tile (padded-head layout; the
+      // padding lanes hold exact zeros), pb overwrites qt (each lane owns its float4s)
 #pragma unroll
       for (int h = 0; h < H; ++h) {
         const float inv = cnt ? 1.0f / lrun[h] : 0.0f;
 #pragma unroll
-        for (int s = 0; s < NS; ++s) {
-          float4 o = acc[h][s];
+        for (int s = h * SH; s < (h + 1) * SH; ++s) {
+          float4 o = accv[s];
           o.x *= inv; o.y *= inv; o.z *= inv; o.w *= inv;
-          *reinterpret_cast<float4*>(zw + h * Zp + s * kSlot) = o;
+          *reinterpret_cast<float4*>(Xs + local * ll.ldx + s * kSlot + 4u * sub) = o;
+        }
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+          float4 o = accp[h][t];
+          o.x *= inv; o.y *= inv; o.z *= inv; o.w *= inv;
+          *reinterpret_cast<float4*>(Zs + local * ll.ldz + h * Ztp + t * kSlot + 4u * sub) = o;
         }
       }
     }
-    // ================================================================ phase 4: o_h = zb_h W_V,h
+    // ================================================================ phase 4: o_h += pb_h W_V,h[time]
     {
-      // K runs over the slots, one chunk per slot; the operands of the next slot are in flight
+      // K runs over the time slots, one chunk per slot; the operands of the next slot are in flight
       // during the current one.  The weights of the first slot are requested ahead of the barrier.
       Ops16<2> ov[2];
       uint32_t x = wave;
-      auto wv = [&](uint32_t h, uint32_t nt) { return a.WV + (size_t)(h * ntk + nt) * g_z * kGrpFloats; };
+      auto wv = [&](uint32_t h, uint32_t nt) { return a.WV + (size_t)(h * ntk + nt) * g_zt * kGrpFloats; };
       uint32_t h4 = 0, n0 = 0, n1 = 0;
       bool two4 = false;
       auto decode4 = [&](uint32_t xx) {
@@ -533,21 +544,21 @@ __global__ __launch_bounds__(256, 2) void layer_kernel(LayerArgs a, const uint32
       load_b16(wv(h4, n0), 0, ov[0].b[0]);
       load_b16(wv(h4, n1), 0, ov[0].b[1]);
       __syncthreads();
-      if (pf_ok) stage_b(); else stage_none();                // next tile's rows, in flight during phases 4 and 5
+      if (pf_ok) stage_b(); else stage_none();                // next tile's rows, in flight during phases 4 to 6
       for (; x < nunits4; x += 4) {
         if (x != wave) {
           decode4(x);
           load_b16(wv(h4, n0), 0, ov[0].b[0]);
           load_b16(wv(h4, n1), 0, ov[0].b[1]);
         }
-        const float* Ap = Zs + h4 * Zp + a_z;
+        const float* Ap = Zs + h4 * Ztp + a_z;
         const float* B0 = wv(h4, n0);
         const float* B1 = wv(h4, n1);
         load_a16(Ap, 0, ov[0].a);
         floatx4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
-        for (int c = 0; c < NS; ++c) {
-          if (c + 1 < NS) {
+        for (int c = 0; c < NT; ++c) {
+          if (c + 1 < NT) {
             load_a16(Ap, (c + 1) * kCG, ov[(c + 1) & 1].a);
             load_b16(B0, (c + 1) * kCG, ov[(c + 1) & 1].b[0]);
             load_b16(B1, (c + 1) * kCG, ov[(c + 1) & 1].b[1]);
@@ -560,9 +571,9 @@ __global__ __launch_bounds__(256, 2) void layer_kernel(LayerArgs a, const uint32
         for (int t = 0; t < 2; ++t) {
           const uint32_t col = (t ? n1 : n0) * 16 + m16_col(lane);
           if ((t == 0 || two4) && col < dk) {
-            float* op = Xs + c_off_x - m16_col(lane) + h4 * dk + col;
+            float* op = Xs + c_off_x - m16_col(lane) + h4 * (SH * kSlot) + col;    // one lane per (row, column)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) op[r * ll.ldx] = acc[t][r];
+            for (int r = 0; r < 4; ++r) op[r * ll.ldx] += acc[t][r];
           }
         }
       }
@@ -570,15 +581,15 @@ __global__ __launch_bounds__(256, 2) void layer_kernel(LayerArgs a, const uint32
     // ================================================================ phase 5: h' = o W_O + b_O
     {
       Ops16<2> oo;
-      load_b16(a.WO + (size_t)w1 * g_de * kGrpFloats, 0, oo.b[0]);
-      load_b16(a.WO + (size_t)(w1 + 4 < ntd ? w1 + 4 : w1) * g_de * kGrpFloats, 0, oo.b[1]);
+      load_b16(a.WO + (size_t)w1 * g_o * kGrpFloats, 0, oo.b[0]);
+      load_b16(a.WO + (size_t)(w1 + 4 < ntd ? w1 + 4 : w1) * g_o * kGrpFloats, 0, oo.b[1]);
       __syncthreads();
       for (uint32_t nt = wave; nt < ntd; nt += 8) {
         const bool two = nt + 4 < ntd;
-        const float* const Bt[2] = {a.WO + (size_t)nt * g_de * kGrpFloats, a.WO + (size_t)(two ? nt + 4 : nt) * g_de * kGrpFloats};
+        const float* const Bt[2] = {a.WO + (size_t)nt * g_o * kGrpFloats, a.WO + (size_t)(two ? nt + 4 : nt) * g_o * kGrpFloats};
         floatx4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
         if (nt != wave) { load_b16(Bt[0], 0, oo.b[0]); load_b16(Bt[1], 0, oo.b[1]); }
-        mfma16_gemm_pre<2>(Xs + a_x, c_de, Bt, acc, oo);
+        mfma16_gemm_pre<2>(Xs + a_x, KS, Bt, acc, oo);
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
           const uint32_t col = (nt + 4 * t) * 16 + m16_col(lane);
@@ -587,8 +598,33 @@ __global__ __launch_bounds__(256, 2) void layer_kernel(LayerArgs a, const uint32
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
               const uint32_t node = s_node[m16_row(lane, r)];
-              if (node != 0xFFFFFFFFu) a.Hout[(size_t)node * a.ld_out + col] = acc[t][r] + b;
+              const float v = acc[t][r] + b;
+              if (node != 0xFFFFFFFFu) a.Hout[(size_t)node * a.ld_out + col] = v;
+              Qs[c_off_q - m16_col(lane) + r * ll.ldq + col] = v;     // operand of phase 6 (q is no longer needed)
             }
+          }
+        }
+      }
+    }
+    // ================================================================ phase 6: next layer's cached keys | values of these rows
+    if (a.KVout) {
+      constexpr uint32_t ntkv = 8u * KS;                      // column tiles of a cached row; a wave takes tiles w + 8 i, w + 8 i + 4
+      Ops16<2> ok;
+      load_b16(a.WKVnext + (size_t)wave * g_de * kGrpFloats, 0, ok.b[0]);
+      load_b16(a.WKVnext + (size_t)(wave + 4) * g_de * kGrpFloats, 0, ok.b[1]);
+      __syncthreads();
+      for (uint32_t nt = wave; nt < ntkv; nt += 8) {
+        const float* const Bt[2] = {a.WKVnext + (size_t)nt * g_de * kGrpFloats, a.WKVnext + (size_t)(nt + 4) * g_de * kGrpFloats};
+        floatx4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+        if (nt != wave) { load_b16(Bt[0], 0, ok.b[0]); load_b16(Bt[1], 0, ok.b[1]); }
+        mfma16_gemm_pre<2>(Qs + a_q, c_de, Bt, acc, ok);
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+          const uint32_t col = (nt + 4 * t) * 16 + m16_col(lane);   // every column is written: padding columns get exact zeros
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const uint32_t node = s_node[m16_row(lane, r)];
+            if (node != 0xFFFFFFFFu) a.KVout[(size_t)node * a.ld_kv + col] = acc[t][r];
           }
         }
       }
@@ -604,51 +640,56 @@ __global__ __launch_bounds__(256, 2) void layer_kernel(LayerArgs a, const uint32
   if (blockIdx.x == 0 && threadIdx.x == 0 && n) atomicAdd((unsigned long long*)&a.ctrl->tot_rows, (unsigned long long)n);
 }
 
-// ---- dispatch over (slots, time slots, heads, chunk)
+// ---- dispatch over (heads, key slots, time slots)
 struct LaunchArgs {
   LayerArgs k;
   hipStream_t s; const uint32_t* rows; const uint32_t* cp; uint32_t cm;
-  uint32_t nt;                      // time slots of this layer
-  uint32_t grid_cap;                // workgroups that are resident at once (two per CU)
+  uint32_t ks, nt, heads;
+  uint32_t num_cu;                  // compute units of the device
   bool set_attr; size_t lds; hipError_t err;
+  int query_wgs; uint32_t wgs;      // query_wgs: only report the workgroups per CU of the variant in `wgs`
 };
 
-template <int NS, int NT, int H, int JC>
+template <int KS, int NT, int H, int JC, int WGS>
 void go(LaunchArgs& a) {
-  auto kern = layer_kernel<NS, NT, H, JC>;
+  auto kern = layer_kernel<KS, NT, H, JC, WGS>;
+  if (a.query_wgs) { a.wgs = WGS; return; }
   if (a.set_attr) {
     a.err = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)a.lds);
     return;
   }
   uint64_t blocks = ((uint64_t)a.cm + kTM - 1) / kTM;
-  if (blocks > a.grid_cap) blocks = a.grid_cap;   // persistent: each workgroup strides over the tiles, staging one tile ahead
+  const uint64_t cap = (uint64_t)WGS * (a.num_cu ? a.num_cu : 256u);   // persistent: each workgroup strides over the tiles,
+  if (blocks > cap) blocks = cap;                                      // staging one tile ahead
   if (blocks < 1) blocks = 1;
   hipLaunchKernelGGL(kern, dim3((uint32_t)blocks), dim3(256), a.lds, a.s, a.k, a.rows, a.cp, a.cm);
 }
 
-template <int NS, int NT>
-void go_h(LaunchArgs& a) {
-  // ring entries per chunk are bounded by registers (two chunks of JC * NS float4 per lane in flight,
-  // beside 2 * H * NS float4 of accumulators and qt values)
-  switch (a.k.heads) {
-    case 1: go<NS, NT, 1, (NS <= 4 ? 4 : NS == 5 ? 2 : 1)>(a); break;
-    case 2: go<NS, NT, 2, (NS <= 4 ? 2 : 1)>(a); break;
-    default: go<NS, NT, 4, 1>(a); break;
-  }
+// Ring entries per chunk and workgroups per CU are bounded by registers: two chunks of JC * 4 KS
+// float4 per lane are in flight beside 2 (KS + H NT) float4 of accumulators and query values.
+template <int KS, int NT, int H>
+void go_jc(LaunchArgs& a) {
+  if constexpr (KS == 1) go<KS, NT, H, 2, 3>(a);
+  else if constexpr (KS == 2) go<KS, NT, H, 1, 2>(a);
+  else go<KS, NT, H, 1, 2>(a);
 }
 
-template <int NS>
-void go_nt(LaunchArgs& a) {
-  if constexpr (NS >= 3) {
-    if (a.nt == 2) { go_h<NS, 2>(a); return; }
+template <int H>
+void go_h(LaunchArgs& a) {
+  const uint32_t sh = a.ks / H;
+  if (a.nt == 1) {
+    if (sh == 1) go_jc<H, 1, H>(a);
+    else if constexpr (H <= 2) { if (sh == 2) go_jc<2 * H, 1, H>(a); else if constexpr (H == 1) go_jc<4, 1, 1>(a); }
+  } else {
+    if (sh == 1) go_jc<H, 2, H>(a);
+    else if constexpr (H <= 2) { if (sh == 2) go_jc<2 * H, 2, H>(a); else if constexpr (H == 1) go_jc<4, 2, 1>(a); }
   }
-  go_h<NS, 1>(a);
 }
 
 }  // namespace layer_impl
 
-// one translation unit per slot count instantiates this (keeps the build parallel)
-template <int NS>
-void layer_entry(layer_impl::LaunchArgs& a) { layer_impl::go_nt<NS>(a); }
+// one translation unit per head count instantiates this (keeps the build parallel)
+template <int H>
+void layer_entry(layer_impl::LaunchArgs& a) { layer_impl::go_h<H>(a); }
 
 }  // namespace stgn

@@ -56,33 +56,33 @@ struct Table {
   uint32_t ld;
 };
 
-// Packed parameters of one attention layer (device pointers)
-// The attention input z = [h_u | e | phi(dt)] is kept in a slot layout: each of the three segments
-// is padded to a multiple of 64 floats (one slot = 16 lanes x float4), so a slot never mixes
-// segments.  Zp = 64 * ns floats per head.
+// Packed parameters of one attention layer (device pointers).
+//
+// Keys and values are linear in the attention input z_j = [h_{u_j} | e_j | phi(dt)], so they split by
+// input block (paper Eq. attn_detail):  K_j = h_{u_j} W_K[node rows] + e_j W_K[edge rows] + phi W_K[time rows].
+// The first term depends on the neighbour alone and the second on the edge alone; both are kept as
+// cached rows (KV tables below: per node and layer, refreshed whenever the node's input row changes;
+// per edge and layer, written once when the edge arrives).  Only the time term depends on the pair and
+// is evaluated re-associated:  q_h . (phi W_K,h) = (W_K,h[time] q_h) . phi  and
+// sum_j a_j (phi_j W_V,h) = (sum_j a_j phi_j) W_V,h[time], so every dense product runs over rows, not
+// over (row, neighbour) pairs.
+//
+// A cached row holds [keys | values]; each head occupies whole slots of 64 floats (one slot = 16
+// lanes x float4), columns past dk are exact zeros: ld_kv = 2 * 64 * ks floats, ks = heads * ceil(dk / 64).
 constexpr uint32_t kSlot = 64;
-constexpr uint32_t kMaxSlots = 8;
+constexpr uint32_t kMaxKeySlots = 4;     // ks
+constexpr uint32_t kMaxTimeSlots = 2;    // ceil(d_time / 64)
 struct LayerDev {
-  uint32_t d_in, d_in2;          // input width, padded to even
-  uint32_t Zdim, Zp;             // d_in + d_edge + d_time; padded (slot layout) width
-  uint32_t ns, nt;               // slots in total, time slots (the last nt of them)
-  uint8_t  kind[kMaxSlots];      // 0 node row, 1 edge-feature row, 2 time encoding
-  uint16_t valid[kMaxSlots];     // valid floats in the slot (1..64)
-  uint16_t segoff[kMaxSlots];    // offset of the slot inside its segment's source row
-  const float* WQn;              // [d_in4 x Np(d_emb)]            node block of W_Q (K padded to 4, columns to 16)
-  const float* cQ;               // [d_emb]                        phi(0) * (time block of W_Q)
-  const float* WKT;              // [heads][dk4 x Zp]              (W_K head block)^T / sqrt(dk); time rows * sqrt(1/d_t)
-  const float* WV;               // [heads][Zp x Np(dk)]           W_V head block; time rows * sqrt(1/d_t)
-  const float* WO;               // [d_emb2 x Np(d_emb)]
+  uint32_t d_in;                 // input width
+  const float* WQn;              // [d_in x d_emb]            node block of W_Q / sqrt(dk)
+  const float* cQ;               // [d_emb]                   phi(0) * (time block of W_Q) / sqrt(dk)
+  const float* WKT;              // [dk x heads * 64 nt]      (time rows of W_K, head block)^T * sqrt(1/d_t)
+  const float* WV;               // [64 nt x heads * R16(dk)] time rows of W_V, head block, * sqrt(1/d_t)
+  const float* WO;               // [64 ks x d_emb]           rows in the padded-head layout of the head outputs
   const float* bO;               // [d_emb]
+  const float* WKVn;             // [d_in x 128 ks]           node rows of [W_K | W_V] in the cached-row layout
+  const float* WKVe;             // [d_edge x 128 ks]         edge rows of [W_K | W_V] (null without edge features)
 };
-
-// position of original column z of [h_u | e | phi] in the slot layout
-inline __host__ __device__ uint32_t slot_pos(uint32_t z, uint32_t d_in, uint32_t d_edge) {
-  const uint32_t e0 = (d_in + kSlot - 1) / kSlot * kSlot;
-  const uint32_t t0 = e0 + (d_edge + kSlot - 1) / kSlot * kSlot;
-  return z < d_in ? z : z < d_in + d_edge ? e0 + (z - d_in) : t0 + (z - d_in - d_edge);
-}
 
 struct Dev {
   // configuration
@@ -100,6 +100,10 @@ struct Dev {
   uint32_t* pool_eid;                // adjacency pool: edge id
   uint32_t* blk;                     // [N x maxb] block bases in units of kMinBlock entries
   Table    efeat;                    // [max_edges x ld]
+  // cached key|value rows (see LayerDev): KV[l] of the rows of H[l], KVE[l] of the edge features
+  Table    KV[STGN_MAX_LAYERS];      // [N x ld_kv]
+  Table    KVE[STGN_MAX_LAYERS];     // [max_edges x ld_kv]; one zero row (ld 0) without edge features
+  uint32_t sh, ks, nt, ld_kv;        // slots per head, key slots, time slots, floats per cached row
   double*  ets;                      // [max_edges] edge timestamps
   // per-batch scratch
   Ctrl*    ctrl;
@@ -138,7 +142,7 @@ inline __host__ __device__ uint32_t round_up(uint32_t x, uint32_t m) { return (x
 
 // Kernel classes for the optional event timing
 enum KernelClass { KC_SORT = 0, KC_MEMORY, KC_APPLY, KC_PLAN, KC_EXPAND, KC_COMPACT, KC_LAYER,
-                   KC_GATHER, KC_NOOP, KC_COUNT };
+                   KC_GATHER, KC_NOOP, KC_PROJECT, KC_COUNT };
 
 // ---- launch wrappers (one per kernel family), defined in the .hip files ----
 void launch_stage_sort(const Dev& d, hipStream_t s, uint32_t n, const uint32_t* src, const uint32_t* dst,
@@ -156,7 +160,10 @@ void launch_gather_rows(const Dev& d, hipStream_t s, uint32_t layer, uint32_t n,
 void launch_init_state(const Dev& d, hipStream_t s);
 void launch_zero(float* p, size_t n, hipStream_t s);
 void launch_noop(hipStream_t s);
-int  attn_supported(uint32_t d_in, uint32_t d_edge, uint32_t d_time, uint32_t heads);
+int  attn_supported(uint32_t d_emb, uint32_t d_time, uint32_t heads);
+// cached key|value rows: of the batch's endpoints (layer 0) and edges (every layer), or of all nodes (layer 0)
+void launch_project_batch(const Dev& d, hipStream_t s, const float* ef);
+void launch_project_nodes(const Dev& d, hipStream_t s);
 constexpr size_t kMaxLds = 160 * 1024;   // LDS per workgroup on gfx950
 int  setup_ingest_attributes(const Dev& d);
 int  setup_embed_attributes(const Dev& d);
