@@ -174,7 +174,15 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
   };
   // ---- phase-4 work units: (head, pair of head-output column tiles)
   const uint32_t np4 = (ntk + 1u) >> 1, nunits4 = H * np4;
-  // ---- phases 1 and 5: column tiles nt and nt + 4 of the d_emb outputs form a unit
+  // ---- phases 1 and 5: column tiles nt and nt + 4 of the d_emb outputs form a unit; the bias values of
+  // a wave's first unit stay in registers (further units, d_emb > 128, read theirs when they get there)
+  float cq_r[2], bo_r[2];
+#pragma unroll
+  for (int t = 0; t < 2; ++t) {
+    const uint32_t col = (wave + 4 * t) * 16 + m16_col(lane);
+    cq_r[t] = col < a.d_emb ? a.cQ[col] : 0.0f;
+    bo_r[t] = col < a.d_emb ? a.bO[col] : 0.0f;
+  }
   __syncthreads();
 
   // ---- staging of a tile, one tile ahead.  Stage A reads the tile's row ids into s_next; stage B
@@ -337,7 +345,7 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
       for (int t = 0; t < 2; ++t) {
         const uint32_t col = (nt + 4 * t) * 16 + m16_col(lane);
         if ((t == 0 || two) && col < a.d_emb) {
-          const float cq = a.cQ[col];
+          const float cq = nt == wave ? cq_r[t] : a.cQ[col];
           const uint32_t h = col / dk;
           float* qp = Qs + m16_row(lane, 0) * ll.ldq + h * (SH * kSlot) + (col - h * dk);
 #pragma unroll
@@ -394,14 +402,10 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
 #pragma unroll
       for (int h = 0; h < H; ++h) { mref[h] = -INFINITY; lrun[h] = 0.0f; }
       // this lane's share of the row's q and qt vectors stays in registers for the whole phase
-      float4 qk[KS], qt[H][NT];
+      float4 qk[KS];
 #pragma unroll
       for (int s = 0; s < KS; ++s) qk[s] = *reinterpret_cast<const float4*>(Qs + local * ll.ldq + s * kSlot + 4u * sub);
-#pragma unroll
-      for (int h = 0; h < H; ++h)
-#pragma unroll
-        for (int t = 0; t < NT; ++t)
-          qt[h][t] = *reinterpret_cast<const float4*>(Zs + local * ll.ldz + h * Ztp + t * kSlot + 4u * sub);
+      const float* zq = Zs + local * ll.ldz + 4u * sub;       // qt of head h, time slot t: + h Ztp + 64 t (read per chunk)
       auto attend = [&](uint32_t c, const ZBuf& zb) {
         // time encodings of the chunk's entries (computed for every lane, then masked: no branches)
         float4 zt[JC][NT];
@@ -446,7 +450,7 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
               p = dot4(qk[s], kk, p);
             }
 #pragma unroll
-            for (int t = 0; t < NT; ++t) p = dot4(qt[h][t], zt[jc][t], p);
+            for (int t = 0; t < NT; ++t) p = dot4(*reinterpret_cast<const float4*>(zq + h * Ztp + t * kSlot), zt[jc][t], p);
             const float tsum = row16_sum(p);
             sc[jc][h] = vj[jc] ? tsum : -INFINITY;
           }
@@ -594,7 +598,7 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
         for (int t = 0; t < 2; ++t) {
           const uint32_t col = (nt + 4 * t) * 16 + m16_col(lane);
           if ((t == 0 || two) && col < a.d_emb) {
-            const float b = a.bO[col];
+            const float b = nt == wave ? bo_r[t] : a.bO[col];
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
               const uint32_t node = s_node[m16_row(lane, r)];
