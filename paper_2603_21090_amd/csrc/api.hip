@@ -138,6 +138,7 @@ size_t layout(const stgn_config& c, char* base, Dev* d) {
   d->efeat.base = b.take<float>((size_t)c.max_edges * d->efeat.ld);
   d->ets = b.take<double>(c.max_edges);
   d->sh = (d->dk + kSlot - 1) / kSlot;
+  if (d->sh == 3) d->sh = 4;                                  // kernel variants exist for 1, 2 and 4 slots per head
   d->ks = c.heads * d->sh;
   d->nt = (c.d_time + kSlot - 1) / kSlot;
   d->ld_kv = 2 * kSlot * d->ks;

@@ -129,7 +129,8 @@ void go_heads(LaunchArgs& a) {
 // the time encoding takes at most two
 int attn_supported(uint32_t d_emb, uint32_t d_time, uint32_t heads) {
   if (!(heads == 1 || heads == 2 || heads == 4) || d_emb == 0 || d_emb % heads) return 0;
-  const uint32_t sh = (d_emb / heads + kSlot - 1) / kSlot;
+  uint32_t sh = (d_emb / heads + kSlot - 1) / kSlot;
+  if (sh == 3) sh = 4;
   return d_time >= 1 && d_time <= kMaxTimeSlots * kSlot && heads * sh <= kMaxKeySlots;
 }
 

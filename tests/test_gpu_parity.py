@@ -104,6 +104,9 @@ def test_c1_full_stream(binding):
     dict(layers=2, d_mem=100, d_edge=172, d_time=100, d_emb=100, d_msg=100, heads=2, k=10),   # the paper's widths
     dict(layers=2, d_mem=0, d_node=100, d_edge=64, d_time=100, d_emb=100, heads=2, k=20),     # config-5 widths
     dict(layers=1, d_mem=136, d_edge=20, d_time=24, d_emb=32, d_msg=140, heads=2, k=3),       # wide memory: chunked GRU path
+    dict(layers=2, d_mem=12, d_edge=9, d_time=70, d_emb=130, d_msg=16, heads=1, k=3),         # one wide head: three key slots rounded to four
+    dict(layers=2, d_mem=0, d_node=20, d_edge=0, d_time=16, d_emb=140, heads=2, k=4),         # two slots per head, no edge features
+    dict(layers=3, d_mem=16, d_edge=5, d_time=100, d_emb=100, d_msg=16, heads=1, k=3),        # one 100-wide head (two key slots), two time slots
 ])
 def test_small_graphs_all_shapes(binding, kw):
     w = tiny_workload(num_nodes=150, num_edges=1500, batch=50, zipf_s=1.0, **kw)
