@@ -34,21 +34,42 @@ MFMA_F32_PEAK_TFLOPS = 157.3   # MI355X dense fp32 matrix, published
 
 
 def algorithmic_bytes(w, rows, entries):
-    """Bytes one attention layer must move for `rows` target rows that hold `entries` recent-
-    neighbour records in total: per row the own layer-input row, the last-interaction time and the
-    output row; per record the 16-byte ring entry, one neighbour row and one edge-feature row
-    (fp32).  With full rings (entries = k * rows) this is the per-(node, layer) figure
-    4 d + 8 + 4 d + k (16 + 4 d + 4 d_edge)."""
+    """Bytes one attention layer must move, by the plain definition of the layer, for `rows` target
+    rows that hold `entries` recent-neighbour records in total: per row the own layer-input row, the
+    last-interaction time and the output row; per record the 16-byte ring entry, one neighbour row
+    and one edge-feature row (fp32).  With full rings (entries = k * rows) this is the
+    per-(node, layer) figure 4 d + 8 + 4 d + k (16 + 4 d + 4 d_edge)."""
     d_in = np.mean([(w.d_mem + w.d_node) if l == 0 else w.d_emb for l in range(w.layers)])
     return rows * (4 * d_in + 8 + 4 * w.d_emb) + entries * (16 + 4 * d_in + 4 * w.d_edge)
 
 
+def cached_row_floats(w):
+    """Floats of one cached key|value row: every head takes whole 64-float slots (1, 2 or 4 of them)."""
+    sh = -(-(w.d_emb // w.heads) // 64)
+    sh = 4 if sh == 3 else sh
+    return 2 * 64 * w.heads * sh
+
+
+def layout_bytes(w, rows, entries):
+    """Bytes the layer kernel's own data layout moves: per record the ring entry and two cached
+    key|value rows (the neighbour's and the edge's) instead of the raw rows; per target row its input
+    row, time, output row and, for every layer but the last, its own cached row for the next layer."""
+    d_in = np.mean([(w.d_mem + w.d_node) if l == 0 else w.d_emb for l in range(w.layers)])
+    kv = 4 * cached_row_floats(w)
+    per_row = 4 * d_in + 8 + 4 * w.d_emb + kv * (w.layers - 1) / w.layers
+    return rows * per_row + entries * (16 + kv * (2 if w.d_edge else 1))
+
+
 def projection_flops_per_row(w, layer):
-    """FLOPs the re-associated projections execute for one (node, layer), by kernel."""
+    """FLOPs of the dense products the layer kernel executes for one (node, layer), padding not
+    counted: the query; the time parts of keys and values, re-associated; the output projection; and,
+    for every layer but the last, the row's cached keys and values for the next layer.  (The node and
+    edge parts of keys and values are cached rows: computed once per changed row / once per edge.)"""
     d_in = (w.d_mem + w.d_node) if layer == 0 else w.d_emb
-    z = d_in + w.d_edge + w.d_time
-    q = 2 * (d_in * w.d_emb + w.d_emb * z)          # q, then q W_K^T per head (heads * dk = d_emb)
-    o = 2 * (z * w.d_emb + w.d_emb * w.d_emb)       # zb W_V per head, then W_O
+    q = 2 * (d_in * w.d_emb + w.d_emb * w.d_time)                 # q, then qt_h = W_K,h[time] q_h
+    o = 2 * (w.d_time * w.d_emb + w.d_emb * w.d_emb)              # pb_h W_V,h[time], then W_O
+    if layer + 1 < w.layers:
+        o += 2 * (w.d_emb * 2 * w.d_emb)                          # cached keys | values of the next layer
     return q, o
 
 
@@ -232,6 +253,7 @@ def main():
                     "mfma_f32_frac": kernels["layer"]["frac_mfma_f32"]}
         if dom != "layer":
             roofline["note"] = f"largest total time is in {dom}, which moves too little data for a roofline"
+        roofline["layout_bytes_per_launch"] = layout_bytes(w, rows_per_launch, entries_per_launch)
         roofline["rows_per_launch"] = rows_per_launch
         roofline["ring_entries_per_launch"] = entries_per_launch
         roofline["avg_launch_us"] = kernels[roofline["kernel"]]["avg_us"]

@@ -551,7 +551,6 @@ int stgn_ingest_batch(stgn_ctx* ctx, uint32_t n, const uint32_t* src, const uint
   if (c.d_mem) { Scope t(ctx, KC_MEMORY); launch_memory_update(d, s, dsrc, ddst, dts, def); }
   if (ev) hipEventRecord(ev[2], s);
   { Scope t(ctx, KC_APPLY); launch_apply(d, s, dsrc, ddst, dts, def); }
-  { Scope t(ctx, KC_PROJECT); launch_project_batch(d, s, def); }
   if (ev) hipEventRecord(ev[3], s);
   for (uint32_t hop = 0; hop < c.layers; ++hop) {
     { Scope t(ctx, KC_PLAN); launch_plan(d, s, hop); }

@@ -3,6 +3,7 @@
 // commit).  Paper Sec. 3.2.1 (edge queue), 3.2.2 (temporal adjacency list), 3.3.2 (neighbour
 // cache), 3.3.5 (adjacency append, in-place memory write-back).
 #include "stgn_internal.h"
+#include "mfma16.h"
 
 namespace stgn {
 
@@ -215,14 +216,104 @@ __device__ inline uint64_t log_addr(const Dev& d, uint32_t node, uint32_t pos) {
   return (uint64_t)d.blk[(size_t)node * d.maxb + b] * kMinBlock + off;
 }
 
+// Cached key|value rows that do not come out of a layer kernel (see LayerDev):
+//   per batch:  KV[0][v] = [memory'(v) | features(v)] [W_K | W_V](node rows of layer 0) for the batch's
+//       endpoints v (their memory just changed; skipped without a memory), and for every layer l
+//       KVE[l][e] = feat_e [W_K | W_V](edge rows of layer l) for the batch's edges e;
+//   all_nodes (initial state, full rebuild):  KV[0][v] for every node.
+// One workgroup (four waves) per 16 rows: the rows go through LDS as the A operand, wave w computes
+// the column tiles w + 8 i and w + 8 i + 4 of the 128 ks output columns.  `bid` / `nblk` are the
+// workgroup's index and count among the workgroups that project.
+constexpr uint32_t kProjRows = 16;
+__device__ void project_rows(const Dev& d, const float* __restrict__ ef, uint32_t all_nodes, uint32_t bid, uint32_t nblk,
+                             float* lds) {
+  const Ctrl* c = d.ctrl;
+  const uint32_t nD = all_nodes ? d.N : (d.d_mem ? c->nD : 0u);
+  const uint32_t nE = (all_nodes || !d.d_edge) ? 0u : c->n_edges;
+  const uint64_t E0 = c->E_base;
+  const uint32_t tD = (nD + kProjRows - 1) / kProjRows, tE = (nE + kProjRows - 1) / kProjRows;
+  const uint32_t ntiles = tD + d.layers * tE;
+  const uint32_t kmax = d.d0 > d.d_edge ? d.d0 : d.d_edge;
+  const uint32_t lda = round_up(kmax, kGrpK) + 4;
+  const uint32_t lane = threadIdx.x & 63u;
+  const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  const uint32_t a_off = a16_lane_off(lda);
+  const uint32_t ntkv = 8u * d.ks;
+  // operand padding must be finite: clear the tile once (one chunk of slack behind the last row)
+  for (uint32_t x = threadIdx.x; x < kProjRows * lda + 4 * kGrpK; x += 256) lds[x] = 0.0f;
+  __syncthreads();
+  for (uint32_t tile = bid; tile < ntiles; tile += nblk) {
+    const bool node_job = tile < tD;
+    const uint32_t layer = node_job ? 0u : (tile - tD) / tE;
+    const uint32_t r0 = (node_job ? tile : (tile - tD) - layer * tE) * kProjRows;
+    const uint32_t nrows = node_job ? nD : nE;
+    const uint32_t K = node_job ? d.d0 : d.d_edge;
+    const float* W = node_job ? d.L[0].WKVn : d.L[layer].WKVe;
+    float* out = node_job ? d.KV[0].base : d.KVE[layer].base;
+    // stage the rows (columns K .. lda keep zeros or finite leftovers of a wider job: they meet zero weights).
+    // A batch endpoint's new memory is read from the batch's scratch rows: the write-back into the
+    // memory table runs in the same launch.
+    for (uint32_t x = threadIdx.x; x < kProjRows * K; x += 256) {
+      const uint32_t r = x / K, col = x - r * K;
+      float v = 0.0f;
+      if (r0 + r < nrows) {
+        if (!node_job) v = ef[(size_t)(r0 + r) * d.d_edge + col];
+        else if (all_nodes) v = d.H[0].base[(size_t)(r0 + r) * d.H[0].ld + col];
+        else if (col < d.d_mem) v = d.mem_new[(size_t)(r0 + r) * d.d_mem + col];
+        else v = d.H[0].base[(size_t)d.D[r0 + r] * d.H[0].ld + col];
+      }
+      lds[r * lda + col] = v;
+    }
+    __syncthreads();
+    const uint32_t ck = chunks_of(K), gk = kCG * ck;
+    for (uint32_t nt = wave; nt < ntkv; nt += 8) {
+      const float* const Bt[2] = {W + (size_t)nt * gk * kGrpFloats, W + (size_t)(nt + 4) * gk * kGrpFloats};
+      floatx4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+      mfma16_gemm<2>(lds + a_off, ck, Bt, acc);
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        const uint32_t col = (nt + 4 * t) * 16 + m16_col(lane);     // every column is written: padding columns get exact zeros
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const uint32_t row = r0 + m16_row(lane, r);
+          if (row < nrows) {
+            const size_t orow = node_job ? (size_t)(all_nodes ? row : d.D[row]) : (size_t)(E0 + row);
+            out[orow * d.ld_kv + col] = acc[t][r];
+          }
+        }
+      }
+    }
+    __syncthreads();
+  }
+}
+
+size_t project_lds(const Dev& d) {
+  const uint32_t kmax = d.d0 > d.d_edge ? d.d0 : d.d_edge;
+  return ((size_t)kProjRows * (round_up(kmax, kGrpK) + 4) + 4 * kGrpK) * sizeof(float);
+}
+
+__global__ __launch_bounds__(256) void project_nodes_kernel(Dev d) {
+  extern __shared__ __align__(16) float lds[];
+  project_rows(d, nullptr, 1u, blockIdx.x, gridDim.x, lds);
+}
+
+// The first `proj_blocks` workgroups compute the batch's cached key|value rows (project_rows: the
+// longer job, so it is dispatched first); the others append the batch to the graph state.  Neither
+// group reads what the other writes.
 __global__ __launch_bounds__(256) void apply_kernel(Dev d, const uint32_t* __restrict__ src,
                                                     const uint32_t* __restrict__ dst,
-                                                    const double* __restrict__ ts, const float* __restrict__ ef) {
+                                                    const double* __restrict__ ts, const float* __restrict__ ef,
+                                                    uint32_t proj_blocks) {
+  extern __shared__ __align__(16) float lds[];
   const Ctrl* c = d.ctrl;
   if (c->skip) return;
+  if (blockIdx.x < proj_blocks) {
+    project_rows(d, ef, 0u, blockIdx.x, proj_blocks, lds);
+    return;
+  }
   const uint32_t n = c->n_edges, nD = c->nD;
   const uint64_t E0 = c->E_base;
-  const uint32_t tid = blockIdx.x * blockDim.x + threadIdx.x, nth = gridDim.x * blockDim.x;
+  const uint32_t tid = (blockIdx.x - proj_blocks) * blockDim.x + threadIdx.x, nth = (gridDim.x - proj_blocks) * blockDim.x;
 
   // adjacency entries and ring slots, one thread per (edge, side)
   for (uint32_t s = tid; s < 2 * n; s += nth) {
@@ -306,7 +397,19 @@ void launch_apply(const Dev& d, hipStream_t s, const uint32_t* src, const uint32
   uint32_t blocks = (work + 255) / 256;
   if (blocks > 2048) blocks = 2048;
   if (blocks < 1) blocks = 1;
-  hipLaunchKernelGGL(apply_kernel, dim3(blocks), dim3(256), 0, s, d, src, dst, ts, ef);
+  // workgroups that project: one per 16-row tile of the largest batch (endpoints, and edges per layer)
+  const uint32_t per = (d.max_batch + kProjRows - 1) / kProjRows;
+  uint32_t pblocks = (d.d_mem ? 2 * per : 0) + (d.d_edge ? d.layers * per : 0);
+  if (pblocks > 2048) pblocks = 2048;
+  hipLaunchKernelGGL(apply_kernel, dim3(blocks + pblocks), dim3(256), pblocks ? project_lds(d) : 0, s, d, src, dst, ts, ef,
+                     pblocks);
+}
+
+void launch_project_nodes(const Dev& d, hipStream_t s) {
+  uint32_t blocks = (d.N + kProjRows - 1) / kProjRows;
+  const uint32_t cap = 8u * (d.num_cu ? d.num_cu : 256u);
+  if (blocks > cap) blocks = cap;
+  hipLaunchKernelGGL(project_nodes_kernel, dim3(blocks), dim3(256), project_lds(d), s, d);
 }
 
 void launch_init_state(const Dev& d, hipStream_t s) {
@@ -320,10 +423,14 @@ void launch_zero(float* p, size_t n, hipStream_t s) {
   hipLaunchKernelGGL(zero_kernel, dim3(2048), dim3(256), 0, s, p, n);
 }
 
-int setup_ingest_attributes(const Dev&) {
-  hipError_t e = hipFuncSetAttribute((const void*)stage_sort_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                     2 * STGN_MAX_BATCH * (int)sizeof(uint64_t));
-  return e == hipSuccess ? 0 : -1;
+int setup_ingest_attributes(const Dev& d) {
+  if (hipFuncSetAttribute((const void*)stage_sort_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                          2 * STGN_MAX_BATCH * (int)sizeof(uint64_t)) != hipSuccess) return -1;
+  if (project_lds(d) + 1024 > kMaxLds) return -1;
+  if (hipFuncSetAttribute((const void*)apply_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                          (int)project_lds(d)) != hipSuccess) return -1;
+  return hipFuncSetAttribute((const void*)project_nodes_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                             (int)project_lds(d)) == hipSuccess ? 0 : -1;
 }
 
 }  // namespace stgn

@@ -161,8 +161,7 @@ void launch_init_state(const Dev& d, hipStream_t s);
 void launch_zero(float* p, size_t n, hipStream_t s);
 void launch_noop(hipStream_t s);
 int  attn_supported(uint32_t d_emb, uint32_t d_time, uint32_t heads);
-// cached key|value rows: of the batch's endpoints (layer 0) and edges (every layer), or of all nodes (layer 0)
-void launch_project_batch(const Dev& d, hipStream_t s, const float* ef);
+// cached key|value rows of all nodes for layer 0 (those of a batch's endpoints and edges are computed by launch_apply)
 void launch_project_nodes(const Dev& d, hipStream_t s);
 constexpr size_t kMaxLds = 160 * 1024;   // LDS per workgroup on gfx950
 int  setup_ingest_attributes(const Dev& d);
