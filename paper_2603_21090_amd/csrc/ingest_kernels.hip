@@ -221,9 +221,10 @@ __device__ inline uint64_t log_addr(const Dev& d, uint32_t node, uint32_t pos) {
 //       endpoints v (their memory just changed; skipped without a memory), and for every layer l
 //       KVE[l][e] = feat_e [W_K | W_V](edge rows of layer l) for the batch's edges e;
 //   all_nodes (initial state, full rebuild):  KV[0][v] for every node.
-// One workgroup (four waves) per 16 rows: the rows go through LDS as the A operand, wave w computes
-// the column tiles w + 8 i and w + 8 i + 4 of the 128 ks output columns.  `bid` / `nblk` are the
-// workgroup's index and count among the workgroups that project.
+// One workgroup (four waves) per 16 rows and 128 of the 128 ks output columns: the rows go through
+// LDS as the A operand, wave w computes the column tiles w and w + 4 of the workgroup's column group
+// (these launches are small and latency-bound: more, shorter workgroups finish sooner).  `bid` / `nblk`
+// are the workgroup's index and count among the workgroups that project.
 constexpr uint32_t kProjRows = 16;
 __device__ void project_rows(const Dev& d, const float* __restrict__ ef, uint32_t all_nodes, uint32_t bid, uint32_t nblk,
                              float* lds) {
@@ -232,17 +233,17 @@ __device__ void project_rows(const Dev& d, const float* __restrict__ ef, uint32_
   const uint32_t nE = (all_nodes || !d.d_edge) ? 0u : c->n_edges;
   const uint64_t E0 = c->E_base;
   const uint32_t tD = (nD + kProjRows - 1) / kProjRows, tE = (nE + kProjRows - 1) / kProjRows;
-  const uint32_t ntiles = tD + d.layers * tE;
+  const uint32_t ntiles = (tD + d.layers * tE) * d.ks;       // (row tile, column group)
   const uint32_t kmax = d.d0 > d.d_edge ? d.d0 : d.d_edge;
   const uint32_t lda = round_up(kmax, kGrpK) + 4;
   const uint32_t lane = threadIdx.x & 63u;
   const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
   const uint32_t a_off = a16_lane_off(lda);
-  const uint32_t ntkv = 8u * d.ks;
   // operand padding must be finite: clear the tile once (one chunk of slack behind the last row)
   for (uint32_t x = threadIdx.x; x < kProjRows * lda + 4 * kGrpK; x += 256) lds[x] = 0.0f;
   __syncthreads();
-  for (uint32_t tile = bid; tile < ntiles; tile += nblk) {
+  for (uint32_t item = bid; item < ntiles; item += nblk) {
+    const uint32_t tile = item / d.ks, nt = wave + 8u * (item - tile * d.ks);
     const bool node_job = tile < tD;
     const uint32_t layer = node_job ? 0u : (tile - tD) / tE;
     const uint32_t r0 = (node_job ? tile : (tile - tD) - layer * tE) * kProjRows;
@@ -250,6 +251,11 @@ __device__ void project_rows(const Dev& d, const float* __restrict__ ef, uint32_
     const uint32_t K = node_job ? d.d0 : d.d_edge;
     const float* W = node_job ? d.L[0].WKVn : d.L[layer].WKVe;
     float* out = node_job ? d.KV[0].base : d.KVE[layer].base;
+    const uint32_t ck = chunks_of(K), gk = kCG * ck;
+    const float* const Bt[2] = {W + (size_t)nt * gk * kGrpFloats, W + (size_t)(nt + 4) * gk * kGrpFloats};
+    Ops16<2> P;                                               // first weight chunk, requested ahead of the staging
+    load_b16(Bt[0], 0, P.b[0]);
+    load_b16(Bt[1], 0, P.b[1]);
     // stage the rows (columns K .. lda keep zeros or finite leftovers of a wider job: they meet zero weights).
     // A batch endpoint's new memory is read from the batch's scratch rows: the write-back into the
     // memory table runs in the same launch.
@@ -265,11 +271,9 @@ __device__ void project_rows(const Dev& d, const float* __restrict__ ef, uint32_
       lds[r * lda + col] = v;
     }
     __syncthreads();
-    const uint32_t ck = chunks_of(K), gk = kCG * ck;
-    for (uint32_t nt = wave; nt < ntkv; nt += 8) {
-      const float* const Bt[2] = {W + (size_t)nt * gk * kGrpFloats, W + (size_t)(nt + 4) * gk * kGrpFloats};
+    {
       floatx4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
-      mfma16_gemm<2>(lds + a_off, ck, Bt, acc);
+      mfma16_gemm_pre<2>(lds + a_off, ck, Bt, acc, P);
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
         const uint32_t col = (nt + 4 * t) * 16 + m16_col(lane);     // every column is written: padding columns get exact zeros
@@ -399,17 +403,17 @@ void launch_apply(const Dev& d, hipStream_t s, const uint32_t* src, const uint32
   if (blocks < 1) blocks = 1;
   // workgroups that project: one per 16-row tile of the largest batch (endpoints, and edges per layer)
   const uint32_t per = (d.max_batch + kProjRows - 1) / kProjRows;
-  uint32_t pblocks = (d.d_mem ? 2 * per : 0) + (d.d_edge ? d.layers * per : 0);
+  uint32_t pblocks = ((d.d_mem ? 2 * per : 0) + (d.d_edge ? d.layers * per : 0)) * d.ks;
   if (pblocks > 2048) pblocks = 2048;
   hipLaunchKernelGGL(apply_kernel, dim3(blocks + pblocks), dim3(256), pblocks ? project_lds(d) : 0, s, d, src, dst, ts, ef,
                      pblocks);
 }
 
 void launch_project_nodes(const Dev& d, hipStream_t s) {
-  uint32_t blocks = (d.N + kProjRows - 1) / kProjRows;
+  uint64_t blocks = (uint64_t)((d.N + kProjRows - 1) / kProjRows) * d.ks;
   const uint32_t cap = 8u * (d.num_cu ? d.num_cu : 256u);
   if (blocks > cap) blocks = cap;
-  hipLaunchKernelGGL(project_nodes_kernel, dim3(blocks), dim3(256), project_lds(d), s, d);
+  hipLaunchKernelGGL(project_nodes_kernel, dim3((uint32_t)blocks), dim3(256), project_lds(d), s, d);
 }
 
 void launch_init_state(const Dev& d, hipStream_t s) {
