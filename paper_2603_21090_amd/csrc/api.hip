@@ -29,6 +29,9 @@ struct stgn_ctx {
   std::string err;
   uint64_t host_edges = 0;          // upper bound of edges enqueued so far
   bool host_t_known = true;         // host knows the last ingested timestamp
+  // Per hop: the last batch whose statistics the host has seen preferred the pull direction.  Such a
+  // hop is enqueued without its plan kernel and told to pull; a stale hint costs speed, never correctness.
+  bool pull_hint[STGN_MAX_LAYERS + 1] = {};
   bool any_edges = false;
   double host_t_last = 0.0;
   // pinned staging for host inputs, double buffered
@@ -367,6 +370,8 @@ int sync_and_poll(stgn_ctx* ctx) {
   int rc = read_ctrl(ctx);
   if (rc) return rc;
   if (ctx->timing) drain_timing(ctx);
+  if (!ctx->ctrl_host->skip && ctx->ctrl_host->n_edges)
+    for (uint32_t h = 0; h < ctx->cfg.layers; ++h) ctx->pull_hint[h] = (ctx->ctrl_host->pulled[h] & 2u) != 0;
   const int code = ctx->ctrl_host->err_code;
   if (code != 0) {
     const int32_t zero = 0;
@@ -553,8 +558,9 @@ int stgn_ingest_batch(stgn_ctx* ctx, uint32_t n, const uint32_t* src, const uint
   { Scope t(ctx, KC_APPLY); launch_apply(d, s, dsrc, ddst, dts, def); }
   if (ev) hipEventRecord(ev[3], s);
   for (uint32_t hop = 0; hop < c.layers; ++hop) {
-    { Scope t(ctx, KC_PLAN); launch_plan(d, s, hop); }
-    { Scope t(ctx, KC_EXPAND); launch_expand(d, s, hop); }
+    const bool planned = !ctx->pull_hint[hop];
+    if (planned) { Scope t(ctx, KC_PLAN); launch_plan(d, s, hop); }
+    { Scope t(ctx, KC_EXPAND); launch_expand(d, s, hop, planned); }
   }
   { Scope t(ctx, KC_COMPACT); launch_compact(d, s, 0); }
   { Scope t(ctx, KC_COMPACT); launch_compact(d, s, 1); }
@@ -575,7 +581,7 @@ int stgn_ingest_batch(stgn_ctx* ctx, uint32_t n, const uint32_t* src, const uint
     stats->entries_scanned = h.scanned;
     stats->pull_hops = 0;
     stats->reserved = 0;
-    for (uint32_t i = 0; i < ctx->cfg.layers; ++i) stats->pull_hops |= (h.pulled[i] ? 1u : 0u) << i;
+    for (uint32_t i = 0; i < ctx->cfg.layers; ++i) stats->pull_hops |= (h.pulled[i] & 1u) << i;
     for (int i = 0; i < 5; ++i) {
       float ms = 0.0f;
       hipEventElapsedTime(&ms, ev[i], ev[i + 1]);

@@ -62,6 +62,8 @@ __device__ inline uint32_t block_scan_256(uint32_t v, uint32_t* s, uint32_t* exc
 // its items (one counter update per chunk), a second pass writes them, the 64 lanes filling the
 // items of up to 64 frontier nodes together so that a hub's thousands of items do not land on one lane.
 __device__ inline bool pull_hop(const Dev& d, const Ctrl* c, uint32_t hop) { return c->front_deg[hop] >= (uint64_t)(d.N / 2u); }
+// pulled[hop]: bit 0 the hop ran in pull mode, bit 1 the frontier was large enough to prefer pulling
+constexpr uint32_t kRanPull = 1u, kWantsPull = 2u;
 
 __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Dev d, uint32_t hop, uint32_t rounds) {
   __shared__ uint32_t s_off[kPlanWaves][64], s_v[kPlanWaves][64];
@@ -149,7 +151,10 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Dev d, uint32_t hop,
   }
 }
 
-__global__ __launch_bounds__(256) void expand_kernel(Dev d, uint32_t hop) {
+// planned = 0: the host launched no plan kernel for this hop (its last look at the statistics said the
+// hop pulls), so there are no work items and the hop pulls whatever the frontier's size: both modes
+// flag the same nodes.
+__global__ __launch_bounds__(256) void expand_kernel(Dev d, uint32_t hop, uint32_t planned) {
   __shared__ unsigned long long s_deg[4], s_scan[4];
   Ctrl* c = d.ctrl;
   if (c->skip) return;
@@ -157,7 +162,8 @@ __global__ __launch_bounds__(256) void expand_kernel(Dev d, uint32_t hop) {
   const uint8_t value = (uint8_t)(hop + 2u);
   unsigned long long newdeg = 0;                 // log entries owned by the nodes this thread flags
   unsigned long long looked = 0;                 // ring slots a pull hop examined
-  if (pull_hop(d, c, hop)) {
+  const bool wants_pull = pull_hop(d, c, hop);
+  if (wants_pull || !planned) {
     // ---- pull: one clean node per lane
     const uint8_t want = (uint8_t)(hop + 1u);
     const uint32_t k = d.k;
@@ -180,7 +186,7 @@ __global__ __launch_bounds__(256) void expand_kernel(Dev d, uint32_t hop) {
       }
       if (hit) { d.mark[w] = value; newdeg += dg; }
     }
-    if (blockIdx.x == 0 && threadIdx.x == 0) c->pulled[hop] = 1;
+    if (blockIdx.x == 0 && threadIdx.x == 0) c->pulled[hop] = kRanPull | (wants_pull ? kWantsPull : 0u);
   } else {
     // ---- push: one wavefront per work item of the frontier's logs
     const uint32_t n_items = c->n_items[hop];
@@ -326,11 +332,11 @@ void launch_plan(const Dev& d, hipStream_t s, uint32_t hop) {
   hipLaunchKernelGGL(plan_kernel, dim3(blocks), dim3(kPlanThreads), 0, s, d, hop, rounds);
 }
 
-void launch_expand(const Dev& d, hipStream_t s, uint32_t hop) {
+void launch_expand(const Dev& d, hipStream_t s, uint32_t hop, bool planned) {
   // one wave per work item, grid-stride; enough waves to fill the chip without a long empty tail
   uint64_t want = ((uint64_t)d.N + 3) / 4;
   uint32_t blocks = want > 4096 ? 4096u : (uint32_t)(want ? want : 1);
-  hipLaunchKernelGGL(expand_kernel, dim3(blocks), dim3(256), 0, s, d, hop);
+  hipLaunchKernelGGL(expand_kernel, dim3(blocks), dim3(256), 0, s, d, hop, planned ? 1u : 0u);
 }
 
 void launch_compact(const Dev& d, hipStream_t s, int phase) {

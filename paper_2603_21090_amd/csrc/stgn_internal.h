@@ -47,7 +47,7 @@ struct Ctrl {
   // estimate after a push hop): decides between pushing along the frontier's logs and pulling
   // through the rings of the clean nodes
   uint64_t front_deg[STGN_MAX_LAYERS + 1];
-  uint32_t pulled[STGN_MAX_LAYERS + 1];   // 1: hop h ran in pull mode (statistics)
+  uint32_t pulled[STGN_MAX_LAYERS + 1];   // bit 0: hop h ran in pull mode; bit 1: its frontier preferred pulling
 };
 
 // Row-table descriptor: row v starts at base + v * ld (floats)
@@ -152,7 +152,7 @@ void launch_memory_update(const Dev& d, hipStream_t s, const uint32_t* src, cons
 void launch_apply(const Dev& d, hipStream_t s, const uint32_t* src, const uint32_t* dst, const double* ts,
                   const float* ef);
 void launch_plan(const Dev& d, hipStream_t s, uint32_t hop);
-void launch_expand(const Dev& d, hipStream_t s, uint32_t hop);
+void launch_expand(const Dev& d, hipStream_t s, uint32_t hop, bool planned);
 void launch_compact(const Dev& d, hipStream_t s, int phase);
 void launch_layer(const Dev& d, hipStream_t s, uint32_t layer, const uint32_t* rows, const uint32_t* count_ptr,
                   uint32_t count_max);

@@ -160,6 +160,47 @@ def test_push_and_pull_hops_give_the_same_affected_set(binding):
     g.close()
 
 
+def test_unplanned_hops_and_stale_direction_hints(binding):
+    """The host enqueues a hop without its planning kernel when the last statistics it saw said the
+    hop pulls, and the device then pulls whatever the frontier's size; a planned hop may still push
+    a frontier that has grown large since.  Both are only slower, never different: batches of very
+    different sizes are enqueued back to back without a host read in between (so the hints go stale
+    in both directions) and the whole state is compared with the oracle afterwards."""
+    w = tiny_workload(num_nodes=2000, num_edges=4000, batch=400, layers=2, k=3, d_mem=8, d_edge=4, d_time=8, d_emb=8,
+                      d_msg=8, zipf_s=1.2)
+    st = synth.EdgeStream(w)
+    W = synth.make_weights(w)
+    o = orc.Oracle.from_workload(w, W)
+    g = binding.StreamTGN.from_workload(w, W)
+    allnodes = np.arange(w.num_nodes, dtype=np.uint32)
+    # (edges in the batch, poll the statistics afterwards)
+    plan = [(400, True), (1, False), (2, False), (1, False), (400, False), (1, True), (400, False), (300, False),
+            (1, False), (400, True), (3, False), (400, False), (1, False)]
+    lo, directions = 0, set()
+    for n, poll in plan:
+        hi = lo + n
+        s, d, t, ef = st.src[lo:hi], st.dst[lo:hi], st.ts[lo:hi], st.edge_features(lo, hi)
+        rc, D, A = o.ingest(s, d, t, ef)
+        assert rc == 0
+        if poll:
+            stats = g.ingest_batch(s, d, t, ef, stats=True)
+            assert stats["n_affected"] == len(A)
+            directions.add(stats["pull_hops"] & 1)
+        else:
+            g.ingest_batch(s, d, t, ef)
+        lo = hi
+    assert np.array_equal(g.get_affected(), A)
+    assert directions == {0, 1}, "the polled batches never disagreed about the direction of hop 0"
+    gm, gt = g.get_memory(allnodes)
+    om, ot = o.memory(allnodes)
+    assert np.array_equal(gt, ot)
+    check_rows(gm, om, "memory")
+    ref = o.embed_all()
+    for l in range(1, w.layers + 1):
+        check_rows(g.get_embeddings(allnodes, layer=l), ref[l - 1], f"layer {l}")
+    g.close()
+
+
 def test_device_inputs_match_host_inputs(binding):
     w = tiny_workload(num_nodes=300, num_edges=3000, batch=100, d_mem=16, d_edge=12, d_time=16, d_emb=16, d_msg=16, k=4)
     g, o, st = run_stream(binding, w, device_inputs=True, full_check_at={0, 7, 15})
