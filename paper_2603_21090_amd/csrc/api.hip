@@ -26,6 +26,14 @@ struct stgn_ctx {
   stgn_config cfg;
   Dev d;
   hipStream_t stream = nullptr;
+  // A batch's front part (input copies, validation + sort, memory update) touches nothing the previous
+  // batch's attention layers touch, so it runs on a second stream and overlaps them: it starts once the
+  // previous batch's compaction is done (ev_compact, recorded on `stream`), and the batch's apply step
+  // on `stream` waits for it (ev_front, recorded on `front`).  Calls that ask for per-stage statistics,
+  // and all calls while per-kernel timing is on, run everything on `stream`.
+  hipStream_t front = nullptr;
+  hipEvent_t ev_compact = nullptr, ev_front = nullptr;
+  bool compact_recorded = false;
   std::string err;
   uint64_t host_edges = 0;          // upper bound of edges enqueued so far
   bool host_t_known = true;         // host knows the last ingested timestamp
@@ -329,12 +337,12 @@ hipEvent_t get_event(stgn_ctx* ctx) {
 }
 
 struct Scope {
-  stgn_ctx* ctx; int cls; hipEvent_t a = nullptr, b = nullptr;
-  Scope(stgn_ctx* c, int k) : ctx(c), cls(k) {
-    if (ctx->timing) { a = get_event(ctx); b = get_event(ctx); if (a) hipEventRecord(a, ctx->stream); }
+  stgn_ctx* ctx; int cls; hipStream_t st; hipEvent_t a = nullptr, b = nullptr;
+  Scope(stgn_ctx* c, int k, hipStream_t on = nullptr) : ctx(c), cls(k), st(on ? on : c->stream) {
+    if (ctx->timing) { a = get_event(ctx); b = get_event(ctx); if (a) hipEventRecord(a, st); }
   }
   ~Scope() {
-    if (ctx->timing && a && b) { hipEventRecord(b, ctx->stream); ctx->pending.push_back({cls, a, b}); }
+    if (ctx->timing && a && b) { hipEventRecord(b, st); ctx->pending.push_back({cls, a, b}); }
   }
 };
 
@@ -454,6 +462,12 @@ int stgn_create(const stgn_config* cfg, const stgn_weights* w, const float* node
   }
   for (auto& e : ctx->stage_ev)
     if (hipEventCreate(&e) != hipSuccess) { ctx->err = "event creation failed"; return bail(STGN_E_DEVICE); }
+  if (hipStreamCreateWithFlags(&ctx->front, hipStreamNonBlocking) != hipSuccess ||
+      hipEventCreateWithFlags(&ctx->ev_compact, hipEventDisableTiming) != hipSuccess ||
+      hipEventCreateWithFlags(&ctx->ev_front, hipEventDisableTiming) != hipSuccess) {
+    ctx->err = "second stream or its events could not be created";
+    return bail(STGN_E_DEVICE);
+  }
   {
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) == hipSuccess &&
@@ -487,7 +501,11 @@ int stgn_create(const stgn_config* cfg, const stgn_weights* w, const float* node
 
 void stgn_destroy(stgn_ctx* ctx) {
   if (!ctx) return;
+  if (ctx->front) hipStreamSynchronize(ctx->front);
   if (ctx->stream || ctx->ctrl_host) hipStreamSynchronize(ctx->stream);
+  if (ctx->front) hipStreamDestroy(ctx->front);
+  if (ctx->ev_compact) hipEventDestroy(ctx->ev_compact);
+  if (ctx->ev_front) hipEventDestroy(ctx->ev_front);
   for (int i = 0; i < 2; ++i) {
     if (ctx->pin[i]) hipHostFree(ctx->pin[i]);
     if (ctx->pin_ev[i]) hipEventDestroy(ctx->pin_ev[i]);
@@ -511,6 +529,10 @@ int stgn_ingest_batch(stgn_ctx* ctx, uint32_t n, const uint32_t* src, const uint
   const uint32_t *dsrc = src, *ddst = dst;
   const double* dts = ts;
   const float* def = efeat;
+  // stream of the front part (see stgn_ctx::front)
+  const bool overlapped = stats == nullptr && !ctx->timing;     // per-kernel timing wants every kernel on its own
+  hipStream_t sf = overlapped ? ctx->front : ctx->stream;
+  if (overlapped && ctx->compact_recorded) HIPCHK(ctx, hipStreamWaitEvent(ctx->front, ctx->ev_compact, 0));
   if (!inputs_on_device) {
     // host-side validation: nothing is enqueued for a bad batch
     double prev = (ctx->any_edges && ctx->host_t_known) ? ctx->host_t_last : -INFINITY;
@@ -530,12 +552,12 @@ int stgn_ingest_batch(stgn_ctx* ctx, uint32_t n, const uint32_t* src, const uint
       memcpy(p + o_dst, dst, (size_t)n * 4);
       memcpy(p + o_ts, ts, (size_t)n * 8);
       if (c.d_edge) memcpy(p + o_ef, efeat, (size_t)n * c.d_edge * 4);
-      HIPCHK(ctx, hipMemcpyAsync(d.st_src, p, (size_t)n * 4, hipMemcpyHostToDevice, ctx->stream));
-      HIPCHK(ctx, hipMemcpyAsync(d.st_dst, p + o_dst, (size_t)n * 4, hipMemcpyHostToDevice, ctx->stream));
-      HIPCHK(ctx, hipMemcpyAsync(d.st_ts, p + o_ts, (size_t)n * 8, hipMemcpyHostToDevice, ctx->stream));
+      HIPCHK(ctx, hipMemcpyAsync(d.st_src, p, (size_t)n * 4, hipMemcpyHostToDevice, sf));
+      HIPCHK(ctx, hipMemcpyAsync(d.st_dst, p + o_dst, (size_t)n * 4, hipMemcpyHostToDevice, sf));
+      HIPCHK(ctx, hipMemcpyAsync(d.st_ts, p + o_ts, (size_t)n * 8, hipMemcpyHostToDevice, sf));
       if (c.d_edge)
-        HIPCHK(ctx, hipMemcpyAsync(d.st_ef, p + o_ef, (size_t)n * c.d_edge * 4, hipMemcpyHostToDevice, ctx->stream));
-      HIPCHK(ctx, hipEventRecord(ctx->pin_ev[pb], ctx->stream));
+        HIPCHK(ctx, hipMemcpyAsync(d.st_ef, p + o_ef, (size_t)n * c.d_edge * 4, hipMemcpyHostToDevice, sf));
+      HIPCHK(ctx, hipEventRecord(ctx->pin_ev[pb], sf));
       ctx->pin_used[pb] = true;
       ctx->host_t_last = ts[n - 1];
       ctx->host_t_known = true;
@@ -551,10 +573,14 @@ int stgn_ingest_batch(stgn_ctx* ctx, uint32_t n, const uint32_t* src, const uint
   hipStream_t s = ctx->stream;
   hipEvent_t* ev = stats ? ctx->stage_ev : nullptr;
   if (ev) hipEventRecord(ev[0], s);
-  { Scope t(ctx, KC_SORT); launch_stage_sort(d, s, n, dsrc, ddst, dts); }
+  { Scope t(ctx, KC_SORT, sf); launch_stage_sort(d, sf, n, dsrc, ddst, dts); }
   if (ev) hipEventRecord(ev[1], s);
-  if (c.d_mem) { Scope t(ctx, KC_MEMORY); launch_memory_update(d, s, dsrc, ddst, dts, def); }
+  if (c.d_mem) { Scope t(ctx, KC_MEMORY, sf); launch_memory_update(d, sf, dsrc, ddst, dts, def); }
   if (ev) hipEventRecord(ev[2], s);
+  if (overlapped) {
+    HIPCHK(ctx, hipEventRecord(ctx->ev_front, ctx->front));
+    HIPCHK(ctx, hipStreamWaitEvent(s, ctx->ev_front, 0));
+  }
   { Scope t(ctx, KC_APPLY); launch_apply(d, s, dsrc, ddst, dts, def); }
   if (ev) hipEventRecord(ev[3], s);
   for (uint32_t hop = 0; hop < c.layers; ++hop) {
@@ -564,6 +590,8 @@ int stgn_ingest_batch(stgn_ctx* ctx, uint32_t n, const uint32_t* src, const uint
   }
   { Scope t(ctx, KC_COMPACT); launch_compact(d, s, 0); }
   { Scope t(ctx, KC_COMPACT); launch_compact(d, s, 1); }
+  HIPCHK(ctx, hipEventRecord(ctx->ev_compact, s));
+  ctx->compact_recorded = true;
   if (ev) hipEventRecord(ev[4], s);
   run_layers(ctx, false);
   if (ctx->timing) { Scope t(ctx, KC_NOOP); launch_noop(s); }   // event-pair overhead, for calibration

@@ -105,7 +105,8 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
   static_assert(KS % H == 0, "whole slots per head");
   constexpr int SH = KS / H;                  // slots per head
   constexpr uint32_t Ztp = NT * kSlot;        // floats of one head's qt / pb vector
-  if (count_ptr && a.ctrl->skip) return;
+  // (a batch that failed validation leaves every per-layer count at zero: nothing to test here, and the
+  // control block's batch fields may already belong to the next batch, whose front part runs concurrently)
   uint32_t n = count_max;
   if (count_ptr) { const uint32_t c = *count_ptr; n = c < count_max ? c : count_max; }
   const uint32_t ntiles = (n + kTM - 1) / kTM;
