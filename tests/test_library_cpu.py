@@ -40,14 +40,24 @@ def test_workspace_sizes_scale_with_the_configuration():
     sizes = {name: binding.query_workspace(cfg_of(w)) for name, w in synth.WORKLOADS.items()}
     assert sizes["C1"] < sizes["C2"] < sizes["C3"] < sizes["C4"] < sizes["C5"]
     assert sizes["C5"] < 200 * 2**30          # the largest workload fits one MI355X (288 GB)
-    # the edge-feature table (128-byte aligned rows) must be inside
+    # the edge-feature table (128-byte aligned rows) and one cached key|value row per edge and layer
+    # (two heads of 50: 2 x 2 x 64 floats) must be inside
     w = synth.WORKLOADS["C4"]
-    assert sizes["C4"] > w.num_edges * 128 * 4
+    assert sizes["C4"] > w.num_edges * (128 * 4 + w.layers * 256 * 4)
+
+
+@pytest.mark.parametrize("ok", [dict(d_emb=256, heads=4), dict(d_emb=256, heads=1), dict(d_emb=130, heads=1),
+                                dict(d_emb=128, heads=2, d_time=128)])
+def test_widest_supported_attention_shapes(lib, ok):
+    n = C.c_size_t(0)
+    assert lib.stgn_query_workspace(C.byref(cfg_of(synth.WORKLOADS["C1"], **ok)), C.byref(n)) == 0 and n.value > 0
 
 
 @pytest.mark.parametrize("bad", [dict(num_nodes=0), dict(max_edges=0), dict(max_batch=0), dict(max_batch=8193),
                                  dict(layers=0), dict(layers=5), dict(k=0), dict(heads=3), dict(heads=0),
-                                 dict(d_emb=0), dict(d_time=0), dict(d_mem=0, d_node=0), dict(max_edges=2**31)])
+                                 dict(d_emb=0), dict(d_time=0), dict(d_mem=0, d_node=0), dict(max_edges=2**31),
+                                 dict(d_emb=300, heads=4),      # 75-wide heads: 8 key slots, more than a cached row has
+                                 dict(d_emb=260, heads=1), dict(d_time=129)])
 def test_bad_configurations_are_rejected(lib, bad):
     w = synth.WORKLOADS["C1"]
     n = C.c_size_t(0)
