@@ -119,13 +119,13 @@ void stgn_destroy(stgn_ctx *ctx);
  * with device inputs the check runs on the device, a failing batch is skipped as a whole and
  * its code is returned by the next synchronising call (stgn_sync, stgn_get_*, or this call with
  * stats != NULL).
- * The call is asynchronous.  With stats == NULL the batch's front part (input copies, validation,
- * memory update) runs on a stream of the library's own so that it overlaps the previous batch's
- * attention layers; the rest runs on hip_stream, and work enqueued on hip_stream after the call
- * is ordered after the whole batch.  Device inputs must therefore hold their final contents when
- * the call is made (they are not ordered after work still pending on hip_stream) and must stay
- * unchanged until the batch has completed.  With stats != NULL everything runs on hip_stream and
- * the call synchronises; while per-kernel timing is enabled everything runs on hip_stream too. */
+ * The call is asynchronous.  A batch with device inputs and stats == NULL that follows another
+ * asynchronous call without a synchronising call in between runs its front part (validation, memory update) on a stream of the library's own so
+ * that it overlaps the previous batch's attention layers; the rest runs on hip_stream, and work
+ * enqueued on hip_stream after the call is ordered after the whole batch.  Device inputs must
+ * therefore hold their final contents when the call is made (they are not ordered after work still
+ * pending on hip_stream) and must stay unchanged until the batch has completed.  Host inputs are
+ * copied before the call returns.  With stats != NULL the call synchronises. */
 int stgn_ingest_batch(stgn_ctx *ctx, uint32_t n, const uint32_t *src, const uint32_t *dst,
                       const double *ts, const float *efeat, int inputs_on_device,
                       stgn_batch_stats *stats /* host, nullable */);

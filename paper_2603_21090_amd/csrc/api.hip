@@ -28,12 +28,15 @@ struct stgn_ctx {
   hipStream_t stream = nullptr;
   // A batch's front part (input copies, validation + sort, memory update) touches nothing the previous
   // batch's attention layers touch, so it runs on a second stream and overlaps them: it starts once the
-  // previous batch's compaction is done (ev_compact, recorded on `stream`), and the batch's apply step
-  // on `stream` waits for it (ev_front, recorded on `front`).  Calls that ask for per-stage statistics,
-  // and all calls while per-kernel timing is on, run everything on `stream`.
+  // previous batch's compaction is done (ev_compact[], recorded on `stream`), and the batch's apply step
+  // on `stream` waits for it (ev_front, recorded on `front`).  Only batches with device inputs that find
+  // `stream` busy take this path; calls that ask for per-stage statistics, calls with host inputs, and
+  // all calls while per-kernel timing is on, run everything on `stream`.
   hipStream_t front = nullptr;
-  hipEvent_t ev_compact = nullptr, ev_front = nullptr;
-  bool compact_recorded = false;
+  hipEvent_t ev_compact[2] = {nullptr, nullptr}, ev_front = nullptr;   // ev_compact alternates with the batches
+  bool compact_recorded[2] = {false, false};
+  int parity = 0;                   // staging block and compaction event of the next batch
+  bool idle = true;                 // nothing was enqueued since the library last synchronised `stream`
   std::string err;
   uint64_t host_edges = 0;          // upper bound of edges enqueued so far
   bool host_t_known = true;         // host knows the last ingested timestamp
@@ -116,6 +119,9 @@ void put_tiled(std::vector<float>& dst, uint32_t K, uint32_t k, uint32_t j, doub
   dst[block * kGrpFloats + (((k % kGrpK) / 4) * 16 + j % 16) * 4 + k % 4] = (float)v;
 }
 
+// Host inputs travel as one block: src at 0, dst at 4 B, ts at 8 B, edge features at 16 B per edge of the largest batch.
+size_t stage_bytes(const stgn_config& c) { return (size_t)c.max_batch * (16 + (size_t)c.d_edge * sizeof(float)); }
+
 // Lays the whole device state out in one workspace; base == nullptr only measures.
 size_t layout(const stgn_config& c, char* base, Dev* d) {
   Bump b{base};
@@ -160,10 +166,9 @@ size_t layout(const stgn_config& c, char* base, Dev* d) {
     d->KVE[l].base = b.take<float>((size_t)(c.d_edge ? c.max_edges : 1) * d->ld_kv);
   }
   d->ctrl = b.take<Ctrl>(1);
-  d->st_src = b.take<uint32_t>(c.max_batch);
-  d->st_dst = b.take<uint32_t>(c.max_batch);
-  d->st_ts = b.take<double>(c.max_batch);
-  d->st_ef = b.take<float>((size_t)c.max_batch * c.d_edge);
+  // staging for host inputs: two blocks (batches alternate), each laid out like the pinned host block
+  // [src | dst | ts | efeat] so that one copy moves a batch
+  for (int i = 0; i < 2; ++i) d->stage[i] = b.take<char>(stage_bytes(c));
   d->D = b.take<uint32_t>(B2);
   d->seg_start = b.take<uint32_t>(B2 + 1);
   d->last_slot = b.take<uint32_t>(B2);
@@ -370,6 +375,7 @@ void run_layers(stgn_ctx* ctx, bool all_rows) {
 int read_ctrl(stgn_ctx* ctx) {
   HIPCHK(ctx, hipMemcpyAsync(ctx->ctrl_host, ctx->d.ctrl, sizeof(Ctrl), hipMemcpyDeviceToHost, ctx->stream));
   HIPCHK(ctx, hipStreamSynchronize(ctx->stream));
+  ctx->idle = true;
   return STGN_OK;
 }
 
@@ -448,7 +454,7 @@ int stgn_create(const stgn_config* cfg, const stgn_weights* w, const float* node
   ctx->stream = (hipStream_t)hip_stream;
   auto bail = [&](int code) { g_create_error = ctx->err; stgn_destroy(ctx); return code; };
 
-  ctx->pin_bytes = (size_t)cfg->max_batch * (2 * sizeof(uint32_t) + sizeof(double) + (size_t)cfg->d_edge * sizeof(float));
+  ctx->pin_bytes = stage_bytes(*cfg);
   for (int i = 0; i < 2; ++i) {
     if (hipHostMalloc((void**)&ctx->pin[i], ctx->pin_bytes, hipHostMallocDefault) != hipSuccess ||
         hipEventCreateWithFlags(&ctx->pin_ev[i], hipEventDisableTiming) != hipSuccess) {
@@ -463,7 +469,8 @@ int stgn_create(const stgn_config* cfg, const stgn_weights* w, const float* node
   for (auto& e : ctx->stage_ev)
     if (hipEventCreate(&e) != hipSuccess) { ctx->err = "event creation failed"; return bail(STGN_E_DEVICE); }
   if (hipStreamCreateWithFlags(&ctx->front, hipStreamNonBlocking) != hipSuccess ||
-      hipEventCreateWithFlags(&ctx->ev_compact, hipEventDisableTiming) != hipSuccess ||
+      hipEventCreateWithFlags(&ctx->ev_compact[0], hipEventDisableTiming) != hipSuccess ||
+      hipEventCreateWithFlags(&ctx->ev_compact[1], hipEventDisableTiming) != hipSuccess ||
       hipEventCreateWithFlags(&ctx->ev_front, hipEventDisableTiming) != hipSuccess) {
     ctx->err = "second stream or its events could not be created";
     return bail(STGN_E_DEVICE);
@@ -504,7 +511,7 @@ void stgn_destroy(stgn_ctx* ctx) {
   if (ctx->front) hipStreamSynchronize(ctx->front);
   if (ctx->stream || ctx->ctrl_host) hipStreamSynchronize(ctx->stream);
   if (ctx->front) hipStreamDestroy(ctx->front);
-  if (ctx->ev_compact) hipEventDestroy(ctx->ev_compact);
+  for (auto& e : ctx->ev_compact) if (e) hipEventDestroy(e);
   if (ctx->ev_front) hipEventDestroy(ctx->ev_front);
   for (int i = 0; i < 2; ++i) {
     if (ctx->pin[i]) hipHostFree(ctx->pin[i]);
@@ -530,9 +537,15 @@ int stgn_ingest_batch(stgn_ctx* ctx, uint32_t n, const uint32_t* src, const uint
   const double* dts = ts;
   const float* def = efeat;
   // stream of the front part (see stgn_ctx::front)
-  const bool overlapped = stats == nullptr && !ctx->timing;     // per-kernel timing wants every kernel on its own
+  // Only worth it, and only used, when there is something to overlap with (work was enqueued on
+  // hip_stream since the library last synchronised it) and
+  // the inputs are already on the device: a host-to-device copy on the second stream was measured to
+  // halve the rate of the host-input path.
+  const bool overlapped = stats == nullptr && !ctx->timing && inputs_on_device && !ctx->idle;
+  ctx->idle = false;
   hipStream_t sf = overlapped ? ctx->front : ctx->stream;
-  if (overlapped && ctx->compact_recorded) HIPCHK(ctx, hipStreamWaitEvent(ctx->front, ctx->ev_compact, 0));
+  const int par = ctx->parity;
+  ctx->parity ^= 1;
   if (!inputs_on_device) {
     // host-side validation: nothing is enqueued for a bad batch
     double prev = (ctx->any_edges && ctx->host_t_known) ? ctx->host_t_last : -INFINITY;
@@ -552,23 +565,26 @@ int stgn_ingest_batch(stgn_ctx* ctx, uint32_t n, const uint32_t* src, const uint
       memcpy(p + o_dst, dst, (size_t)n * 4);
       memcpy(p + o_ts, ts, (size_t)n * 8);
       if (c.d_edge) memcpy(p + o_ef, efeat, (size_t)n * c.d_edge * 4);
-      HIPCHK(ctx, hipMemcpyAsync(d.st_src, p, (size_t)n * 4, hipMemcpyHostToDevice, sf));
-      HIPCHK(ctx, hipMemcpyAsync(d.st_dst, p + o_dst, (size_t)n * 4, hipMemcpyHostToDevice, sf));
-      HIPCHK(ctx, hipMemcpyAsync(d.st_ts, p + o_ts, (size_t)n * 8, hipMemcpyHostToDevice, sf));
-      if (c.d_edge)
-        HIPCHK(ctx, hipMemcpyAsync(d.st_ef, p + o_ef, (size_t)n * c.d_edge * 4, hipMemcpyHostToDevice, sf));
+      // host inputs run on hip_stream alone, in order: one copy moves the batch
+      HIPCHK(ctx, hipMemcpyAsync(d.stage[par], p, o_ef + (size_t)n * c.d_edge * 4, hipMemcpyHostToDevice, sf));
       HIPCHK(ctx, hipEventRecord(ctx->pin_ev[pb], sf));
       ctx->pin_used[pb] = true;
       ctx->host_t_last = ts[n - 1];
       ctx->host_t_known = true;
       ctx->any_edges = true;
     }
-    dsrc = d.st_src; ddst = d.st_dst; dts = d.st_ts; def = d.st_ef;
+    char* st = d.stage[par];
+    dsrc = reinterpret_cast<const uint32_t*>(st);
+    ddst = reinterpret_cast<const uint32_t*>(st + (size_t)c.max_batch * 4);
+    dts = reinterpret_cast<const double*>(st + (size_t)c.max_batch * 8);
+    def = reinterpret_cast<const float*>(st + (size_t)c.max_batch * 16);
   } else if (n) {
     ctx->host_t_known = false;
     ctx->any_edges = true;
   }
   ctx->host_edges += n;
+  // the front part may start once the previous batch's compaction is done
+  if (overlapped && ctx->compact_recorded[par ^ 1]) HIPCHK(ctx, hipStreamWaitEvent(sf, ctx->ev_compact[par ^ 1], 0));
 
   hipStream_t s = ctx->stream;
   hipEvent_t* ev = stats ? ctx->stage_ev : nullptr;
@@ -590,8 +606,8 @@ int stgn_ingest_batch(stgn_ctx* ctx, uint32_t n, const uint32_t* src, const uint
   }
   { Scope t(ctx, KC_COMPACT); launch_compact(d, s, 0); }
   { Scope t(ctx, KC_COMPACT); launch_compact(d, s, 1); }
-  HIPCHK(ctx, hipEventRecord(ctx->ev_compact, s));
-  ctx->compact_recorded = true;
+  HIPCHK(ctx, hipEventRecord(ctx->ev_compact[par], s));
+  ctx->compact_recorded[par] = true;
   if (ev) hipEventRecord(ev[4], s);
   run_layers(ctx, false);
   if (ctx->timing) { Scope t(ctx, KC_NOOP); launch_noop(s); }   // event-pair overhead, for calibration
@@ -625,6 +641,7 @@ int stgn_ingest_batch(stgn_ctx* ctx, uint32_t n, const uint32_t* src, const uint
 
 int stgn_full_rebuild(stgn_ctx* ctx) {
   if (!ctx) return STGN_E_INVALID_ARG;
+  ctx->idle = false;
   run_layers(ctx, true);
   HIPCHK(ctx, hipGetLastError());
   return STGN_OK;
@@ -644,6 +661,7 @@ int stgn_get_embeddings(stgn_ctx* ctx, uint32_t layer, uint32_t n, const uint32_
   if (n == 0) return on_device ? STGN_OK : sync_and_poll(ctx);
   if (!nodes || !out) return fail(ctx, STGN_E_INVALID_ARG, "NULL nodes or out");
   if (on_device) {
+    ctx->idle = false;
     Scope t(ctx, KC_GATHER);
     launch_gather_rows(d, ctx->stream, layer, n, nodes, out);
     return STGN_OK;

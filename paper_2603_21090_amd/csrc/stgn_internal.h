@@ -107,7 +107,7 @@ struct Dev {
   double*  ets;                      // [max_edges] edge timestamps
   // per-batch scratch
   Ctrl*    ctrl;
-  uint32_t* st_src; uint32_t* st_dst; double* st_ts; float* st_ef;   // staging for host inputs
+  char*    stage[2];                 // staging blocks for host inputs (batches alternate)
   uint32_t* D;                       // [2*max_batch] sorted distinct endpoints
   uint32_t* seg_start;               // [2*max_batch + 1]
   uint32_t* last_slot;               // [2*max_batch] per D entry: slot (2*i + side) of its last edge

@@ -207,6 +207,57 @@ def test_device_inputs_match_host_inputs(binding):
     g.close()
 
 
+def test_back_to_back_device_batches_overlap_and_a_skipped_batch(binding):
+    """Device batches enqueued back to back without a synchronising call run their validation and
+    memory update on the library's second stream, beside the previous batch's attention layers.  The
+    whole stream goes in that way, with one invalid batch (skipped on the device) in the middle; the
+    final state must equal the oracle's, which never saw the invalid batch."""
+    import torch
+    w = tiny_workload(num_nodes=400, num_edges=6000, batch=100, layers=2, k=4, d_mem=16, d_edge=12, d_time=16,
+                      d_emb=16, d_msg=16, zipf_s=1.1)
+    st = synth.EdgeStream(w)
+    W = synth.make_weights(w)
+    o = orc.Oracle.from_workload(w, W)
+    g = binding.StreamTGN.from_workload(w, W)
+    allnodes = np.arange(w.num_nodes, dtype=np.uint32)
+
+    def dev(s, d, t, ef):
+        return (torch.from_numpy(s.astype(np.int32)).cuda(), torch.from_numpy(d.astype(np.int32)).cuda(),
+                torch.from_numpy(t).cuda(), torch.from_numpy(ef).cuda())
+
+    nb = w.num_batches - 1                                           # the skipped batch counts against the edge capacity
+    batches = [dev(*st.batch(b)) for b in range(nb)]                 # all inputs resident before the first call
+    s, d, t, ef = [a.copy() for a in st.batch(31)]
+    t[5] = t[4] - 1.0                                                # out of order: the device rejects the whole batch
+    bad = dev(s, d, t, ef)
+    torch.cuda.synchronize()
+    for b in range(nb):
+        rc, D, A = o.ingest(*st.batch(b))
+        assert rc == 0
+        assert g.ingest_batch(*batches[b], check=False) == 0
+        if b == 30:
+            assert g.ingest_batch(*bad, check=False) == 0
+    assert g.sync(check=False) == -3                                 # the skipped batch is reported once
+    assert g.sync(check=False) == 0
+    assert np.array_equal(g.get_affected(), A)
+    gm, gt = g.get_memory(allnodes)
+    om, ot = o.memory(allnodes)
+    assert np.array_equal(gt, ot)
+    check_rows(gm, om, "memory")
+    ref = o.embed_all()
+    for l in range(1, w.layers + 1):
+        check_rows(g.get_embeddings(allnodes, layer=l), ref[l - 1], f"layer {l}")
+    check_neighbours(g, o, allnodes)
+    # the same stream through the serial path (a synchronising call after every batch) gives the same bits
+    g2 = binding.StreamTGN.from_workload(w, W)
+    for b in range(nb):
+        g2.ingest_batch(*st.batch(b))
+        g2.sync()
+    for l in range(1, w.layers + 1):
+        assert np.array_equal(g.get_embeddings(allnodes, layer=l), g2.get_embeddings(allnodes, layer=l))
+    g.close(); g2.close()
+
+
 def test_rows_outside_A_untouched_and_rebuild_is_bit_identical(binding):
     """Theorem 'Equivalence of Incremental Computation': cached rows outside the affected set are
     bit-identical before and after a batch; a full rebuild reproduces every cached row bit for bit
