@@ -110,7 +110,10 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
   uint32_t n = count_max;
   if (count_ptr) { const uint32_t c = *count_ptr; n = c < count_max ? c : count_max; }
   const uint32_t ntiles = (n + kTM - 1) / kTM;
-  const uint32_t lane = threadIdx.x & 63u, sub = lane & 15u, grp = lane >> 4;
+  // Per-lane indices and everything derived from them are re-derived at the top of every tile from an
+  // opaque copy of the thread index: otherwise the compiler hoists dozens of loop-invariant address
+  // registers out of the persistent tile loop and keeps them alive (or spilled) across all phases.
+  uint32_t tid = threadIdx.x, lane = tid & 63u, sub = lane & 15u, grp = lane >> 4;
   // wave index, made provably uniform so that tile indices and weight addresses stay in scalar registers
   const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
   const uint32_t k = a.k, dk = a.dk;
@@ -135,15 +138,23 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
   // operand padding (columns nobody writes) must be finite: clear the tiles once
   for (uint32_t x = threadIdx.x; x < ll.off_r; x += 256) lds[x] = 0.0f;
   bool tok[NT][4];
-#pragma unroll
-  for (int t = 0; t < NT; ++t)
-#pragma unroll
-    for (int c = 0; c < 4; ++c) tok[t][c] = (uint32_t)t * kSlot + 4u * sub + c < a.d_time;
   uint32_t gathered = 0;
-  const uint32_t a_x = a16_lane_off(ll.ldx), a_q = a16_lane_off(ll.ldq), a_z = a16_lane_off(ll.ldz);
-  const uint32_t c_off_x = m16_row(lane, 0) * ll.ldx + m16_col(lane);
-  const uint32_t c_off_q = m16_row(lane, 0) * ll.ldq + m16_col(lane);
-  const uint32_t c_off_z = m16_row(lane, 0) * ll.ldz + m16_col(lane);
+  uint32_t a_x, a_q, a_z, c_off_x, c_off_q, c_off_z;
+  auto derive_lane = [&]() {
+    asm volatile("" : "+v"(tid));
+    lane = tid & 63u; sub = lane & 15u; grp = lane >> 4;
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+      for (int c = 0; c < 4; ++c) tok[t][c] = (uint32_t)t * kSlot + 4u * sub + c < a.d_time;
+    a_x = (lane & 15u) * ll.ldx + 4u * (lane >> 4);
+    a_q = (lane & 15u) * ll.ldq + 4u * (lane >> 4);
+    a_z = (lane & 15u) * ll.ldz + 4u * (lane >> 4);
+    c_off_x = (4u * (lane >> 4)) * ll.ldx + (lane & 15u);
+    c_off_q = (4u * (lane >> 4)) * ll.ldq + (lane & 15u);
+    c_off_z = (4u * (lane >> 4)) * ll.ldz + (lane & 15u);
+  };
+  derive_lane();
 
   // ---- phase-2 work units: (head, pair of valid qt column tiles); wave w owns units w, w + 4, ...
   // Lane i of `udesc` holds the description of the wave's i-th unit (head, first tile, whether a
@@ -199,15 +210,15 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
   double p_tl[2];
   float4 p_x[2];
   auto stage_a = [&](uint32_t t) {
-    if (threadIdx.x < kTM) {
-      const uint32_t r = t * kTM + threadIdx.x;
-      s_next[threadIdx.x] = (t < ntiles && r < n) ? (rows ? rows[r] : r) : 0xFFFFFFFFu;
+    if (tid < kTM) {
+      const uint32_t r = t * kTM + tid;
+      s_next[tid] = (t < ntiles && r < n) ? (rows ? rows[r] : r) : 0xFFFFFFFFu;
     }
   };
   auto stage_b = [&]() {
 #pragma unroll
     for (int e = 0; e < 2; ++e) {
-      const uint32_t x = threadIdx.x + 256u * e;
+      const uint32_t x = tid + 256u * e;
       {
         const uint32_t xc = x < kTM * k ? x : 0u;
         const uint32_t r = xc / k, sl = xc - r * k;
@@ -250,17 +261,18 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
   if (pf_ok) stage_b(); else stage_none();
 
   for (uint32_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+    derive_lane();
     // ================================================================ phase 0: stage the tile
     Ops16<2> oq;                                              // first weight chunk of this wave's first unit
     const uint32_t w1 = wave < ntd ? wave : 0u;              // loads are unconditional (clamped), products are not
     load_b16(a.WQ + (size_t)w1 * g_in * kGrpFloats, 0, oq.b[0]);
     load_b16(a.WQ + (size_t)(w1 + 4 < ntd ? w1 + 4 : w1) * g_in * kGrpFloats, 0, oq.b[1]);
-    if (threadIdx.x < kTM) s_node[threadIdx.x] = s_next[threadIdx.x];
+    if (tid < kTM) s_node[tid] = s_next[tid];
     if (pf_ok) {
       // everything was fetched a tile ago: registers -> LDS
 #pragma unroll
       for (int e = 0; e < 2; ++e) {
-        const uint32_t x = threadIdx.x + 256u * e;
+        const uint32_t x = tid + 256u * e;
         if (x < kTM * k) {
           const uint32_t r = x / k, sl = x - r * k;
           place_ring(r, sl, s_next[r] != 0xFFFFFFFFu, p_ring[e], p_deg[e], p_tl[e]);
@@ -275,7 +287,7 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
     __syncthreads();
     if (!pf_ok) {
       // thread (row, slot) fetches its slot without waiting for the row's degree (both loads leave together)
-      for (uint32_t x = threadIdx.x; x < kTM * k; x += 256) {
+      for (uint32_t x = tid; x < kTM * k; x += 256) {
         const uint32_t r = x / k, sl = x - r * k;
         const uint32_t node = s_node[r];
         const bool live = node != 0xFFFFFFFFu;
@@ -283,7 +295,7 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
         place_ring(r, sl, live, a.ring[(size_t)nn * k + sl], a.deg[nn], a.t_last[nn]);
       }
       const uint32_t total = kTM * qpr;
-      for (uint32_t x0 = threadIdx.x; x0 < total; x0 += 512u) {
+      for (uint32_t x0 = tid; x0 < total; x0 += 512u) {
         float4 v[2];
         uint32_t rr[2], cc[2];
         bool ok[2];
