@@ -54,8 +54,12 @@ typedef struct stgn_ctx stgn_ctx;
 /* Model and capacity description (paper Sec. 2.2 for the dimensions).
  * d_mem = 0 selects a memoryless (TGAT-style) model: no message/GRU stage, layer-0 rows
  * are the static node features.  Layer-0 width is d_mem + d_node and must be > 0.
- * heads must divide d_emb; d_emb / heads <= 128; layers <= STGN_MAX_LAYERS;
- * max_batch <= STGN_MAX_BATCH; max_edges < 2^31. */
+ * heads is 1, 2 or 4 and divides d_emb; heads * ceil(d_emb / heads / 64) <= 4 (so d_emb <= 256);
+ * d_time <= 128; d_mem + d_node <= 512; d_edge <= 1024; layers <= STGN_MAX_LAYERS;
+ * max_batch <= STGN_MAX_BATCH; max_edges < 2^31.
+ * Keys and values of Eq. attn_detail are linear in [h_u | e | phi(dt)]; their node and edge parts
+ * are kept as cached rows (per node and layer, per edge and layer: 2 * 64 * heads * ceil(d_emb /
+ * heads / 64) floats each), so the workspace grows by layers * max_edges such rows. */
 typedef struct {
   uint32_t num_nodes;
   uint64_t max_edges;
@@ -98,7 +102,8 @@ typedef struct {
                                               | embed | total; microseconds from HIP events    */
 } stgn_batch_stats;
 
-/* Device bytes stgn_create needs for this configuration (host computation only). */
+/* Device bytes stgn_create needs for this configuration (host computation only): the whole
+ * device-resident state, dominated by the per-edge tables (adjacency, features, cached rows). */
 int stgn_query_workspace(const stgn_config *cfg, size_t *device_bytes);
 
 /* Builds the state on the current device: zero memory (Sec. 2.2.4), empty adjacency, every
