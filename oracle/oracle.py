@@ -52,6 +52,7 @@ def lib():
         _lib.orc_ingest.argtypes = [C.c_void_p, C.c_uint32, _u32p, _u32p, _f64p, _f32p, _u32p, _u32p, _u32p, _u32p]
         _lib.orc_embed_all.argtypes = [C.c_void_p, _f32p]
         _lib.orc_embed_nodes.argtypes = [C.c_void_p, C.c_uint32, C.c_uint32, _u32p, _f32p]
+        _lib.orc_predict.argtypes = [C.c_void_p, C.c_uint32, _u32p, _u32p, _f64p, C.c_int, _f32p, C.c_float, _f64p]
         _lib.orc_neighbors.restype = C.c_uint32
         _lib.orc_neighbors.argtypes = [C.c_void_p, C.c_uint32, _u32p, _u32p, _f64p]
         _lib.orc_degree.restype = C.c_uint32
@@ -136,6 +137,18 @@ class Oracle:
         layer = self.layers if layer is None else layer
         out = np.empty((len(nodes), self.d_emb), dtype=np.float32)
         lib().orc_embed_nodes(self._h, layer, len(nodes), _p(nodes, _u32p), _p(out, _f32p))
+        return out
+
+    def predict(self, src, dst, ts, w, b, at_edge_time=False) -> np.ndarray:
+        """Link scores of a batch that has not been ingested yet (root embeddings from the current state)."""
+        src = np.ascontiguousarray(src, dtype=np.uint32)
+        dst = np.ascontiguousarray(dst, dtype=np.uint32)
+        ts = np.ascontiguousarray(ts, dtype=np.float64)
+        w = _f32(w)
+        assert w.shape == (2 * self.d_emb,)
+        out = np.empty(len(src), dtype=np.float64)
+        lib().orc_predict(self._h, len(src), _p(src, _u32p), _p(dst, _u32p), _p(ts, _f64p), int(at_edge_time),
+                          _p(w, _f32p), float(b), _p(out, _f64p))
         return out
 
     def neighbors(self, node):

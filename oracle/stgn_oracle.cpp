@@ -22,6 +22,7 @@
 //                              Incremental Computation" is the property it must give
 //   batching ................. Sec. 3.6.2 (pre-batch memory for all reads, one GRU
 //                              transition per node per batch)
+//   root inference + score ... Algorithm 1 (embed, predict, then update), Eq. (parallel_embed)
 //
 // Pins (tests/test_oracle_*.py): closed forms for the time encoding and the GRU,
 // library GRU cell and library scaled-dot-product attention as cross-checks,
@@ -161,12 +162,11 @@ void h0_row(const Oracle& o, uint32_t v, float* row) {
   for (uint32_t i = 0; i < o.d_node; ++i) row[o.d_mem + i] = o.xfeat[(size_t)v * o.d_node + i];
 }
 
-// One target row of layer l (1-based) given a callback that yields layer l-1 rows.
+// One target row of layer l (1-based) at query time tq, given a callback that yields layer l-1 rows.
 template <class PrevRow>
-void embed_row(const Oracle& o, uint32_t l, uint32_t v, PrevRow prev, float* out_row) {
+void embed_row_at(const Oracle& o, uint32_t l, uint32_t v, double tq, PrevRow prev, float* out_row) {
   const Layer& Ly = o.L[l - 1];
   const uint32_t din = Ly.d_in, d = o.d_emb, dt = o.d_time, de = o.d_edge;
-  const double tq = o.t_last[v];
   std::vector<double> qin(din + dt), q(d);
   std::vector<float> hrow(din);
   prev(v, hrow.data());
@@ -187,6 +187,12 @@ void embed_row(const Oracle& o, uint32_t l, uint32_t v, PrevRow prev, float* out
   std::vector<double> res(d);
   attention(d, o.heads, n, q.data(), K.data(), V.data(), Ly.WO.data(), Ly.bO.data(), res.data());
   for (uint32_t i = 0; i < d; ++i) out_row[i] = (float)res[i];
+}
+
+// The row a refreshed cache holds: query time = time of the node's latest edge.
+template <class PrevRow>
+void embed_row(const Oracle& o, uint32_t l, uint32_t v, PrevRow prev, float* out_row) {
+  embed_row_at(o, l, v, o.t_last[v], prev, out_row);
 }
 
 void copyf(std::vector<float>& dst, const float* src, size_t n) {
@@ -360,6 +366,32 @@ static void embed_rec(const Oracle& o, uint32_t l, uint32_t v, float* row) {
 void orc_embed_nodes(void* h, uint32_t layer, uint32_t n, const uint32_t* nodes, float* out) {
   Oracle& o = *(Oracle*)h;
   for (uint32_t i = 0; i < n; ++i) embed_rec(o, layer, nodes[i], out + (size_t)i * o.d_emb);
+}
+
+// Per-batch root-node inference (Algorithm 1, "Link prediction"; Sec. 3.6.2, Eq. parallel_embed): for every
+// edge (u, v, t) of a batch that has NOT been ingested yet, the embeddings of u and v from the current
+// (pre-batch) state and the link score, which the paper's error analysis takes as a linear function of the
+// concatenated embeddings:  y = [h_u || h_v] . w + b.
+//   at_edge_time = 0: h = the refreshed cache row (query time = the node's latest edge);
+//   at_edge_time = 1: the final layer is evaluated at the edge's own time t (time gaps t - t_j, query side
+//                     phi(0)); the layers below it are the refreshed rows (layered snapshot).
+// w: [2 d_emb] (source half first).  out: [n] fp64.
+void orc_predict(void* h, uint32_t n, const uint32_t* src, const uint32_t* dst, const double* ts, int at_edge_time,
+                 const float* w, float b, double* out) {
+  Oracle& o = *(Oracle*)h;
+  const uint32_t d = o.d_emb;
+  std::vector<float> hu(d), hv(d);
+  auto root = [&](uint32_t v, double t, float* row) {
+    if (!at_edge_time) { embed_rec(o, o.layers, v, row); return; }
+    embed_row_at(o, o.layers, v, t, [&](uint32_t u, float* r) { embed_rec(o, o.layers - 1, u, r); }, row);
+  };
+  for (uint32_t i = 0; i < n; ++i) {
+    root(src[i], ts[i], hu.data());
+    root(dst[i], ts[i], hv.data());
+    double y = (double)b;
+    for (uint32_t c = 0; c < d; ++c) y += (double)hu[c] * (double)w[c] + (double)hv[c] * (double)w[d + c];
+    out[i] = y;
+  }
 }
 
 // most recent <= k neighbours of `node`, most recent first; returns the count

@@ -137,8 +137,9 @@ def torch_phi(omega, phase, x):
     return torch.cos(x[..., None] * om + ph) / math.sqrt(len(omega))
 
 
-def torch_embed_all(w, W, rings, ts_all, efeat_all, H0, t_last):
-    """Layered embeddings with padded neighbour tensors and library attention (fp64)."""
+def torch_embed_all(w, W, rings, ts_all, efeat_all, H0, t_last, t_final=None):
+    """Layered embeddings with padded neighbour tensors and library attention (fp64).  t_final: query
+    times of the LAST layer (default: t_last, like every other layer)."""
     N, k, H = w.num_nodes, w.k, w.heads
     nbr = torch.zeros((N, k), dtype=torch.long)
     eid = torch.zeros((N, k), dtype=torch.long)
@@ -156,6 +157,8 @@ def torch_embed_all(w, W, rings, ts_all, efeat_all, H0, t_last):
     for l in range(w.layers):
         T = lambda a: torch.tensor(a[l], dtype=torch.float64)
         q = torch.cat([Hprev, phi0], 1) @ T(W["W_Q"])
+        if t_final is not None and l == w.layers - 1:
+            phi = torch_phi(W["omega"], W["phase"], torch.tensor(t_final)[:, None] - torch.tensor(ts_all)[eid])
         z = torch.cat([Hprev[nbr], E, phi], 2)
         K, V = z @ T(W["W_K"]), z @ T(W["W_V"])
         dk = w.d_emb // H
