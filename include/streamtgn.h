@@ -144,6 +144,27 @@ int stgn_get_embeddings(stgn_ctx *ctx, uint32_t layer, uint32_t n, const uint32_
 /* Recompute every layer for every node from the current state (Sec. 3.5, full rebuild). */
 int stgn_full_rebuild(stgn_ctx *ctx);
 
+/* Link-prediction head (Algorithm 1, "Link prediction").  The paper's error analysis (Sec. 3.6.3)
+ * takes the score as a linear function of the concatenated source and destination embeddings:
+ *     y = [h_u | h_v] . w + b.
+ * w: host [2 * d_emb], source half first; copied.  May be called again at any time. */
+int stgn_set_predictor(stgn_ctx *ctx, const float *w, float b);
+
+/* Per-batch root-node inference (Algorithm 1: embed, predict, THEN update; Sec. 3.6.2,
+ * Eq. parallel_embed): link scores of n edges (u_i, v_i, t_i) that have NOT been ingested yet,
+ * from the current (pre-batch) state.  Call it before stgn_ingest_batch of the same edges.
+ *   at_edge_time = 0: h_u, h_v are the cached final-layer rows (two O(1) lookups per edge: the
+ *       caches are exact after every batch, so no root is ever dirty at this point);
+ *   at_edge_time = 1: the final layer is evaluated for the 2n roots at the edge's own time (time
+ *       gaps t_i - t_j to the root's recent neighbours, query side phi(0)); the layers below are
+ *       the cached rows.  With one layer this is Eq. parallel_embed evaluated at t_i.
+ * src, dst, ts, scores: [n], all on the host (inputs_on_device = 0; synchronises) or all on the
+ * device (1; asynchronous on hip_stream).  n <= max_batch.  Needs stgn_set_predictor.  Host
+ * inputs with an id >= num_nodes return STGN_E_NODE_OUT_OF_RANGE; device inputs give that edge
+ * the score NaN.  Changes no state. */
+int stgn_predict_batch(stgn_ctx *ctx, uint32_t n, const uint32_t *src, const uint32_t *dst,
+                       const double *ts, int at_edge_time, int inputs_on_device, float *scores);
+
 /* Waits for the stream; returns the code of the first skipped device-side batch (and clears it). */
 int stgn_sync(stgn_ctx *ctx);
 

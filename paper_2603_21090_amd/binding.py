@@ -57,7 +57,8 @@ _lib = None
 
 EXPORTS = ("stgn_query_workspace", "stgn_create", "stgn_destroy", "stgn_ingest_batch", "stgn_get_embeddings",
            "stgn_full_rebuild", "stgn_sync", "stgn_get_affected", "stgn_get_neighbors", "stgn_get_history",
-           "stgn_get_memory", "stgn_get_totals", "stgn_kernel_times", "stgn_last_error", "stgn_version")
+           "stgn_get_memory", "stgn_get_totals", "stgn_kernel_times", "stgn_last_error", "stgn_version",
+           "stgn_set_predictor", "stgn_predict_batch")
 
 
 def load_library():
@@ -85,6 +86,8 @@ def load_library():
     L.stgn_get_totals.argtypes = [vp] + [C.POINTER(C.c_uint64)] * 6
     L.stgn_kernel_times.argtypes = [vp, C.c_int, C.c_int, C.c_uint32, C.POINTER(C.c_char_p), _f64p,
                                     C.POINTER(C.c_uint64)]
+    L.stgn_set_predictor.argtypes = [vp, vp, C.c_float]
+    L.stgn_predict_batch.argtypes = [vp, C.c_uint32, vp, vp, vp, C.c_int, C.c_int, vp]
     L.stgn_last_error.argtypes = [vp]
     L.stgn_last_error.restype = C.c_char_p
     L.stgn_version.restype = C.c_char_p
@@ -219,6 +222,29 @@ class StreamTGN:
         nodes = np.ascontiguousarray(nodes, dtype=np.uint32)
         out = np.empty((len(nodes), self.cfg.d_emb), dtype=np.float32)
         self._check(self._L.stgn_get_embeddings(self._h, layer, len(nodes), _ptr(nodes), _ptr(out), 0))
+        return out
+
+    def set_predictor(self, w, b):
+        w = np.ascontiguousarray(w, dtype=np.float32)
+        assert w.shape == (2 * self.cfg.d_emb,)
+        self._check(self._L.stgn_set_predictor(self._h, _ptr(w), float(b)))
+
+    def predict_batch(self, src, dst, ts, at_edge_time=False):
+        """Link scores of edges that have not been ingested yet: numpy in, numpy out (synchronises), or
+        torch device tensors in, a device tensor out (asynchronous)."""
+        torch = self._torch
+        if isinstance(src, torch.Tensor):
+            out = torch.empty(src.shape[0], dtype=torch.float32, device=src.device)
+            self._check(self._L.stgn_predict_batch(self._h, src.shape[0], C.c_void_p(src.data_ptr()),
+                                                   C.c_void_p(dst.data_ptr()), C.c_void_p(ts.data_ptr()),
+                                                   int(at_edge_time), 1, C.c_void_p(out.data_ptr())))
+            return out
+        src = np.ascontiguousarray(src, dtype=np.uint32)
+        dst = np.ascontiguousarray(dst, dtype=np.uint32)
+        ts = np.ascontiguousarray(ts, dtype=np.float64)
+        out = np.empty(len(src), dtype=np.float32)
+        self._check(self._L.stgn_predict_batch(self._h, len(src), _ptr(src), _ptr(dst), _ptr(ts), int(at_edge_time), 0,
+                                               _ptr(out)))
         return out
 
     def full_rebuild(self):

@@ -14,7 +14,7 @@ using namespace stgn;
 namespace {
 
 const char* const kClassNames[KC_COUNT] = {"stage_sort", "memory_update", "apply", "plan", "expand", "compact",
-                                           "layer", "gather_rows", "noop", "project"};
+                                           "layer", "gather_rows", "noop", "project", "predict"};
 
 std::string g_create_error;
 
@@ -37,6 +37,7 @@ struct stgn_ctx {
   bool compact_recorded[2] = {false, false};
   int parity = 0;                   // staging block and compaction event of the next batch
   bool idle = true;                 // nothing was enqueued since the library last synchronised `stream`
+  bool have_predictor = false;      // stgn_set_predictor was called
   std::string err;
   uint64_t host_edges = 0;          // upper bound of edges enqueued so far
   bool host_t_known = true;         // host knows the last ingested timestamp
@@ -188,6 +189,14 @@ size_t layout(const stgn_config& c, char* base, Dev* d) {
     else { d->R[l] = b.take<uint32_t>(N); ++d->n_lists; }
   }
   for (uint32_t l = 0; l < c.layers; ++l) d->L[l].d_in = l == 0 ? d->d0 : c.d_emb;
+  d->pred_rows = b.take<uint32_t>(B2);
+  d->pred_tq = b.take<double>(B2);
+  d->pred_out = b.take<float>((size_t)B2 * c.d_emb);
+  d->pred_src = b.take<uint32_t>(c.max_batch);
+  d->pred_dst = b.take<uint32_t>(c.max_batch);
+  d->pred_ts = b.take<double>(c.max_batch);
+  d->pred_scores = b.take<float>(c.max_batch);
+  d->pred_w = b.take<float>(2 * c.d_emb + 1);
   d->q_cap = 65536;
   d->qnodes = b.take<uint32_t>(d->q_cap);
   d->qout = b.take<float>((size_t)d->q_cap * std::max(d->d0, c.d_emb));
@@ -644,6 +653,57 @@ int stgn_full_rebuild(stgn_ctx* ctx) {
   ctx->idle = false;
   run_layers(ctx, true);
   HIPCHK(ctx, hipGetLastError());
+  return STGN_OK;
+}
+
+int stgn_set_predictor(stgn_ctx* ctx, const float* w, float b) {
+  if (!ctx) return STGN_E_INVALID_ARG;
+  if (!w) return fail(ctx, STGN_E_INVALID_ARG, "NULL weights");
+  const uint32_t d2 = 2 * ctx->cfg.d_emb;
+  std::vector<float> wb(w, w + d2);
+  wb.push_back(b);
+  // ordered after predictions already enqueued, before those that follow
+  HIPCHK(ctx, hipStreamSynchronize(ctx->stream));
+  HIPCHK(ctx, hipMemcpy(ctx->d.pred_w, wb.data(), wb.size() * sizeof(float), hipMemcpyHostToDevice));
+  ctx->have_predictor = true;
+  return STGN_OK;
+}
+
+int stgn_predict_batch(stgn_ctx* ctx, uint32_t n, const uint32_t* src, const uint32_t* dst, const double* ts,
+                       int at_edge_time, int inputs_on_device, float* scores) {
+  if (!ctx) return STGN_E_INVALID_ARG;
+  const stgn_config& c = ctx->cfg;
+  const Dev& d = ctx->d;
+  if (!ctx->have_predictor) return fail(ctx, STGN_E_INVALID_ARG, "stgn_set_predictor has not been called");
+  if (n > c.max_batch) return fail(ctx, STGN_E_BATCH_TOO_LARGE, "more edges than max_batch");
+  if (n == 0) return inputs_on_device ? STGN_OK : sync_and_poll(ctx);
+  if (!src || !dst || !ts || !scores) return fail(ctx, STGN_E_INVALID_ARG, "NULL array");
+  hipStream_t s = ctx->stream;
+  const uint32_t *dsrc = src, *ddst = dst;
+  const double* dts = ts;
+  float* dout = scores;
+  if (!inputs_on_device) {
+    for (uint32_t i = 0; i < n; ++i)
+      if (src[i] >= c.num_nodes || dst[i] >= c.num_nodes) return fail(ctx, STGN_E_NODE_OUT_OF_RANGE, "endpoint id >= num_nodes");
+    HIPCHK(ctx, hipMemcpyAsync(d.pred_src, src, (size_t)n * 4, hipMemcpyHostToDevice, s));
+    HIPCHK(ctx, hipMemcpyAsync(d.pred_dst, dst, (size_t)n * 4, hipMemcpyHostToDevice, s));
+    HIPCHK(ctx, hipMemcpyAsync(d.pred_ts, ts, (size_t)n * 8, hipMemcpyHostToDevice, s));
+    dsrc = d.pred_src; ddst = d.pred_dst; dts = d.pred_ts; dout = d.pred_scores;
+  }
+  ctx->idle = false;
+  {
+    Scope t(ctx, KC_PREDICT);
+    if (at_edge_time) {
+      launch_predict_prep(d, s, n, dsrc, ddst, dts);
+      launch_layer_roots(d, s, 2 * n);
+    }
+    launch_predict_head(d, s, n, dsrc, ddst, at_edge_time, dout);
+  }
+  HIPCHK(ctx, hipGetLastError());
+  if (!inputs_on_device) {
+    HIPCHK(ctx, hipMemcpyAsync(scores, d.pred_scores, (size_t)n * sizeof(float), hipMemcpyDeviceToHost, s));
+    return sync_and_poll(ctx);
+  }
   return STGN_OK;
 }
 

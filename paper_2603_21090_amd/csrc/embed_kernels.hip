@@ -22,6 +22,41 @@ __global__ void gather_rows_kernel(Table T, uint32_t width, uint32_t n, const ui
   }
 }
 
+// Roots of n edges for stgn_predict_batch: source and destination of edge i at list positions 2i and
+// 2i + 1, both queried at the edge's time.  An id past the node count becomes a dead row.
+__global__ void predict_prep_kernel(Dev d, uint32_t n, const uint32_t* __restrict__ src, const uint32_t* __restrict__ dst,
+                                    const double* __restrict__ ts) {
+  for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
+    const uint32_t u = src[i], v = dst[i];
+    d.pred_rows[2 * i] = u < d.N ? u : 0xFFFFFFFFu;
+    d.pred_rows[2 * i + 1] = v < d.N ? v : 0xFFFFFFFFu;
+    d.pred_tq[2 * i] = ts[i];
+    d.pred_tq[2 * i + 1] = ts[i];
+  }
+}
+
+// Linear link score (Algorithm 1, "Link prediction"): one 64-lane wave per edge,
+// y = h_u . w[0 : d) + h_v . w[d : 2d) + b, the two rows either cached final-layer rows or the rows
+// the final layer just produced for the roots.
+__global__ __launch_bounds__(256) void predict_head_kernel(Dev d, uint32_t n, const uint32_t* __restrict__ src,
+                                                           const uint32_t* __restrict__ dst, int at_edge_time,
+                                                           float* __restrict__ scores) {
+  const uint32_t lane = threadIdx.x & 63u;
+  const uint32_t wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, nwaves = (gridDim.x * blockDim.x) >> 6;
+  const uint32_t de = d.d_emb;
+  const Table HL = d.H[d.layers];
+  for (uint32_t i = wave; i < n; i += nwaves) {
+    const uint32_t u = src[i], v = dst[i];
+    const bool ok = u < d.N && v < d.N;
+    const float* hu = at_edge_time ? d.pred_out + (size_t)(2 * i) * de : HL.base + (size_t)(ok ? u : 0u) * HL.ld;
+    const float* hv = at_edge_time ? d.pred_out + (size_t)(2 * i + 1) * de : HL.base + (size_t)(ok ? v : 0u) * HL.ld;
+    float acc = 0.0f;
+    for (uint32_t c = lane; c < de; c += 64) acc = fmaf(hu[c], d.pred_w[c], fmaf(hv[c], d.pred_w[de + c], acc));
+    for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
+    if (lane == 0) scores[i] = ok ? acc + d.pred_w[2 * de] : __builtin_nanf("");
+  }
+}
+
 LaunchArgs make_args(const Dev& d, uint32_t layer) {
   const LayerDev& L = d.L[layer];
   LaunchArgs a{};
@@ -65,6 +100,24 @@ void launch_layer(const Dev& d, hipStream_t s, uint32_t layer, const uint32_t* r
   LaunchArgs a = make_args(d, layer);
   a.s = s; a.rows = rows; a.cp = cp; a.cm = cm; a.set_attr = false;
   go_heads(a);
+}
+
+void launch_predict_prep(const Dev& d, hipStream_t s, uint32_t n, const uint32_t* src, const uint32_t* dst, const double* ts) {
+  hipLaunchKernelGGL(predict_prep_kernel, dim3((n + 255) / 256), dim3(256), 0, s, d, n, src, dst, ts);
+}
+
+// the final layer for the roots listed in pred_rows, at the times in pred_tq, into pred_out
+void launch_layer_roots(const Dev& d, hipStream_t s, uint32_t nroots) {
+  LaunchArgs a = make_args(d, d.layers - 1);
+  a.k.tq_rows = d.pred_tq;
+  a.k.out_rows = d.pred_out;
+  a.s = s; a.rows = d.pred_rows; a.cp = nullptr; a.cm = nroots; a.set_attr = false;
+  go_heads(a);
+}
+
+void launch_predict_head(const Dev& d, hipStream_t s, uint32_t n, const uint32_t* src, const uint32_t* dst,
+                         int at_edge_time, float* scores) {
+  hipLaunchKernelGGL(predict_head_kernel, dim3((n + 3) / 4), dim3(256), 0, s, d, n, src, dst, at_edge_time, scores);
 }
 
 void launch_gather_rows(const Dev& d, hipStream_t s, uint32_t layer, uint32_t n, const uint32_t* nodes, float* out) {

@@ -79,6 +79,9 @@ struct LayerArgs {
   const float* Hin; float* Hout;
   const float* KVn; const float* KVe;              // cached key|value rows of the input table's nodes / of the edges
   float* KVout;                                    // the next layer's node table (null for the last layer)
+  // root-node inference: query time per list row instead of the node's last-interaction time, and the
+  // output rows go to out_rows[list position] instead of the layer cache (both null otherwise)
+  const double* tq_rows; float* out_rows;
   const RingEntry* ring; const uint32_t* deg; const double* t_last;
   const double* om_rev; const double* ph_rev;
   Ctrl* ctrl;
@@ -100,7 +103,7 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
                                                          const uint32_t* count_ptr, uint32_t count_max) {
   extern __shared__ __align__(16) float lds[];
   __shared__ uint32_t s_node[kTM], s_cnt[kTM], s_next[kTM];
-  __shared__ double s_tq[kTM];
+  __shared__ double s_tq[kTM], s_tqn[kTM];
   __shared__ __align__(16) double s_om[NT * kSlot], s_ph[NT * kSlot];
   static_assert(KS % H == 0, "whole slots per head");
   constexpr int SH = KS / H;                  // slots per head
@@ -213,6 +216,7 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
     if (tid < kTM) {
       const uint32_t r = t * kTM + tid;
       s_next[tid] = (t < ntiles && r < n) ? (rows ? rows[r] : r) : 0xFFFFFFFFu;
+      s_tqn[tid] = (a.tq_rows && t < ntiles && r < n) ? a.tq_rows[r] : 0.0;
     }
   };
   auto stage_b = [&]() {
@@ -247,7 +251,7 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
     const uint32_t j = newest >= sl ? newest - sl : newest + k - sl;
     if (j >= cnt) { e.nbr = 0u; e.eid = 0u; e.t = 0.0; }
     Rs[r * k + j] = e;
-    if (sl == 0) { s_cnt[r] = cnt; s_tq[r] = tl; }
+    if (sl == 0) { s_cnt[r] = cnt; s_tq[r] = a.tq_rows ? s_tqn[r] : tl; }
   };
   stage_a(blockIdx.x);
   __syncthreads();
@@ -616,7 +620,12 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
             for (int r = 0; r < 4; ++r) {
               const uint32_t node = s_node[m16_row(lane, r)];
               const float v = acc[t][r] + b;
-              if (node != 0xFFFFFFFFu) a.Hout[(size_t)node * a.ld_out + col] = v;
+              if (a.out_rows) {
+                const uint32_t lr = tile * kTM + m16_row(lane, r);
+                if (lr < n) a.out_rows[(size_t)lr * a.d_emb + col] = v;
+              } else if (node != 0xFFFFFFFFu) {
+                a.Hout[(size_t)node * a.ld_out + col] = v;
+              }
               Qs[c_off_q - m16_col(lane) + r * ll.ldq + col] = v;     // operand of phase 6 (q is no longer needed)
             }
           }
@@ -653,8 +662,8 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
                         (uint32_t)__builtin_amdgcn_readlane((int)gathered, 16) +
                         (uint32_t)__builtin_amdgcn_readlane((int)gathered, 32) +
                         (uint32_t)__builtin_amdgcn_readlane((int)gathered, 48);
-  if (lane == 0 && gsum) atomicAdd((unsigned long long*)&a.ctrl->tot_gathered, (unsigned long long)gsum);
-  if (blockIdx.x == 0 && threadIdx.x == 0 && n) atomicAdd((unsigned long long*)&a.ctrl->tot_rows, (unsigned long long)n);
+  if (lane == 0 && gsum && !a.out_rows) atomicAdd((unsigned long long*)&a.ctrl->tot_gathered, (unsigned long long)gsum);
+  if (blockIdx.x == 0 && threadIdx.x == 0 && n && !a.out_rows) atomicAdd((unsigned long long*)&a.ctrl->tot_rows, (unsigned long long)n);
 }
 
 // ---- dispatch over (heads, key slots, time slots)

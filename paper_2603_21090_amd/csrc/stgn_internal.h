@@ -126,6 +126,11 @@ struct Dev {
   uint32_t* R[STGN_MAX_LAYERS];
   uint32_t thr[STGN_MAX_LAYERS];
   uint32_t n_lists;                  // separate lists (layers whose threshold does not cover every flag)
+  // root-node inference (stgn_predict_batch): the 2n roots (source, destination of edge i at 2i, 2i+1),
+  // their query times, their final-layer rows, staging for host inputs / outputs, and the head [w | b]
+  uint32_t* pred_rows; double* pred_tq; float* pred_out;
+  uint32_t* pred_src; uint32_t* pred_dst; double* pred_ts; float* pred_scores;
+  float*   pred_w;
   uint32_t* qnodes; float* qout;     // staging for host-side get_embeddings
   uint32_t q_cap;
   // parameters
@@ -142,7 +147,7 @@ inline __host__ __device__ uint32_t round_up(uint32_t x, uint32_t m) { return (x
 
 // Kernel classes for the optional event timing
 enum KernelClass { KC_SORT = 0, KC_MEMORY, KC_APPLY, KC_PLAN, KC_EXPAND, KC_COMPACT, KC_LAYER,
-                   KC_GATHER, KC_NOOP, KC_PROJECT, KC_COUNT };
+                   KC_GATHER, KC_NOOP, KC_PROJECT, KC_PREDICT, KC_COUNT };
 
 // ---- launch wrappers (one per kernel family), defined in the .hip files ----
 void launch_stage_sort(const Dev& d, hipStream_t s, uint32_t n, const uint32_t* src, const uint32_t* dst,
@@ -157,6 +162,11 @@ void launch_compact(const Dev& d, hipStream_t s, int phase);
 void launch_layer(const Dev& d, hipStream_t s, uint32_t layer, const uint32_t* rows, const uint32_t* count_ptr,
                   uint32_t count_max);
 void launch_gather_rows(const Dev& d, hipStream_t s, uint32_t layer, uint32_t n, const uint32_t* nodes, float* out);
+// root-node inference: roots and query times of n edges; the final layer for the 2n roots; the linear head
+void launch_predict_prep(const Dev& d, hipStream_t s, uint32_t n, const uint32_t* src, const uint32_t* dst, const double* ts);
+void launch_layer_roots(const Dev& d, hipStream_t s, uint32_t nroots);
+void launch_predict_head(const Dev& d, hipStream_t s, uint32_t n, const uint32_t* src, const uint32_t* dst,
+                         int at_edge_time, float* scores);
 void launch_init_state(const Dev& d, hipStream_t s);
 void launch_zero(float* p, size_t n, hipStream_t s);
 void launch_noop(hipStream_t s);
