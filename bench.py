@@ -95,6 +95,7 @@ def main():
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", default="C2")
+    ap.add_argument("--predict-reps", type=int, default=20, help="timed repetitions of the root-inference call per mode")
     ap.add_argument("--latency-steps", type=int, default=None)
     ap.add_argument("--kernel-steps", type=int, default=None)
     ap.add_argument("--host-steps", type=int, default=None,
@@ -283,6 +284,26 @@ def main():
                    "algorithmic_GBs": rb_bytes / rw / 1e9, "frac_hbm": rb_bytes / rw / 1e9 / HBM_PEAK_GBS,
                    "ring_entries": ent / w.layers}
 
+    # per-batch root-node inference (Algorithm 1: embed and score the batch's endpoints BEFORE the batch is
+    # applied): link scores of one batch of edges from the current state, device inputs, call + wait.
+    # Prediction changes no state, so the same batch can be scored repeatedly.
+    roots = None
+    if args.predict_reps > 0:
+        rng = np.random.default_rng(1)
+        g.set_predictor((rng.standard_normal(2 * w.d_emb) / np.sqrt(w.d_emb)).astype(np.float32), 0.0)
+        lo = (b if (b + 1) * w.batch <= used else b - 1) * w.batch
+        ps, pd, pt = d_src[lo:lo + w.batch], d_dst[lo:lo + w.batch], d_ts[lo:lo + w.batch]
+        roots = {"edges": int(ps.shape[0])}
+        for name, mode in (("cached_rows", False), ("edge_time", True)):
+            g.predict_batch(ps, pd, pt, at_edge_time=mode); g.sync()
+            a = time.perf_counter()
+            for _ in range(args.predict_reps):
+                g.predict_batch(ps, pd, pt, at_edge_time=mode)
+                g.sync()
+            dt_ = (time.perf_counter() - a) / args.predict_reps
+            roots[name + "_us"] = dt_ * 1e6
+            roots[name + "_edges_per_s"] = ps.shape[0] / dt_
+
     cpu = None
     if not args.no_cpu and args.cpu_steps > 0:
         from oracle import oracle as orc
@@ -332,6 +353,7 @@ def main():
         "paper_bound_2BLK": binding.paper_affected_bound(w.batch, w.k, w.layers),
         "host_input_edges_per_s": (host_edges / host_wall) if host_wall else None,
         "full_rebuild": rebuild,
+        "root_inference": roots,
         "stage_us": dict(zip(("sort", "memory", "apply", "propagate", "embed", "total"),
                              (stage_us / max(n_stage, 1)).round(2).tolist())),
         "kernels": kernels,
