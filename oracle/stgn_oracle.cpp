@@ -32,11 +32,11 @@
 // paper: that part is "parity unpinned" by the paper and pinned only by the
 // special cases and library cross-checks above.
 
+#include <algorithm>
 #include <cmath>
 #include <cstdint>
 #include <cstring>
 #include <vector>
-#include <algorithm>
 
 namespace {
 
@@ -48,6 +48,7 @@ struct Layer {
 };
 
 struct Oracle {
+  double window = 0.0;               // T_w; <= 0: no expiry
   uint32_t N, d_mem, d_node, d_edge, d_time, d_emb, d_msg, k, heads, layers;
   std::vector<float> omega, phase;
   std::vector<float> W_msg, b_msg, W_z, U_z, b_z, W_r, U_r, b_r, W_h, U_h, b_h;
@@ -173,7 +174,10 @@ void embed_row_at(const Oracle& o, uint32_t l, uint32_t v, double tq, PrevRow pr
   for (uint32_t i = 0; i < din; ++i) qin[i] = hrow[i];
   time_encode(dt, o.omega.data(), o.phase.data(), 0.0, qin.data() + din);
   vecmat(qin.data(), Ly.WQ.data(), nullptr, din + dt, d, q.data());
-  const std::vector<Entry> nb = recent(o, v);
+  // the most recent entries, without those that fall outside the temporal window [tq - T_w, tq]
+  std::vector<Entry> nb = recent(o, v);
+  if (o.window > 0.0)
+    nb.erase(std::remove_if(nb.begin(), nb.end(), [&](const Entry& e) { return tq - o.ts[e.eid] > o.window; }), nb.end());
   const uint32_t n = (uint32_t)nb.size();
   std::vector<double> K((size_t)n * d), V((size_t)n * d), z(din + de + dt);
   for (uint32_t j = 0; j < n; ++j) {
@@ -206,6 +210,7 @@ extern "C" {
 
 struct orc_config {
   uint32_t num_nodes, d_mem, d_node, d_edge, d_time, d_emb, d_msg, k, heads, layers;
+  double window;     // temporal window T_w of the neighbour cache (Sec. 3.3.2, "Invalidate"); <= 0: none
 };
 
 struct orc_weights {
@@ -221,6 +226,7 @@ void* orc_create(const orc_config* c, const orc_weights* w, const float* node_fe
   o->N = c->num_nodes; o->d_mem = c->d_mem; o->d_node = c->d_node; o->d_edge = c->d_edge;
   o->d_time = c->d_time; o->d_emb = c->d_emb; o->d_msg = c->d_msg; o->k = c->k;
   o->heads = c->heads; o->layers = c->layers;
+  o->window = c->window;
   copyf(o->omega, w->omega, o->d_time);
   copyf(o->phase, w->phase, o->d_time);
   if (o->d_mem) {

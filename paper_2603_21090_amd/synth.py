@@ -44,6 +44,7 @@ class Workload:
     d_emb: int = 100
     d_msg: int = 100
     bipartite: tuple | None = None   # (n_left, n_right): src from left, dst from right
+    window: float = 0.0              # temporal window T_w of the neighbour cache; 0 = no expiry
 
     @property
     def seed(self) -> int:

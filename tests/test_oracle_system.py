@@ -137,9 +137,10 @@ def torch_phi(omega, phase, x):
     return torch.cos(x[..., None] * om + ph) / math.sqrt(len(omega))
 
 
-def torch_embed_all(w, W, rings, ts_all, efeat_all, H0, t_last, t_final=None):
+def torch_embed_all(w, W, rings, ts_all, efeat_all, H0, t_last, t_final=None, window=None):
     """Layered embeddings with padded neighbour tensors and library attention (fp64).  t_final: query
-    times of the LAST layer (default: t_last, like every other layer)."""
+    times of the LAST layer (default: t_last, like every other layer).  window: entries older than
+    (query time - window) are masked out."""
     N, k, H = w.num_nodes, w.k, w.heads
     nbr = torch.zeros((N, k), dtype=torch.long)
     eid = torch.zeros((N, k), dtype=torch.long)
@@ -158,15 +159,17 @@ def torch_embed_all(w, W, rings, ts_all, efeat_all, H0, t_last, t_final=None):
         T = lambda a: torch.tensor(a[l], dtype=torch.float64)
         q = torch.cat([Hprev, phi0], 1) @ T(W["W_Q"])
         if t_final is not None and l == w.layers - 1:
-            phi = torch_phi(W["omega"], W["phase"], torch.tensor(t_final)[:, None] - torch.tensor(ts_all)[eid])
+            dt = torch.tensor(t_final)[:, None] - torch.tensor(ts_all)[eid]
+            phi = torch_phi(W["omega"], W["phase"], dt)
+        live = valid if window is None else valid & (dt <= window)
         z = torch.cat([Hprev[nbr], E, phi], 2)
         K, V = z @ T(W["W_K"]), z @ T(W["W_V"])
         dk = w.d_emb // H
         qh = q.reshape(N, H, 1, dk)
         Kh = K.reshape(N, k, H, dk).permute(0, 2, 1, 3)
         Vh = V.reshape(N, k, H, dk).permute(0, 2, 1, 3)
-        mask = valid[:, None, None, :].expand(N, H, 1, k).clone()
-        empty = ~valid.any(1)
+        mask = live[:, None, None, :].expand(N, H, 1, k).clone()
+        empty = ~live.any(1)
         mask[empty] = True                                    # avoid NaN rows; zeroed below
         o = torch.nn.functional.scaled_dot_product_attention(qh, Kh, Vh, attn_mask=mask).reshape(N, w.d_emb)
         o[empty] = 0.0
@@ -225,3 +228,45 @@ def test_full_pipeline_against_vectorised_torch(d_mem, d_node):
     want = torch_embed_all(w, W, rings, st.ts, st.edge_features(0, hi), H0, t_last)
     got = o.embed_all()
     assert np.abs(got.astype(np.float64) - want).max() < 5e-7
+
+
+# ------------------------------------------------------------------ temporal window of the neighbour cache
+
+def _windowed(window, layers=2, d_mem=8):
+    w = tiny_workload(d_mem=d_mem, layers=layers, heads=2, k=4, num_nodes=30, num_edges=240, batch=16, window=window)
+    W = synth.make_weights(w)
+    st, _, o = stream_and_oracle(w, None, W)
+    for b in range(w.num_batches):
+        assert o.ingest(*st.batch(b))[0] == 0
+    return w, W, st, o
+
+
+def test_window_special_cases():
+    """A window wider than the stream changes nothing; a window narrower than every gap leaves a node
+    only the entries that carry its own last timestamp (gap 0), i.e. exactly its latest edge here."""
+    w0, W, st, o0 = _windowed(0.0)
+    ref = o0.embed_all()
+    assert np.array_equal(_windowed(1e9)[3].embed_all(), ref)
+    # synthetic timestamps are strictly increasing: with a tiny window every node sees one entry, which is
+    # what a ring of capacity k = 1 holds
+    _, W1, st1, ot = _windowed(1e-9, layers=1)
+    tiny = ot.embed_all()
+    w1 = tiny_workload(d_mem=8, layers=1, heads=2, k=1, num_nodes=30, num_edges=240, batch=16)
+    o1 = orc.Oracle.from_workload(w1, W1)
+    for b in range(w1.num_batches):
+        assert o1.ingest(*st1.batch(b))[0] == 0
+    assert np.array_equal(tiny, o1.embed_all())
+    assert not np.array_equal(tiny, _windowed(0.0, layers=1)[3].embed_all())
+
+
+@pytest.mark.parametrize("window", [3.0, 12.0, 40.0])
+def test_window_against_vectorised_torch(window):
+    w, W, st, o = _windowed(window)
+    nodes = np.arange(w.num_nodes, dtype=np.uint32)
+    mem, t_last = o.memory(nodes)
+    rings = brute_rings(st.src, st.dst, w.num_edges, w.num_nodes, w.k)
+    want = torch_embed_all(w, W, rings, st.ts, st.edge_features(0, w.num_edges), mem, t_last, window=window)
+    got = o.embed_all()
+    assert np.abs(got.astype(np.float64) - want).max() < 5e-7
+    full = torch_embed_all(w, W, rings, st.ts, st.edge_features(0, w.num_edges), mem, t_last)
+    assert np.abs(want - full).max() > 1e-3, "this window expires nothing: the case tests nothing"
