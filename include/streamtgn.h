@@ -68,6 +68,9 @@ typedef struct {
   uint32_t k;        /* most recent neighbours kept per node (Sec. 3.3.2)   */
   uint32_t heads;    /* attention heads                                    */
   uint32_t layers;   /* attention layers = hops of dirty-flag propagation   */
+  double   window;   /* temporal window T_w of the neighbour cache (Sec. 3.3.2, "Invalidate"): a recent-
+                        neighbour entry older than the query time minus T_w is not attended to;
+                        <= 0: no expiry.  The affected set does not depend on it (a sound superset). */
 } stgn_config;
 
 /* Parameters, host pointers, copied (and re-packed) by stgn_create.

@@ -131,6 +131,7 @@ size_t layout(const stgn_config& c, char* base, Dev* d) {
   d->d_mem = c.d_mem; d->d_node = c.d_node; d->d0 = c.d_mem + c.d_node; d->d_edge = c.d_edge;
   d->d_time = c.d_time; d->d_emb = c.d_emb; d->d_msg = c.d_msg; d->dk = c.d_emb / c.heads;
   d->max_batch = c.max_batch; d->max_edges = c.max_edges;
+  d->window = c.window > 0.0 ? c.window : (double)INFINITY;
   d->num_cu = 0;
   // adjacency blocks of 8, 16, 32, ... entries: capacity after b blocks is 8 (2^b - 1)
   uint32_t maxb = 1;

@@ -69,6 +69,7 @@ LaunchArgs make_args(const Dev& d, uint32_t layer) {
   k.om_rev = d.om_rev; k.ph_rev = d.ph_rev; k.ctrl = d.ctrl;
   k.WQ = L.WQn; k.cQ = L.cQ; k.WKT = L.WKT; k.WV = L.WV; k.WO = L.WO; k.bO = L.bO;
   k.ld_in = d.H[layer].ld; k.ld_out = d.H[layer + 1].ld; k.ld_kv = d.ld_kv; k.ld_kve = d.KVE[layer].ld;
+  k.window = d.window;
   k.k = d.k; k.d_in = L.d_in; k.d_emb = d.d_emb; k.dk = d.dk; k.d_time = d.d_time;
   a.ks = d.ks; a.nt = d.nt; a.heads = d.heads;
   a.num_cu = d.num_cu;

@@ -82,6 +82,7 @@ struct LayerArgs {
   // root-node inference: query time per list row instead of the node's last-interaction time, and the
   // output rows go to out_rows[list position] instead of the layer cache (both null otherwise)
   const double* tq_rows; float* out_rows;
+  double window;                                   // ring entries older than the query time minus this are ignored (+inf: none)
   const RingEntry* ring; const uint32_t* deg; const double* t_last;
   const double* om_rev; const double* ph_rev;
   Ctrl* ctrl;
@@ -438,8 +439,8 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
 #pragma unroll
         for (int jc = 0; jc < JC; ++jc) {
           const uint32_t j = c * JC + jc;
-          vj[jc] = j < cnt;
           const double dt = tq - rrow[j < k ? j : k - 1u].t;
+          vj[jc] = j < cnt && dt <= a.window;          // inside the temporal window [tq - T_w, tq] (Sec. 3.3.2)
 #pragma unroll
           for (int t = 0; t < NT; ++t) {
             const float c0 = cos_rev(om[t][0].x * dt + ph[t][0].x), c1 = cos_rev(om[t][0].y * dt + ph[t][0].y);
@@ -531,7 +532,7 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
       // padding lanes hold exact zeros), pb overwrites qt (each lane owns its float4s)
 #pragma unroll
       for (int h = 0; h < H; ++h) {
-        const float inv = cnt ? 1.0f / lrun[h] : 0.0f;
+        const float inv = lrun[h] > 0.0f ? 1.0f / lrun[h] : 0.0f;    // no entry, or none inside the window: b_O alone
 #pragma unroll
         for (int s = h * SH; s < (h + 1) * SH; ++s) {
           float4 o = accv[s];

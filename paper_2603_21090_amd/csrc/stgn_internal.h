@@ -88,6 +88,7 @@ struct Dev {
   // configuration
   uint32_t N, k, heads, layers, d_mem, d_node, d0, d_edge, d_time, d_emb, d_msg, dk;
   uint32_t max_batch, maxb;      // maxb: adjacency blocks per node in the block table
+  double   window;               // temporal window of the neighbour cache (+inf: no expiry)
   uint32_t num_cu;               // compute units of the device the context lives on
   uint64_t max_edges, pool_cap_units;
   // persistent state

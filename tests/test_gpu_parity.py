@@ -201,6 +201,31 @@ def test_unplanned_hops_and_stale_direction_hints(binding):
     g.close()
 
 
+@pytest.mark.parametrize("window", [2.0, 15.0])
+def test_temporal_window_of_the_neighbour_cache(binding, window):
+    """Ring entries older than the query time minus T_w are not attended to (Sec. 3.3.2, Invalidate);
+    with the narrow window many nodes are left with no entry at all and hold b_O.  Root-node inference
+    at the edge's own time applies the window at that time."""
+    w = tiny_workload(num_nodes=150, num_edges=1500, batch=50, layers=2, k=5, d_mem=16, d_edge=6, d_time=16, d_emb=16,
+                      d_msg=16, heads=2, zipf_s=1.0, window=window)
+    g, o, st = run_stream(binding, w, batches=29, full_check_at=set(range(0, 29, 7)))
+    ref_no_window = orc.Oracle.from_workload(w.scaled(window=0.0), synth.make_weights(w))
+    for b in range(29):
+        ref_no_window.ingest(*st.batch(b))
+    assert np.abs(ref_no_window.embed_all()[-1] - o.embed_all()[-1]).max() > 1e-3, "this window expires nothing"
+    rng = np.random.default_rng(2)
+    wp = (rng.standard_normal(2 * w.d_emb) / 4).astype(np.float32)
+    g.set_predictor(wp, 0.0)
+    s, d, t, _ = st.batch(29)
+    t = t + 5.0                                  # later than any stored edge: more entries have expired by then
+    want = o.predict(s, d, t, wp, 0.0, at_edge_time=True)
+    got = g.predict_batch(s, d, t, at_edge_time=True)
+    H = o.embed_all()[-1].astype(np.float64)
+    bound = REL * (np.linalg.norm(H[s], axis=1) + np.linalg.norm(H[d], axis=1)) * np.linalg.norm(wp) + 1e-5
+    assert (np.abs(got - want) <= bound).all(), np.abs(got - want).max()
+    g.close()
+
+
 def test_device_inputs_match_host_inputs(binding):
     w = tiny_workload(num_nodes=300, num_edges=3000, batch=100, d_mem=16, d_edge=12, d_time=16, d_emb=16, d_msg=16, k=4)
     g, o, st = run_stream(binding, w, device_inputs=True, full_check_at={0, 7, 15})
