@@ -30,7 +30,7 @@ def build(force: bool = False) -> str:
 class _Config(C.Structure):
     _fields_ = [(n, C.c_uint32) for n in
                 ("num_nodes", "d_mem", "d_node", "d_edge", "d_time", "d_emb", "d_msg", "k", "heads", "layers")] + \
-               [("window", C.c_double)]
+               [("window", C.c_double), ("aggregator", C.c_uint32), ("reserved", C.c_uint32)]
 
 
 class _Weights(C.Structure):
@@ -79,9 +79,10 @@ class Oracle:
     """Full-recompute TGN/TGAT state machine on the CPU."""
 
     def __init__(self, *, num_nodes, d_mem, d_node, d_edge, d_time, d_emb, d_msg, k, heads, layers,
-                 weights: dict, node_feat=None, window=0.0):
+                 weights: dict, node_feat=None, window=0.0, aggregator=0):
         L = lib()
-        self.cfg = _Config(num_nodes, d_mem, d_node, d_edge, d_time, d_emb, d_msg, k, heads, layers, float(window))
+        self.cfg = _Config(num_nodes, d_mem, d_node, d_edge, d_time, d_emb, d_msg, k, heads, layers, float(window),
+                           int(aggregator), 0)
         self._keep = []
         w = _Weights()
         for name in ("omega", "phase", "W_msg", "b_msg", "W_z", "U_z", "b_z", "W_r", "U_r", "b_r", "W_h", "U_h", "b_h"):
@@ -106,7 +107,8 @@ class Oracle:
     def from_workload(cls, w, weights, node_feat=None):
         return cls(num_nodes=w.num_nodes, d_mem=w.d_mem, d_node=w.d_node, d_edge=w.d_edge, d_time=w.d_time,
                    d_emb=w.d_emb, d_msg=w.d_msg, k=w.k, heads=w.heads, layers=w.layers,
-                   weights=weights, node_feat=node_feat, window=getattr(w, "window", 0.0))
+                   weights=weights, node_feat=node_feat, window=getattr(w, "window", 0.0),
+                   aggregator=getattr(w, "aggregator", 0))
 
     def __del__(self):
         if getattr(self, "_h", None):

@@ -49,6 +49,7 @@ struct Layer {
 
 struct Oracle {
   double window = 0.0;               // T_w; <= 0: no expiry
+  uint32_t aggregator = 0;           // 0 Last, 1 Mean, 2 Sum
   uint32_t N, d_mem, d_node, d_edge, d_time, d_emb, d_msg, k, heads, layers;
   std::vector<float> omega, phase;
   std::vector<float> W_msg, b_msg, W_z, U_z, b_z, W_r, U_r, b_r, W_h, U_h, b_h;
@@ -211,6 +212,8 @@ extern "C" {
 struct orc_config {
   uint32_t num_nodes, d_mem, d_node, d_edge, d_time, d_emb, d_msg, k, heads, layers;
   double window;     // temporal window T_w of the neighbour cache (Sec. 3.3.2, "Invalidate"); <= 0: none
+  uint32_t aggregator;   // Eq. (agg_functions): 0 Last, 1 Mean, 2 Sum
+  uint32_t reserved;
 };
 
 struct orc_weights {
@@ -227,6 +230,8 @@ void* orc_create(const orc_config* c, const orc_weights* w, const float* node_fe
   o->d_time = c->d_time; o->d_emb = c->d_emb; o->d_msg = c->d_msg; o->k = c->k;
   o->heads = c->heads; o->layers = c->layers;
   o->window = c->window;
+  if (c->aggregator > 2) { delete o; return nullptr; }
+  o->aggregator = c->aggregator;
   copyf(o->omega, w->omega, o->d_time);
   copyf(o->phase, w->phase, o->d_time);
   if (o->d_mem) {
@@ -278,11 +283,13 @@ int orc_ingest(void* h, uint32_t n, const uint32_t* src, const uint32_t* dst, co
   std::vector<uint32_t> D;
   for (uint32_t v = 0; v < o.N; ++v) if (isd[v]) D.push_back(v);
 
-  // 2. messages for every edge and both roles from PRE-batch memory and t_last, keep the
-  //    message of the highest batch index per node ("Last"), one GRU transition per node.
+  // 2. messages for every edge and both roles from PRE-batch memory and t_last, aggregated per node
+  //    (Eq. agg_functions: the message of the highest batch index, "Last"; or the mean / the sum of the
+  //    node's messages, added in batch order), one GRU transition per node.
   if (o.d_mem) {
     std::vector<int64_t> last_edge(o.N, -1);
-    std::vector<double> last_msg((size_t)D.size() * o.d_msg);
+    std::vector<uint32_t> n_msg(D.size(), 0);
+    std::vector<double> last_msg((size_t)D.size() * o.d_msg, 0.0);
     std::vector<uint32_t> slot_of(o.N, 0);
     for (size_t d = 0; d < D.size(); ++d) slot_of[D[d]] = (uint32_t)d;
     std::vector<double> m(o.d_msg);
@@ -291,12 +298,21 @@ int orc_ingest(void* h, uint32_t n, const uint32_t* src, const uint32_t* dst, co
         const uint32_t self = role ? dst[i] : src[i], other = role ? src[i] : dst[i];
         message(o, &o.mem[(size_t)self * o.d_mem], &o.mem[(size_t)other * o.d_mem],
                 ef + (size_t)i * o.d_edge, ts[i] - o.t_last[self], m.data());
-        if ((int64_t)i >= last_edge[self]) {
-          last_edge[self] = i;
-          std::copy(m.begin(), m.end(), last_msg.begin() + (size_t)slot_of[self] * o.d_msg);
+        double* agg = &last_msg[(size_t)slot_of[self] * o.d_msg];
+        n_msg[slot_of[self]] += 1;
+        if (o.aggregator == 0) {
+          if ((int64_t)i >= last_edge[self]) {
+            last_edge[self] = i;
+            std::copy(m.begin(), m.end(), agg);
+          }
+        } else {
+          for (uint32_t c = 0; c < o.d_msg; ++c) agg[c] += m[c];
         }
       }
     }
+    if (o.aggregator == 1)
+      for (size_t d = 0; d < D.size(); ++d)
+        for (uint32_t c = 0; c < o.d_msg; ++c) last_msg[d * o.d_msg + c] /= (double)n_msg[d];
     std::vector<float> new_mem((size_t)D.size() * o.d_mem);
     std::vector<double> s(o.d_mem), sn(o.d_mem);
     for (size_t d = 0; d < D.size(); ++d) {

@@ -45,6 +45,7 @@ class Workload:
     d_msg: int = 100
     bipartite: tuple | None = None   # (n_left, n_right): src from left, dst from right
     window: float = 0.0              # temporal window T_w of the neighbour cache; 0 = no expiry
+    aggregator: int = 0              # message aggregation per node and batch: 0 Last, 1 Mean, 2 Sum
 
     @property
     def seed(self) -> int:

@@ -270,3 +270,64 @@ def test_window_against_vectorised_torch(window):
     assert np.abs(got.astype(np.float64) - want).max() < 5e-7
     full = torch_embed_all(w, W, rings, st.ts, st.edge_features(0, w.num_edges), mem, t_last)
     assert np.abs(want - full).max() > 1e-3, "this window expires nothing: the case tests nothing"
+
+
+# ------------------------------------------------------------------ Mean / Sum message aggregation
+
+def test_aggregators_coincide_when_every_node_has_one_message_per_batch():
+    """Eq. agg_functions: with one edge per batch a node never has two messages, so the mean, the sum and
+    the last message are the same vector."""
+    ref = None
+    for agg in (0, 1, 2):
+        w = tiny_workload(d_mem=8, layers=1, num_nodes=30, num_edges=60, batch=1, aggregator=agg)
+        st, _, o = stream_and_oracle(w)
+        for b in range(w.num_batches):
+            assert o.ingest(*st.batch(b))[0] == 0
+        mem = o.memory(np.arange(w.num_nodes))[0]
+        if ref is None:
+            ref = mem
+        assert np.array_equal(mem, ref)
+
+
+@pytest.mark.parametrize("agg", [1, 2])
+def test_mean_and_sum_aggregators_against_vectorised_torch(agg):
+    """Every (edge, role) message from pre-batch state with a library matmul, summed per node with
+    index_add (divided by the count for the mean), then the library GRU cell (diagonal U_h)."""
+    w = tiny_workload(d_mem=8, layers=1, heads=2, k=4, num_nodes=12, num_edges=240, batch=16, zipf_s=1.3, aggregator=agg)
+    W = synth.make_weights(w)
+    W["U_h"] = np.diag(np.diag(W["U_h"])).astype(np.float32)
+    st, _, o = stream_and_oracle(w, None, W)
+    d_mem = w.d_mem
+    mem = np.zeros((w.num_nodes, d_mem), np.float32)
+    t_last = np.zeros(w.num_nodes)
+    cell = torch.nn.GRUCell(w.d_msg, d_mem, dtype=torch.float64)
+    with torch.no_grad():
+        cell.weight_ih.copy_(torch.tensor(np.concatenate([W["W_r"].T, W["W_z"].T, W["W_h"].T]), dtype=torch.float64))
+        cell.weight_hh.copy_(torch.tensor(np.concatenate([W["U_r"].T, W["U_z"].T, W["U_h"].T]), dtype=torch.float64))
+        cell.bias_ih.copy_(torch.tensor(np.concatenate([W["b_r"], W["b_z"], W["b_h"]]), dtype=torch.float64))
+        cell.bias_hh.zero_()
+    multi = 0
+    for b in range(w.num_batches):
+        s, d, t, ef = st.batch(b)
+        assert o.ingest(s, d, t, ef)[0] == 0
+        self_ = np.concatenate([s, d]).astype(np.int64)            # one row per (edge, role)
+        oth = np.concatenate([d, s]).astype(np.int64)
+        idx = np.concatenate([np.arange(len(s)), np.arange(len(s))])
+        T64 = lambda a: torch.tensor(a, dtype=torch.float64)
+        x = torch.cat([T64(mem[self_]), T64(mem[oth]), T64(ef[idx]),
+                       torch_phi(W["omega"], W["phase"], torch.tensor(t[idx]) - torch.tensor(t_last[self_]))], 1)
+        m = x @ T64(W["W_msg"]) + T64(W["b_msg"])
+        nodes, inv, cnt = np.unique(self_, return_inverse=True, return_counts=True)
+        multi += int((cnt > 1).sum())
+        acc = torch.zeros((len(nodes), w.d_msg), dtype=torch.float64).index_add_(0, torch.tensor(inv), m)
+        if agg == 1:
+            acc = acc / torch.tensor(cnt, dtype=torch.float64)[:, None]
+        with torch.no_grad():
+            new = cell(acc, T64(mem[nodes])).to(torch.float32).numpy()
+        mem[nodes] = new
+        for i in range(len(s)):
+            t_last[s[i]] = t[i]; t_last[d[i]] = t[i]
+        got = o.memory(np.arange(w.num_nodes))[0]
+        assert np.abs(got.astype(np.float64) - mem).max() <= 5e-7
+        mem = got.copy()                                             # follow the oracle's rounding
+    assert multi > 50, "the stream has no node with several messages in one batch: the case tests nothing"
