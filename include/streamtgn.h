@@ -49,6 +49,8 @@ enum {
   STGN_E_WORKSPACE         = -8   /* workspace missing, misaligned or too small                */
 };
 
+enum { STGN_AGG_LAST = 0, STGN_AGG_MEAN = 1, STGN_AGG_SUM = 2 };
+
 typedef struct stgn_ctx stgn_ctx;
 
 /* Model and capacity description (paper Sec. 2.2 for the dimensions).
@@ -71,6 +73,9 @@ typedef struct {
   double   window;   /* temporal window T_w of the neighbour cache (Sec. 3.3.2, "Invalidate"): a recent-
                         neighbour entry older than the query time minus T_w is not attended to;
                         <= 0: no expiry.  The affected set does not depend on it (a sound superset). */
+  uint32_t aggregator; /* Eq. agg_functions, how a node's messages of one batch become one: STGN_AGG_LAST
+                        (the latest), STGN_AGG_MEAN, STGN_AGG_SUM (added in batch order).  Ignored when d_mem = 0. */
+  uint32_t reserved;   /* 0 */
 } stgn_config;
 
 /* Parameters, host pointers, copied (and re-packed) by stgn_create.

@@ -27,7 +27,7 @@ class Config(C.Structure):
     _fields_ = [("num_nodes", C.c_uint32), ("max_edges", C.c_uint64), ("max_batch", C.c_uint32),
                 ("d_mem", C.c_uint32), ("d_node", C.c_uint32), ("d_edge", C.c_uint32), ("d_time", C.c_uint32),
                 ("d_emb", C.c_uint32), ("d_msg", C.c_uint32), ("k", C.c_uint32), ("heads", C.c_uint32),
-                ("layers", C.c_uint32), ("window", C.c_double)]
+                ("layers", C.c_uint32), ("window", C.c_double), ("aggregator", C.c_uint32), ("reserved", C.c_uint32)]
 
 
 class Weights(C.Structure):
@@ -104,9 +104,9 @@ def _ptr(a):
 
 
 def make_config(*, num_nodes, max_edges, max_batch, d_mem, d_node, d_edge, d_time, d_emb, d_msg, k, heads, layers,
-                window=0.0):
+                window=0.0, aggregator=0):
     return Config(num_nodes, max_edges, max_batch, d_mem, d_node, d_edge, d_time, d_emb, d_msg, k, heads, layers,
-                  float(window))
+                  float(window), int(aggregator), 0)
 
 
 def query_workspace(cfg: Config) -> int:
@@ -166,7 +166,8 @@ class StreamTGN:
     def from_workload(cls, w, weights, node_feat=None, max_edges=None, max_batch=None, **kw):
         cfg = make_config(num_nodes=w.num_nodes, max_edges=max_edges or w.num_edges, max_batch=max_batch or w.batch,
                           d_mem=w.d_mem, d_node=w.d_node, d_edge=w.d_edge, d_time=w.d_time, d_emb=w.d_emb,
-                          d_msg=w.d_msg, k=w.k, heads=w.heads, layers=w.layers, window=getattr(w, "window", 0.0))
+                          d_msg=w.d_msg, k=w.k, heads=w.heads, layers=w.layers, window=getattr(w, "window", 0.0),
+                          aggregator=getattr(w, "aggregator", 0))
         return cls(cfg, weights, node_feat, **kw)
 
     def close(self):

@@ -102,6 +102,7 @@ int check_config(const stgn_config* c, std::string* why) {
   if (c->d_mem + c->d_node == 0 || c->d_mem + c->d_node > 512) return bad("layer-0 width (d_mem + d_node) out of range");
   if (c->d_mem && (c->d_msg == 0 || c->d_msg > 512)) return bad("d_msg out of range");
   if (c->heads == 0 || c->d_emb % c->heads != 0) return bad("heads must divide d_emb");
+  if (c->aggregator > STGN_AGG_SUM) return bad("aggregator must be STGN_AGG_LAST, STGN_AGG_MEAN or STGN_AGG_SUM");
   if (!attn_supported(c->d_emb, c->d_time, c->heads))
     return bad("unsupported attention shape: heads in {1,2,4}, d_time <= 128, and heads * ceil(d_emb / heads / 64) <= 4 "
                "(every head takes whole 64-float slots of a cached key row)");
@@ -132,6 +133,7 @@ size_t layout(const stgn_config& c, char* base, Dev* d) {
   d->d_time = c.d_time; d->d_emb = c.d_emb; d->d_msg = c.d_msg; d->dk = c.d_emb / c.heads;
   d->max_batch = c.max_batch; d->max_edges = c.max_edges;
   d->window = c.window > 0.0 ? c.window : (double)INFINITY;
+  d->aggregator = c.aggregator;
   d->num_cu = 0;
   // adjacency blocks of 8, 16, 32, ... entries: capacity after b blocks is 8 (2^b - 1)
   uint32_t maxb = 1;
@@ -177,6 +179,7 @@ size_t layout(const stgn_config& c, char* base, Dev* d) {
   d->deg_new = b.take<uint32_t>(B2);
   d->slot_pos = b.take<uint32_t>(B2);
   d->slot_d = b.take<uint32_t>(B2);
+  d->slot_sorted = b.take<uint32_t>(B2);
   d->mem_new = b.take<float>((size_t)B2 * c.d_mem);
   d->mark = b.take<uint8_t>(mark_bytes(N));
   d->items_cap = (uint64_t)N + 2 * c.max_edges / kLogChunk + 1024;

@@ -159,6 +159,7 @@ __global__ __launch_bounds__(kSortThreads) void stage_sort_kernel(Dev d, uint32_
       const uint32_t rank = i - d.seg_start[di];
       d.slot_pos[slot] = d.deg[node] + rank;
       d.slot_d[slot] = di;
+      d.slot_sorted[i] = slot;
     }
   }
 

@@ -50,6 +50,11 @@ __global__ __launch_bounds__(kThreads) void memory_update_kernel(Dev d, const ui
   extern __shared__ __align__(16) float lds[];
   __shared__ uint32_t s_self[kRows], s_oth[kRows], s_ef[kRows], s_live[kRows];
   __shared__ double s_dt[kRows];
+  // Mean / Sum aggregation: the row's slots in sorted order [s_seg, s_seg + s_n), its last-interaction time,
+  // and the factor of the aggregated message (the slot count for Sum, 1 otherwise)
+  __shared__ uint32_t s_seg[kRows], s_n[kRows];
+  __shared__ double s_tl[kRows];
+  __shared__ float s_scale[kRows];
   const Ctrl* c = d.ctrl;
   if (c->skip) return;
   const uint32_t nD = c->nD;
@@ -81,10 +86,12 @@ __global__ __launch_bounds__(kThreads) void memory_update_kernel(Dev d, const ui
     // per-row metadata first (one thread per row: node, partner, edge, time gap), through LDS
     if (threadIdx.x < kRows) {
       const uint32_t r = threadIdx.x;
-      uint32_t so = 0, oo = 0, eo = 0, live = 0;
-      double dtv = 0.0;
+      uint32_t so = 0, oo = 0, eo = 0, live = 0, seg = 0, cnt = 0;
+      double dtv = 0.0, tl = 0.0;
       if (r0 + r < nD) {
         const uint32_t node = d.D[r0 + r];
+        seg = d.seg_start[r0 + r]; cnt = d.seg_start[r0 + r + 1] - seg;
+        tl = d.t_last[node];
         const uint32_t slot = d.last_slot[r0 + r];
         const uint32_t i = slot >> 1;
         const uint32_t other = (slot & 1) ? src[i] : dst[i];
@@ -92,8 +99,43 @@ __global__ __launch_bounds__(kThreads) void memory_update_kernel(Dev d, const ui
         dtv = ts[i] - d.t_last[node];
       }
       s_self[r] = so; s_oth[r] = oo; s_ef[r] = eo; s_live[r] = live; s_dt[r] = dtv;
+      s_seg[r] = seg; s_n[r] = cnt; s_tl[r] = tl;
+      s_scale[r] = d.aggregator == 2u ? (float)cnt : 1.0f;
     }
     __syncthreads();
+    if (!UP && d.aggregator != 0u) {       // (the all-weights-up-front variant is only launched for Last)
+      // Mean / Sum (Eq. agg_functions).  The message is linear in its input, so the node's inputs are
+      // averaged instead of its messages (added in slot order = batch order, a fixed order): the mean
+      // message is mean(x) W_msg + b_msg and the sum is the slot count times that.  The node's own
+      // memory is the same in every one of its inputs and is staged as it is.
+      const uint32_t total = kRows * Kmsg;
+      for (uint32_t x = threadIdx.x; x < total; x += kThreads) {
+        const uint32_t r = x / Kmsg, col = x - r * Kmsg;
+        float val = 0.0f;
+        if (s_live[r]) {
+          if (col < dm) {
+            val = H0.base[s_self[r] + col];
+          } else {
+            const uint32_t n = s_n[r];
+            float acc = 0.0f;
+            for (uint32_t j = 0; j < n; ++j) {
+              const uint32_t slot = d.slot_sorted[s_seg[r] + j], i = slot >> 1;
+              if (col < 2 * dm) {
+                const uint32_t other = (slot & 1) ? src[i] : dst[i];
+                acc += H0.base[(size_t)other * H0.ld + (col - dm)];
+              } else if (col < 2 * dm + de) {
+                acc += ef[(size_t)i * de + (col - 2 * dm)];
+              } else {
+                const uint32_t q = col - 2 * dm - de;
+                acc += cos_rev64(d.om_rev[q] * (ts[i] - s_tl[r]) + d.ph_rev[q]);
+              }
+            }
+            val = acc / (float)n;
+          }
+        }
+        Xs[r * ll.ldx + col] = val;
+      }
+    } else
     // then every thread issues its loads in batches of sixteen, unconditionally (dead elements read a
     // valid dummy address and are zeroed afterwards), so the latencies overlap
     {
@@ -151,7 +193,7 @@ __global__ __launch_bounds__(kThreads) void memory_update_kernel(Dev d, const ui
         if (col < dg) {
           const float b = d.bmsg[col];
 #pragma unroll
-          for (int r = 0; r < 4; ++r) Ms[(row0 + r) * ll.ldm + col] = acc[0][r] + b;
+          for (int r = 0; r < 4; ++r) Ms[(row0 + r) * ll.ldm + col] = (acc[0][r] + b) * s_scale[row0 + r];
         }
       }
     }
@@ -229,7 +271,7 @@ __global__ __launch_bounds__(kThreads) void memory_update_kernel(Dev d, const ui
 // shapes the all-weights-up-front variant covers: every stage one column tile per wave, the products
 // short enough for their whole B operand to sit in registers
 bool memory_upfront(const Dev& d) {
-  return chunks_of(d.Kmsg) <= 8u && chunks_of(d.d_msg) <= 2u && chunks_of(d.d_mem) <= 2u &&
+  return d.aggregator == 0u && chunks_of(d.Kmsg) <= 8u && chunks_of(d.d_msg) <= 2u && chunks_of(d.d_mem) <= 2u &&
          round_up(d.d_msg, 16) / 16 <= kWaves && round_up(d.d_mem, 16) / 16 <= kWaves;
 }
 

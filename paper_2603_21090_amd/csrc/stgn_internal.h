@@ -89,6 +89,7 @@ struct Dev {
   uint32_t N, k, heads, layers, d_mem, d_node, d0, d_edge, d_time, d_emb, d_msg, dk;
   uint32_t max_batch, maxb;      // maxb: adjacency blocks per node in the block table
   double   window;               // temporal window of the neighbour cache (+inf: no expiry)
+  uint32_t aggregator;           // Eq. agg_functions: 0 Last, 1 Mean, 2 Sum
   uint32_t num_cu;               // compute units of the device the context lives on
   uint64_t max_edges, pool_cap_units;
   // persistent state
@@ -115,6 +116,7 @@ struct Dev {
   uint32_t* deg_new;                 // [2*max_batch] per D entry: degree after the batch
   uint32_t* slot_pos;                // [2*max_batch] per slot: position in its node's adjacency
   uint32_t* slot_d;                  // [2*max_batch] per slot: index into D
+  uint32_t* slot_sorted;             // [2*max_batch] slots ordered by (node, slot): D entry x owns [seg_start[x], seg_start[x+1])
   float*   mem_new;                  // [2*max_batch x d_mem]
   uint8_t* mark;                     // [mark_bytes(N)] dirty flags, one byte per node
   uint64_t* items;                   // propagation work items (node, chunk)

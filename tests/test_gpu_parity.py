@@ -226,6 +226,21 @@ def test_temporal_window_of_the_neighbour_cache(binding, window):
     g.close()
 
 
+@pytest.mark.parametrize("agg", [1, 2])
+def test_mean_and_sum_aggregators(binding, agg):
+    """Eq. agg_functions: a node's messages of one batch are averaged / summed in batch order before the
+    GRU.  Small node count and large batches, so most endpoints have several messages per batch."""
+    w = tiny_workload(num_nodes=60, num_edges=2400, batch=80, layers=2, k=4, d_mem=16, d_edge=12, d_time=16, d_emb=16,
+                      d_msg=16, heads=2, zipf_s=1.2, aggregator=agg)
+    g, o, st = run_stream(binding, w, full_check_at=set(range(0, 30, 6)))
+    last = orc.Oracle.from_workload(w.scaled(aggregator=0), synth.make_weights(w))
+    for b in range(w.num_batches):
+        last.ingest(*st.batch(b))
+    nodes = np.arange(w.num_nodes, dtype=np.uint32)
+    assert np.abs(last.memory(nodes)[0] - o.memory(nodes)[0]).max() > 1e-3, "the aggregator made no difference"
+    g.close()
+
+
 def test_device_inputs_match_host_inputs(binding):
     w = tiny_workload(num_nodes=300, num_edges=3000, batch=100, d_mem=16, d_edge=12, d_time=16, d_emb=16, d_msg=16, k=4)
     g, o, st = run_stream(binding, w, device_inputs=True, full_check_at={0, 7, 15})

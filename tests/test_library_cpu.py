@@ -57,7 +57,7 @@ def test_widest_supported_attention_shapes(lib, ok):
                                  dict(layers=0), dict(layers=5), dict(k=0), dict(heads=3), dict(heads=0),
                                  dict(d_emb=0), dict(d_time=0), dict(d_mem=0, d_node=0), dict(max_edges=2**31),
                                  dict(d_emb=300, heads=4),      # 75-wide heads: 8 key slots, more than a cached row has
-                                 dict(d_emb=260, heads=1), dict(d_time=129)])
+                                 dict(d_emb=260, heads=1), dict(d_time=129), dict(aggregator=3)])
 def test_bad_configurations_are_rejected(lib, bad):
     w = synth.WORKLOADS["C1"]
     n = C.c_size_t(0)
