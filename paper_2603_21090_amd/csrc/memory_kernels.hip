@@ -95,7 +95,7 @@ __global__ __launch_bounds__(kThreads) void memory_update_kernel(Dev d, const ui
         const uint32_t slot = d.last_slot[r0 + r];
         const uint32_t i = slot >> 1;
         const uint32_t other = (slot & 1) ? src[i] : dst[i];
-        so = node * H0.ld; oo = other * H0.ld; eo = i * de; live = 1;
+        so = node; oo = other; eo = i * de; live = 1;          // node ids: row offsets are formed in 64 bits at the use
         dtv = ts[i] - d.t_last[node];
       }
       s_self[r] = so; s_oth[r] = oo; s_ef[r] = eo; s_live[r] = live; s_dt[r] = dtv;
@@ -114,7 +114,7 @@ __global__ __launch_bounds__(kThreads) void memory_update_kernel(Dev d, const ui
         float val = 0.0f;
         if (s_live[r]) {
           if (col < dm) {
-            val = H0.base[s_self[r] + col];
+            val = H0.base[(size_t)s_self[r] * H0.ld + col];
           } else {
             const uint32_t n = s_n[r];
             float acc = 0.0f;
@@ -154,8 +154,8 @@ __global__ __launch_bounds__(kThreads) void memory_update_kernel(Dev d, const ui
           const uint32_t r = x / Kmsg, col = x - r * Kmsg;
           rr[e] = r; cc[e] = col;
           const float* p = H0.base;
-          if (col < dm) p = H0.base + s_self[r] + col;
-          else if (col < 2 * dm) p = H0.base + s_oth[r] + (col - dm);
+          if (col < dm) p = H0.base + (size_t)s_self[r] * H0.ld + col;
+          else if (col < 2 * dm) p = H0.base + (size_t)s_oth[r] * H0.ld + (col - dm);
           else if (col < 2 * dm + de) p = efp + s_ef[r] + (col - 2 * dm);
           v[e] = *p;
         }
