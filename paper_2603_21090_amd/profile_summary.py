@@ -61,8 +61,15 @@ def trace(dirname, bench_json):
           f"(+ {bench['roofline']['event_overhead_us']:.2f} us event-pair overhead already subtracted)")
     if lay:
         r = lay[len(lay) - 1]
-        print(f"layer kernel resources: VGPR {r['VGPR_Count']}, AGPR {r['Accum_VGPR_Count']}, SGPR {r['SGPR_Count']}, "
-              f"LDS {r['LDS_Block_Size']} B, scratch {r['Scratch_Size']} B/lane, workgroup {r['Workgroup_Size_X']}")
+        # fields exactly as the trace reports them: LDS_Block_Size is the static part only (the tiles are
+        # dynamic LDS), and the code object's own register count is about twice the VGPR_Count shown
+        print(f"layer kernel, trace fields: VGPR_Count {r['VGPR_Count']}, Accum_VGPR_Count {r['Accum_VGPR_Count']}, "
+              f"SGPR_Count {r['SGPR_Count']}, LDS_Block_Size {r['LDS_Block_Size']} B (static part), "
+              f"Scratch_Size {r['Scratch_Size']} B/lane (no spills), workgroup {r['Workgroup_Size_X']}"
+              if r['Scratch_Size'] in ('0', 0) else
+              f"layer kernel, trace fields: VGPR_Count {r['VGPR_Count']}, Accum_VGPR_Count {r['Accum_VGPR_Count']}, "
+              f"SGPR_Count {r['SGPR_Count']}, LDS_Block_Size {r['LDS_Block_Size']} B (static part), "
+              f"Scratch_Size {r['Scratch_Size']} B/lane, workgroup {r['Workgroup_Size_X']}")
 
 
 def _counter(dirname, counter):
