@@ -96,6 +96,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", default="C2")
     ap.add_argument("--predict-reps", type=int, default=20, help="timed repetitions of the root-inference call per mode")
+    ap.add_argument("--batch", type=int, default=None, help="override the workload's batch size (ablation sweeps)")
+    ap.add_argument("--k", type=int, default=None, help="override the workload's recent-neighbour count (ablation sweeps)")
     ap.add_argument("--latency-steps", type=int, default=None)
     ap.add_argument("--kernel-steps", type=int, default=None)
     ap.add_argument("--host-steps", type=int, default=None,
@@ -116,6 +118,9 @@ def main():
     from paper_2603_21090_amd import binding, synth
 
     w = synth.WORKLOADS[args.workload]
+    if args.batch or args.k:          # a variant of the named workload; stored traffic figures do not apply to it
+        w = w.scaled(name=f"{w.name}(B={args.batch or w.batch},k={args.k or w.k})", batch=args.batch or w.batch,
+                     k=args.k or w.k)
     nb = w.num_batches
     W = int(0.70 * nb) if args.warmup is None else args.warmup
     K = int(0.15 * nb) if args.steps is None else args.steps
