@@ -274,9 +274,16 @@ def test_back_to_back_device_batches_overlap_and_a_skipped_batch(binding):
     for b in range(nb):
         rc, D, A = o.ingest(*st.batch(b))
         assert rc == 0
+        if b == 20:                                                  # a polled batch in between takes the serial path
+            assert g.ingest_batch(*batches[b], stats=True)["n_affected"] == len(A)
+            continue
         assert g.ingest_batch(*batches[b], check=False) == 0
         if b == 30:
             assert g.ingest_batch(*bad, check=False) == 0
+        if b == 40:                                                  # an empty batch and a rebuild between two overlapped batches
+            e = batches[b]
+            assert g.ingest_batch(e[0][:0], e[1][:0], e[2][:0], e[3][:0], check=False) == 0
+            g.full_rebuild()
     assert g.sync(check=False) == -3                                 # the skipped batch is reported once
     assert g.sync(check=False) == 0
     assert np.array_equal(g.get_affected(), A)
