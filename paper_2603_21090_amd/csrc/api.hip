@@ -35,7 +35,8 @@ struct stgn_ctx {
   hipStream_t front = nullptr;
   hipEvent_t ev_compact[2] = {nullptr, nullptr}, ev_front = nullptr;   // ev_compact alternates with the batches
   bool compact_recorded[2] = {false, false};
-  int parity = 0;                   // staging block and compaction event of the next batch
+  int parity = 0;                   // staging block, scratch set, batch fields and compaction event of the next batch
+  int last_par = 0;                 // parity of the batch enqueued last
   bool idle = true;                 // nothing was enqueued since the library last synchronised `stream`
   bool have_predictor = false;      // stgn_set_predictor was called
   std::string err;
@@ -173,14 +174,17 @@ size_t layout(const stgn_config& c, char* base, Dev* d) {
   // staging for host inputs: two blocks (batches alternate), each laid out like the pinned host block
   // [src | dst | ts | efeat] so that one copy moves a batch
   for (int i = 0; i < 2; ++i) d->stage[i] = b.take<char>(stage_bytes(c));
-  d->D = b.take<uint32_t>(B2);
-  d->seg_start = b.take<uint32_t>(B2 + 1);
-  d->last_slot = b.take<uint32_t>(B2);
-  d->deg_new = b.take<uint32_t>(B2);
-  d->slot_pos = b.take<uint32_t>(B2);
-  d->slot_d = b.take<uint32_t>(B2);
-  d->slot_sorted = b.take<uint32_t>(B2);
-  d->mem_new = b.take<float>((size_t)B2 * c.d_mem);
+  for (Dev::Scratch& s : d->scr) {
+    s.D = b.take<uint32_t>(B2);
+    s.seg_start = b.take<uint32_t>(B2 + 1);
+    s.last_slot = b.take<uint32_t>(B2);
+    s.deg_new = b.take<uint32_t>(B2);
+    s.slot_pos = b.take<uint32_t>(B2);
+    s.slot_d = b.take<uint32_t>(B2);
+    s.slot_sorted = b.take<uint32_t>(B2);
+    s.mem_new = b.take<float>((size_t)B2 * c.d_mem);
+  }
+  *d = bind_batch(*d, 0);
   d->mark = b.take<uint8_t>(mark_bytes(N));
   d->items_cap = (uint64_t)N + 2 * c.max_edges / kLogChunk + 1024;
   d->items = b.take<uint64_t>(d->items_cap);
@@ -375,13 +379,12 @@ void drain_timing(stgn_ctx* ctx) {
 }
 
 // every layer over all rows (initial state, full rebuild) or over the per-layer lists of the last batch
-void run_layers(stgn_ctx* ctx, bool all_rows) {
-  const Dev& d = ctx->d;
+void run_layers(stgn_ctx* ctx, const Dev& d, bool all_rows) {
   if (all_rows) { Scope s(ctx, KC_PROJECT); launch_project_nodes(d, ctx->stream); }   // cached keys|values of the layer-0 rows
   for (uint32_t l = 0; l < d.layers; ++l) {
     Scope s(ctx, KC_LAYER);
     if (all_rows) launch_layer(d, ctx->stream, l, nullptr, nullptr, d.N);
-    else launch_layer(d, ctx->stream, l, d.R[l], &d.ctrl->nR[l], d.N);
+    else launch_layer(d, ctx->stream, l, d.R[l], &d.bc->nR[l], d.N);
   }
 }
 
@@ -397,8 +400,9 @@ int sync_and_poll(stgn_ctx* ctx) {
   int rc = read_ctrl(ctx);
   if (rc) return rc;
   if (ctx->timing) drain_timing(ctx);
-  if (!ctx->ctrl_host->skip && ctx->ctrl_host->n_edges)
-    for (uint32_t h = 0; h < ctx->cfg.layers; ++h) ctx->pull_hint[h] = (ctx->ctrl_host->pulled[h] & 2u) != 0;
+  const BatchCtl& lb = ctx->ctrl_host->b[ctx->last_par];          // the batch enqueued last
+  if (!lb.skip && lb.n_edges)
+    for (uint32_t h = 0; h < ctx->cfg.layers; ++h) ctx->pull_hint[h] = (lb.pulled[h] & 2u) != 0;
   const int code = ctx->ctrl_host->err_code;
   if (code != 0) {
     const int32_t zero = 0;
@@ -511,7 +515,7 @@ int stgn_create(const stgn_config* cfg, const stgn_weights* w, const float* node
   }
   // ring places past a row's entry count read edge 0: its rows must be finite before the first edge arrives
   for (uint32_t l = 0; l < cfg->layers; ++l) launch_zero(ctx->d.KVE[l].base, ctx->d.ld_kv, ctx->stream);
-  run_layers(ctx, true);    // every cache row = empty-neighbourhood embedding
+  run_layers(ctx, ctx->d, true);    // every cache row = empty-neighbourhood embedding
   hipError_t e = hipStreamSynchronize(ctx->stream);
   if (e == hipSuccess) e = hipGetLastError();
   if (e != hipSuccess) { ctx->err = std::string("initial rebuild: ") + hipGetErrorString(e); return bail(STGN_E_DEVICE); }
@@ -541,7 +545,8 @@ int stgn_ingest_batch(stgn_ctx* ctx, uint32_t n, const uint32_t* src, const uint
                       const float* efeat, int inputs_on_device, stgn_batch_stats* stats) {
   if (!ctx) return STGN_E_INVALID_ARG;
   const stgn_config& c = ctx->cfg;
-  const Dev& d = ctx->d;
+  const int par = ctx->parity;                 // the batch's staging block, scratch set and batch fields
+  const Dev d = bind_batch(ctx->d, par);
   if (n > c.max_batch) return fail(ctx, STGN_E_BATCH_TOO_LARGE, "batch larger than max_batch");
   if (n && (!src || !dst || !ts || (c.d_edge && !efeat))) return fail(ctx, STGN_E_INVALID_ARG, "NULL batch array");
   if (ctx->host_edges + n > c.max_edges) return fail(ctx, STGN_E_EDGE_CAPACITY, "max_edges exceeded");
@@ -557,8 +562,6 @@ int stgn_ingest_batch(stgn_ctx* ctx, uint32_t n, const uint32_t* src, const uint
   const bool overlapped = stats == nullptr && !ctx->timing && inputs_on_device && !ctx->idle;
   ctx->idle = false;
   hipStream_t sf = overlapped ? ctx->front : ctx->stream;
-  const int par = ctx->parity;
-  ctx->parity ^= 1;
   if (!inputs_on_device) {
     // host-side validation: nothing is enqueued for a bad batch
     double prev = (ctx->any_edges && ctx->host_t_known) ? ctx->host_t_last : -INFINITY;
@@ -596,6 +599,8 @@ int stgn_ingest_batch(stgn_ctx* ctx, uint32_t n, const uint32_t* src, const uint
     ctx->any_edges = true;
   }
   ctx->host_edges += n;
+  ctx->parity ^= 1;                            // from here on the batch is enqueued
+  ctx->last_par = par;
   // the front part may start once the previous batch's compaction is done
   if (overlapped && ctx->compact_recorded[par ^ 1]) HIPCHK(ctx, hipStreamWaitEvent(sf, ctx->ev_compact[par ^ 1], 0));
 
@@ -622,14 +627,14 @@ int stgn_ingest_batch(stgn_ctx* ctx, uint32_t n, const uint32_t* src, const uint
   HIPCHK(ctx, hipEventRecord(ctx->ev_compact[par], s));
   ctx->compact_recorded[par] = true;
   if (ev) hipEventRecord(ev[4], s);
-  run_layers(ctx, false);
+  run_layers(ctx, d, false);
   if (ctx->timing) { Scope t(ctx, KC_NOOP); launch_noop(s); }   // event-pair overhead, for calibration
   if (ev) hipEventRecord(ev[5], s);
   HIPCHK(ctx, hipGetLastError());
 
   if (stats) {
     int rc = sync_and_poll(ctx);
-    const Ctrl& h = *ctx->ctrl_host;
+    const BatchCtl& h = ctx->ctrl_host->b[par];
     memset(stats, 0, sizeof *stats);
     stats->n_edges = h.n_edges;
     stats->n_direct = h.nD;
@@ -655,7 +660,7 @@ int stgn_ingest_batch(stgn_ctx* ctx, uint32_t n, const uint32_t* src, const uint
 int stgn_full_rebuild(stgn_ctx* ctx) {
   if (!ctx) return STGN_E_INVALID_ARG;
   ctx->idle = false;
-  run_layers(ctx, true);
+  run_layers(ctx, ctx->d, true);
   HIPCHK(ctx, hipGetLastError());
   return STGN_OK;
 }
@@ -745,7 +750,7 @@ int stgn_get_embeddings(stgn_ctx* ctx, uint32_t layer, uint32_t n, const uint32_
 int stgn_get_affected(stgn_ctx* ctx, uint32_t* out, uint32_t cap, uint32_t* count) {
   if (!ctx || !count) return STGN_E_INVALID_ARG;
   int rc = sync_and_poll(ctx);
-  const uint32_t nA = ctx->ctrl_host->nA;
+  const uint32_t nA = ctx->ctrl_host->b[ctx->last_par].nA;
   *count = nA;
   const uint32_t m = std::min(nA, cap);
   if (m && out) HIPCHK(ctx, hipMemcpy(out, ctx->d.A, (size_t)m * 4, hipMemcpyDeviceToHost));

@@ -61,13 +61,13 @@ __device__ inline uint32_t block_scan_256(uint32_t v, uint32_t* s, uint32_t* exc
 // plans whole chunks on its own -- no workgroup barrier anywhere: a first pass over the chunk counts
 // its items (one counter update per chunk), a second pass writes them, the 64 lanes filling the
 // items of up to 64 frontier nodes together so that a hub's thousands of items do not land on one lane.
-__device__ inline bool pull_hop(const Dev& d, const Ctrl* c, uint32_t hop) { return c->front_deg[hop] >= (uint64_t)(d.N / 2u); }
+__device__ inline bool pull_hop(const Dev& d, const BatchCtl* c, uint32_t hop) { return c->front_deg[hop] >= (uint64_t)(d.N / 2u); }
 // pulled[hop]: bit 0 the hop ran in pull mode, bit 1 the frontier was large enough to prefer pulling
 constexpr uint32_t kRanPull = 1u, kWantsPull = 2u;
 
 __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Dev d, uint32_t hop, uint32_t rounds) {
   __shared__ uint32_t s_off[kPlanWaves][64], s_v[kPlanWaves][64];
-  Ctrl* c = d.ctrl;
+  BatchCtl* c = d.bc;
   if (c->skip || pull_hop(d, c, hop)) return;               // a pull hop needs no work items
   const uint32_t lane = threadIdx.x & 63u;
   const uint32_t wib = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
@@ -156,7 +156,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Dev d, uint32_t hop,
 // flag the same nodes.
 __global__ __launch_bounds__(256) void expand_kernel(Dev d, uint32_t hop, uint32_t planned) {
   __shared__ unsigned long long s_deg[4], s_scan[4];
-  Ctrl* c = d.ctrl;
+  BatchCtl* c = d.bc;
   if (c->skip) return;
   const uint32_t lane = threadIdx.x & 63;
   const uint8_t value = (uint8_t)(hop + 2u);
@@ -277,7 +277,7 @@ __global__ __launch_bounds__(256) void compact_count_kernel(Dev d, uint32_t last
   // statistics: nodes first reached by hop h carry the flag h + 2
   for (uint32_t value = 2; value <= last_value; ++value) {
     const uint32_t reached = block_scan_256(bytes_equal(m, value), s, &excl);
-    if (threadIdx.x == 0 && reached) atomicAdd(&d.ctrl->n_front[value - 1u], reached);
+    if (threadIdx.x == 0 && reached) atomicAdd(&d.bc->n_front[value - 1u], reached);
   }
 }
 
@@ -308,12 +308,13 @@ __global__ __launch_bounds__(256) void compact_write_kernel(Dev d) {
   if (m.x | m.y | m.z | m.w) *reinterpret_cast<uint4*>(d.mark + v0) = make_uint4(0u, 0u, 0u, 0u);   // ready for the next batch
   if (blockIdx.x == gridDim.x - 1 && t == 0) {
     Ctrl* c = d.ctrl;
-    c->nA = total[0];
+    BatchCtl* bc = d.bc;
+    bc->nA = total[0];
     uint32_t seen = 0;
-    for (uint32_t l = 0; l < d.layers; ++l) c->nR[l] = d.R[l] != d.A ? total[++seen] : total[0];
+    for (uint32_t l = 0; l < d.layers; ++l) bc->nR[l] = d.R[l] != d.A ? total[++seen] : total[0];
     c->tot_affected += total[0];
-    c->tot_direct += c->nD;
-    c->tot_scanned += c->scanned;
+    c->tot_direct += bc->nD;
+    c->tot_scanned += bc->scanned;
   }
 }
 

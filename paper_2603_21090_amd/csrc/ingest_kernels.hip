@@ -57,6 +57,7 @@ __global__ __launch_bounds__(kSortThreads) void stage_sort_kernel(Dev d, uint32_
   __shared__ uint32_t s_err, s_nD, s_units;
   const uint32_t t = threadIdx.x;
   Ctrl* c = d.ctrl;
+  BatchCtl* bc = d.bc;
   if (t == 0) s_err = 0xFFFFFFFFu;
   __syncthreads();
 
@@ -81,12 +82,12 @@ __global__ __launch_bounds__(kSortThreads) void stage_sort_kernel(Dev d, uint32_
   __syncthreads();
   if (s_err != 0xFFFFFFFFu) {
     if (t == 0) {
-      c->skip = 1;
+      bc->skip = 1;
       if (c->err_code == 0) { c->err_code = -(int32_t)(s_err & 15u); c->err_batch = c->batch_seq; }
       c->batch_seq += 1;
-      c->n_edges = 0; c->nD = 0; c->scanned = 0;
-      for (int h = 0; h < STGN_MAX_LAYERS + 2; ++h) c->n_front[h] = 0;
-      for (int h = 0; h < STGN_MAX_LAYERS + 1; ++h) { c->n_items[h] = 0; c->front_deg[h] = 0; c->pulled[h] = 0; }
+      bc->n_edges = 0; bc->nD = 0; bc->scanned = 0;
+      for (int h = 0; h < STGN_MAX_LAYERS + 2; ++h) bc->n_front[h] = 0;
+      for (int h = 0; h < STGN_MAX_LAYERS + 1; ++h) { bc->n_items[h] = 0; bc->front_deg[h] = 0; bc->pulled[h] = 0; }
     }
     return;
   }
@@ -190,21 +191,21 @@ __global__ __launch_bounds__(kSortThreads) void stage_sort_kernel(Dev d, uint32_
       }
     }
   }
-  if (t == 0) { for (int h = 0; h < STGN_MAX_LAYERS + 1; ++h) { c->front_deg[h] = 0; c->pulled[h] = 0; } }
+  if (t == 0) { for (int h = 0; h < STGN_MAX_LAYERS + 1; ++h) { bc->front_deg[h] = 0; bc->pulled[h] = 0; } }
   __syncthreads();
   for (int off = 32; off > 0; off >>= 1) fdeg += __shfl_xor(fdeg, off);
-  if ((t & 63) == 0 && fdeg) atomicAdd((unsigned long long*)&c->front_deg[0], fdeg);
+  if ((t & 63) == 0 && fdeg) atomicAdd((unsigned long long*)&bc->front_deg[0], fdeg);
   __syncthreads();
   if (t == 0) {
-    c->skip = 0;
+    bc->skip = 0;
     c->batch_seq += 1;
-    c->n_edges = n;
-    c->nD = nD;
-    c->scanned = 0;
-    for (int h = 0; h < STGN_MAX_LAYERS + 2; ++h) c->n_front[h] = 0;
-    for (int h = 0; h < STGN_MAX_LAYERS + 1; ++h) c->n_items[h] = 0;
-    c->n_front[0] = nD;
-    c->E_base = c->E;
+    bc->n_edges = n;
+    bc->nD = nD;
+    bc->scanned = 0;
+    for (int h = 0; h < STGN_MAX_LAYERS + 2; ++h) bc->n_front[h] = 0;
+    for (int h = 0; h < STGN_MAX_LAYERS + 1; ++h) bc->n_items[h] = 0;
+    bc->n_front[0] = nD;
+    bc->E_base = c->E;
     c->E += n;
     c->pool_units += s_units;
     if (n) c->t_stream = ts[n - 1];
@@ -229,7 +230,7 @@ __device__ inline uint64_t log_addr(const Dev& d, uint32_t node, uint32_t pos) {
 constexpr uint32_t kProjRows = 16;
 __device__ void project_rows(const Dev& d, const float* __restrict__ ef, uint32_t all_nodes, uint32_t bid, uint32_t nblk,
                              float* lds) {
-  const Ctrl* c = d.ctrl;
+  const BatchCtl* c = d.bc;
   const uint32_t nD = all_nodes ? d.N : (d.d_mem ? c->nD : 0u);
   const uint32_t nE = (all_nodes || !d.d_edge) ? 0u : c->n_edges;
   const uint64_t E0 = c->E_base;
@@ -310,7 +311,7 @@ __global__ __launch_bounds__(256) void apply_kernel(Dev d, const uint32_t* __res
                                                     const double* __restrict__ ts, const float* __restrict__ ef,
                                                     uint32_t proj_blocks) {
   extern __shared__ __align__(16) float lds[];
-  const Ctrl* c = d.ctrl;
+  const BatchCtl* c = d.bc;
   if (c->skip) return;
   if (blockIdx.x < proj_blocks) {
     project_rows(d, ef, 0u, blockIdx.x, proj_blocks, lds);

@@ -55,7 +55,7 @@ __global__ __launch_bounds__(kThreads) void memory_update_kernel(Dev d, const ui
   __shared__ uint32_t s_seg[kRows], s_n[kRows];
   __shared__ double s_tl[kRows];
   __shared__ float s_scale[kRows];
-  const Ctrl* c = d.ctrl;
+  const BatchCtl* c = d.bc;
   if (c->skip) return;
   const uint32_t nD = c->nD;
   const uint32_t ntiles = (nD + kRows - 1) / kRows;

@@ -22,32 +22,38 @@ struct __align__(16) RingEntry {
 };
 
 // Device-resident control block: every size the kernels need lives here so that a whole batch
-// can be enqueued without reading anything back.
+// can be enqueued without reading anything back.  The fields of one batch are kept twice and the
+// batches alternate between the copies (as they do between two sets of the per-batch scratch lists),
+// so that the next batch can be staged while kernels of the current one still read theirs.
+struct BatchCtl {
+  uint32_t skip;                 // 1: the batch failed validation, all its kernels exit
+  uint32_t n_edges;              // edges of the batch
+  uint32_t nD;                   // |V_direct| of the batch
+  uint32_t nA;                   // |V_aff| of the batch
+  uint32_t n_front[STGN_MAX_LAYERS + 2];  // frontier sizes per hop (n_front[0] = nD)
+  uint32_t n_items[STGN_MAX_LAYERS + 1];  // propagation work items per hop
+  uint32_t nR[STGN_MAX_LAYERS];  // rows layer l recomputes in the batch
+  uint32_t pulled[STGN_MAX_LAYERS + 1];   // bit 0: hop h ran in pull mode; bit 1: its frontier preferred pulling
+  uint64_t scanned;              // adjacency entries scanned in the batch
+  uint64_t E_base;               // edges ingested before the batch
+  // adjacency entries the frontier of hop h owns (exact for hop 0 and after a pull hop, an upper
+  // estimate after a push hop): decides between pushing along the frontier's logs and pulling
+  // through the rings of the clean nodes
+  uint64_t front_deg[STGN_MAX_LAYERS + 1];
+};
+
 struct Ctrl {
-  uint32_t skip;                 // 1: the current batch failed validation, all its kernels exit
   int32_t  err_code;             // first device-side error (sticky until read by the host)
   uint32_t err_batch;
   uint32_t batch_seq;            // batches seen
-  uint32_t n_edges;              // edges of the current batch
-  uint32_t nD;                   // |V_direct| of the current batch
-  uint32_t nA;                   // |V_aff| of the current batch
-  uint32_t n_front[STGN_MAX_LAYERS + 2];  // frontier sizes per hop (n_front[0] = nD)
-  uint32_t n_items[STGN_MAX_LAYERS + 1];  // propagation work items per hop
   uint32_t pad0;
-  uint64_t scanned;              // adjacency entries scanned in the current batch
-  uint64_t E_base;               // edges ingested before the current batch
-  uint64_t E;                    // edges ingested including the current batch
+  uint64_t E;                    // edges ingested including the last staged batch
   uint64_t pool_units;           // adjacency pool cursor, in units of kMinBlock entries
   double   t_stream;             // last ingested timestamp
   uint64_t tot_direct, tot_affected, tot_scanned;
   uint64_t tot_gathered;         // ring entries gathered by the attention kernels (all layers)
   uint64_t tot_rows;             // rows the attention kernels recomputed (all layers)
-  uint32_t nR[STGN_MAX_LAYERS];  // rows layer l recomputes in the current batch
-  // adjacency entries the frontier of hop h owns (exact for hop 0 and after a pull hop, an upper
-  // estimate after a push hop): decides between pushing along the frontier's logs and pulling
-  // through the rings of the clean nodes
-  uint64_t front_deg[STGN_MAX_LAYERS + 1];
-  uint32_t pulled[STGN_MAX_LAYERS + 1];   // bit 0: hop h ran in pull mode; bit 1: its frontier preferred pulling
+  BatchCtl b[2];
 };
 
 // Row-table descriptor: row v starts at base + v * ld (floats)
@@ -107,8 +113,13 @@ struct Dev {
   Table    KVE[STGN_MAX_LAYERS];     // [max_edges x ld_kv]; one zero row (ld 0) without edge features
   uint32_t sh, ks, nt, ld_kv;        // slots per head, key slots, time slots, floats per cached row
   double*  ets;                      // [max_edges] edge timestamps
-  // per-batch scratch
+  // per-batch scratch: two sets, the batches alternate (bind_batch points the plain fields at one of them)
+  struct Scratch {
+    uint32_t *D, *seg_start, *last_slot, *deg_new, *slot_pos, *slot_d, *slot_sorted;
+    float* mem_new;
+  } scr[2];
   Ctrl*    ctrl;
+  BatchCtl* bc;                      // the current batch's copy of the batch fields (set per batch by the host)
   char*    stage[2];                 // staging blocks for host inputs (batches alternate)
   uint32_t* D;                       // [2*max_batch] sorted distinct endpoints
   uint32_t* seg_start;               // [2*max_batch + 1]
@@ -147,6 +158,16 @@ struct Dev {
 };
 
 inline __host__ __device__ uint32_t round_up(uint32_t x, uint32_t m) { return (x + m - 1) / m * m; }
+
+// the device description a batch of the given parity is enqueued with
+inline Dev bind_batch(const Dev& base, int par) {
+  Dev d = base;
+  const Dev::Scratch& s = base.scr[par];
+  d.D = s.D; d.seg_start = s.seg_start; d.last_slot = s.last_slot; d.deg_new = s.deg_new;
+  d.slot_pos = s.slot_pos; d.slot_d = s.slot_d; d.slot_sorted = s.slot_sorted; d.mem_new = s.mem_new;
+  d.bc = base.ctrl ? &base.ctrl->b[par] : nullptr;
+  return d;
+}
 
 // Kernel classes for the optional event timing
 enum KernelClass { KC_SORT = 0, KC_MEMORY, KC_APPLY, KC_PLAN, KC_EXPAND, KC_COMPACT, KC_LAYER,
