@@ -54,7 +54,7 @@ __global__ __launch_bounds__(kSortThreads) void stage_sort_kernel(Dev d, uint32_
                                                                   const double* __restrict__ ts, uint32_t P) {
   extern __shared__ uint64_t keys[];
   __shared__ uint32_t s_buf[kSortThreads / 64];
-  __shared__ uint32_t s_err, s_nD, s_units;
+  __shared__ uint32_t s_err, s_nD;
   const uint32_t t = threadIdx.x;
   Ctrl* c = d.ctrl;
   BatchCtl* bc = d.bc;
@@ -139,47 +139,64 @@ __global__ __launch_bounds__(kSortThreads) void stage_sort_kernel(Dev d, uint32_
   {
     uint32_t dcur = excl;          // number of heads before element lo
     for (uint32_t i = lo; i < hi; ++i) {
-      const uint32_t node = (uint32_t)(keys[i] >> 32);
+      const uint64_t key = keys[i];
+      const uint32_t node = (uint32_t)(key >> 32), slot = (uint32_t)key;
       if (i == 0 || node != (uint32_t)(keys[i - 1] >> 32)) {
         d.D[dcur] = node;
         d.seg_start[dcur] = i;
         ++dcur;
       }
+      const uint32_t di = dcur - 1;
+      d.slot_d[slot] = di;
+      d.slot_sorted[i] = slot;
+      if (i + 1 == m || (uint32_t)(keys[i + 1] >> 32) != node) d.last_slot[di] = slot;
     }
     if (t == 0) d.seg_start[nD] = m;
   }
-  __threadfence_block();
-  __syncthreads();
-  {
-    uint32_t dcur = excl;
-    for (uint32_t i = lo; i < hi; ++i) {
-      const uint64_t key = keys[i];
-      const uint32_t node = (uint32_t)(key >> 32), slot = (uint32_t)key;
-      if (i == 0 || node != (uint32_t)(keys[i - 1] >> 32)) ++dcur;
-      const uint32_t di = dcur - 1;
-      const uint32_t rank = i - d.seg_start[di];
-      d.slot_pos[slot] = d.deg[node] + rank;
-      d.slot_d[slot] = di;
-      d.slot_sorted[i] = slot;
-    }
+  if (t == 0) {
+    bc->skip = 0;
+    c->batch_seq += 1;
+    bc->n_edges = n;
+    bc->nD = nD;
+    bc->scanned = 0;
+    for (int h = 0; h < STGN_MAX_LAYERS + 2; ++h) bc->n_front[h] = 0;
+    for (int h = 0; h < STGN_MAX_LAYERS + 1; ++h) { bc->n_items[h] = 0; bc->front_deg[h] = 0; bc->pulled[h] = 0; }
+    bc->n_front[0] = nD;
+    bc->E_base = c->E;
+    c->E += n;
+    if (n) c->t_stream = ts[n - 1];
   }
+}
 
-  // ---- per distinct endpoint: new degree, last slot, adjacency blocks to allocate
-  const uint32_t eptd = (m + nth - 1) / nth;
-  const uint32_t dlo = t * eptd, dhi = min(dlo + eptd, nD);
+// Second half of the staging, the part that depends on the degrees the previous batch's apply step
+// left behind (the first half only looks at the batch itself and may run a batch ahead): position
+// of every endpoint slot in its node's adjacency log, the endpoints' new degrees, the adjacency
+// blocks they need (allocated in endpoint order, so the placement is deterministic) and the number
+// of adjacency entries the endpoints own, which the first propagation hop plans with.
+__global__ __launch_bounds__(kSortThreads) void place_kernel(Dev d) {
+  __shared__ uint32_t s_buf[kSortThreads / 64];
+  __shared__ uint32_t s_units;
+  Ctrl* c = d.ctrl;
+  BatchCtl* bc = d.bc;
+  if (bc->skip) return;
+  const uint32_t t = threadIdx.x, nth = blockDim.x;
+  const uint32_t m = 2 * bc->n_edges, nD = bc->nD;
+  for (uint32_t i = t; i < m; i += nth) {
+    const uint32_t slot = d.slot_sorted[i];
+    const uint32_t di = d.slot_d[slot];
+    d.slot_pos[slot] = d.deg[d.D[di]] + (i - d.seg_start[di]);
+  }
+  const uint32_t eptd = (nD + nth - 1) / nth;     // contiguous endpoints per thread
+  const uint32_t dlo = min(t * eptd, nD), dhi = min(dlo + eptd, nD);
   uint32_t units = 0;
   unsigned long long fdeg = 0;              // adjacency entries the endpoints own after this batch
   for (uint32_t x = dlo; x < dhi; ++x) {
-    const uint32_t node = d.D[x];
-    const uint32_t s0 = d.seg_start[x], s1 = d.seg_start[x + 1];
-    const uint32_t dp = d.deg[node], dn = dp + (s1 - s0);
+    const uint32_t dp = d.deg[d.D[x]], dn = dp + (d.seg_start[x + 1] - d.seg_start[x]);
     d.deg_new[x] = dn;
     fdeg += dn;
-    d.last_slot[x] = (uint32_t)keys[s1 - 1];
-    const uint32_t b0 = blocks_for(dp), b1 = blocks_for(dn);
-    units += (1u << b1) - (1u << b0);
+    units += (1u << blocks_for(dn)) - (1u << blocks_for(dp));
   }
-  uint32_t uexcl = block_excl_scan(units, s_buf, &s_units);
+  const uint32_t uexcl = block_excl_scan(units, s_buf, &s_units);
   {
     uint64_t base = c->pool_units + uexcl;
     for (uint32_t x = dlo; x < dhi; ++x) {
@@ -191,25 +208,10 @@ __global__ __launch_bounds__(kSortThreads) void stage_sort_kernel(Dev d, uint32_
       }
     }
   }
-  if (t == 0) { for (int h = 0; h < STGN_MAX_LAYERS + 1; ++h) { bc->front_deg[h] = 0; bc->pulled[h] = 0; } }
-  __syncthreads();
   for (int off = 32; off > 0; off >>= 1) fdeg += __shfl_xor(fdeg, off);
   if ((t & 63) == 0 && fdeg) atomicAdd((unsigned long long*)&bc->front_deg[0], fdeg);
-  __syncthreads();
-  if (t == 0) {
-    bc->skip = 0;
-    c->batch_seq += 1;
-    bc->n_edges = n;
-    bc->nD = nD;
-    bc->scanned = 0;
-    for (int h = 0; h < STGN_MAX_LAYERS + 2; ++h) bc->n_front[h] = 0;
-    for (int h = 0; h < STGN_MAX_LAYERS + 1; ++h) bc->n_items[h] = 0;
-    bc->n_front[0] = nD;
-    bc->E_base = c->E;
-    c->E += n;
-    c->pool_units += s_units;
-    if (n) c->t_stream = ts[n - 1];
-  }
+  __syncthreads();                          // every thread has read pool_units
+  if (t == 0) c->pool_units += s_units;
 }
 
 __device__ inline uint64_t log_addr(const Dev& d, uint32_t node, uint32_t pos) {
@@ -394,6 +396,12 @@ void launch_stage_sort(const Dev& d, hipStream_t s, uint32_t n, const uint32_t* 
   uint32_t threads = P / 2;
   threads = threads < 256 ? 256 : threads > (uint32_t)kSortThreads ? (uint32_t)kSortThreads : threads;
   hipLaunchKernelGGL(stage_sort_kernel, dim3(1), dim3(threads), P * sizeof(uint64_t), s, d, n, src, dst, ts, P);
+}
+
+void launch_place(const Dev& d, hipStream_t s, uint32_t n) {
+  uint32_t threads = (2 * n + 63u) & ~63u;     // one endpoint slot per thread where the batch allows
+  threads = threads < 64 ? 64 : threads > (uint32_t)kSortThreads ? (uint32_t)kSortThreads : threads;
+  hipLaunchKernelGGL(place_kernel, dim3(1), dim3(threads), 0, s, d);
 }
 
 void launch_apply(const Dev& d, hipStream_t s, const uint32_t* src, const uint32_t* dst, const double* ts,
