@@ -27,20 +27,18 @@ struct stgn_ctx {
   Dev d;
   hipStream_t stream = nullptr;
   // A batch's front part (validation + sort, placement, memory update) can run on a second stream beside
-  // the previous batch's main part.  Its first kernel looks only at the batch itself and the running edge
-  // count and writes the batch's own scratch set and batch fields (both held twice, by batch parity): it
-  // waits for the compaction of the batch before the previous one (ev_compact[], recorded on `stream`),
-  // the last kernel that read that set.  Placement and the memory update read the degrees and memory the
-  // previous apply step left: they wait for it (ev_apply[], recorded on `stream`) and then run beside the
-  // previous batch's propagation, compaction and attention layers, none of which writes what they read
-  // or reads what they write.  The batch's own apply step on `stream` waits for the front part (ev_front,
-  // recorded on `front`).  Only batches with device inputs that find `stream` busy take this path; calls
-  // that ask for per-stage statistics, calls with host inputs, and all calls while per-kernel timing is
-  // on, run everything on `stream`.
+  // the previous batch's main part.  It reads the degrees and memory the previous apply step left and
+  // writes the batch's own scratch set and batch fields (both held twice, by batch parity; the set was
+  // last used by the batch before the previous one, whose propagation and compaction precede the previous
+  // apply step on `stream`): it waits for that apply step (ev_apply[], recorded on `stream`) and then runs
+  // beside the previous batch's propagation, compaction and attention layers, none of which writes what
+  // it reads or reads what it writes.  The batch's own apply step on `stream` waits for the front part
+  // (ev_front, recorded on `front`).  Only batches with device inputs that find `stream` busy take this
+  // path; calls that ask for per-stage statistics, calls with host inputs, and all calls while per-kernel
+  // timing is on, run everything on `stream`.
   hipStream_t front = nullptr;
-  hipEvent_t ev_compact[2] = {nullptr, nullptr}, ev_apply[2] = {nullptr, nullptr}, ev_front = nullptr;
-  bool recorded[2] = {false, false};      // ev_compact / ev_apply of that parity have been recorded
-  bool prev_on_front = false;       // the previous batch's front part ran on `front`
+  hipEvent_t ev_apply[2] = {nullptr, nullptr}, ev_front = nullptr;   // ev_apply alternates with the batches
+  bool recorded[2] = {false, false};      // ev_apply of that parity has been recorded
   int parity = 0;                   // staging block, scratch set, batch fields and compaction event of the next batch
   int last_par = 0;                 // parity of the batch enqueued last
   bool idle = true;                 // nothing was enqueued since the library last synchronised `stream`
@@ -191,7 +189,10 @@ size_t layout(const stgn_config& c, char* base, Dev* d) {
     s.mem_new = b.take<float>((size_t)B2 * c.d_mem);
   }
   *d = bind_batch(*d, 0);
-  d->mark = b.take<uint8_t>(mark_bytes(N));
+  d->mark_set[0] = b.take<uint8_t>(mark_bytes(N));
+  d->mark_set[1] = compact_in_one(*d) ? b.take<uint8_t>(mark_bytes(N)) : d->mark_set[0];
+  d->mark = d->mark_set[0];
+  d->mark_other = d->mark_set[1];
   d->items_cap = (uint64_t)N + 2 * c.max_edges / kLogChunk + 1024;
   d->items = b.take<uint64_t>(d->items_cap);
   d->blocksum = b.take<uint32_t>((size_t)(c.layers + 1) * (mark_bytes(N) / kMarkPad + 2));
@@ -492,8 +493,6 @@ int stgn_create(const stgn_config* cfg, const stgn_weights* w, const float* node
   for (auto& e : ctx->stage_ev)
     if (hipEventCreate(&e) != hipSuccess) { ctx->err = "event creation failed"; return bail(STGN_E_DEVICE); }
   if (hipStreamCreateWithFlags(&ctx->front, hipStreamNonBlocking) != hipSuccess ||
-      hipEventCreateWithFlags(&ctx->ev_compact[0], hipEventDisableTiming) != hipSuccess ||
-      hipEventCreateWithFlags(&ctx->ev_compact[1], hipEventDisableTiming) != hipSuccess ||
       hipEventCreateWithFlags(&ctx->ev_apply[0], hipEventDisableTiming) != hipSuccess ||
       hipEventCreateWithFlags(&ctx->ev_apply[1], hipEventDisableTiming) != hipSuccess ||
       hipEventCreateWithFlags(&ctx->ev_front, hipEventDisableTiming) != hipSuccess) {
@@ -536,7 +535,6 @@ void stgn_destroy(stgn_ctx* ctx) {
   if (ctx->front) hipStreamSynchronize(ctx->front);
   if (ctx->stream || ctx->ctrl_host) hipStreamSynchronize(ctx->stream);
   if (ctx->front) hipStreamDestroy(ctx->front);
-  for (auto& e : ctx->ev_compact) if (e) hipEventDestroy(e);
   for (auto& e : ctx->ev_apply) if (e) hipEventDestroy(e);
   if (ctx->ev_front) hipEventDestroy(ctx->ev_front);
   for (int i = 0; i < 2; ++i) {
@@ -611,17 +609,11 @@ int stgn_ingest_batch(stgn_ctx* ctx, uint32_t n, const uint32_t* src, const uint
   ctx->parity ^= 1;                            // from here on the batch is enqueued
   ctx->last_par = par;
   hipStream_t s = ctx->stream;
-  if (overlapped) {
-    // the scratch set and batch fields of this parity are free once the batch that used them last is compacted;
-    // a previous batch whose front part ran on `stream` orders its sort before this one through its apply event
-    if (ctx->recorded[par]) HIPCHK(ctx, hipStreamWaitEvent(sf, ctx->ev_compact[par], 0));
-    if (!ctx->prev_on_front && ctx->recorded[par ^ 1]) HIPCHK(ctx, hipStreamWaitEvent(sf, ctx->ev_apply[par ^ 1], 0));
-  }
+  // degrees and memory as the previous apply step left them; the scratch set of this parity is free by then
+  if (overlapped && ctx->recorded[par ^ 1]) HIPCHK(ctx, hipStreamWaitEvent(sf, ctx->ev_apply[par ^ 1], 0));
   hipEvent_t* ev = stats ? ctx->stage_ev : nullptr;
   if (ev) hipEventRecord(ev[0], s);
   { Scope t(ctx, KC_SORT, sf); launch_stage_sort(d, sf, n, dsrc, ddst, dts); }
-  // degrees and memory as the previous apply step left them
-  if (overlapped && ctx->prev_on_front && ctx->recorded[par ^ 1]) HIPCHK(ctx, hipStreamWaitEvent(sf, ctx->ev_apply[par ^ 1], 0));
   { Scope t(ctx, KC_PLACE, sf); launch_place(d, sf, n); }
   if (ev) hipEventRecord(ev[1], s);
   if (c.d_mem) { Scope t(ctx, KC_MEMORY, sf); launch_memory_update(d, sf, dsrc, ddst, dts, def); }
@@ -630,9 +622,9 @@ int stgn_ingest_batch(stgn_ctx* ctx, uint32_t n, const uint32_t* src, const uint
     HIPCHK(ctx, hipEventRecord(ctx->ev_front, ctx->front));
     HIPCHK(ctx, hipStreamWaitEvent(s, ctx->ev_front, 0));
   }
-  ctx->prev_on_front = overlapped;
   { Scope t(ctx, KC_APPLY); launch_apply(d, s, dsrc, ddst, dts, def); }
   HIPCHK(ctx, hipEventRecord(ctx->ev_apply[par], s));
+  ctx->recorded[par] = true;
   if (ev) hipEventRecord(ev[3], s);
   for (uint32_t hop = 0; hop < c.layers; ++hop) {
     const bool planned = !ctx->pull_hint[hop];
@@ -640,9 +632,7 @@ int stgn_ingest_batch(stgn_ctx* ctx, uint32_t n, const uint32_t* src, const uint
     { Scope t(ctx, KC_EXPAND); launch_expand(d, s, hop, planned); }
   }
   { Scope t(ctx, KC_COMPACT); launch_compact(d, s, 0); }
-  { Scope t(ctx, KC_COMPACT); launch_compact(d, s, 1); }
-  HIPCHK(ctx, hipEventRecord(ctx->ev_compact[par], s));
-  ctx->recorded[par] = true;
+  if (!compact_in_one(d)) { Scope t(ctx, KC_COMPACT); launch_compact(d, s, 1); }
   if (ev) hipEventRecord(ev[4], s);
   run_layers(ctx, d, false);
   if (ctx->timing) { Scope t(ctx, KC_NOOP); launch_noop(s); }   // event-pair overhead, for calibration

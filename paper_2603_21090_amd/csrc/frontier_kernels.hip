@@ -318,6 +318,66 @@ __global__ __launch_bounds__(256) void compact_write_kernel(Dev d) {
   }
 }
 
+// Count and write in one launch, for flag arrays of at most kSmallBlocks blocks: a workgroup counts
+// the flags of the blocks before its own instead of waiting for their sums (a few KiB of reads that
+// hit L2), so no workgroup depends on another.  The batch's flags stay as they are (other workgroups
+// may still be counting them); each workgroup clears its block of the other parity's array, which
+// the next batch uses and nobody reads now.
+constexpr uint32_t kSmallBlocks = 16;
+__global__ __launch_bounds__(256) void compact_small_kernel(Dev d, uint32_t last_value) {
+  __shared__ uint32_t s[256];
+  const uint32_t t = threadIdx.x;
+  const uint32_t v0 = blockIdx.x * kFlagsPerBlock + t * kFlagsPerThread;
+  const uint32_t nl = d.n_lists + 1u;
+  uint32_t thr[STGN_MAX_LAYERS + 1], part[STGN_MAX_LAYERS + 1], total[STGN_MAX_LAYERS + 1];
+#pragma unroll
+  for (uint32_t list = 0; list <= STGN_MAX_LAYERS; ++list) {
+    thr[list] = list < nl ? list_threshold(d, list) : 0u;
+    part[list] = 0u; total[list] = 0u;
+  }
+  for (uint32_t b = 0; b < blockIdx.x; ++b) {
+    const uint4 pm = *reinterpret_cast<const uint4*>(d.mark + b * kFlagsPerBlock + t * kFlagsPerThread);
+#pragma unroll
+    for (uint32_t list = 0; list <= STGN_MAX_LAYERS; ++list)
+      if (list < nl) part[list] += (uint32_t)__popc(bytes_upto(pm, thr[list]));
+  }
+  uint4 m = make_uint4(0u, 0u, 0u, 0u);
+  if (v0 < d.N) m = *reinterpret_cast<const uint4*>(d.mark + v0);     // the flag array is padded to whole blocks
+  uint32_t excl;
+#pragma unroll
+  for (uint32_t list = 0; list <= STGN_MAX_LAYERS; ++list) {
+    if (list < nl) {                                                   // uniform
+      const uint32_t before = block_scan_256(part[list], s, &excl);
+      uint32_t bits = bytes_upto(m, thr[list]);
+      const uint32_t block_total = block_scan_256((uint32_t)__popc(bits), s, &excl);
+      uint32_t* out = list_base(d, list) + before + excl;
+      while (bits) {
+        const uint32_t bit = (uint32_t)__ffs((int)bits) - 1u;
+        *out++ = v0 + bit;
+        bits &= bits - 1u;
+      }
+      total[list] = before + block_total;
+    }
+  }
+  // statistics: nodes first reached by hop h carry the flag h + 2
+  for (uint32_t value = 2; value <= last_value; ++value) {
+    const uint32_t reached = block_scan_256(bytes_equal(m, value), s, &excl);
+    if (t == 0 && reached) atomicAdd(&d.bc->n_front[value - 1u], reached);
+  }
+  if (blockIdx.x == gridDim.x - 1 && t == 0) {
+    Ctrl* c = d.ctrl;
+    BatchCtl* bc = d.bc;
+    bc->nA = total[0];
+    uint32_t seen = 0;
+    for (uint32_t l = 0; l < d.layers; ++l) bc->nR[l] = d.R[l] != d.A ? total[++seen] : total[0];
+    c->tot_affected += total[0];
+    c->tot_direct += bc->nD;
+    c->tot_scanned += bc->scanned;
+  }
+  // the next batch's flags
+  reinterpret_cast<uint4*>(d.mark_other)[blockIdx.x * (kFlagsPerBlock / 16u) + t] = make_uint4(0u, 0u, 0u, 0u);
+}
+
 }  // namespace
 
 void launch_plan(const Dev& d, hipStream_t s, uint32_t hop) {
@@ -340,8 +400,14 @@ void launch_expand(const Dev& d, hipStream_t s, uint32_t hop, bool planned) {
   hipLaunchKernelGGL(expand_kernel, dim3(blocks), dim3(256), 0, s, d, hop, planned ? 1u : 0u);
 }
 
+bool compact_in_one(const Dev& d) { return (d.N + kFlagsPerBlock - 1) / kFlagsPerBlock <= kSmallBlocks; }
+
 void launch_compact(const Dev& d, hipStream_t s, int phase) {
   const uint32_t blocks = (d.N + kFlagsPerBlock - 1) / kFlagsPerBlock;
+  if (compact_in_one(d)) {
+    if (phase == 0) hipLaunchKernelGGL(compact_small_kernel, dim3(blocks), dim3(256), 0, s, d, d.layers + 1u);
+    return;
+  }
   if (phase == 0) hipLaunchKernelGGL(compact_count_kernel, dim3(blocks), dim3(256), 0, s, d, d.layers + 1u);
   else hipLaunchKernelGGL(compact_write_kernel, dim3(blocks), dim3(256), 0, s, d);
 }

@@ -377,7 +377,7 @@ __global__ void init_state_kernel(Dev d) {
   const size_t h0 = (size_t)d.N * d.H[0].ld;
   for (size_t x = tid; x < h0; x += nth) d.H[0].base[x] = 0.0f;
   const size_t nw = mark_bytes(d.N) / 4;
-  for (size_t x = tid; x < nw; x += nth) reinterpret_cast<uint32_t*>(d.mark)[x] = 0;
+  for (size_t x = tid; x < nw; x += nth) { reinterpret_cast<uint32_t*>(d.mark_set[0])[x] = 0; reinterpret_cast<uint32_t*>(d.mark_set[1])[x] = 0; }
   const size_t nr = (size_t)d.N * d.k;
   for (size_t x = tid; x < nr; x += nth) { RingEntry r; r.nbr = 0; r.eid = 0; r.t = 0.0; d.ring[x] = r; d.ring_nbr[x] = 0; }
   if (tid == 0) {

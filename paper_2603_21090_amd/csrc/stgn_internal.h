@@ -129,7 +129,12 @@ struct Dev {
   uint32_t* slot_d;                  // [2*max_batch] per slot: index into D
   uint32_t* slot_sorted;             // [2*max_batch] slots ordered by (node, slot): D entry x owns [seg_start[x], seg_start[x+1])
   float*   mem_new;                  // [2*max_batch x d_mem]
-  uint8_t* mark;                     // [mark_bytes(N)] dirty flags, one byte per node
+  uint8_t* mark;                     // [mark_bytes(N)] dirty flags, one byte per node (of the bound batch)
+  // Small flag arrays are held twice, by batch parity: a batch's one-launch compaction leaves its own
+  // flags alone (other workgroups may still be counting them) and clears the other array, which the
+  // next batch uses.  Large arrays are one array (both entries equal), cleared by the compaction's second launch.
+  uint8_t* mark_set[2];
+  uint8_t* mark_other;               // the array of the other parity (bound batch)
   uint64_t* items;                   // propagation work items (node, chunk)
   uint64_t items_cap;
   uint32_t* blocksum;                // compaction partial sums
@@ -166,6 +171,7 @@ inline Dev bind_batch(const Dev& base, int par) {
   d.D = s.D; d.seg_start = s.seg_start; d.last_slot = s.last_slot; d.deg_new = s.deg_new;
   d.slot_pos = s.slot_pos; d.slot_d = s.slot_d; d.slot_sorted = s.slot_sorted; d.mem_new = s.mem_new;
   d.bc = base.ctrl ? &base.ctrl->b[par] : nullptr;
+  d.mark = base.mark_set[par]; d.mark_other = base.mark_set[par ^ 1];
   return d;
 }
 
@@ -184,6 +190,7 @@ void launch_apply(const Dev& d, hipStream_t s, const uint32_t* src, const uint32
 void launch_plan(const Dev& d, hipStream_t s, uint32_t hop);
 void launch_expand(const Dev& d, hipStream_t s, uint32_t hop, bool planned);
 void launch_compact(const Dev& d, hipStream_t s, int phase);
+bool compact_in_one(const Dev& d);   // the compaction is a single launch (phase 0) for this node count
 void launch_layer(const Dev& d, hipStream_t s, uint32_t layer, const uint32_t* rows, const uint32_t* count_ptr,
                   uint32_t count_max);
 void launch_gather_rows(const Dev& d, hipStream_t s, uint32_t layer, uint32_t n, const uint32_t* nodes, float* out);
