@@ -193,6 +193,9 @@ size_t layout(const stgn_config& c, char* base, Dev* d) {
   d->mark_set[1] = compact_in_one(*d) ? b.take<uint8_t>(mark_bytes(N)) : d->mark_set[0];
   d->mark = d->mark_set[0];
   d->mark_other = d->mark_set[1];
+  for (int i = 0; i < 2; ++i) d->stripes_set[i] = b.take<uint64_t>((size_t)kStripedCounters * kStripes * kStripeWords);
+  d->stripes = d->stripes_set[0];
+  d->gathered_slots = b.take<uint64_t>(kStatSlots);
   d->items_cap = (uint64_t)N + 2 * c.max_edges / kLogChunk + 1024;
   d->items = b.take<uint64_t>(d->items_cap);
   d->blocksum = b.take<uint32_t>((size_t)(c.layers + 1) * (mark_bytes(N) / kMarkPad + 2));
@@ -853,7 +856,14 @@ int stgn_get_totals(stgn_ctx* ctx, uint64_t* edges, uint64_t* direct, uint64_t* 
   if (direct) *direct = h.tot_direct;
   if (affected) *affected = h.tot_affected;
   if (scanned) *scanned = h.tot_scanned;
-  if (gathered) *gathered = h.tot_gathered;
+  if (gathered) {
+    // the layer kernel keeps one plain counter per workgroup index (no atomic updates)
+    std::vector<uint64_t> slots(kStatSlots);
+    HIPCHK(ctx, hipMemcpy(slots.data(), ctx->d.gathered_slots, kStatSlots * sizeof(uint64_t), hipMemcpyDeviceToHost));
+    uint64_t sum = 0;
+    for (uint64_t v : slots) sum += v;
+    *gathered = sum;
+  }
   if (rows) *rows = h.tot_rows;
   return rc;
 }

@@ -66,7 +66,7 @@ LaunchArgs make_args(const Dev& d, uint32_t layer) {
   k.KVout = layer + 1 < d.layers ? d.KV[layer + 1].base : nullptr;
   k.WKVnext = layer + 1 < d.layers ? d.L[layer + 1].WKVn : nullptr;
   k.ring = d.ring; k.deg = d.deg; k.t_last = d.t_last;
-  k.om_rev = d.om_rev; k.ph_rev = d.ph_rev; k.ctrl = d.ctrl;
+  k.om_rev = d.om_rev; k.ph_rev = d.ph_rev; k.ctrl = d.ctrl; k.gathered_slots = d.gathered_slots;
   k.WQ = L.WQn; k.cQ = L.cQ; k.WKT = L.WKT; k.WV = L.WV; k.WO = L.WO; k.bO = L.bO;
   k.ld_in = d.H[layer].ld; k.ld_out = d.H[layer + 1].ld; k.ld_kv = d.ld_kv; k.ld_kve = d.KVE[layer].ld;
   k.window = d.window;

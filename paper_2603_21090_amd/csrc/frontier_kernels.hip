@@ -61,14 +61,15 @@ __device__ inline uint32_t block_scan_256(uint32_t v, uint32_t* s, uint32_t* exc
 // plans whole chunks on its own -- no workgroup barrier anywhere: a first pass over the chunk counts
 // its items (one counter update per chunk), a second pass writes them, the 64 lanes filling the
 // items of up to 64 frontier nodes together so that a hub's thousands of items do not land on one lane.
-__device__ inline bool pull_hop(const Dev& d, const BatchCtl* c, uint32_t hop) { return c->front_deg[hop] >= (uint64_t)(d.N / 2u); }
+// (wave-collective: every lane of the calling wave must be active)
+__device__ inline bool pull_hop(const Dev& d, uint32_t hop) { return stripes_sum_wave(d, hop) >= (unsigned long long)(d.N / 2u); }
 // pulled[hop]: bit 0 the hop ran in pull mode, bit 1 the frontier was large enough to prefer pulling
 constexpr uint32_t kRanPull = 1u, kWantsPull = 2u;
 
 __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Dev d, uint32_t hop, uint32_t rounds) {
   __shared__ uint32_t s_off[kPlanWaves][64], s_v[kPlanWaves][64];
   BatchCtl* c = d.bc;
-  if (c->skip || pull_hop(d, c, hop)) return;               // a pull hop needs no work items
+  if (c->skip || pull_hop(d, hop)) return;               // a pull hop needs no work items
   const uint32_t lane = threadIdx.x & 63u;
   const uint32_t wib = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
   const uint32_t gw = blockIdx.x * kPlanWaves + wib, nw = gridDim.x * kPlanWaves;
@@ -114,7 +115,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(Dev d, uint32_t hop,
     uint32_t out = 0;
     if (lane == 0) {
       out = atomicAdd(&c->n_items[hop], items);
-      atomicAdd((unsigned long long*)&c->scanned, scanned);
+      atomicAdd(stripe(d, kScannedCounter, gw), scanned);
     }
     out = (uint32_t)__builtin_amdgcn_readfirstlane((int)out);
     // ---- pass 2: write the items, up to 64 frontier nodes per step
@@ -162,7 +163,7 @@ __global__ __launch_bounds__(256) void expand_kernel(Dev d, uint32_t hop, uint32
   const uint8_t value = (uint8_t)(hop + 2u);
   unsigned long long newdeg = 0;                 // log entries owned by the nodes this thread flags
   unsigned long long looked = 0;                 // ring slots a pull hop examined
-  const bool wants_pull = pull_hop(d, c, hop);
+  const bool wants_pull = pull_hop(d, hop);
   if (wants_pull || !planned) {
     // ---- pull: one clean node per lane
     const uint8_t want = (uint8_t)(hop + 1u);
@@ -218,9 +219,9 @@ __global__ __launch_bounds__(256) void expand_kernel(Dev d, uint32_t hop, uint32
   __syncthreads();
   if (threadIdx.x == 0) {
     const unsigned long long tot = s_deg[0] + s_deg[1] + s_deg[2] + s_deg[3];
-    if (tot) atomicAdd((unsigned long long*)&c->front_deg[hop + 1], tot);
+    if (tot) atomicAdd(stripe(d, hop + 1, blockIdx.x), tot);
     const unsigned long long sc = s_scan[0] + s_scan[1] + s_scan[2] + s_scan[3];
-    if (sc) atomicAdd((unsigned long long*)&c->scanned, sc);
+    if (sc) atomicAdd(stripe(d, kScannedCounter, blockIdx.x), sc);
   }
 }
 
@@ -314,6 +315,7 @@ __global__ __launch_bounds__(256) void compact_write_kernel(Dev d) {
     for (uint32_t l = 0; l < d.layers; ++l) bc->nR[l] = d.R[l] != d.A ? total[++seen] : total[0];
     c->tot_affected += total[0];
     c->tot_direct += bc->nD;
+    bc->scanned = stripes_sum_thread(d, kScannedCounter);
     c->tot_scanned += bc->scanned;
   }
 }
@@ -372,6 +374,7 @@ __global__ __launch_bounds__(256) void compact_small_kernel(Dev d, uint32_t last
     for (uint32_t l = 0; l < d.layers; ++l) bc->nR[l] = d.R[l] != d.A ? total[++seen] : total[0];
     c->tot_affected += total[0];
     c->tot_direct += bc->nD;
+    bc->scanned = stripes_sum_thread(d, kScannedCounter);
     c->tot_scanned += bc->scanned;
   }
   // the next batch's flags

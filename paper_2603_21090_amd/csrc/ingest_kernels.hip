@@ -59,6 +59,8 @@ __global__ __launch_bounds__(kSortThreads) void stage_sort_kernel(Dev d, uint32_
   Ctrl* c = d.ctrl;
   BatchCtl* bc = d.bc;
   if (t == 0) s_err = 0xFFFFFFFFu;
+  // the batch's striped counters start at zero (nothing else touches this parity's set now)
+  if (t < kStripedCounters * kStripes) *stripe(d, t / kStripes, t % kStripes) = 0ull;
   __syncthreads();
 
   // ---- validation: first offending edge decides the code (ids, self loop, time order)
@@ -87,7 +89,7 @@ __global__ __launch_bounds__(kSortThreads) void stage_sort_kernel(Dev d, uint32_
       c->batch_seq += 1;
       bc->n_edges = 0; bc->nD = 0; bc->scanned = 0;
       for (int h = 0; h < STGN_MAX_LAYERS + 2; ++h) bc->n_front[h] = 0;
-      for (int h = 0; h < STGN_MAX_LAYERS + 1; ++h) { bc->n_items[h] = 0; bc->front_deg[h] = 0; bc->pulled[h] = 0; }
+      for (int h = 0; h < STGN_MAX_LAYERS + 1; ++h) { bc->n_items[h] = 0; bc->pulled[h] = 0; }
     }
     return;
   }
@@ -160,7 +162,7 @@ __global__ __launch_bounds__(kSortThreads) void stage_sort_kernel(Dev d, uint32_
     bc->nD = nD;
     bc->scanned = 0;
     for (int h = 0; h < STGN_MAX_LAYERS + 2; ++h) bc->n_front[h] = 0;
-    for (int h = 0; h < STGN_MAX_LAYERS + 1; ++h) { bc->n_items[h] = 0; bc->front_deg[h] = 0; bc->pulled[h] = 0; }
+    for (int h = 0; h < STGN_MAX_LAYERS + 1; ++h) { bc->n_items[h] = 0; bc->pulled[h] = 0; }
     bc->n_front[0] = nD;
     bc->E_base = c->E;
     c->E += n;
@@ -209,7 +211,7 @@ __global__ __launch_bounds__(kSortThreads) void place_kernel(Dev d) {
     }
   }
   for (int off = 32; off > 0; off >>= 1) fdeg += __shfl_xor(fdeg, off);
-  if ((t & 63) == 0 && fdeg) atomicAdd((unsigned long long*)&bc->front_deg[0], fdeg);
+  if ((t & 63) == 0 && fdeg) atomicAdd(stripe(d, 0, t >> 6), fdeg);
   __syncthreads();                          // every thread has read pool_units
   if (t == 0) c->pool_units += s_units;
 }
@@ -380,6 +382,8 @@ __global__ void init_state_kernel(Dev d) {
   for (size_t x = tid; x < nw; x += nth) { reinterpret_cast<uint32_t*>(d.mark_set[0])[x] = 0; reinterpret_cast<uint32_t*>(d.mark_set[1])[x] = 0; }
   const size_t nr = (size_t)d.N * d.k;
   for (size_t x = tid; x < nr; x += nth) { RingEntry r; r.nbr = 0; r.eid = 0; r.t = 0.0; d.ring[x] = r; d.ring_nbr[x] = 0; }
+  for (size_t x = tid; x < (size_t)kStripedCounters * kStripes * kStripeWords; x += nth) { d.stripes_set[0][x] = 0; d.stripes_set[1][x] = 0; }
+  for (size_t x = tid; x < kStatSlots; x += nth) d.gathered_slots[x] = 0;
   if (tid == 0) {
     Ctrl z = {};
     *d.ctrl = z;

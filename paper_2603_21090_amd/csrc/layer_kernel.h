@@ -86,6 +86,7 @@ struct LayerArgs {
   const RingEntry* ring; const uint32_t* deg; const double* t_last;
   const double* om_rev; const double* ph_rev;
   Ctrl* ctrl;
+  uint64_t* gathered_slots;                        // statistic: ring entries gathered, one plain counter per workgroup index
   const float *WQ, *cQ, *WKT, *WV, *WO, *bO, *WKVnext;   // matrices group-major (mfma16.h)
   uint32_t ld_in, ld_out, ld_kv, ld_kve;           // ld_kve = 0 without edge features (every edge reads one zero row)
   uint32_t k, d_in, d_emb, dk, d_time;
@@ -658,13 +659,22 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
     }
     __syncthreads();
   }
-  // statistics: one atomic per wave
+  // statistics: the workgroup's count goes into the slot of its index with a plain update (launches
+  // on one stream follow each other, and no other workgroup of a launch has this index); thousands of
+  // same-address atomic updates at the end of a launch were measured to cost a third of its duration
   const uint32_t gsum = (uint32_t)__builtin_amdgcn_readlane((int)gathered, 0) +
                         (uint32_t)__builtin_amdgcn_readlane((int)gathered, 16) +
                         (uint32_t)__builtin_amdgcn_readlane((int)gathered, 32) +
                         (uint32_t)__builtin_amdgcn_readlane((int)gathered, 48);
-  if (lane == 0 && gsum && !a.out_rows) atomicAdd((unsigned long long*)&a.ctrl->tot_gathered, (unsigned long long)gsum);
-  if (blockIdx.x == 0 && threadIdx.x == 0 && n && !a.out_rows) atomicAdd((unsigned long long*)&a.ctrl->tot_rows, (unsigned long long)n);
+  if (!a.out_rows) {
+    if (lane == 0) s_cnt[wave] = gsum;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      const uint32_t tot = s_cnt[0] + s_cnt[1] + s_cnt[2] + s_cnt[3];
+      if (tot) a.gathered_slots[blockIdx.x] += tot;
+      if (blockIdx.x == 0 && n) a.ctrl->tot_rows += n;
+    }
+  }
 }
 
 // ---- dispatch over (heads, key slots, time slots)
@@ -686,8 +696,9 @@ void go(LaunchArgs& a) {
     return;
   }
   uint64_t blocks = ((uint64_t)a.cm + kTM - 1) / kTM;
-  const uint64_t cap = (uint64_t)WGS * (a.num_cu ? a.num_cu : 256u);   // persistent: each workgroup strides over the tiles,
-  if (blocks > cap) blocks = cap;                                      // staging one tile ahead
+  uint64_t cap = (uint64_t)WGS * (a.num_cu ? a.num_cu : 256u);         // persistent: each workgroup strides over the tiles,
+  if (cap > kStatSlots) cap = kStatSlots;                              // staging one tile ahead
+  if (blocks > cap) blocks = cap;
   if (blocks < 1) blocks = 1;
   hipLaunchKernelGGL(kern, dim3((uint32_t)blocks), dim3(256), a.lds, a.s, a.k, a.rows, a.cp, a.cm);
 }

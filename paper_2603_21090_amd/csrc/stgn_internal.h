@@ -34,13 +34,21 @@ struct BatchCtl {
   uint32_t n_items[STGN_MAX_LAYERS + 1];  // propagation work items per hop
   uint32_t nR[STGN_MAX_LAYERS];  // rows layer l recomputes in the batch
   uint32_t pulled[STGN_MAX_LAYERS + 1];   // bit 0: hop h ran in pull mode; bit 1: its frontier preferred pulling
-  uint64_t scanned;              // adjacency entries scanned in the batch
+  uint64_t scanned;              // adjacency entries scanned in the batch (summed up by the compaction)
   uint64_t E_base;               // edges ingested before the batch
-  // adjacency entries the frontier of hop h owns (exact for hop 0 and after a pull hop, an upper
-  // estimate after a push hop): decides between pushing along the frontier's logs and pulling
-  // through the rings of the clean nodes
-  uint64_t front_deg[STGN_MAX_LAYERS + 1];
 };
+// Counters that every workgroup of a kernel adds to are STRIPED: same-address atomic updates from
+// thousands of workgroups serialise (measured: about 5 ns each, 60 us for the two counters of one
+// propagation hop on a million nodes), so a counter is kStripes values in cache lines of their own,
+// a workgroup adds to the stripe of its index and readers sum the stripes.  Per batch (held twice, by
+// batch parity): counter h = adjacency entries the frontier of hop h owns (exact for hop 0 and after a
+// pull hop, an upper estimate after a push hop; decides between pushing along the frontier's logs and
+// pulling through the rings of the clean nodes), counter kScannedCounter = adjacency entries scanned.
+constexpr uint32_t kStripes = 32;
+constexpr uint32_t kStripeWords = 16;                        // uint64 per 128-byte line
+constexpr uint32_t kScannedCounter = STGN_MAX_LAYERS + 1;
+constexpr uint32_t kStripedCounters = STGN_MAX_LAYERS + 2;
+constexpr uint32_t kStatSlots = 1024;                        // per-workgroup statistic slots of the layer kernel (its grid never exceeds this)
 
 struct Ctrl {
   int32_t  err_code;             // first device-side error (sticky until read by the host)
@@ -51,7 +59,6 @@ struct Ctrl {
   uint64_t pool_units;           // adjacency pool cursor, in units of kMinBlock entries
   double   t_stream;             // last ingested timestamp
   uint64_t tot_direct, tot_affected, tot_scanned;
-  uint64_t tot_gathered;         // ring entries gathered by the attention kernels (all layers)
   uint64_t tot_rows;             // rows the attention kernels recomputed (all layers)
   BatchCtl b[2];
 };
@@ -135,6 +142,9 @@ struct Dev {
   // next batch uses.  Large arrays are one array (both entries equal), cleared by the compaction's second launch.
   uint8_t* mark_set[2];
   uint8_t* mark_other;               // the array of the other parity (bound batch)
+  uint64_t* stripes_set[2];          // [kStripedCounters][kStripes] lines of kStripeWords words, per batch parity
+  uint64_t* stripes;                 // ... of the bound batch
+  uint64_t* gathered_slots;          // [kStatSlots] ring entries gathered by the layer kernel, one slot per workgroup index
   uint64_t* items;                   // propagation work items (node, chunk)
   uint64_t items_cap;
   uint32_t* blocksum;                // compaction partial sums
@@ -172,7 +182,25 @@ inline Dev bind_batch(const Dev& base, int par) {
   d.slot_pos = s.slot_pos; d.slot_d = s.slot_d; d.slot_sorted = s.slot_sorted; d.mem_new = s.mem_new;
   d.bc = base.ctrl ? &base.ctrl->b[par] : nullptr;
   d.mark = base.mark_set[par]; d.mark_other = base.mark_set[par ^ 1];
+  d.stripes = base.stripes_set[par];
   return d;
+}
+
+__device__ inline unsigned long long* stripe(const Dev& d, uint32_t counter, uint32_t index) {
+  return reinterpret_cast<unsigned long long*>(d.stripes) + ((size_t)counter * kStripes + (index & (kStripes - 1u))) * kStripeWords;
+}
+// sum of a striped counter; every lane of the calling wave must be active, all receive the sum
+__device__ inline unsigned long long stripes_sum_wave(const Dev& d, uint32_t counter) {
+  const uint32_t lane = threadIdx.x & 63u;
+  unsigned long long v = lane < kStripes ? *stripe(d, counter, lane) : 0ull;
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+  return v;
+}
+// ... by a single thread
+__device__ inline unsigned long long stripes_sum_thread(const Dev& d, uint32_t counter) {
+  unsigned long long v = 0;
+  for (uint32_t s = 0; s < kStripes; ++s) v += *stripe(d, counter, s);
+  return v;
 }
 
 // Kernel classes for the optional event timing
