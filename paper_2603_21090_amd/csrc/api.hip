@@ -14,7 +14,7 @@ using namespace stgn;
 namespace {
 
 const char* const kClassNames[KC_COUNT] = {"stage_sort", "memory_update", "apply", "plan", "expand", "compact",
-                                           "layer", "gather_rows", "noop", "project", "predict", "place"};
+                                           "layer", "gather_rows", "noop", "project", "predict"};
 
 std::string g_create_error;
 
@@ -617,7 +617,6 @@ int stgn_ingest_batch(stgn_ctx* ctx, uint32_t n, const uint32_t* src, const uint
   hipEvent_t* ev = stats ? ctx->stage_ev : nullptr;
   if (ev) hipEventRecord(ev[0], s);
   { Scope t(ctx, KC_SORT, sf); launch_stage_sort(d, sf, n, dsrc, ddst, dts); }
-  { Scope t(ctx, KC_PLACE, sf); launch_place(d, sf, n); }
   if (ev) hipEventRecord(ev[1], s);
   if (c.d_mem) { Scope t(ctx, KC_MEMORY, sf); launch_memory_update(d, sf, dsrc, ddst, dts, def); }
   if (ev) hipEventRecord(ev[2], s);

@@ -264,6 +264,19 @@ __device__ inline uint32_t* list_base(const Dev& d, uint32_t list) {
   return d.A;
 }
 
+// Last step of a batch's compaction, by one thread: list sizes and running totals.
+__device__ inline void finish_batch(const Dev& d, const uint32_t (&total)[STGN_MAX_LAYERS + 1]) {
+  Ctrl* c = d.ctrl;
+  BatchCtl* bc = d.bc;
+  bc->nA = total[0];
+  uint32_t seen = 0;
+  for (uint32_t l = 0; l < d.layers; ++l) bc->nR[l] = d.R[l] != d.A ? total[++seen] : total[0];
+  c->tot_affected += total[0];
+  c->tot_direct += bc->nD;
+  bc->scanned = stripes_sum_thread(d, kScannedCounter);
+  c->tot_scanned += bc->scanned;
+}
+
 __global__ __launch_bounds__(256) void compact_count_kernel(Dev d, uint32_t last_value) {
   __shared__ uint32_t s[256];
   const uint32_t v0 = blockIdx.x * kFlagsPerBlock + threadIdx.x * kFlagsPerThread;
@@ -307,17 +320,7 @@ __global__ __launch_bounds__(256) void compact_write_kernel(Dev d) {
     total[list] = before + block_total;
   }
   if (m.x | m.y | m.z | m.w) *reinterpret_cast<uint4*>(d.mark + v0) = make_uint4(0u, 0u, 0u, 0u);   // ready for the next batch
-  if (blockIdx.x == gridDim.x - 1 && t == 0) {
-    Ctrl* c = d.ctrl;
-    BatchCtl* bc = d.bc;
-    bc->nA = total[0];
-    uint32_t seen = 0;
-    for (uint32_t l = 0; l < d.layers; ++l) bc->nR[l] = d.R[l] != d.A ? total[++seen] : total[0];
-    c->tot_affected += total[0];
-    c->tot_direct += bc->nD;
-    bc->scanned = stripes_sum_thread(d, kScannedCounter);
-    c->tot_scanned += bc->scanned;
-  }
+  if (blockIdx.x == gridDim.x - 1 && t == 0) finish_batch(d, total);
 }
 
 // Count and write in one launch, for flag arrays of at most kSmallBlocks blocks: a workgroup counts
@@ -337,11 +340,21 @@ __global__ __launch_bounds__(256) void compact_small_kernel(Dev d, uint32_t last
     thr[list] = list < nl ? list_threshold(d, list) : 0u;
     part[list] = 0u; total[list] = 0u;
   }
+  // statistics: nodes first reached by hop h carry the flag h + 2; the last workgroup has seen every block
+  uint32_t eq[STGN_MAX_LAYERS + 1];
+#pragma unroll
+  for (uint32_t i = 0; i <= STGN_MAX_LAYERS; ++i) eq[i] = 0u;
+  const bool last_block = blockIdx.x == gridDim.x - 1;
   for (uint32_t b = 0; b < blockIdx.x; ++b) {
     const uint4 pm = *reinterpret_cast<const uint4*>(d.mark + b * kFlagsPerBlock + t * kFlagsPerThread);
 #pragma unroll
     for (uint32_t list = 0; list <= STGN_MAX_LAYERS; ++list)
       if (list < nl) part[list] += (uint32_t)__popc(bytes_upto(pm, thr[list]));
+    if (last_block) {
+#pragma unroll
+      for (uint32_t i = 0; i <= STGN_MAX_LAYERS; ++i)
+        if (i + 2u <= last_value) eq[i] += bytes_equal(pm, i + 2u);
+    }
   }
   uint4 m = make_uint4(0u, 0u, 0u, 0u);
   if (v0 < d.N) m = *reinterpret_cast<const uint4*>(d.mark + v0);     // the flag array is padded to whole blocks
@@ -361,21 +374,20 @@ __global__ __launch_bounds__(256) void compact_small_kernel(Dev d, uint32_t last
       total[list] = before + block_total;
     }
   }
-  // statistics: nodes first reached by hop h carry the flag h + 2
-  for (uint32_t value = 2; value <= last_value; ++value) {
-    const uint32_t reached = block_scan_256(bytes_equal(m, value), s, &excl);
-    if (t == 0 && reached) atomicAdd(&d.bc->n_front[value - 1u], reached);
-  }
-  if (blockIdx.x == gridDim.x - 1 && t == 0) {
-    Ctrl* c = d.ctrl;
-    BatchCtl* bc = d.bc;
-    bc->nA = total[0];
-    uint32_t seen = 0;
-    for (uint32_t l = 0; l < d.layers; ++l) bc->nR[l] = d.R[l] != d.A ? total[++seen] : total[0];
-    c->tot_affected += total[0];
-    c->tot_direct += bc->nD;
-    bc->scanned = stripes_sum_thread(d, kScannedCounter);
-    c->tot_scanned += bc->scanned;
+  if (last_block) {                                                    // uniform
+    uint32_t reached[STGN_MAX_LAYERS + 1];
+#pragma unroll
+    for (uint32_t i = 0; i <= STGN_MAX_LAYERS; ++i) {
+      reached[i] = 0u;
+      if (i + 2u <= last_value) reached[i] = block_scan_256(eq[i] + bytes_equal(m, i + 2u), s, &excl);
+    }
+    if (t == 0) {
+      BatchCtl* bc = d.bc;
+#pragma unroll
+      for (uint32_t i = 0; i <= STGN_MAX_LAYERS; ++i)
+        if (i + 2u <= last_value) bc->n_front[i + 1u] = reached[i];
+      finish_batch(d, total);
+    }
   }
   // the next batch's flags
   reinterpret_cast<uint4*>(d.mark_other)[blockIdx.x * (kFlagsPerBlock / 16u) + t] = make_uint4(0u, 0u, 0u, 0u);

@@ -49,12 +49,54 @@ __device__ inline uint32_t blocks_for(uint32_t x) {
 }
 
 // One workgroup.  keys: (node << 32 | slot), slot = 2*i (source side) or 2*i + 1 (destination).
+// Second half of the staging, the part that depends on the degrees the previous batch's apply step
+// left behind (the first half only looks at the batch itself): position of every endpoint slot in its
+// node's adjacency log, the endpoints' new degrees, the adjacency blocks they need (allocated in
+// endpoint order, so the placement is deterministic) and the number of adjacency entries the
+// endpoints own, which the first propagation hop plans with.  Called by the whole workgroup once the
+// sorted lists are visible to it; returns (to thread 0, through *units_total) the pool units taken.
+__device__ inline void place_rows(const Dev& d, uint32_t n, uint32_t nD, uint32_t* s_buf, uint32_t* units_total) {
+  const Ctrl* c = d.ctrl;
+  const uint32_t t = threadIdx.x, nth = blockDim.x;
+  const uint32_t m = 2 * n;
+  for (uint32_t i = t; i < m; i += nth) {
+    const uint32_t slot = d.slot_sorted[i];
+    const uint32_t di = d.slot_d[slot];
+    d.slot_pos[slot] = d.deg[d.D[di]] + (i - d.seg_start[di]);
+  }
+  const uint32_t eptd = (nD + nth - 1) / nth;     // contiguous endpoints per thread
+  const uint32_t dlo = min(t * eptd, nD), dhi = min(dlo + eptd, nD);
+  uint32_t units = 0;
+  unsigned long long fdeg = 0;              // adjacency entries the endpoints own after this batch
+  for (uint32_t x = dlo; x < dhi; ++x) {
+    const uint32_t dp = d.deg[d.D[x]], dn = dp + (d.seg_start[x + 1] - d.seg_start[x]);
+    d.deg_new[x] = dn;
+    fdeg += dn;
+    units += (1u << blocks_for(dn)) - (1u << blocks_for(dp));
+  }
+  const uint32_t uexcl = block_excl_scan(units, s_buf, units_total);
+  {
+    uint64_t base = c->pool_units + uexcl;
+    for (uint32_t x = dlo; x < dhi; ++x) {
+      const uint32_t node = d.D[x];
+      const uint32_t b0 = blocks_for(d.deg[node]), b1 = blocks_for(d.deg_new[x]);
+      for (uint32_t b = b0; b < b1; ++b) {
+        d.blk[(size_t)node * d.maxb + b] = (uint32_t)base;
+        base += 1u << b;
+      }
+    }
+  }
+  for (int off = 32; off > 0; off >>= 1) fdeg += __shfl_xor(fdeg, off);
+  if ((t & 63) == 0 && fdeg) atomicAdd(stripe(d, 0, t >> 6), fdeg);
+  __syncthreads();                          // every thread has read pool_units
+}
+
 __global__ __launch_bounds__(kSortThreads) void stage_sort_kernel(Dev d, uint32_t n, const uint32_t* __restrict__ src,
                                                                   const uint32_t* __restrict__ dst,
                                                                   const double* __restrict__ ts, uint32_t P) {
   extern __shared__ uint64_t keys[];
   __shared__ uint32_t s_buf[kSortThreads / 64];
-  __shared__ uint32_t s_err, s_nD;
+  __shared__ uint32_t s_err, s_nD, s_units;
   const uint32_t t = threadIdx.x;
   Ctrl* c = d.ctrl;
   BatchCtl* bc = d.bc;
@@ -155,6 +197,9 @@ __global__ __launch_bounds__(kSortThreads) void stage_sort_kernel(Dev d, uint32_
     }
     if (t == 0) d.seg_start[nD] = m;
   }
+  __threadfence_block();
+  __syncthreads();                          // the sorted lists are visible to the whole workgroup
+  place_rows(d, n, nD, s_buf, &s_units);
   if (t == 0) {
     bc->skip = 0;
     c->batch_seq += 1;
@@ -166,54 +211,9 @@ __global__ __launch_bounds__(kSortThreads) void stage_sort_kernel(Dev d, uint32_
     bc->n_front[0] = nD;
     bc->E_base = c->E;
     c->E += n;
+    c->pool_units += s_units;
     if (n) c->t_stream = ts[n - 1];
   }
-}
-
-// Second half of the staging, the part that depends on the degrees the previous batch's apply step
-// left behind (the first half only looks at the batch itself and may run a batch ahead): position
-// of every endpoint slot in its node's adjacency log, the endpoints' new degrees, the adjacency
-// blocks they need (allocated in endpoint order, so the placement is deterministic) and the number
-// of adjacency entries the endpoints own, which the first propagation hop plans with.
-__global__ __launch_bounds__(kSortThreads) void place_kernel(Dev d) {
-  __shared__ uint32_t s_buf[kSortThreads / 64];
-  __shared__ uint32_t s_units;
-  Ctrl* c = d.ctrl;
-  BatchCtl* bc = d.bc;
-  if (bc->skip) return;
-  const uint32_t t = threadIdx.x, nth = blockDim.x;
-  const uint32_t m = 2 * bc->n_edges, nD = bc->nD;
-  for (uint32_t i = t; i < m; i += nth) {
-    const uint32_t slot = d.slot_sorted[i];
-    const uint32_t di = d.slot_d[slot];
-    d.slot_pos[slot] = d.deg[d.D[di]] + (i - d.seg_start[di]);
-  }
-  const uint32_t eptd = (nD + nth - 1) / nth;     // contiguous endpoints per thread
-  const uint32_t dlo = min(t * eptd, nD), dhi = min(dlo + eptd, nD);
-  uint32_t units = 0;
-  unsigned long long fdeg = 0;              // adjacency entries the endpoints own after this batch
-  for (uint32_t x = dlo; x < dhi; ++x) {
-    const uint32_t dp = d.deg[d.D[x]], dn = dp + (d.seg_start[x + 1] - d.seg_start[x]);
-    d.deg_new[x] = dn;
-    fdeg += dn;
-    units += (1u << blocks_for(dn)) - (1u << blocks_for(dp));
-  }
-  const uint32_t uexcl = block_excl_scan(units, s_buf, &s_units);
-  {
-    uint64_t base = c->pool_units + uexcl;
-    for (uint32_t x = dlo; x < dhi; ++x) {
-      const uint32_t node = d.D[x];
-      const uint32_t b0 = blocks_for(d.deg[node]), b1 = blocks_for(d.deg_new[x]);
-      for (uint32_t b = b0; b < b1; ++b) {
-        d.blk[(size_t)node * d.maxb + b] = (uint32_t)base;
-        base += 1u << b;
-      }
-    }
-  }
-  for (int off = 32; off > 0; off >>= 1) fdeg += __shfl_xor(fdeg, off);
-  if ((t & 63) == 0 && fdeg) atomicAdd(stripe(d, 0, t >> 6), fdeg);
-  __syncthreads();                          // every thread has read pool_units
-  if (t == 0) c->pool_units += s_units;
 }
 
 __device__ inline uint64_t log_addr(const Dev& d, uint32_t node, uint32_t pos) {
@@ -400,12 +400,6 @@ void launch_stage_sort(const Dev& d, hipStream_t s, uint32_t n, const uint32_t* 
   uint32_t threads = P / 2;
   threads = threads < 256 ? 256 : threads > (uint32_t)kSortThreads ? (uint32_t)kSortThreads : threads;
   hipLaunchKernelGGL(stage_sort_kernel, dim3(1), dim3(threads), P * sizeof(uint64_t), s, d, n, src, dst, ts, P);
-}
-
-void launch_place(const Dev& d, hipStream_t s, uint32_t n) {
-  uint32_t threads = (2 * n + 63u) & ~63u;     // one endpoint slot per thread where the batch allows
-  threads = threads < 64 ? 64 : threads > (uint32_t)kSortThreads ? (uint32_t)kSortThreads : threads;
-  hipLaunchKernelGGL(place_kernel, dim3(1), dim3(threads), 0, s, d);
 }
 
 void launch_apply(const Dev& d, hipStream_t s, const uint32_t* src, const uint32_t* dst, const double* ts,

@@ -205,12 +205,11 @@ __device__ inline unsigned long long stripes_sum_thread(const Dev& d, uint32_t c
 
 // Kernel classes for the optional event timing
 enum KernelClass { KC_SORT = 0, KC_MEMORY, KC_APPLY, KC_PLAN, KC_EXPAND, KC_COMPACT, KC_LAYER,
-                   KC_GATHER, KC_NOOP, KC_PROJECT, KC_PREDICT, KC_PLACE, KC_COUNT };
+                   KC_GATHER, KC_NOOP, KC_PROJECT, KC_PREDICT, KC_COUNT };
 
 // ---- launch wrappers (one per kernel family), defined in the .hip files ----
 void launch_stage_sort(const Dev& d, hipStream_t s, uint32_t n, const uint32_t* src, const uint32_t* dst,
                        const double* ts);
-void launch_place(const Dev& d, hipStream_t s, uint32_t n);
 void launch_memory_update(const Dev& d, hipStream_t s, const uint32_t* src, const uint32_t* dst, const double* ts,
                           const float* ef);
 void launch_apply(const Dev& d, hipStream_t s, const uint32_t* src, const uint32_t* dst, const double* ts,
