@@ -135,6 +135,32 @@ def test_layers_recompute_only_rows_whose_inputs_changed(binding, d_mem, d_node)
     g.close()
 
 
+@pytest.mark.parametrize("num_nodes", [61000, 65536, 65537, 70000])
+def test_compaction_on_both_sides_of_the_one_launch_limit(binding, num_nodes):
+    """Flag arrays of at most 16 blocks of 4096 nodes are compacted in one launch (every workgroup
+    counts the blocks before its own, the flags are held twice), larger ones in two; the affected
+    sets, the per-layer lists (through the embeddings) and the frontier statistics must come out
+    the same on both sides of the limit, and through many batches (the flag arrays alternate)."""
+    w = tiny_workload(num_nodes=num_nodes, num_edges=6000, batch=300, zipf_s=0.6, k=3, layers=2)
+    st = synth.EdgeStream(w)
+    W = synth.make_weights(w)
+    o = orc.Oracle.from_workload(w, W, None)
+    g = binding.StreamTGN.from_workload(w, W, None)
+    for b in range(w.num_batches):
+        s, d, t, ef = st.batch(b)
+        rc, D, A = o.ingest(s, d, t, ef)
+        assert rc == 0
+        stats = g.ingest_batch(s, d, t, ef, stats=True)
+        assert stats["n_direct"] == len(D)
+        assert np.array_equal(g.get_affected(), A), f"batch {b}: affected set differs"
+        assert sum(stats["frontier"][: w.layers + 1]) == len(A), f"batch {b}: frontier sizes {stats['frontier']}"
+    sample = np.unique(np.concatenate([A[:: max(1, len(A) // 400)], np.arange(0, num_nodes, 997, dtype=np.uint32),
+                                       np.array([num_nodes - 1], dtype=np.uint32)])).astype(np.uint32)
+    for l in range(1, w.layers + 1):
+        check_rows(g.get_embeddings(sample, layer=l), o.embed_nodes(sample, layer=l), f"layer {l}")
+    g.close()
+
+
 def test_push_and_pull_hops_give_the_same_affected_set(binding):
     """The expansion pushes along the frontier's logs while the frontier owns few adjacency entries
     and pulls through the clean nodes' rings once it owns more than half the node count; the flags
