@@ -326,8 +326,8 @@ __global__ __launch_bounds__(256) void compact_write_kernel(Dev d) {
 // Count and write in one launch, for flag arrays of at most kSmallBlocks blocks: a workgroup counts
 // the flags of the blocks before its own instead of waiting for their sums (a few KiB of reads that
 // hit L2), so no workgroup depends on another.  The batch's flags stay as they are (other workgroups
-// may still be counting them); each workgroup clears its block of the other parity's array, which
-// the next batch uses and nobody reads now.
+// may still be counting them): small flag arrays are held twice, by batch parity, and the next
+// batch's apply step clears this one.
 constexpr uint32_t kSmallBlocks = 16;
 __global__ __launch_bounds__(256) void compact_small_kernel(Dev d, uint32_t last_value) {
   __shared__ uint32_t s[256];
@@ -389,8 +389,6 @@ __global__ __launch_bounds__(256) void compact_small_kernel(Dev d, uint32_t last
       finish_batch(d, total);
     }
   }
-  // the next batch's flags
-  reinterpret_cast<uint4*>(d.mark_other)[blockIdx.x * (kFlagsPerBlock / 16u) + t] = make_uint4(0u, 0u, 0u, 0u);
 }
 
 }  // namespace

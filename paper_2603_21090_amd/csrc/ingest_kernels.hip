@@ -64,6 +64,12 @@ __device__ inline void place_rows(const Dev& d, uint32_t n, uint32_t nD, uint32_
     const uint32_t di = d.slot_d[slot];
     d.slot_pos[slot] = d.deg[d.D[di]] + (i - d.seg_start[di]);
   }
+  // dirty seeds of the propagation.  With two flag arrays (small node counts) this batch's array is
+  // clean already -- the previous batch's apply step cleared it -- and seeding here lets the first hop
+  // run ahead of the apply step; a single array is still being compacted by the previous batch now,
+  // and the apply step seeds it.
+  if (d.mark_other != d.mark)
+    for (uint32_t x = t; x < nD; x += nth) d.mark[d.D[x]] = 1;
   const uint32_t eptd = (nD + nth - 1) / nth;     // contiguous endpoints per thread
   const uint32_t dlo = min(t * eptd, nD), dhi = min(dlo + eptd, nD);
   uint32_t units = 0;
@@ -316,6 +322,13 @@ __global__ __launch_bounds__(256) void apply_kernel(Dev d, const uint32_t* __res
                                                     uint32_t proj_blocks) {
   extern __shared__ __align__(16) float lds[];
   const BatchCtl* c = d.bc;
+  const uint32_t tid = (blockIdx.x - proj_blocks) * blockDim.x + threadIdx.x, nth = (gridDim.x - proj_blocks) * blockDim.x;
+  // Two flag arrays: the other one was last read by the previous batch's compaction and is seeded
+  // next by the next batch's staging, which waits for this kernel -- cleared here, skipped batch or not.
+  if (blockIdx.x >= proj_blocks && d.mark_other != d.mark) {
+    const uint32_t words = (uint32_t)(mark_bytes(d.N) / 16);
+    for (uint32_t x = tid; x < words; x += nth) reinterpret_cast<uint4*>(d.mark_other)[x] = make_uint4(0u, 0u, 0u, 0u);
+  }
   if (c->skip) return;
   if (blockIdx.x < proj_blocks) {
     project_rows(d, ef, 0u, blockIdx.x, proj_blocks, lds);
@@ -323,7 +336,6 @@ __global__ __launch_bounds__(256) void apply_kernel(Dev d, const uint32_t* __res
   }
   const uint32_t n = c->n_edges, nD = c->nD;
   const uint64_t E0 = c->E_base;
-  const uint32_t tid = (blockIdx.x - proj_blocks) * blockDim.x + threadIdx.x, nth = (gridDim.x - proj_blocks) * blockDim.x;
 
   // adjacency entries and ring slots, one thread per (edge, side)
   for (uint32_t s = tid; s < 2 * n; s += nth) {
@@ -347,7 +359,7 @@ __global__ __launch_bounds__(256) void apply_kernel(Dev d, const uint32_t* __res
     const uint32_t v = d.D[x];
     d.deg[v] = d.deg_new[x];
     d.t_last[v] = ts[d.last_slot[x] >> 1];
-    d.mark[v] = 1;
+    if (d.mark_other == d.mark) d.mark[v] = 1;
   }
   // in-place memory write-back (all reads of the old rows happened in the previous kernel)
   if (d.d_mem) {

@@ -146,6 +146,7 @@ struct Dev {
   uint64_t* stripes;                 // ... of the bound batch
   uint64_t* gathered_slots;          // [kStatSlots] ring entries gathered by the layer kernel, one slot per workgroup index
   uint64_t* items;                   // propagation work items (node, chunk)
+  uint64_t* items_set[2];            // ... held twice, by batch parity: a batch's first hop may run beside the previous batch's last
   uint64_t items_cap;
   uint32_t* blocksum;                // compaction partial sums
   uint32_t* A;                       // [N] affected set, ascending
@@ -183,6 +184,7 @@ inline Dev bind_batch(const Dev& base, int par) {
   d.bc = base.ctrl ? &base.ctrl->b[par] : nullptr;
   d.mark = base.mark_set[par]; d.mark_other = base.mark_set[par ^ 1];
   d.stripes = base.stripes_set[par];
+  d.items = base.items_set[par];
   return d;
 }
 
