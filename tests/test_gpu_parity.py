@@ -331,6 +331,48 @@ def test_back_to_back_device_batches_overlap_and_a_skipped_batch(binding):
     g.close(); g2.close()
 
 
+@pytest.mark.parametrize("num_nodes,batch,zipf_s,expect_pull", [(400, 100, 1.1, True), (6000, 60, 0.3, False)])
+def test_overlapped_pairs_give_the_oracles_affected_sets(binding, num_nodes, batch, zipf_s, expect_pull):
+    """Device batches go in in pairs without a synchronising call in between, so the second batch of
+    every pair runs its front part -- staging, the first propagation hop, the memory update -- beside
+    the first one's main part.  After each pair the second batch's affected set, frontier sizes and
+    direction bits are compared with the oracle.  The dense graph pulls, the sparse one pushes
+    (work items planned in the front part while the previous batch's last hop reads its own)."""
+    import torch
+    w = tiny_workload(num_nodes=num_nodes, num_edges=40 * batch, batch=batch, layers=2, k=4, d_mem=16, d_edge=6,
+                      d_time=8, d_emb=16, d_msg=16, zipf_s=zipf_s)
+    st = synth.EdgeStream(w)
+    W = synth.make_weights(w)
+    o = orc.Oracle.from_workload(w, W)
+    g = binding.StreamTGN.from_workload(w, W)
+
+    def dev(s, d, t, ef):
+        return (torch.from_numpy(s.astype(np.int32)).cuda(), torch.from_numpy(d.astype(np.int32)).cuda(),
+                torch.from_numpy(t).cuda(), torch.from_numpy(ef).cuda())
+
+    batches = [dev(*st.batch(b)) for b in range(w.num_batches)]
+    torch.cuda.synchronize()
+    for b in range(0, w.num_batches - 2, 2):
+        rc, D0, A0 = o.ingest(*st.batch(b))
+        rc1, D1, A1 = o.ingest(*st.batch(b + 1))
+        assert rc == 0 and rc1 == 0
+        assert g.ingest_batch(*batches[b], check=False) == 0
+        assert g.ingest_batch(*batches[b + 1], check=False) == 0
+        assert g.sync() == 0
+        assert np.array_equal(g.get_affected(), A1), f"batch {b + 1}: affected set differs"
+    # which direction the hops of this graph take (a polled batch reports it)
+    last = w.num_batches - 2                                          # the batch after the last pair
+    rc, D, A = o.ingest(*st.batch(last))
+    stats = g.ingest_batch(*batches[last], stats=True)
+    assert stats["n_affected"] == len(A)
+    assert (stats["pull_hops"] != 0) == expect_pull, stats
+    allnodes = np.arange(w.num_nodes, dtype=np.uint32)
+    ref = o.embed_all()
+    for l in range(1, w.layers + 1):
+        check_rows(g.get_embeddings(allnodes, layer=l), ref[l - 1], f"layer {l}")
+    g.close()
+
+
 def test_rows_outside_A_untouched_and_rebuild_is_bit_identical(binding):
     """Theorem 'Equivalence of Incremental Computation': cached rows outside the affected set are
     bit-identical before and after a batch; a full rebuild reproduces every cached row bit for bit
