@@ -618,22 +618,25 @@ int stgn_ingest_batch(stgn_ctx* ctx, uint32_t n, const uint32_t* src, const uint
   hipEvent_t* ev = stats ? ctx->stage_ev : nullptr;
   if (ev) hipEventRecord(ev[0], s);
   { Scope t(ctx, KC_SORT, sf); launch_stage_sort(d, sf, n, dsrc, ddst, dts); }
-  // With two flag arrays the staging kernel has seeded the dirty flags, and the first hop may run in
-  // the front part, ahead of the apply step: a node that is not an endpoint of the batch keeps its
-  // ring, degree and log through the apply step and endpoints are dirty from the start, so the hop
-  // sets the same flags before the apply step as after it.
-  // (one hop, and only beside at least two layer launches: with both hops of a two-layer model there, or
-  // with the only hop of a one-layer model, the front part no longer fits beside the previous batch's
-  // layers -- measured 117 instead of 110 us per batch, and 82 instead of 72 us)
-  const uint32_t first_main_hop = overlapped && compact_in_one(d) && c.layers >= 2 ? 1u : 0u;
+  if (ev) hipEventRecord(ev[1], s);
+  if (c.d_mem) { Scope t(ctx, KC_MEMORY, sf); launch_memory_update(d, sf, dsrc, ddst, dts, def); }
+  if (ev) hipEventRecord(ev[2], s);
+  // With two flag arrays the staging kernel has seeded the dirty flags, and the propagation hops may
+  // run in the front part, ahead of the apply step: a node that is not an endpoint of the batch keeps
+  // its ring, degree and log through the apply step and endpoints are dirty from the start, so a hop
+  // sets the same flags before the apply step as after it.  They follow the memory update: that
+  // kernel's few large workgroups need CUs of their own and find them while the previous batch's
+  // first layer launch (fewer rows than the last) leaves some free, whereas the hops' small
+  // workgroups fit beside the layer kernel's on any CU.  (Measured on C2, per batch: hops on the
+  // caller's stream 112 us; first hop in front of the memory update 110; behind it 105; both hops
+  // behind it 103; both in front of it 117.)  Only beside at least two layer launches: the single
+  // launch of a one-layer model is shorter than the front part (C1: 82 instead of 72 us).
+  const uint32_t first_main_hop = overlapped && compact_in_one(d) && c.layers >= 2 ? c.layers : 0u;
   for (uint32_t hop = 0; hop < first_main_hop; ++hop) {
     const bool planned = !ctx->pull_hint[hop];
     if (planned) { Scope t(ctx, KC_PLAN, sf); launch_plan(d, sf, hop); }
     { Scope t(ctx, KC_EXPAND, sf); launch_expand(d, sf, hop, planned); }
   }
-  if (ev) hipEventRecord(ev[1], s);
-  if (c.d_mem) { Scope t(ctx, KC_MEMORY, sf); launch_memory_update(d, sf, dsrc, ddst, dts, def); }
-  if (ev) hipEventRecord(ev[2], s);
   if (overlapped) {
     HIPCHK(ctx, hipEventRecord(ctx->ev_front, ctx->front));
     HIPCHK(ctx, hipStreamWaitEvent(s, ctx->ev_front, 0));
