@@ -37,10 +37,11 @@ struct stgn_ctx {
   // path; calls that ask for per-stage statistics, calls with host inputs, and all calls while per-kernel
   // timing is on, run everything on `stream`.
   hipStream_t front = nullptr;
-  hipEvent_t ev_apply[2] = {nullptr, nullptr}, ev_front = nullptr;   // ev_apply alternates with the batches
-  bool recorded[2] = {false, false};      // ev_apply of that parity has been recorded
-  int parity = 0;                   // staging block, scratch set, batch fields and compaction event of the next batch
-  int last_par = 0;                 // parity of the batch enqueued last
+  hipEvent_t ev_apply[kSets] = {}, ev_front = nullptr;   // ev_apply cycles with the batches' state sets
+  bool recorded[kSets] = {};        // ev_apply of that set has been recorded
+  int set = 0;                      // state set (scratch lists, batch fields, counters, work items, apply event) of the next batch
+  int parity = 0;                   // staging block and dirty-flag array of the next batch
+  int last_par = 0;                 // state set of the batch enqueued last
   bool idle = true;                 // nothing was enqueued since the library last synchronised `stream`
   bool have_predictor = false;      // stgn_set_predictor was called
   std::string err;
@@ -188,16 +189,16 @@ size_t layout(const stgn_config& c, char* base, Dev* d) {
     s.slot_sorted = b.take<uint32_t>(B2);
     s.mem_new = b.take<float>((size_t)B2 * c.d_mem);
   }
-  *d = bind_batch(*d, 0);
+  *d = bind_batch(*d, 0, 0);
   d->mark_set[0] = b.take<uint8_t>(mark_bytes(N));
   d->mark_set[1] = compact_in_one(*d) ? b.take<uint8_t>(mark_bytes(N)) : d->mark_set[0];
   d->mark = d->mark_set[0];
   d->mark_other = d->mark_set[1];
-  for (int i = 0; i < 2; ++i) d->stripes_set[i] = b.take<uint64_t>((size_t)kStripedCounters * kStripes * kStripeWords);
+  for (int i = 0; i < kSets; ++i) d->stripes_set[i] = b.take<uint64_t>((size_t)kStripedCounters * kStripes * kStripeWords);
   d->stripes = d->stripes_set[0];
   d->gathered_slots = b.take<uint64_t>(kStatSlots);
   d->items_cap = (uint64_t)N + 2 * c.max_edges / kLogChunk + 1024;
-  for (int i = 0; i < 2; ++i) d->items_set[i] = b.take<uint64_t>(d->items_cap);
+  for (int i = 0; i < kSets; ++i) d->items_set[i] = b.take<uint64_t>(d->items_cap);
   d->items = d->items_set[0];
   d->blocksum = b.take<uint32_t>((size_t)(c.layers + 1) * (mark_bytes(N) / kMarkPad + 2));
   d->A = b.take<uint32_t>(N);
@@ -499,6 +500,7 @@ int stgn_create(const stgn_config* cfg, const stgn_weights* w, const float* node
   if (hipStreamCreateWithFlags(&ctx->front, hipStreamNonBlocking) != hipSuccess ||
       hipEventCreateWithFlags(&ctx->ev_apply[0], hipEventDisableTiming) != hipSuccess ||
       hipEventCreateWithFlags(&ctx->ev_apply[1], hipEventDisableTiming) != hipSuccess ||
+      hipEventCreateWithFlags(&ctx->ev_apply[2], hipEventDisableTiming) != hipSuccess ||
       hipEventCreateWithFlags(&ctx->ev_front, hipEventDisableTiming) != hipSuccess) {
     ctx->err = "second stream or its events could not be created";
     return bail(STGN_E_DEVICE);
@@ -556,8 +558,10 @@ int stgn_ingest_batch(stgn_ctx* ctx, uint32_t n, const uint32_t* src, const uint
                       const float* efeat, int inputs_on_device, stgn_batch_stats* stats) {
   if (!ctx) return STGN_E_INVALID_ARG;
   const stgn_config& c = ctx->cfg;
-  const int par = ctx->parity;                 // the batch's staging block, scratch set and batch fields
-  const Dev d = bind_batch(ctx->d, par);
+  const int par = ctx->parity;                 // the batch's staging block and dirty-flag array
+  const int set = ctx->set;                    // ... and its state set
+  const int prev = (set + kSets - 1) % kSets, prev2 = (set + kSets - 2) % kSets;   // the sets of the two batches before
+  const Dev d = bind_batch(ctx->d, set, par);
   if (n > c.max_batch) return fail(ctx, STGN_E_BATCH_TOO_LARGE, "batch larger than max_batch");
   if (n && (!src || !dst || !ts || (c.d_edge && !efeat))) return fail(ctx, STGN_E_INVALID_ARG, "NULL batch array");
   if (ctx->host_edges + n > c.max_edges) return fail(ctx, STGN_E_EDGE_CAPACITY, "max_edges exceeded");
@@ -611,13 +615,20 @@ int stgn_ingest_batch(stgn_ctx* ctx, uint32_t n, const uint32_t* src, const uint
   }
   ctx->host_edges += n;
   ctx->parity ^= 1;                            // from here on the batch is enqueued
-  ctx->last_par = par;
+  ctx->set = (set + 1) % kSets;
+  ctx->last_par = set;
   hipStream_t s = ctx->stream;
-  // degrees and memory as the previous apply step left them; the scratch set of this parity is free by then
-  if (overlapped && ctx->recorded[par ^ 1]) HIPCHK(ctx, hipStreamWaitEvent(sf, ctx->ev_apply[par ^ 1], 0));
+  // The staging kernel looks only at the batch and the running edge count and writes the batch's own
+  // state set, last used three batches ago: it is ordered behind the apply step of the batch before
+  // the previous one (whose stream position is behind everything that used the set) and so may run
+  // beside the previous batch's main part, a batch ahead of the rest of the front part.
+  if (overlapped && ctx->recorded[prev2]) HIPCHK(ctx, hipStreamWaitEvent(sf, ctx->ev_apply[prev2], 0));
   hipEvent_t* ev = stats ? ctx->stage_ev : nullptr;
   if (ev) hipEventRecord(ev[0], s);
   { Scope t(ctx, KC_SORT, sf); launch_stage_sort(d, sf, n, dsrc, ddst, dts); }
+  // degrees and memory as the previous apply step left them
+  if (overlapped && ctx->recorded[prev]) HIPCHK(ctx, hipStreamWaitEvent(sf, ctx->ev_apply[prev], 0));
+  { Scope t(ctx, KC_SORT, sf); launch_place(d, sf, n); }
   if (ev) hipEventRecord(ev[1], s);
   if (c.d_mem) { Scope t(ctx, KC_MEMORY, sf); launch_memory_update(d, sf, dsrc, ddst, dts, def); }
   if (ev) hipEventRecord(ev[2], s);
@@ -642,8 +653,8 @@ int stgn_ingest_batch(stgn_ctx* ctx, uint32_t n, const uint32_t* src, const uint
     HIPCHK(ctx, hipStreamWaitEvent(s, ctx->ev_front, 0));
   }
   { Scope t(ctx, KC_APPLY); launch_apply(d, s, dsrc, ddst, dts, def); }
-  HIPCHK(ctx, hipEventRecord(ctx->ev_apply[par], s));
-  ctx->recorded[par] = true;
+  HIPCHK(ctx, hipEventRecord(ctx->ev_apply[set], s));
+  ctx->recorded[set] = true;
   if (ev) hipEventRecord(ev[3], s);
   for (uint32_t hop = first_main_hop; hop < c.layers; ++hop) {
     const bool planned = !ctx->pull_hint[hop];
@@ -660,7 +671,7 @@ int stgn_ingest_batch(stgn_ctx* ctx, uint32_t n, const uint32_t* src, const uint
 
   if (stats) {
     int rc = sync_and_poll(ctx);
-    const BatchCtl& h = ctx->ctrl_host->b[par];
+    const BatchCtl& h = ctx->ctrl_host->b[set];
     memset(stats, 0, sizeof *stats);
     stats->n_edges = h.n_edges;
     stats->n_direct = h.nD;

@@ -97,12 +97,21 @@ __device__ inline void place_rows(const Dev& d, uint32_t n, uint32_t nD, uint32_
   __syncthreads();                          // every thread has read pool_units
 }
 
+__global__ __launch_bounds__(kSortThreads) void place_kernel(Dev d) {
+  __shared__ uint32_t s_buf[kSortThreads / 64];
+  __shared__ uint32_t s_units;
+  const BatchCtl* bc = d.bc;
+  if (bc->skip) return;
+  place_rows(d, bc->n_edges, bc->nD, s_buf, &s_units);
+  if (threadIdx.x == 0) d.ctrl->pool_units += s_units;
+}
+
 __global__ __launch_bounds__(kSortThreads) void stage_sort_kernel(Dev d, uint32_t n, const uint32_t* __restrict__ src,
                                                                   const uint32_t* __restrict__ dst,
                                                                   const double* __restrict__ ts, uint32_t P) {
   extern __shared__ uint64_t keys[];
   __shared__ uint32_t s_buf[kSortThreads / 64];
-  __shared__ uint32_t s_err, s_nD, s_units;
+  __shared__ uint32_t s_err, s_nD;
   const uint32_t t = threadIdx.x;
   Ctrl* c = d.ctrl;
   BatchCtl* bc = d.bc;
@@ -203,9 +212,6 @@ __global__ __launch_bounds__(kSortThreads) void stage_sort_kernel(Dev d, uint32_
     }
     if (t == 0) d.seg_start[nD] = m;
   }
-  __threadfence_block();
-  __syncthreads();                          // the sorted lists are visible to the whole workgroup
-  place_rows(d, n, nD, s_buf, &s_units);
   if (t == 0) {
     bc->skip = 0;
     c->batch_seq += 1;
@@ -217,7 +223,6 @@ __global__ __launch_bounds__(kSortThreads) void stage_sort_kernel(Dev d, uint32_
     bc->n_front[0] = nD;
     bc->E_base = c->E;
     c->E += n;
-    c->pool_units += s_units;
     if (n) c->t_stream = ts[n - 1];
   }
 }
@@ -394,7 +399,8 @@ __global__ void init_state_kernel(Dev d) {
   for (size_t x = tid; x < nw; x += nth) { reinterpret_cast<uint32_t*>(d.mark_set[0])[x] = 0; reinterpret_cast<uint32_t*>(d.mark_set[1])[x] = 0; }
   const size_t nr = (size_t)d.N * d.k;
   for (size_t x = tid; x < nr; x += nth) { RingEntry r; r.nbr = 0; r.eid = 0; r.t = 0.0; d.ring[x] = r; d.ring_nbr[x] = 0; }
-  for (size_t x = tid; x < (size_t)kStripedCounters * kStripes * kStripeWords; x += nth) { d.stripes_set[0][x] = 0; d.stripes_set[1][x] = 0; }
+  for (size_t x = tid; x < (size_t)kStripedCounters * kStripes * kStripeWords; x += nth)
+    for (int i = 0; i < kSets; ++i) d.stripes_set[i][x] = 0;
   for (size_t x = tid; x < kStatSlots; x += nth) d.gathered_slots[x] = 0;
   if (tid == 0) {
     Ctrl z = {};
@@ -412,6 +418,12 @@ void launch_stage_sort(const Dev& d, hipStream_t s, uint32_t n, const uint32_t* 
   uint32_t threads = P / 2;
   threads = threads < 256 ? 256 : threads > (uint32_t)kSortThreads ? (uint32_t)kSortThreads : threads;
   hipLaunchKernelGGL(stage_sort_kernel, dim3(1), dim3(threads), P * sizeof(uint64_t), s, d, n, src, dst, ts, P);
+}
+
+void launch_place(const Dev& d, hipStream_t s, uint32_t n) {
+  uint32_t threads = (2 * n + 63u) & ~63u;     // one endpoint slot per thread where the batch allows
+  threads = threads < 64 ? 64 : threads > (uint32_t)kSortThreads ? (uint32_t)kSortThreads : threads;
+  hipLaunchKernelGGL(place_kernel, dim3(1), dim3(threads), 0, s, d);
 }
 
 void launch_apply(const Dev& d, hipStream_t s, const uint32_t* src, const uint32_t* dst, const double* ts,

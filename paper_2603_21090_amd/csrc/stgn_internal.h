@@ -25,6 +25,11 @@ struct __align__(16) RingEntry {
 // can be enqueued without reading anything back.  The fields of one batch are kept twice and the
 // batches alternate between the copies (as they do between two sets of the per-batch scratch lists),
 // so that the next batch can be staged while kernels of the current one still read theirs.
+// Per-batch state (batch fields of the control block, sorted endpoint lists, striped counters, work
+// items) is held kSets times: a batch's staging kernel may run while the previous batch's main part
+// is still at work and the one before that has only just finished.
+constexpr int kSets = 3;
+
 struct BatchCtl {
   uint32_t skip;                 // 1: the batch failed validation, all its kernels exit
   uint32_t n_edges;              // edges of the batch
@@ -60,7 +65,7 @@ struct Ctrl {
   double   t_stream;             // last ingested timestamp
   uint64_t tot_direct, tot_affected, tot_scanned;
   uint64_t tot_rows;             // rows the attention kernels recomputed (all layers)
-  BatchCtl b[2];
+  BatchCtl b[kSets];
 };
 
 // Row-table descriptor: row v starts at base + v * ld (floats)
@@ -124,7 +129,7 @@ struct Dev {
   struct Scratch {
     uint32_t *D, *seg_start, *last_slot, *deg_new, *slot_pos, *slot_d, *slot_sorted;
     float* mem_new;
-  } scr[2];
+  } scr[kSets];
   Ctrl*    ctrl;
   BatchCtl* bc;                      // the current batch's copy of the batch fields (set per batch by the host)
   char*    stage[2];                 // staging blocks for host inputs (batches alternate)
@@ -142,11 +147,11 @@ struct Dev {
   // next batch uses.  Large arrays are one array (both entries equal), cleared by the compaction's second launch.
   uint8_t* mark_set[2];
   uint8_t* mark_other;               // the array of the other parity (bound batch)
-  uint64_t* stripes_set[2];          // [kStripedCounters][kStripes] lines of kStripeWords words, per batch parity
+  uint64_t* stripes_set[kSets];          // [kStripedCounters][kStripes] lines of kStripeWords words, per batch parity
   uint64_t* stripes;                 // ... of the bound batch
   uint64_t* gathered_slots;          // [kStatSlots] ring entries gathered by the layer kernel, one slot per workgroup index
   uint64_t* items;                   // propagation work items (node, chunk)
-  uint64_t* items_set[2];            // ... held twice, by batch parity: a batch's first hop may run beside the previous batch's last
+  uint64_t* items_set[kSets];            // ... held twice, by batch parity: a batch's first hop may run beside the previous batch's last
   uint64_t items_cap;
   uint32_t* blocksum;                // compaction partial sums
   uint32_t* A;                       // [N] affected set, ascending
@@ -176,15 +181,16 @@ struct Dev {
 inline __host__ __device__ uint32_t round_up(uint32_t x, uint32_t m) { return (x + m - 1) / m * m; }
 
 // the device description a batch of the given parity is enqueued with
-inline Dev bind_batch(const Dev& base, int par) {
+// set: which copy of the per-batch state (0 .. kSets - 1); flag_par: which dirty-flag array (0 / 1)
+inline Dev bind_batch(const Dev& base, int set, int flag_par) {
   Dev d = base;
-  const Dev::Scratch& s = base.scr[par];
+  const Dev::Scratch& s = base.scr[set];
   d.D = s.D; d.seg_start = s.seg_start; d.last_slot = s.last_slot; d.deg_new = s.deg_new;
   d.slot_pos = s.slot_pos; d.slot_d = s.slot_d; d.slot_sorted = s.slot_sorted; d.mem_new = s.mem_new;
-  d.bc = base.ctrl ? &base.ctrl->b[par] : nullptr;
-  d.mark = base.mark_set[par]; d.mark_other = base.mark_set[par ^ 1];
-  d.stripes = base.stripes_set[par];
-  d.items = base.items_set[par];
+  d.bc = base.ctrl ? &base.ctrl->b[set] : nullptr;
+  d.mark = base.mark_set[flag_par]; d.mark_other = base.mark_set[flag_par ^ 1];
+  d.stripes = base.stripes_set[set];
+  d.items = base.items_set[set];
   return d;
 }
 
@@ -212,6 +218,7 @@ enum KernelClass { KC_SORT = 0, KC_MEMORY, KC_APPLY, KC_PLAN, KC_EXPAND, KC_COMP
 // ---- launch wrappers (one per kernel family), defined in the .hip files ----
 void launch_stage_sort(const Dev& d, hipStream_t s, uint32_t n, const uint32_t* src, const uint32_t* dst,
                        const double* ts);
+void launch_place(const Dev& d, hipStream_t s, uint32_t n);
 void launch_memory_update(const Dev& d, hipStream_t s, const uint32_t* src, const uint32_t* dst, const double* ts,
                           const float* ef);
 void launch_apply(const Dev& d, hipStream_t s, const uint32_t* src, const uint32_t* dst, const double* ts,
