@@ -39,6 +39,7 @@ struct stgn_ctx {
   hipStream_t front = nullptr;
   hipEvent_t ev_apply[kSets] = {}, ev_front = nullptr;   // ev_apply cycles with the batches' state sets
   bool recorded[kSets] = {};        // ev_apply of that set has been recorded
+  bool prev_on_front = false;       // the previous batch's front part ran on `front`
   int set = 0;                      // state set (scratch lists, batch fields, counters, work items, apply event) of the next batch
   int parity = 0;                   // staging block and dirty-flag array of the next batch
   int last_par = 0;                 // state set of the batch enqueued last
@@ -617,12 +618,16 @@ int stgn_ingest_batch(stgn_ctx* ctx, uint32_t n, const uint32_t* src, const uint
   ctx->parity ^= 1;                            // from here on the batch is enqueued
   ctx->set = (set + 1) % kSets;
   ctx->last_par = set;
+  const bool prev_on_front = ctx->prev_on_front;
+  ctx->prev_on_front = overlapped;
   hipStream_t s = ctx->stream;
   // The staging kernel looks only at the batch and the running edge count and writes the batch's own
   // state set, last used three batches ago: it is ordered behind the apply step of the batch before
   // the previous one (whose stream position is behind everything that used the set) and so may run
   // beside the previous batch's main part, a batch ahead of the rest of the front part.
-  if (overlapped && ctx->recorded[prev2]) HIPCHK(ctx, hipStreamWaitEvent(sf, ctx->ev_apply[prev2], 0));
+  // (when the previous batch's front part ran on `front` too, its own wait for that event already
+  // stands in front of this kernel in stream order)
+  if (overlapped && !prev_on_front && ctx->recorded[prev2]) HIPCHK(ctx, hipStreamWaitEvent(sf, ctx->ev_apply[prev2], 0));
   hipEvent_t* ev = stats ? ctx->stage_ev : nullptr;
   if (ev) hipEventRecord(ev[0], s);
   { Scope t(ctx, KC_SORT, sf); launch_stage_sort(d, sf, n, dsrc, ddst, dts); }
@@ -652,7 +657,9 @@ int stgn_ingest_batch(stgn_ctx* ctx, uint32_t n, const uint32_t* src, const uint
     HIPCHK(ctx, hipEventRecord(ctx->ev_front, ctx->front));
     HIPCHK(ctx, hipStreamWaitEvent(s, ctx->ev_front, 0));
   }
-  { Scope t(ctx, KC_APPLY); launch_apply(d, s, dsrc, ddst, dts, def); }
+  // the propagation is done: the compaction depends on the flags alone and shares the apply step's launch
+  const bool fused_compaction = first_main_hop != 0;
+  { Scope t(ctx, KC_APPLY); launch_apply(d, s, dsrc, ddst, dts, def, fused_compaction); }
   HIPCHK(ctx, hipEventRecord(ctx->ev_apply[set], s));
   ctx->recorded[set] = true;
   if (ev) hipEventRecord(ev[3], s);
@@ -661,8 +668,10 @@ int stgn_ingest_batch(stgn_ctx* ctx, uint32_t n, const uint32_t* src, const uint
     if (planned) { Scope t(ctx, KC_PLAN); launch_plan(d, s, hop); }
     { Scope t(ctx, KC_EXPAND); launch_expand(d, s, hop, planned); }
   }
-  { Scope t(ctx, KC_COMPACT); launch_compact(d, s, 0); }
-  if (!compact_in_one(d)) { Scope t(ctx, KC_COMPACT); launch_compact(d, s, 1); }
+  if (!fused_compaction) {
+    { Scope t(ctx, KC_COMPACT); launch_compact(d, s, 0); }
+    if (!compact_in_one(d)) { Scope t(ctx, KC_COMPACT); launch_compact(d, s, 1); }
+  }
   if (ev) hipEventRecord(ev[4], s);
   run_layers(ctx, d, false);
   if (ctx->timing) { Scope t(ctx, KC_NOOP); launch_noop(s); }   // event-pair overhead, for calibration

@@ -4,6 +4,7 @@
 // cache), 3.3.5 (adjacency append, in-place memory write-back).
 #include "stgn_internal.h"
 #include "mfma16.h"
+#include "compaction.h"
 
 namespace stgn {
 
@@ -319,15 +320,24 @@ __global__ __launch_bounds__(256) void project_nodes_kernel(Dev d) {
 }
 
 // The first `proj_blocks` workgroups compute the batch's cached key|value rows (project_rows: the
-// longer job, so it is dispatched first); the others append the batch to the graph state.  Neither
-// group reads what the other writes.
+// longer job, so it is dispatched first); the next `compact_blocks` compact the dirty flags when the
+// propagation has already run in the front part (one-launch compaction of small flag arrays: it
+// depends on the flags alone, not on the apply step); the others append the batch to the graph
+// state.  No group reads what another writes.
 __global__ __launch_bounds__(256) void apply_kernel(Dev d, const uint32_t* __restrict__ src,
                                                     const uint32_t* __restrict__ dst,
                                                     const double* __restrict__ ts, const float* __restrict__ ef,
-                                                    uint32_t proj_blocks) {
+                                                    uint32_t proj_blocks, uint32_t compact_blocks) {
   extern __shared__ __align__(16) float lds[];
+  __shared__ uint32_t s_scan[256];
   const BatchCtl* c = d.bc;
-  const uint32_t tid = (blockIdx.x - proj_blocks) * blockDim.x + threadIdx.x, nth = (gridDim.x - proj_blocks) * blockDim.x;
+  if (blockIdx.x >= proj_blocks && blockIdx.x < proj_blocks + compact_blocks) {
+    // (also for a batch that failed validation: its flags are all clear and its lists come out empty)
+    compact_small_block(d, d.layers + 1u, blockIdx.x - proj_blocks, compact_blocks, s_scan);
+    return;
+  }
+  const uint32_t first = proj_blocks + compact_blocks;      // first workgroup of the append group
+  const uint32_t tid = (blockIdx.x - first) * blockDim.x + threadIdx.x, nth = (gridDim.x - first) * blockDim.x;
   // Two flag arrays: the other one was last read by the previous batch's compaction and is seeded
   // next by the next batch's staging, which waits for this kernel -- cleared here, skipped batch or not.
   if (blockIdx.x >= proj_blocks && d.mark_other != d.mark) {
@@ -427,7 +437,7 @@ void launch_place(const Dev& d, hipStream_t s, uint32_t n) {
 }
 
 void launch_apply(const Dev& d, hipStream_t s, const uint32_t* src, const uint32_t* dst, const double* ts,
-                  const float* ef) {
+                  const float* ef, bool with_compaction) {
   // sized for the largest section (feature rows of a full batch), grid-stride inside
   const uint32_t work = d.max_batch * (d.efeat.ld > 2 ? d.efeat.ld : 2);
   uint32_t blocks = (work + 255) / 256;
@@ -437,8 +447,9 @@ void launch_apply(const Dev& d, hipStream_t s, const uint32_t* src, const uint32
   const uint32_t per = (d.max_batch + kProjRows - 1) / kProjRows;
   uint32_t pblocks = ((d.d_mem ? 2 * per : 0) + (d.d_edge ? d.layers * per : 0)) * d.ks;
   if (pblocks > 2048) pblocks = 2048;
-  hipLaunchKernelGGL(apply_kernel, dim3(blocks + pblocks), dim3(256), pblocks ? project_lds(d) : 0, s, d, src, dst, ts, ef,
-                     pblocks);
+  const uint32_t cblocks = with_compaction ? compact_blocks_of(d.N) : 0u;
+  hipLaunchKernelGGL(apply_kernel, dim3(blocks + pblocks + cblocks), dim3(256), pblocks ? project_lds(d) : 0, s, d, src, dst,
+                     ts, ef, pblocks, cblocks);
 }
 
 void launch_project_nodes(const Dev& d, hipStream_t s) {

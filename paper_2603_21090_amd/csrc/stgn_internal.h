@@ -222,7 +222,7 @@ void launch_place(const Dev& d, hipStream_t s, uint32_t n);
 void launch_memory_update(const Dev& d, hipStream_t s, const uint32_t* src, const uint32_t* dst, const double* ts,
                           const float* ef);
 void launch_apply(const Dev& d, hipStream_t s, const uint32_t* src, const uint32_t* dst, const double* ts,
-                  const float* ef);
+                  const float* ef, bool with_compaction);   // with_compaction: only for compact_in_one(d), after the propagation
 void launch_plan(const Dev& d, hipStream_t s, uint32_t hop);
 void launch_expand(const Dev& d, hipStream_t s, uint32_t hop, bool planned);
 void launch_compact(const Dev& d, hipStream_t s, int phase);
