@@ -26,16 +26,15 @@ struct stgn_ctx {
   stgn_config cfg;
   Dev d;
   hipStream_t stream = nullptr;
-  // A batch's front part (validation + sort, placement, memory update) can run on a second stream beside
-  // the previous batch's main part.  It reads the degrees and memory the previous apply step left and
-  // writes the batch's own scratch set and batch fields (both held twice, by batch parity; the set was
-  // last used by the batch before the previous one, whose propagation and compaction precede the previous
-  // apply step on `stream`): it waits for that apply step (ev_apply[], recorded on `stream`) and then runs
-  // beside the previous batch's propagation, compaction and attention layers, none of which writes what
-  // it reads or reads what it writes.  The batch's own apply step on `stream` waits for the front part
-  // (ev_front, recorded on `front`).  Only batches with device inputs that find `stream` busy take this
-  // path; calls that ask for per-stage statistics, calls with host inputs, and all calls while per-kernel
-  // timing is on, run everything on `stream`.
+  // A batch's front part (staging, placement, memory update and, for small flag arrays, the propagation
+  // hops) can run on a second stream beside the previous batch's main part.  The staging kernel needs only
+  // the batch and writes the batch's own state set (held kSets times): it runs a batch ahead.  The rest
+  // reads the degrees, memory, rings and logs the previous apply step left and waits for it (ev_apply[],
+  // recorded on `stream`); nothing in the previous batch's main part writes what the front part reads or
+  // reads what it writes.  The batch's own apply step on `stream` waits for the front part (ev_front,
+  // recorded on `front`).  Only batches with device inputs that find `stream` busy take this path; calls
+  // that ask for per-stage statistics, calls with host inputs, and all calls while per-kernel timing is
+  // on, run everything on `stream`.
   hipStream_t front = nullptr;
   hipEvent_t ev_apply[kSets] = {}, ev_front = nullptr;   // ev_apply cycles with the batches' state sets
   bool recorded[kSets] = {};        // ev_apply of that set has been recorded
