@@ -646,7 +646,8 @@ int stgn_ingest_batch(stgn_ctx* ctx, uint32_t n, const uint32_t* src, const uint
   // caller's stream 112 us; first hop in front of the memory update 110; behind it 105; both hops
   // behind it 103; both in front of it 117.)  Only beside at least two layer launches: the single
   // launch of a one-layer model is shorter than the front part (C1: 82 instead of 72 us).
-  const uint32_t first_main_hop = overlapped && compact_in_one(d) && c.layers >= 2 ? c.layers : 0u;
+  // (calls that ask for statistics keep the plain order, so that their stage times mean what they say)
+  const uint32_t first_main_hop = !stats && !ctx->timing && compact_in_one(d) && (c.layers >= 2 || !overlapped) ? c.layers : 0u;
   for (uint32_t hop = 0; hop < first_main_hop; ++hop) {
     const bool planned = !ctx->pull_hint[hop];
     if (planned) { Scope t(ctx, KC_PLAN, sf); launch_plan(d, sf, hop); }
