@@ -125,8 +125,8 @@ def main():
     W = int(0.70 * nb) if args.warmup is None else args.warmup
     K = int(0.15 * nb) if args.steps is None else args.steps
     rest = max(nb - W - K, 0)
-    LAT = min(rest * 8 // 15, 160) if args.latency_steps is None else args.latency_steps
-    HOST = min(rest * 2 // 15, 40) if args.host_steps is None else args.host_steps
+    LAT = min(rest * 6 // 15, 160) if args.latency_steps is None else args.latency_steps
+    HOST = min(rest * 4 // 15, 48) if args.host_steps is None else args.host_steps
     KER = min(rest - LAT - HOST, 100) if args.kernel_steps is None else args.kernel_steps
     if W + K + LAT + HOST + KER > nb or K <= 0:
         print(f"bench.py: warmup {W} + steps {K} + latency {LAT} + host {HOST} + kernel {KER} exceed the stream "
@@ -204,9 +204,15 @@ def main():
     host_edges, host_wall = 0, 0.0
     if HOST:
         hb = [st.batch(b + i) for i in range(HOST)]
+        # untimed: once per process, about ten calls into a run of back-to-back host batches, one call takes 6 ms
+        # (the runtime sets something up lazily for copies on a stream that has work queued behind events;
+        # copies on the idle stream at create time do not trigger it) -- not part of the steady-state rate
+        n_pre = min(16, HOST // 2)
+        for s_, d_, t_, e_ in hb[:n_pre]:
+            g.ingest_batch(s_, d_, t_, e_)
         g.sync()
         a = time.perf_counter()
-        for s_, d_, t_, e_ in hb:
+        for s_, d_, t_, e_ in hb[n_pre:]:
             g.ingest_batch(s_, d_, t_, e_)
             host_edges += len(s_)
         g.sync()

@@ -132,12 +132,11 @@ void stgn_destroy(stgn_ctx *ctx);
  * with device inputs the check runs on the device, a failing batch is skipped as a whole and
  * its code is returned by the next synchronising call (stgn_sync, stgn_get_*, or this call with
  * stats != NULL).
- * The call is asynchronous.  A batch with device inputs and stats == NULL that follows another
- * asynchronous call without a synchronising call in between runs its front part (validation,
- * endpoint sort, memory update) on a stream of the library's own, from the moment the previous
- * batch's edges are applied, so that it overlaps the previous batch's propagation and attention
- * layers; the rest runs on hip_stream, and work enqueued on hip_stream after the call is ordered
- * after the whole batch.  Device inputs must
+ * The call is asynchronous.  A batch with stats == NULL that follows another asynchronous call
+ * without a synchronising call in between runs its front part (the copy of host inputs,
+ * validation, endpoint sort, memory update and, on small graphs, the propagation) on a stream of
+ * the library's own so that it overlaps the previous batch's attention layers; the rest runs on
+ * hip_stream, and work enqueued on hip_stream after the call is ordered after the whole batch.  Device inputs must
  * therefore hold their final contents when the call is made (they are not ordered after work still
  * pending on hip_stream) and must stay unchanged until the batch has completed.  Host inputs are
  * copied before the call returns.  With stats != NULL the call synchronises. */

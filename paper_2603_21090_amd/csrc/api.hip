@@ -560,7 +560,7 @@ int stgn_ingest_batch(stgn_ctx* ctx, uint32_t n, const uint32_t* src, const uint
   const stgn_config& c = ctx->cfg;
   const int par = ctx->parity;                 // the batch's staging block and dirty-flag array
   const int set = ctx->set;                    // ... and its state set
-  const int prev = (set + kSets - 1) % kSets, prev2 = (set + kSets - 2) % kSets;   // the sets of the two batches before
+  const int prev = (set + kSets - 1) % kSets, prev2 = (set + kSets - 2) % kSets;   // the state sets of the two batches before
   const Dev d = bind_batch(ctx->d, set, par);
   if (n > c.max_batch) return fail(ctx, STGN_E_BATCH_TOO_LARGE, "batch larger than max_batch");
   if (n && (!src || !dst || !ts || (c.d_edge && !efeat))) return fail(ctx, STGN_E_INVALID_ARG, "NULL batch array");
@@ -571,12 +571,17 @@ int stgn_ingest_batch(stgn_ctx* ctx, uint32_t n, const uint32_t* src, const uint
   const float* def = efeat;
   // stream of the front part (see stgn_ctx::front)
   // Only worth it, and only used, when there is something to overlap with (work was enqueued on
-  // hip_stream since the library last synchronised it) and
-  // the inputs are already on the device: a host-to-device copy on the second stream was measured to
-  // halve the rate of the host-input path.
-  const bool overlapped = stats == nullptr && !ctx->timing && inputs_on_device && !ctx->idle;
+  // hip_stream since the library last synchronised it).  Host inputs are copied on the same stream,
+  // ahead of the staging kernel: like it, the copy runs a batch ahead.
+  const bool overlapped = stats == nullptr && !ctx->timing && !ctx->idle;
   ctx->idle = false;
   hipStream_t sf = overlapped ? ctx->front : ctx->stream;
+  const bool prev_on_front = ctx->prev_on_front;
+  // The batch's state set and staging block were last used three / two batches ago: whatever the front
+  // part writes first is ordered behind the apply step of the batch before the previous one, whose
+  // stream position is behind everything that used them.  (When the previous batch's front part ran
+  // on `front` too, its own wait for that event already stands in front in stream order.)
+  if (overlapped && !prev_on_front && ctx->recorded[prev2]) HIPCHK(ctx, hipStreamWaitEvent(sf, ctx->ev_apply[prev2], 0));
   if (!inputs_on_device) {
     // host-side validation: nothing is enqueued for a bad batch
     double prev = (ctx->any_edges && ctx->host_t_known) ? ctx->host_t_last : -INFINITY;
@@ -596,7 +601,7 @@ int stgn_ingest_batch(stgn_ctx* ctx, uint32_t n, const uint32_t* src, const uint
       memcpy(p + o_dst, dst, (size_t)n * 4);
       memcpy(p + o_ts, ts, (size_t)n * 8);
       if (c.d_edge) memcpy(p + o_ef, efeat, (size_t)n * c.d_edge * 4);
-      // host inputs run on hip_stream alone, in order: one copy moves the batch
+      // one copy moves the batch
       HIPCHK(ctx, hipMemcpyAsync(d.stage[par], p, o_ef + (size_t)n * c.d_edge * 4, hipMemcpyHostToDevice, sf));
       HIPCHK(ctx, hipEventRecord(ctx->pin_ev[pb], sf));
       ctx->pin_used[pb] = true;
@@ -617,16 +622,10 @@ int stgn_ingest_batch(stgn_ctx* ctx, uint32_t n, const uint32_t* src, const uint
   ctx->parity ^= 1;                            // from here on the batch is enqueued
   ctx->set = (set + 1) % kSets;
   ctx->last_par = set;
-  const bool prev_on_front = ctx->prev_on_front;
   ctx->prev_on_front = overlapped;
   hipStream_t s = ctx->stream;
   // The staging kernel looks only at the batch and the running edge count and writes the batch's own
-  // state set, last used three batches ago: it is ordered behind the apply step of the batch before
-  // the previous one (whose stream position is behind everything that used the set) and so may run
-  // beside the previous batch's main part, a batch ahead of the rest of the front part.
-  // (when the previous batch's front part ran on `front` too, its own wait for that event already
-  // stands in front of this kernel in stream order)
-  if (overlapped && !prev_on_front && ctx->recorded[prev2]) HIPCHK(ctx, hipStreamWaitEvent(sf, ctx->ev_apply[prev2], 0));
+  // state set: it may run beside the previous batch's main part, a batch ahead of the rest of the front part.
   hipEvent_t* ev = stats ? ctx->stage_ev : nullptr;
   if (ev) hipEventRecord(ev[0], s);
   { Scope t(ctx, KC_SORT, sf); launch_stage_sort(d, sf, n, dsrc, ddst, dts); }

@@ -331,8 +331,45 @@ def test_back_to_back_device_batches_overlap_and_a_skipped_batch(binding):
     g.close(); g2.close()
 
 
+def test_back_to_back_host_batches(binding):
+    """A whole stream of host batches without a synchronising call in between: each batch is copied
+    into one of two pinned blocks and from there into one of two device staging blocks on the
+    library's second stream, a batch ahead of the kernels that read it.  The final state must equal
+    the oracle's and, bit for bit, that of the same stream with a synchronising call after every batch."""
+    w = tiny_workload(num_nodes=500, num_edges=8000, batch=80, layers=2, k=4, d_mem=16, d_edge=12, d_time=16,
+                      d_emb=16, d_msg=16, zipf_s=0.9)
+    st = synth.EdgeStream(w)
+    W = synth.make_weights(w)
+    o = orc.Oracle.from_workload(w, W)
+    g = binding.StreamTGN.from_workload(w, W)
+    g2 = binding.StreamTGN.from_workload(w, W)
+    allnodes = np.arange(w.num_nodes, dtype=np.uint32)
+    for b in range(w.num_batches):
+        rc, D, A = o.ingest(*st.batch(b))
+        assert rc == 0
+        s, d, t, ef = [a.copy() for a in st.batch(b)]
+        assert g.ingest_batch(s, d, t, ef, check=False) == 0
+        s[:] = 0; d[:] = 0; t[:] = 0.0; ef[:] = 0.0          # host inputs are copied before the call returns
+        g2.ingest_batch(*st.batch(b))
+        g2.sync()
+    assert g.sync() == 0
+    assert np.array_equal(g.get_affected(), A)
+    gm, gt = g.get_memory(allnodes)
+    om, ot = o.memory(allnodes)
+    assert np.array_equal(gt, ot)
+    check_rows(gm, om, "memory")
+    ref = o.embed_all()
+    for l in range(1, w.layers + 1):
+        got = g.get_embeddings(allnodes, layer=l)
+        check_rows(got, ref[l - 1], f"layer {l}")
+        assert np.array_equal(got, g2.get_embeddings(allnodes, layer=l))
+    check_neighbours(g, o, allnodes)
+    g.close(); g2.close()
+
+
+@pytest.mark.parametrize("host_inputs", [False, True])
 @pytest.mark.parametrize("num_nodes,batch,zipf_s,expect_pull", [(400, 100, 1.1, True), (6000, 60, 0.3, False)])
-def test_overlapped_pairs_give_the_oracles_affected_sets(binding, num_nodes, batch, zipf_s, expect_pull):
+def test_overlapped_pairs_give_the_oracles_affected_sets(binding, num_nodes, batch, zipf_s, expect_pull, host_inputs):
     """Device batches go in in pairs without a synchronising call in between, so the second batch of
     every pair runs its front part -- staging, the first propagation hop, the memory update -- beside
     the first one's main part.  After each pair the second batch's affected set, frontier sizes and
@@ -350,7 +387,8 @@ def test_overlapped_pairs_give_the_oracles_affected_sets(binding, num_nodes, bat
         return (torch.from_numpy(s.astype(np.int32)).cuda(), torch.from_numpy(d.astype(np.int32)).cuda(),
                 torch.from_numpy(t).cuda(), torch.from_numpy(ef).cuda())
 
-    batches = [dev(*st.batch(b)) for b in range(w.num_batches)]
+    # host inputs take the same path: their copy to the device runs ahead like the staging kernel
+    batches = [st.batch(b) if host_inputs else dev(*st.batch(b)) for b in range(w.num_batches)]
     torch.cuda.synchronize()
     for b in range(0, w.num_batches - 2, 2):
         rc, D0, A0 = o.ingest(*st.batch(b))
