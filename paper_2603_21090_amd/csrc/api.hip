@@ -584,12 +584,12 @@ int stgn_ingest_batch(stgn_ctx* ctx, uint32_t n, const uint32_t* src, const uint
   if (overlapped && !prev_on_front && ctx->recorded[prev2]) HIPCHK(ctx, hipStreamWaitEvent(sf, ctx->ev_apply[prev2], 0));
   if (!inputs_on_device) {
     // host-side validation: nothing is enqueued for a bad batch
-    double prev = (ctx->any_edges && ctx->host_t_known) ? ctx->host_t_last : -INFINITY;
+    double t_before = (ctx->any_edges && ctx->host_t_known) ? ctx->host_t_last : -INFINITY;
     for (uint32_t i = 0; i < n; ++i) {
       if (src[i] >= c.num_nodes || dst[i] >= c.num_nodes) return fail(ctx, STGN_E_NODE_OUT_OF_RANGE, "endpoint id >= num_nodes");
       if (src[i] == dst[i]) return fail(ctx, STGN_E_SELF_LOOP, "self loop");
-      if (!(ts[i] >= prev)) return fail(ctx, STGN_E_TIME_ORDER, "timestamps must be non-decreasing");
-      prev = ts[i];
+      if (!(ts[i] >= t_before)) return fail(ctx, STGN_E_TIME_ORDER, "timestamps must be non-decreasing");
+      t_before = ts[i];
     }
     if (n) {
       const int pb = ctx->pin_next;
@@ -635,7 +635,7 @@ int stgn_ingest_batch(stgn_ctx* ctx, uint32_t n, const uint32_t* src, const uint
   if (ev) hipEventRecord(ev[1], s);
   if (c.d_mem) { Scope t(ctx, KC_MEMORY, sf); launch_memory_update(d, sf, dsrc, ddst, dts, def); }
   if (ev) hipEventRecord(ev[2], s);
-  // With two flag arrays the staging kernel has seeded the dirty flags, and the propagation hops may
+  // With two flag arrays the placement kernel has seeded the dirty flags, and the propagation hops may
   // run in the front part, ahead of the apply step: a node that is not an endpoint of the batch keeps
   // its ring, degree and log through the apply step and endpoints are dirty from the start, so a hop
   // sets the same flags before the apply step as after it.  They follow the memory update: that
