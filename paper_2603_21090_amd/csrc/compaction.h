@@ -88,7 +88,7 @@ __device__ inline void finish_batch(const Dev& d, const uint32_t (&total)[STGN_M
 // hit L2), so no workgroup depends on another.  The batch's flags stay as they are (other workgroups
 // may still be counting them): small flag arrays are held twice, by batch parity, and the next
 // batch's apply step clears this one.
-constexpr uint32_t kSmallBlocks = 16;
+constexpr uint32_t kSmallBlocks = 32;
 // bid / nblk: the workgroup's index and count among those that compact; s: 256 words of LDS.
 __device__ inline void compact_small_block(const Dev& d, uint32_t last_value, uint32_t bid, uint32_t nblk, uint32_t* s) {
   const uint32_t t = threadIdx.x;

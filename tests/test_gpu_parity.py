@@ -135,9 +135,9 @@ def test_layers_recompute_only_rows_whose_inputs_changed(binding, d_mem, d_node)
     g.close()
 
 
-@pytest.mark.parametrize("num_nodes", [61000, 65536, 65537, 70000])
+@pytest.mark.parametrize("num_nodes", [61000, 131072, 131073, 140000])
 def test_compaction_on_both_sides_of_the_one_launch_limit(binding, num_nodes):
-    """Flag arrays of at most 16 blocks of 4096 nodes are compacted in one launch (every workgroup
+    """Flag arrays of at most 32 blocks of 4096 nodes are compacted in one launch (every workgroup
     counts the blocks before its own, the flags are held twice), larger ones in two; the affected
     sets, the per-layer lists (through the embeddings) and the frontier statistics must come out
     the same on both sides of the limit, and through many batches (the flag arrays alternate)."""
