@@ -331,6 +331,92 @@ def test_back_to_back_device_batches_overlap_and_a_skipped_batch(binding):
     g.close(); g2.close()
 
 
+@pytest.mark.parametrize("seed", [1, 2])
+def test_random_mix_of_calls_between_overlapped_batches(binding, seed):
+    """A seeded random mix of everything a caller can put between two batches -- device and host
+    batches without a synchronising call, polled batches, empty batches, full rebuilds, link scores
+    of the next batch (both modes, on the device), embedding look-ups on the device, synchronising
+    calls -- with the oracle beside it: every result that comes back is compared when it comes back,
+    the whole state at the end."""
+    import torch
+    rng = np.random.default_rng(seed)
+    w = tiny_workload(num_nodes=700, num_edges=9000, batch=90, layers=2, k=4, d_mem=16, d_edge=8, d_time=16,
+                      d_emb=16, d_msg=16, zipf_s=0.9)
+    st = synth.EdgeStream(w)
+    W = synth.make_weights(w)
+    o = orc.Oracle.from_workload(w, W)
+    g = binding.StreamTGN.from_workload(w, W)
+    wp = rng.standard_normal(2 * w.d_emb).astype(np.float32)
+    g.set_predictor(wp, 0.25)
+    allnodes = np.arange(w.num_nodes, dtype=np.uint32)
+    dev_nodes = torch.from_numpy(allnodes.astype(np.int32)).cuda()
+
+    def dev(s, d, t, ef):
+        return (torch.from_numpy(s.astype(np.int32)).cuda(), torch.from_numpy(d.astype(np.int32)).cuda(),
+                torch.from_numpy(t).cuda(), torch.from_numpy(ef).cuda())
+
+    pending = []                                    # (what, device tensor, expected) of asynchronous results
+    A = None
+    for b in range(w.num_batches):
+        s, d, t, ef = st.batch(b)
+        # calls before the batch
+        for _ in range(int(rng.integers(0, 3))):
+            what = int(rng.integers(0, 5))
+            if what == 0:
+                g.full_rebuild()
+            elif what == 1:
+                mode = bool(rng.integers(0, 2))
+                ds, dd, dt, _ = dev(s, d, t, ef)
+                H = o.embed_all()[-1].astype(np.float64)
+                bound = 2 * REL * (np.linalg.norm(H[s], axis=1) * np.linalg.norm(wp[:w.d_emb]) +
+                                   np.linalg.norm(H[d], axis=1) * np.linalg.norm(wp[w.d_emb:])) + 1e-5
+                pending.append((f"scores before batch {b}, mode {mode}", g.predict_batch(ds, dd, dt, at_edge_time=mode),
+                                o.predict(s, d, t, wp, 0.25, at_edge_time=mode), bound))
+            elif what == 2:
+                layer = int(rng.integers(1, w.layers + 1))
+                pending.append((f"rows of layer {layer} before batch {b}", g.get_embeddings(dev_nodes, layer=layer),
+                                o.embed_nodes(allnodes, layer=layer), None))
+            elif what == 3:
+                assert g.sync() == 0
+            else:
+                z = dev(s[:0], d[:0], t[:0], ef[:0])
+                assert g.ingest_batch(*z, check=False) == 0
+        rc, D, A = o.ingest(s, d, t, ef)
+        assert rc == 0
+        how = int(rng.integers(0, 4))
+        if how == 0:
+            assert g.ingest_batch(*dev(s, d, t, ef), check=False) == 0
+        elif how == 1:
+            assert g.ingest_batch(s, d, t, ef, check=False) == 0
+        elif how == 2:
+            stats = g.ingest_batch(*dev(s, d, t, ef), stats=True)
+            assert stats["n_affected"] == len(A) and stats["n_direct"] == len(D)
+        else:
+            assert g.ingest_batch(s, d, t, ef, check=False) == 0
+            assert g.sync() == 0
+            assert np.array_equal(g.get_affected(), A), f"batch {b}"
+        if len(pending) > 6 or b == w.num_batches - 1:
+            assert g.sync() == 0
+            for name, got, ref, bound in pending:
+                got = got.cpu().numpy()
+                if got.ndim == 1:
+                    assert (np.abs(got - ref) <= bound).all(), f"{name}: worst {np.abs(got - ref).max():.3e}"
+                else:
+                    check_rows(got, ref, name)
+            pending = []
+    assert g.sync() == 0
+    assert np.array_equal(g.get_affected(), A)
+    gm, gt = g.get_memory(allnodes)
+    om, ot = o.memory(allnodes)
+    assert np.array_equal(gt, ot)
+    check_rows(gm, om, "memory")
+    ref = o.embed_all()
+    for l in range(1, w.layers + 1):
+        check_rows(g.get_embeddings(allnodes, layer=l), ref[l - 1], f"layer {l}")
+    check_neighbours(g, o, allnodes)
+    g.close()
+
+
 def test_back_to_back_host_batches(binding):
     """A whole stream of host batches without a synchronising call in between: each batch is copied
     into one of two pinned blocks and from there into one of two device staging blocks on the
