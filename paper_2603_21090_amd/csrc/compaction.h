@@ -84,8 +84,8 @@ __device__ inline void finish_batch(const Dev& d, const uint32_t (&total)[STGN_M
 }
 
 // Count and write in one launch, for flag arrays of at most kSmallBlocks blocks: a workgroup counts
-// the flags of the blocks before its own instead of waiting for their sums (a few KiB of reads that
-// hit L2), so no workgroup depends on another.  The batch's flags stay as they are (other workgroups
+// the flags of the blocks before its own instead of waiting for their sums (at most 124 KiB of reads
+// that hit L2), so no workgroup depends on another.  The batch's flags stay as they are (other workgroups
 // may still be counting them): small flag arrays are held twice, by batch parity, and the next
 // batch's apply step clears this one.
 constexpr uint32_t kSmallBlocks = 32;

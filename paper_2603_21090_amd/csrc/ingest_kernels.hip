@@ -339,7 +339,7 @@ __global__ __launch_bounds__(256) void apply_kernel(Dev d, const uint32_t* __res
   const uint32_t first = proj_blocks + compact_blocks;      // first workgroup of the append group
   const uint32_t tid = (blockIdx.x - first) * blockDim.x + threadIdx.x, nth = (gridDim.x - first) * blockDim.x;
   // Two flag arrays: the other one was last read by the previous batch's compaction and is seeded
-  // next by the next batch's staging, which waits for this kernel -- cleared here, skipped batch or not.
+  // next by the next batch's placement kernel, which waits for this kernel -- cleared here, skipped batch or not.
   if (blockIdx.x >= proj_blocks && d.mark_other != d.mark) {
     const uint32_t words = (uint32_t)(mark_bytes(d.N) / 16);
     for (uint32_t x = tid; x < words; x += nth) reinterpret_cast<uint4*>(d.mark_other)[x] = make_uint4(0u, 0u, 0u, 0u);
