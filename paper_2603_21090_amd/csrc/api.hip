@@ -631,9 +631,14 @@ int stgn_ingest_batch(stgn_ctx* ctx, uint32_t n, const uint32_t* src, const uint
   { Scope t(ctx, KC_SORT, sf); launch_stage_sort(d, sf, n, dsrc, ddst, dts); }
   // degrees and memory as the previous apply step left them
   if (overlapped && ctx->recorded[prev]) HIPCHK(ctx, hipStreamWaitEvent(sf, ctx->ev_apply[prev], 0));
-  { Scope t(ctx, KC_SORT, sf); launch_place(d, sf, n); }
+  // (calls that ask for statistics keep the plain order, so that their stage times mean what they say)
+  const uint32_t first_main_hop = !stats && !ctx->timing && compact_in_one(d) && (c.layers >= 2 || !overlapped) ? c.layers : 0u;
+  // the front part's last kernel carries the event the apply step waits for
+  hipEvent_t front_done = overlapped ? ctx->ev_front : nullptr;
+  const int last_front = first_main_hop ? 2 : c.d_mem ? 1 : 0;          // hops / memory update / placement
+  { Scope t(ctx, KC_SORT, sf); launch_place(d, sf, n, last_front == 0 ? front_done : nullptr); }
   if (ev) hipEventRecord(ev[1], s);
-  if (c.d_mem) { Scope t(ctx, KC_MEMORY, sf); launch_memory_update(d, sf, dsrc, ddst, dts, def); }
+  if (c.d_mem) { Scope t(ctx, KC_MEMORY, sf); launch_memory_update(d, sf, dsrc, ddst, dts, def, last_front == 1 ? front_done : nullptr); }
   if (ev) hipEventRecord(ev[2], s);
   // With two flag arrays the placement kernel has seeded the dirty flags, and the propagation hops may
   // run in the front part, ahead of the apply step: a node that is not an endpoint of the batch keeps
@@ -645,21 +650,16 @@ int stgn_ingest_batch(stgn_ctx* ctx, uint32_t n, const uint32_t* src, const uint
   // caller's stream 112 us; first hop in front of the memory update 110; behind it 105; both hops
   // behind it 103; both in front of it 117.)  Only beside at least two layer launches: the single
   // launch of a one-layer model is shorter than the front part (C1: 82 instead of 72 us).
-  // (calls that ask for statistics keep the plain order, so that their stage times mean what they say)
-  const uint32_t first_main_hop = !stats && !ctx->timing && compact_in_one(d) && (c.layers >= 2 || !overlapped) ? c.layers : 0u;
   for (uint32_t hop = 0; hop < first_main_hop; ++hop) {
     const bool planned = !ctx->pull_hint[hop];
     if (planned) { Scope t(ctx, KC_PLAN, sf); launch_plan(d, sf, hop); }
-    { Scope t(ctx, KC_EXPAND, sf); launch_expand(d, sf, hop, planned); }
+    { Scope t(ctx, KC_EXPAND, sf); launch_expand(d, sf, hop, planned, hop + 1 == first_main_hop ? front_done : nullptr); }
   }
-  if (overlapped) {
-    HIPCHK(ctx, hipEventRecord(ctx->ev_front, ctx->front));
-    HIPCHK(ctx, hipStreamWaitEvent(s, ctx->ev_front, 0));
-  }
+  if (overlapped) HIPCHK(ctx, hipStreamWaitEvent(s, ctx->ev_front, 0));
   // the propagation is done: the compaction depends on the flags alone and shares the apply step's launch
   const bool fused_compaction = first_main_hop != 0;
-  { Scope t(ctx, KC_APPLY); launch_apply(d, s, dsrc, ddst, dts, def, fused_compaction); }
-  HIPCHK(ctx, hipEventRecord(ctx->ev_apply[set], s));
+  // ... and its own completion is the event the next batch's front part waits for
+  { Scope t(ctx, KC_APPLY); launch_apply(d, s, dsrc, ddst, dts, def, fused_compaction, ctx->ev_apply[set]); }
   ctx->recorded[set] = true;
   if (ev) hipEventRecord(ev[3], s);
   for (uint32_t hop = first_main_hop; hop < c.layers; ++hop) {

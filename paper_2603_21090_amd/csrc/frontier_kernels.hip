@@ -267,12 +267,12 @@ void launch_plan(const Dev& d, hipStream_t s, uint32_t hop) {
   hipLaunchKernelGGL(plan_kernel, dim3(blocks), dim3(kPlanThreads), 0, s, d, hop, rounds);
 }
 
-void launch_expand(const Dev& d, hipStream_t s, uint32_t hop, bool planned) {
+void launch_expand(const Dev& d, hipStream_t s, uint32_t hop, bool planned, hipEvent_t done) {
   // one wave per work item (push) or one lane per node (pull), grid-stride.  A node per lane four
   // times over: small graphs get few workgroups, which all find room at once beside another kernel's.
   uint64_t want = ((uint64_t)d.N + 63) / 64;
   uint32_t blocks = want > 4096 ? 4096u : (uint32_t)(want ? want : 1);
-  hipLaunchKernelGGL(expand_kernel, dim3(blocks), dim3(256), 0, s, d, hop, planned ? 1u : 0u);
+  launch_done(expand_kernel, dim3(blocks), dim3(256), 0, s, done, d, hop, planned ? 1u : 0u);
 }
 
 bool compact_in_one(const Dev& d) { return (d.N + kFlagsPerBlock - 1) / kFlagsPerBlock <= kSmallBlocks; }

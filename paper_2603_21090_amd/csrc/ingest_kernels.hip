@@ -430,14 +430,14 @@ void launch_stage_sort(const Dev& d, hipStream_t s, uint32_t n, const uint32_t* 
   hipLaunchKernelGGL(stage_sort_kernel, dim3(1), dim3(threads), P * sizeof(uint64_t), s, d, n, src, dst, ts, P);
 }
 
-void launch_place(const Dev& d, hipStream_t s, uint32_t n) {
+void launch_place(const Dev& d, hipStream_t s, uint32_t n, hipEvent_t done) {
   uint32_t threads = (2 * n + 63u) & ~63u;     // one endpoint slot per thread where the batch allows
   threads = threads < 64 ? 64 : threads > (uint32_t)kSortThreads ? (uint32_t)kSortThreads : threads;
-  hipLaunchKernelGGL(place_kernel, dim3(1), dim3(threads), 0, s, d);
+  launch_done(place_kernel, dim3(1), dim3(threads), 0, s, done, d);
 }
 
 void launch_apply(const Dev& d, hipStream_t s, const uint32_t* src, const uint32_t* dst, const double* ts,
-                  const float* ef, bool with_compaction) {
+                  const float* ef, bool with_compaction, hipEvent_t done) {
   // sized for the largest section (feature rows of a full batch), grid-stride inside
   const uint32_t work = d.max_batch * (d.efeat.ld > 2 ? d.efeat.ld : 2);
   uint32_t blocks = (work + 255) / 256;
@@ -448,8 +448,8 @@ void launch_apply(const Dev& d, hipStream_t s, const uint32_t* src, const uint32
   uint32_t pblocks = ((d.d_mem ? 2 * per : 0) + (d.d_edge ? d.layers * per : 0)) * d.ks;
   if (pblocks > 2048) pblocks = 2048;
   const uint32_t cblocks = with_compaction ? compact_blocks_of(d.N) : 0u;
-  hipLaunchKernelGGL(apply_kernel, dim3(blocks + pblocks + cblocks), dim3(256), pblocks ? project_lds(d) : 0, s, d, src, dst,
-                     ts, ef, pblocks, cblocks);
+  launch_done(apply_kernel, dim3(blocks + pblocks + cblocks), dim3(256), pblocks ? project_lds(d) : 0, s, done, d, src, dst,
+              ts, ef, pblocks, cblocks);
 }
 
 void launch_project_nodes(const Dev& d, hipStream_t s) {

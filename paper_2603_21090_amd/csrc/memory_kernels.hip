@@ -280,13 +280,13 @@ size_t memory_lds(const Dev& d) { return (size_t)memory_lds_layout(d.Kmsg, d.d_m
 }  // namespace
 
 void launch_memory_update(const Dev& d, hipStream_t s, const uint32_t* src, const uint32_t* dst, const double* ts,
-                          const float* ef) {
+                          const float* ef, hipEvent_t done) {
   uint32_t blocks = (2 * d.max_batch + kRows - 1) / kRows;
   if (blocks > 1024) blocks = 1024;
   if (memory_upfront(d))
-    hipLaunchKernelGGL(memory_update_kernel<true>, dim3(blocks), dim3(kThreads), memory_lds(d), s, d, src, dst, ts, ef);
+    launch_done(memory_update_kernel<true>, dim3(blocks), dim3(kThreads), memory_lds(d), s, done, d, src, dst, ts, ef);
   else
-    hipLaunchKernelGGL(memory_update_kernel<false>, dim3(blocks), dim3(kThreads), memory_lds(d), s, d, src, dst, ts, ef);
+    launch_done(memory_update_kernel<false>, dim3(blocks), dim3(kThreads), memory_lds(d), s, done, d, src, dst, ts, ef);
 }
 
 int setup_memory_attributes(const Dev& d) {

@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 #include <stddef.h>
 
@@ -215,16 +216,26 @@ __device__ inline unsigned long long stripes_sum_thread(const Dev& d, uint32_t c
 enum KernelClass { KC_SORT = 0, KC_MEMORY, KC_APPLY, KC_PLAN, KC_EXPAND, KC_COMPACT, KC_LAYER,
                    KC_GATHER, KC_NOOP, KC_PROJECT, KC_PREDICT, KC_COUNT };
 
+// A launch whose completion is an event (`done`, may be null): the event rides on the kernel's own
+// completion signal instead of a marker of its own behind it, which costs the stream a microsecond or
+// two less than hipEventRecord after the launch.  Waits on such an event were checked to be ordered
+// behind the kernel's last store (400 producer / consumer pairs on two streams).
+template <class K, class... Args>
+inline void launch_done(K kernel, dim3 grid, dim3 block, size_t lds, hipStream_t s, hipEvent_t done, Args... args) {
+  if (done) hipExtLaunchKernelGGL(kernel, grid, block, lds, s, nullptr, done, 0, args...);
+  else hipLaunchKernelGGL(kernel, grid, block, lds, s, args...);
+}
+
 // ---- launch wrappers (one per kernel family), defined in the .hip files ----
 void launch_stage_sort(const Dev& d, hipStream_t s, uint32_t n, const uint32_t* src, const uint32_t* dst,
                        const double* ts);
-void launch_place(const Dev& d, hipStream_t s, uint32_t n);
+void launch_place(const Dev& d, hipStream_t s, uint32_t n, hipEvent_t done = nullptr);
 void launch_memory_update(const Dev& d, hipStream_t s, const uint32_t* src, const uint32_t* dst, const double* ts,
-                          const float* ef);
+                          const float* ef, hipEvent_t done = nullptr);
 void launch_apply(const Dev& d, hipStream_t s, const uint32_t* src, const uint32_t* dst, const double* ts,
-                  const float* ef, bool with_compaction);   // with_compaction: only for compact_in_one(d), after the propagation
+                  const float* ef, bool with_compaction, hipEvent_t done = nullptr);   // with_compaction: only for compact_in_one(d), after the propagation
 void launch_plan(const Dev& d, hipStream_t s, uint32_t hop);
-void launch_expand(const Dev& d, hipStream_t s, uint32_t hop, bool planned);
+void launch_expand(const Dev& d, hipStream_t s, uint32_t hop, bool planned, hipEvent_t done = nullptr);
 void launch_compact(const Dev& d, hipStream_t s, int phase);
 bool compact_in_one(const Dev& d);   // the compaction is a single launch (phase 0) for this node count
 void launch_layer(const Dev& d, hipStream_t s, uint32_t layer, const uint32_t* rows, const uint32_t* count_ptr,
