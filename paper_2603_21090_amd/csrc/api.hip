@@ -636,9 +636,11 @@ int stgn_ingest_batch(stgn_ctx* ctx, uint32_t n, const uint32_t* src, const uint
   // the front part's last kernel carries the event the apply step waits for
   hipEvent_t front_done = overlapped ? ctx->ev_front : nullptr;
   const int last_front = first_main_hop ? 2 : c.d_mem ? 1 : 0;          // hops / memory update / placement
-  { Scope t(ctx, KC_SORT, sf); launch_place(d, sf, n, last_front == 0 ? front_done : nullptr); }
+  // (the placement rides in the memory update's launch when there is one)
+  const bool place_in_memory = c.d_mem != 0;
+  if (!place_in_memory) { Scope t(ctx, KC_SORT, sf); launch_place(d, sf, n, last_front == 0 ? front_done : nullptr); }
   if (ev) hipEventRecord(ev[1], s);
-  if (c.d_mem) { Scope t(ctx, KC_MEMORY, sf); launch_memory_update(d, sf, dsrc, ddst, dts, def, last_front == 1 ? front_done : nullptr); }
+  if (c.d_mem) { Scope t(ctx, KC_MEMORY, sf); launch_memory_update(d, sf, dsrc, ddst, dts, def, place_in_memory, last_front == 1 ? front_done : nullptr); }
   if (ev) hipEventRecord(ev[2], s);
   // With two flag arrays the placement kernel has seeded the dirty flags, and the propagation hops may
   // run in the front part, ahead of the apply step: a node that is not an endpoint of the batch keeps

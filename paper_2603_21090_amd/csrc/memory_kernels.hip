@@ -9,6 +9,7 @@
 // them once every read of the old rows is done.
 #include "stgn_internal.h"
 #include "mfma16.h"
+#include "placement.h"
 
 namespace stgn {
 
@@ -46,7 +47,7 @@ template <bool UP>
 __global__ __launch_bounds__(kThreads) void memory_update_kernel(Dev d, const uint32_t* __restrict__ src,
                                                                  const uint32_t* __restrict__ dst,
                                                                  const double* __restrict__ ts,
-                                                                 const float* __restrict__ ef) {
+                                                                 const float* __restrict__ ef, uint32_t with_place) {
   extern __shared__ __align__(16) float lds[];
   __shared__ uint32_t s_self[kRows], s_oth[kRows], s_ef[kRows], s_live[kRows];
   __shared__ double s_dt[kRows];
@@ -55,6 +56,15 @@ __global__ __launch_bounds__(kThreads) void memory_update_kernel(Dev d, const ui
   __shared__ uint32_t s_seg[kRows], s_n[kRows];
   __shared__ double s_tl[kRows];
   __shared__ float s_scale[kRows];
+  // The last workgroup places the batch's endpoint slots in the adjacency logs instead (placement.h):
+  // that step depends on the same staging kernel and the same apply step as the memory update and on
+  // nothing in it, and riding along saves its launch.
+  __shared__ uint32_t s_place[17];
+  if (with_place && blockIdx.x == gridDim.x - 1) {
+    place_batch(d, s_place, s_place + 16);
+    return;
+  }
+  const uint32_t nblk = gridDim.x - (with_place ? 1u : 0u);     // workgroups that update memory rows
   const BatchCtl* c = d.bc;
   if (c->skip) return;
   const uint32_t nD = c->nD;
@@ -76,7 +86,7 @@ __global__ __launch_bounds__(kThreads) void memory_update_kernel(Dev d, const ui
   // operand padding (columns nobody writes) must be finite: clear the tiles once
   for (uint32_t x = threadIdx.x; x < ll.total; x += kThreads) lds[x] = 0.0f;
 
-  for (uint32_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+  for (uint32_t tile = blockIdx.x; tile < ntiles; tile += nblk) {
     const uint32_t r0 = tile * kRows;
     Upfront16<1, 8> um;      // message weights: requested before anything else of the tile
     if constexpr (UP) {
@@ -280,13 +290,15 @@ size_t memory_lds(const Dev& d) { return (size_t)memory_lds_layout(d.Kmsg, d.d_m
 }  // namespace
 
 void launch_memory_update(const Dev& d, hipStream_t s, const uint32_t* src, const uint32_t* dst, const double* ts,
-                          const float* ef, hipEvent_t done) {
+                          const float* ef, bool with_place, hipEvent_t done) {
   uint32_t blocks = (2 * d.max_batch + kRows - 1) / kRows;
   if (blocks > 1024) blocks = 1024;
+  const uint32_t wp = with_place ? 1u : 0u;
+  blocks += wp;
   if (memory_upfront(d))
-    launch_done(memory_update_kernel<true>, dim3(blocks), dim3(kThreads), memory_lds(d), s, done, d, src, dst, ts, ef);
+    launch_done(memory_update_kernel<true>, dim3(blocks), dim3(kThreads), memory_lds(d), s, done, d, src, dst, ts, ef, wp);
   else
-    launch_done(memory_update_kernel<false>, dim3(blocks), dim3(kThreads), memory_lds(d), s, done, d, src, dst, ts, ef);
+    launch_done(memory_update_kernel<false>, dim3(blocks), dim3(kThreads), memory_lds(d), s, done, d, src, dst, ts, ef, wp);
 }
 
 int setup_memory_attributes(const Dev& d) {

@@ -230,8 +230,9 @@ inline void launch_done(K kernel, dim3 grid, dim3 block, size_t lds, hipStream_t
 void launch_stage_sort(const Dev& d, hipStream_t s, uint32_t n, const uint32_t* src, const uint32_t* dst,
                        const double* ts);
 void launch_place(const Dev& d, hipStream_t s, uint32_t n, hipEvent_t done = nullptr);
+// with_place: the launch also places the batch's endpoint slots (no launch_place then)
 void launch_memory_update(const Dev& d, hipStream_t s, const uint32_t* src, const uint32_t* dst, const double* ts,
-                          const float* ef, hipEvent_t done = nullptr);
+                          const float* ef, bool with_place, hipEvent_t done = nullptr);
 void launch_apply(const Dev& d, hipStream_t s, const uint32_t* src, const uint32_t* dst, const double* ts,
                   const float* ef, bool with_compaction, hipEvent_t done = nullptr);   // with_compaction: only for compact_in_one(d), after the propagation
 void launch_plan(const Dev& d, hipStream_t s, uint32_t hop);
