@@ -455,7 +455,8 @@ def test_back_to_back_host_batches(binding):
 
 @pytest.mark.parametrize("host_inputs", [False, True])
 @pytest.mark.parametrize("num_nodes,batch,zipf_s,expect_pull,layers",
-                         [(400, 100, 1.1, True, 2), (6000, 60, 0.3, False, 2), (400, 100, 1.1, True, 1), (3000, 60, 0.3, False, 3)])
+                         [(400, 100, 1.1, True, 2), (6000, 60, 0.3, False, 2), (400, 100, 1.1, True, 1), (3000, 60, 0.3, False, 3),
+                          (401, 100, 1.1, True, 2)])         # 401 nodes: the memoryless variant (placement as a launch of its own)
 def test_overlapped_pairs_give_the_oracles_affected_sets(binding, num_nodes, batch, zipf_s, expect_pull, layers, host_inputs):
     """Device batches go in in pairs without a synchronising call in between, so the second batch of
     every pair runs its front part -- staging, the first propagation hop, the memory update -- beside
@@ -464,12 +465,15 @@ def test_overlapped_pairs_give_the_oracles_affected_sets(binding, num_nodes, bat
     (work items planned in the front part while the previous batch's last hop reads its own); a
     one-layer model keeps its hop and its compaction on the caller's stream."""
     import torch
-    w = tiny_workload(num_nodes=num_nodes, num_edges=40 * batch, batch=batch, layers=layers, k=4, d_mem=16, d_edge=6,
+    memoryless = num_nodes == 401
+    w = tiny_workload(num_nodes=num_nodes, num_edges=40 * batch, batch=batch, layers=layers, k=4,
+                      d_mem=0 if memoryless else 16, d_node=12 if memoryless else 0, d_edge=6,
                       d_time=8, d_emb=16, d_msg=16, zipf_s=zipf_s)
     st = synth.EdgeStream(w)
     W = synth.make_weights(w)
-    o = orc.Oracle.from_workload(w, W)
-    g = binding.StreamTGN.from_workload(w, W)
+    nf = synth.node_features(w)
+    o = orc.Oracle.from_workload(w, W, nf)
+    g = binding.StreamTGN.from_workload(w, W, nf)
 
     def dev(s, d, t, ef):
         return (torch.from_numpy(s.astype(np.int32)).cuda(), torch.from_numpy(d.astype(np.int32)).cuda(),
