@@ -331,7 +331,7 @@ def test_back_to_back_device_batches_overlap_and_a_skipped_batch(binding):
     g.close(); g2.close()
 
 
-@pytest.mark.parametrize("seed", [1, 2])
+@pytest.mark.parametrize("seed", [1, 2, 3])
 def test_random_mix_of_calls_between_overlapped_batches(binding, seed):
     """A seeded random mix of everything a caller can put between two batches -- device and host
     batches without a synchronising call, polled batches, empty batches, full rebuilds, link scores
