@@ -124,8 +124,9 @@ int stgn_create(const stgn_config *cfg, const stgn_weights *w, const float *node
 void stgn_destroy(stgn_ctx *ctx);
 
 /* One incremental step (Sec. 3.3, Algorithm 1; order of Sec. 4 "Global index refresh"):
- * messages + Last aggregation + GRU on the batch endpoints from pre-batch state, append the
- * edges, propagate dirty flags `layers` hops, recompute all layers for the affected set.
+ * messages + aggregation (stgn_config.aggregator) + GRU on the batch endpoints from pre-batch
+ * state, append the edges, propagate dirty flags `layers` hops, recompute all layers for the
+ * affected set.
  * src, dst: [n]; ts: [n] non-decreasing and >= the last ingested timestamp; efeat: [n x d_edge]
  * (may be NULL when d_edge == 0).  All four live on the host (inputs_on_device = 0) or all on
  * the device (1).  Errors found on the host are returned at once and leave the state untouched;
@@ -136,10 +137,11 @@ void stgn_destroy(stgn_ctx *ctx);
  * without a synchronising call in between runs its front part (the copy of host inputs,
  * validation, endpoint sort, memory update and, on small graphs, the propagation) on a stream of
  * the library's own so that it overlaps the previous batch's attention layers; the rest runs on
- * hip_stream, and work enqueued on hip_stream after the call is ordered after the whole batch.  Device inputs must
- * therefore hold their final contents when the call is made (they are not ordered after work still
- * pending on hip_stream) and must stay unchanged until the batch has completed.  Host inputs are
- * copied before the call returns.  With stats != NULL the call synchronises. */
+ * hip_stream, and work enqueued on hip_stream after the call is ordered after the whole batch.
+ * Device inputs must therefore hold their final contents when the call is made (they are not
+ * ordered after work still pending on hip_stream) and must stay unchanged until the batch has
+ * completed.  Host inputs are copied before the call returns.  With stats != NULL the call
+ * synchronises. */
 int stgn_ingest_batch(stgn_ctx *ctx, uint32_t n, const uint32_t *src, const uint32_t *dst,
                       const double *ts, const float *efeat, int inputs_on_device,
                       stgn_batch_stats *stats /* host, nullable */);
