@@ -148,7 +148,8 @@ int stgn_ingest_batch(stgn_ctx *ctx, uint32_t n, const uint32_t *src, const uint
 
 /* Cached final-layer rows (Sec. 3.2.3, O(1) lookup per node).  layer: 1..layers, or 0 for the
  * last one.  nodes/out on host (on_device = 0, synchronises) or device (1, asynchronous).
- * out: [n x d_emb]. */
+ * out: [n x d_emb].  Host ids >= num_nodes return STGN_E_NODE_OUT_OF_RANGE; a device-resident id
+ * >= num_nodes gives that row NaN in every column. */
 int stgn_get_embeddings(stgn_ctx *ctx, uint32_t layer, uint32_t n, const uint32_t *nodes,
                         float *out, int on_device);
 

@@ -161,9 +161,6 @@ size_t layout(const stgn_config& c, char* base, Dev* d) {
   d->pool_nt = b.take<uint2>(d->pool_cap_units * kMinBlock);
   d->pool_eid = b.take<uint32_t>(d->pool_cap_units * kMinBlock);
   d->blk = b.take<uint32_t>((size_t)N * maxb);
-  d->efeat.ld = row_ld(c.d_edge);
-  d->efeat.base = b.take<float>((size_t)c.max_edges * d->efeat.ld);
-  d->ets = b.take<double>(c.max_edges);
   d->sh = (d->dk + kSlot - 1) / kSlot;
   if (d->sh == 3) d->sh = 4;                                  // kernel variants exist for 1, 2 and 4 slots per head
   d->ks = c.heads * d->sh;
@@ -581,7 +578,15 @@ int stgn_ingest_batch(stgn_ctx* ctx, uint32_t n, const uint32_t* src, const uint
   // part writes first is ordered behind the apply step of the batch before the previous one, whose
   // stream position is behind everything that used them.  (When the previous batch's front part ran
   // on `front` too, its own wait for that event already stands in front in stream order.)
-  if (overlapped && !prev_on_front && ctx->recorded[prev2]) HIPCHK(ctx, hipStreamWaitEvent(sf, ctx->ev_apply[prev2], 0));
+  // A previous batch whose front part ran on `stream` has its staging kernel there, possibly still
+  // queued behind work of the caller's: both staging kernels update the running edge count, the stream
+  // time and the batch counter, so this one must not overtake it.  Its apply step follows it in stream
+  // order and is also behind the batch before it, so that one event orders both (once per
+  // synchronising call; the steady state never takes this branch).
+  if (overlapped && !prev_on_front) {
+    if (ctx->recorded[prev]) HIPCHK(ctx, hipStreamWaitEvent(sf, ctx->ev_apply[prev], 0));
+    else if (ctx->recorded[prev2]) HIPCHK(ctx, hipStreamWaitEvent(sf, ctx->ev_apply[prev2], 0));
+  }
   if (!inputs_on_device) {
     // host-side validation: nothing is enqueued for a bad batch
     double t_before = (ctx->any_edges && ctx->host_t_known) ? ctx->host_t_last : -INFINITY;
@@ -877,9 +882,15 @@ int stgn_get_memory(stgn_ctx* ctx, uint32_t n, const uint32_t* nodes, float* mem
     }
   }
   if (t_last) {
-    std::vector<double> all(c.num_nodes);
-    HIPCHK(ctx, hipMemcpy(all.data(), d.t_last, (size_t)c.num_nodes * 8, hipMemcpyDeviceToHost));
-    for (uint32_t i = 0; i < n; ++i) t_last[i] = all[nodes[i]];
+    // the row staging block holds at least q_cap floats per column, i.e. q_cap / 2 doubles per column
+    const uint32_t cap = d.q_cap / 2;
+    for (uint32_t lo = 0; lo < n; lo += cap) {
+      const uint32_t m = std::min(cap, n - lo);
+      HIPCHK(ctx, hipMemcpyAsync(d.qnodes, nodes + lo, (size_t)m * 4, hipMemcpyHostToDevice, ctx->stream));
+      launch_gather_times(d, ctx->stream, m, d.qnodes, reinterpret_cast<double*>(d.qout));
+      HIPCHK(ctx, hipMemcpyAsync(t_last + lo, d.qout, (size_t)m * 8, hipMemcpyDeviceToHost, ctx->stream));
+      HIPCHK(ctx, hipStreamSynchronize(ctx->stream));
+    }
   }
   return rc;
 }

@@ -13,12 +13,23 @@ namespace {
 using layer_impl::LaunchArgs;
 using layer_impl::LayerArgs;
 
-__global__ void gather_rows_kernel(Table T, uint32_t width, uint32_t n, const uint32_t* __restrict__ nodes,
+// Rows of a table for a list of node ids; an id past the node count (device-resident lists are not
+// checked on the host) yields a row of NaN instead of a read outside the table.
+__global__ void gather_rows_kernel(Table T, uint32_t N, uint32_t width, uint32_t n, const uint32_t* __restrict__ nodes,
                                    float* __restrict__ out) {
   const size_t tot = (size_t)n * width;
   for (size_t x = (size_t)blockIdx.x * blockDim.x + threadIdx.x; x < tot; x += (size_t)gridDim.x * blockDim.x) {
     const size_t i = x / width, c = x - i * width;
-    out[x] = T.base[(size_t)nodes[i] * T.ld + c];
+    const uint32_t v = nodes[i];
+    out[x] = v < N ? T.base[(size_t)v * T.ld + c] : __builtin_nanf("");
+  }
+}
+
+__global__ void gather_times_kernel(const double* __restrict__ t, uint32_t N, uint32_t n, const uint32_t* __restrict__ nodes,
+                                    double* __restrict__ out) {
+  for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) {
+    const uint32_t v = nodes[i];
+    out[i] = v < N ? t[v] : __builtin_nan("");
   }
 }
 
@@ -126,7 +137,14 @@ void launch_gather_rows(const Dev& d, hipStream_t s, uint32_t layer, uint32_t n,
   uint64_t blocks = ((uint64_t)n * width + 255) / 256;
   if (blocks > 4096) blocks = 4096;
   if (blocks < 1) blocks = 1;
-  hipLaunchKernelGGL(gather_rows_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, d.H[layer], width, n, nodes, out);
+  hipLaunchKernelGGL(gather_rows_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, d.H[layer], d.N, width, n, nodes, out);
+}
+
+void launch_gather_times(const Dev& d, hipStream_t s, uint32_t n, const uint32_t* nodes, double* out) {
+  uint32_t blocks = (n + 255) / 256;
+  if (blocks > 1024) blocks = 1024;
+  if (blocks < 1) blocks = 1;
+  hipLaunchKernelGGL(gather_times_kernel, dim3(blocks), dim3(256), 0, s, d.t_last, d.N, n, nodes, out);
 }
 
 int setup_embed_attributes(const Dev& d) {

@@ -1,7 +1,8 @@
 // Batch staging (validate + endpoint sort + dedupe + adjacency block allocation) and the apply
 // step (append to the temporal adjacency, recent-neighbour rings, edge-feature table, memory
-// commit).  Paper Sec. 3.2.1 (edge queue), 3.2.2 (temporal adjacency list), 3.3.2 (neighbour
-// cache), 3.3.5 (adjacency append, in-place memory write-back).
+// commit).  Paper Sec. 3.2 "Edge Queue" and "Temporal Adjacency List", Sec. 3.3 "Stage 1:
+// Incremental Neighborhood Sampling" (the neighbour cache) and "Stage 5: Incremental Memory Update"
+// (adjacency append, in-place memory write-back).
 #include "stgn_internal.h"
 #include "mfma16.h"
 #include "compaction.h"
@@ -304,15 +305,8 @@ __global__ __launch_bounds__(256) void apply_kernel(Dev d, const uint32_t* __res
       d.H[0].base[(size_t)d.D[dd] * d.H[0].ld + col] = d.mem_new[(size_t)dd * d.d_mem + col];
     }
   }
-  // edge-feature rows (padding columns zeroed: rows are read with 16-byte gathers) and timestamps
-  if (d.d_edge) {
-    const uint32_t ld = d.efeat.ld, tot = n * ld;
-    for (uint32_t x = tid; x < tot; x += nth) {
-      const uint32_t i = x / ld, col = x - i * ld;
-      d.efeat.base[(E0 + i) * ld + col] = col < d.d_edge ? ef[(size_t)i * d.d_edge + col] : 0.0f;
-    }
-  }
-  for (uint32_t i = tid; i < n; i += nth) d.ets[E0 + i] = ts[i];
+  // (the raw edge-feature rows and timestamps are not kept: an edge's features live on in its cached
+  // key|value rows, written by the projecting workgroups of this launch, and its time in the ring records)
 }
 
 __global__ void zero_kernel(float* p, size_t n) {
@@ -358,8 +352,8 @@ void launch_place(const Dev& d, hipStream_t s, uint32_t n, hipEvent_t done) {
 
 void launch_apply(const Dev& d, hipStream_t s, const uint32_t* src, const uint32_t* dst, const double* ts,
                   const float* ef, bool with_compaction, hipEvent_t done) {
-  // sized for the largest section (feature rows of a full batch), grid-stride inside
-  const uint32_t work = d.max_batch * (d.efeat.ld > 2 ? d.efeat.ld : 2);
+  // sized for the largest section (memory rows of a full batch's endpoints), grid-stride inside
+  const uint32_t work = 2 * d.max_batch * (d.d_mem > 1 ? d.d_mem : 1);
   uint32_t blocks = (work + 255) / 256;
   if (blocks > 2048) blocks = 2048;
   if (blocks < 1) blocks = 1;

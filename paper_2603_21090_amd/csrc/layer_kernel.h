@@ -1,5 +1,6 @@
-// Temporal-attention layer for a list of target rows (paper Eq. attn_detail, Sec. 3.3.4 exact
-// mode, Sec. 3.6.2 "single batched kernel" over the affected set), one fused kernel per layer.
+// Temporal-attention layer for a list of target rows (paper Eq. attn_detail; Sec. 3.3 "Stage 4:
+// Incremental Embedding Generation", exact recomputation of the affected rows; Sec. 3.6 "Parallel
+// Batch Processing", one batched kernel over the affected set), one fused kernel per layer.
 //
 // Keys and values are linear in z_j = [h_{u_j} | e_j | phi(t_v - t_j)].  Their node and edge terms are
 // cached rows (per node / per edge, [keys | values], see LayerDev); the time term is re-associated so

@@ -120,12 +120,10 @@ struct Dev {
   uint2*   pool_nt;                  // adjacency pool: (neighbour, position of the twin entry)
   uint32_t* pool_eid;                // adjacency pool: edge id
   uint32_t* blk;                     // [N x maxb] block bases in units of kMinBlock entries
-  Table    efeat;                    // [max_edges x ld]
   // cached key|value rows (see LayerDev): KV[l] of the rows of H[l], KVE[l] of the edge features
   Table    KV[STGN_MAX_LAYERS];      // [N x ld_kv]
   Table    KVE[STGN_MAX_LAYERS];     // [max_edges x ld_kv]; one zero row (ld 0) without edge features
   uint32_t sh, ks, nt, ld_kv;        // slots per head, key slots, time slots, floats per cached row
-  double*  ets;                      // [max_edges] edge timestamps
   // per-batch scratch: two sets, the batches alternate (bind_batch points the plain fields at one of them)
   struct Scratch {
     uint32_t *D, *seg_start, *last_slot, *deg_new, *slot_pos, *slot_d, *slot_sorted;
@@ -242,6 +240,7 @@ bool compact_in_one(const Dev& d);   // the compaction is a single launch (phase
 void launch_layer(const Dev& d, hipStream_t s, uint32_t layer, const uint32_t* rows, const uint32_t* count_ptr,
                   uint32_t count_max);
 void launch_gather_rows(const Dev& d, hipStream_t s, uint32_t layer, uint32_t n, const uint32_t* nodes, float* out);
+void launch_gather_times(const Dev& d, hipStream_t s, uint32_t n, const uint32_t* nodes, double* out);   // last-interaction times
 // root-node inference: roots and query times of n edges; the final layer for the 2n roots; the linear head
 void launch_predict_prep(const Dev& d, hipStream_t s, uint32_t n, const uint32_t* src, const uint32_t* dst, const double* ts);
 void launch_layer_roots(const Dev& d, hipStream_t s, uint32_t nroots);

@@ -247,7 +247,7 @@ def test_temporal_window_of_the_neighbour_cache(binding, window):
     want = o.predict(s, d, t, wp, 0.0, at_edge_time=True)
     got = g.predict_batch(s, d, t, at_edge_time=True)
     H = o.embed_all()[-1].astype(np.float64)
-    bound = REL * (np.linalg.norm(H[s], axis=1) + np.linalg.norm(H[d], axis=1)) * np.linalg.norm(wp) + 1e-5
+    bound = REL * (np.linalg.norm(H[s], axis=1) + np.linalg.norm(H[d], axis=1)) * np.linalg.norm(wp) + 1e-6
     assert (np.abs(got - want) <= bound).all(), np.abs(got - want).max()
     g.close()
 
@@ -368,8 +368,8 @@ def test_random_mix_of_calls_between_overlapped_batches(binding, seed):
                 mode = bool(rng.integers(0, 2))
                 ds, dd, dt, _ = dev(s, d, t, ef)
                 H = o.embed_all()[-1].astype(np.float64)
-                bound = 2 * REL * (np.linalg.norm(H[s], axis=1) * np.linalg.norm(wp[:w.d_emb]) +
-                                   np.linalg.norm(H[d], axis=1) * np.linalg.norm(wp[w.d_emb:])) + 1e-5
+                bound = REL * (np.linalg.norm(H[s], axis=1) * np.linalg.norm(wp[:w.d_emb]) +
+                               np.linalg.norm(H[d], axis=1) * np.linalg.norm(wp[w.d_emb:])) + 1e-6
                 pending.append((f"scores before batch {b}, mode {mode}", g.predict_batch(ds, dd, dt, at_edge_time=mode),
                                 o.predict(s, d, t, wp, 0.25, at_edge_time=mode), bound))
             elif what == 2:
@@ -414,6 +414,67 @@ def test_random_mix_of_calls_between_overlapped_batches(binding, seed):
     for l in range(1, w.layers + 1):
         check_rows(g.get_embeddings(allnodes, layer=l), ref[l - 1], f"layer {l}")
     check_neighbours(g, o, allnodes)
+    g.close()
+
+
+def test_serial_batch_behind_caller_work_then_overlapped_batch(binding):
+    """The first batch after a synchronising call runs wholly on the caller's stream; the next one runs
+    its front part on the library's second stream.  Both staging kernels update the running edge count,
+    the stream time and the batch counter, so the second must stay behind the first even when the first
+    is still queued behind work of the caller's own on that stream.  A few milliseconds of matrix products
+    are parked on the stream before the two batches go in; edge ids, rings, affected set and rows must
+    come out as the oracle's, and no batch may be rejected (a staging kernel that overtook its
+    predecessor would see a stale stream time and refuse it, or hand out edge ids in the wrong order)."""
+    import torch
+    w = tiny_workload(num_nodes=300, num_edges=3000, batch=100, layers=2, k=4, d_mem=16, d_edge=12, d_time=16,
+                      d_emb=16, d_msg=16, zipf_s=0.9)
+    st = synth.EdgeStream(w)
+    W = synth.make_weights(w)
+    o = orc.Oracle.from_workload(w, W)
+    g = binding.StreamTGN.from_workload(w, W)
+    allnodes = np.arange(w.num_nodes, dtype=np.uint32)
+
+    def dev(b):
+        s, d, t, ef = st.batch(b)
+        return (torch.from_numpy(s.astype(np.int32)).cuda(), torch.from_numpy(d.astype(np.int32)).cuda(),
+                torch.from_numpy(t).cuda(), torch.from_numpy(ef).cuda())
+
+    x = torch.randn(2048, 2048, device="cuda")
+    b = 0
+    for rnd in range(5):
+        for _ in range(2):                                   # some state first, synchronised
+            rc, D, A = o.ingest(*st.batch(b))
+            g.ingest_batch(*dev(b)); b += 1
+        assert g.sync() == 0
+        first, second, third = dev(b), dev(b + 1), dev(b + 2)
+        torch.cuda.synchronize()                             # device inputs hold their final contents
+        y = x
+        for _ in range(12):                                  # caller's work, still running when the batches arrive
+            y = (y @ x) * 0.01
+        g.ingest_batch(*first)                               # serial: everything on the caller's stream, behind the products
+        g.ingest_batch(*second)                              # overlapped: front part on the second stream
+        g.ingest_batch(*third)
+        for i in range(3):
+            rc, D, A = o.ingest(*st.batch(b + i))
+            assert rc == 0
+        b += 3
+        assert g.sync(check=False) == 0, f"round {rnd}: a batch was rejected: {g.last_error()}"
+        assert np.array_equal(g.get_affected(), A), f"round {rnd}: affected set"
+        assert g.totals()["edges"] == b * w.batch
+        deg = np.bincount(np.concatenate([st.src[:b * w.batch], st.dst[:b * w.batch]]), minlength=w.num_nodes)
+        for v in np.argsort(deg)[-3:]:                       # full adjacency (edge ids in arrival order) of the busiest nodes
+            nbr, eid = g.get_history(int(v))
+            inc = np.nonzero((st.src[:b * w.batch] == v) | (st.dst[:b * w.batch] == v))[0]
+            assert np.array_equal(eid, inc.astype(np.uint32)), f"round {rnd}: edge ids of node {v}"
+            assert np.array_equal(nbr, np.where(st.src[inc] == v, st.dst[inc], st.src[inc]))
+        check_neighbours(g, o, allnodes)
+        gm, gt = g.get_memory(allnodes)
+        om, ot = o.memory(allnodes)
+        assert np.array_equal(gt, ot)
+        check_rows(gm, om, f"round {rnd}: memory")
+        ref = o.embed_all()
+        for l in range(1, w.layers + 1):
+            check_rows(g.get_embeddings(allnodes, layer=l), ref[l - 1], f"round {rnd}: layer {l}")
     g.close()
 
 

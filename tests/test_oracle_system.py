@@ -100,6 +100,35 @@ def test_affected_set_brute_force_and_theorem_invariants(layers, d_mem, d_node):
         assert n_strict == w.num_batches
 
 
+def test_expanding_through_a_dirty_nodes_own_ring_misses_a_changed_row():
+    """The other reading of the propagation rule -- a dirty node u dirties the members of ITS OWN ring --
+    is not sound.  Hand-built stream: w meets hub u once; u then meets k other nodes, so w has left u's
+    ring while u is still the only entry of w's ring.  A batch that touches u changes u's memory, hence
+    w's row (w attends to u), but walking u's own ring never reaches w.  The rule the oracle follows
+    (w is dirty when a changed node sits in w's ring) does."""
+    k = 3
+    w_ = tiny_workload(num_nodes=10, k=k, layers=1)
+    _, _, o = stream_and_oracle(w_)
+    u, wn, y = 0, 1, 9
+    others = [2, 3, 4]
+    ef = lambda n: np.full((n, w_.d_edge), 0.25, np.float32)
+    assert o.ingest(np.array([wn], np.uint32), np.array([u], np.uint32), np.array([1.0]), ef(1))[0] == 0
+    src = np.array(others, np.uint32)
+    assert o.ingest(src, np.full(len(others), u, np.uint32), np.array([2.0, 3.0, 4.0]), ef(3))[0] == 0
+    assert wn not in o.neighbors(u)[0] and list(o.neighbors(wn)[0]) == [u]
+    before = o.embed_all()
+    rc, D, A = o.ingest(np.array([u], np.uint32), np.array([y], np.uint32), np.array([5.0]), ef(1))
+    assert rc == 0 and set(map(int, D)) == {u, y}
+    after = o.embed_all()
+    changed = set(np.nonzero((after != before).any(axis=(0, 2)))[0].tolist())
+    assert wn in changed                                   # w's row moved ...
+    own_ring_rule = set(map(int, D))
+    for v in map(int, D):
+        own_ring_rule |= set(map(int, o.neighbors(v)[0]))
+    assert wn not in own_ring_rule                         # ... the own-ring walk leaves it outside
+    assert changed <= set(map(int, A)) and wn in set(map(int, A))   # the reverse-membership rule covers it
+
+
 def test_embed_nodes_recursion_equals_layered_table():
     w = tiny_workload(layers=2)
     st, _, o = stream_and_oracle(w)
