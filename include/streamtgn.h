@@ -177,6 +177,20 @@ int stgn_set_predictor(stgn_ctx *ctx, const float *w, float b);
 int stgn_predict_batch(stgn_ctx *ctx, uint32_t n, const uint32_t *src, const uint32_t *dst,
                        const double *ts, int at_edge_time, int inputs_on_device, float *scores);
 
+/* stgn_predict_batch for callers that cannot allocate (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): device inputs and outputs only, asynchronous on hip_stream,
+ * and no allocation of any kind inside the call.  The scratch its kernels need -- the 2n roots, their
+ * query times and their final-layer rows -- lives in a file-scope device array of the library instead
+ * of the workspace: STGN_STATIC_SCRATCH_BYTES per GPU the library has been used on, held until the
+ * process ends.  n edges of d_emb-wide rows need 2n (4 + 8 + 4 d_emb) bytes (each of the three lists
+ * rounded up to 256); a larger n returns STGN_E_BATCH_TOO_LARGE and enqueues nothing.  Nothing in the
+ * array has to start at zero (every entry read is written first by the same call).  All contexts on a
+ * GPU share the array: calls that overlap on one GPU (two streams, two contexts) race; calls on one
+ * stream follow each other.  Same results as stgn_predict_batch with inputs_on_device = 1. */
+#define STGN_STATIC_SCRATCH_BYTES (4u << 20)
+int stgn_predict_batch_static(stgn_ctx *ctx, uint32_t n, const uint32_t *src, const uint32_t *dst,
+                              const double *ts, int at_edge_time, float *scores);
+
 /* Waits for the stream; returns the code of the first skipped device-side batch (and clears it). */
 int stgn_sync(stgn_ctx *ctx);
 

@@ -58,7 +58,7 @@ _lib = None
 EXPORTS = ("stgn_query_workspace", "stgn_create", "stgn_destroy", "stgn_ingest_batch", "stgn_get_embeddings",
            "stgn_full_rebuild", "stgn_sync", "stgn_get_affected", "stgn_get_neighbors", "stgn_get_history",
            "stgn_get_memory", "stgn_get_totals", "stgn_kernel_times", "stgn_last_error", "stgn_version",
-           "stgn_set_predictor", "stgn_predict_batch")
+           "stgn_set_predictor", "stgn_predict_batch", "stgn_predict_batch_static")
 
 
 def load_library():
@@ -88,6 +88,7 @@ def load_library():
                                     C.POINTER(C.c_uint64)]
     L.stgn_set_predictor.argtypes = [vp, vp, C.c_float]
     L.stgn_predict_batch.argtypes = [vp, C.c_uint32, vp, vp, vp, C.c_int, C.c_int, vp]
+    L.stgn_predict_batch_static.argtypes = [vp, C.c_uint32, vp, vp, vp, C.c_int, vp]
     L.stgn_last_error.argtypes = [vp]
     L.stgn_last_error.restype = C.c_char_p
     L.stgn_version.restype = C.c_char_p
@@ -249,6 +250,20 @@ class StreamTGN:
         self._check(self._L.stgn_predict_batch(self._h, len(src), _ptr(src), _ptr(dst), _ptr(ts), int(at_edge_time), 0,
                                                _ptr(out)))
         return out
+
+    def predict_batch_static(self, src, dst, ts, at_edge_time=False, out=None, check=True):
+        """The variant that allocates nothing inside the library: device tensors in, scores into `out`
+        (a device tensor the caller provides; created here when omitted).  Returns `out`, or the
+        error code when check is off and the call failed."""
+        torch = self._torch
+        if out is None:
+            out = torch.empty(src.shape[0], dtype=torch.float32, device=src.device)
+        rc = self._L.stgn_predict_batch_static(self._h, src.shape[0], C.c_void_p(src.data_ptr()),
+                                               C.c_void_p(dst.data_ptr()), C.c_void_p(ts.data_ptr()),
+                                               int(at_edge_time), C.c_void_p(out.data_ptr()))
+        if check:
+            self._check(rc)
+        return out if rc == 0 else rc
 
     def full_rebuild(self):
         self._check(self._L.stgn_full_rebuild(self._h))

@@ -18,6 +18,29 @@ const char* const kClassNames[KC_COUNT] = {"stage_sort", "memory_update", "apply
 
 std::string g_create_error;
 
+// Scratch of the entry point that allocates nothing (stgn_predict_batch_static): the root list, the
+// roots' query times and their final-layer rows live in this array instead of the caller's workspace.
+// Every device the library runs on holds its own copy at its own address; the name below is only a
+// host-side handle, the address kernels may use is looked up once per device (static_scratch()).
+constexpr size_t kStaticScratchBytes = STGN_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// address of the current device's copy of `scratch`; resolved once per device, with that device current
+hipError_t static_scratch(int dev, void** out) {
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return hipSuccess;
+}
+
 struct TimedLaunch { int cls; hipEvent_t a, b; };
 
 }  // namespace
@@ -44,6 +67,7 @@ struct stgn_ctx {
   int last_par = 0;                 // state set of the batch enqueued last
   bool idle = true;                 // nothing was enqueued since the library last synchronised `stream`
   bool have_predictor = false;      // stgn_set_predictor was called
+  unsigned char* static_scratch = nullptr;   // this device's copy of the static scratch array
   std::string err;
   uint64_t host_edges = 0;          // upper bound of edges enqueued so far
   bool host_t_known = true;         // host knows the last ingested timestamp
@@ -473,8 +497,14 @@ int stgn_create(const stgn_config* cfg, const stgn_weights* w, const float* node
   if (strncmp(prop.gcnArchName, "gfx950", 6) != 0)
     return fail(nullptr, STGN_E_DEVICE, std::string("built for gfx950, current device is ") + prop.gcnArchName);
 
+  void* sscratch = nullptr;
+  {
+    const hipError_t e = static_scratch(dev, &sscratch);
+    if (e != hipSuccess) return fail(nullptr, STGN_E_DEVICE, std::string("static scratch lookup: ") + hipGetErrorString(e));
+  }
   stgn_ctx* ctx = new stgn_ctx();
   ctx->cfg = *cfg;
+  ctx->static_scratch = static_cast<unsigned char*>(sscratch);
   memset(&ctx->d, 0, sizeof(Dev));
   layout(*cfg, (char*)device_workspace, &ctx->d);
   ctx->stream = (hipStream_t)hip_stream;
@@ -765,6 +795,45 @@ int stgn_predict_batch(stgn_ctx* ctx, uint32_t n, const uint32_t* src, const uin
     HIPCHK(ctx, hipMemcpyAsync(scores, d.pred_scores, (size_t)n * sizeof(float), hipMemcpyDeviceToHost, s));
     return sync_and_poll(ctx);
   }
+  return STGN_OK;
+}
+
+// Device bytes of static scratch a prediction of n edges needs: the 2n roots, their query times, their rows.
+static size_t static_predict_bytes(uint32_t n, uint32_t d_emb) {
+  auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
+  return up((size_t)2 * n * sizeof(uint32_t)) + up((size_t)2 * n * sizeof(double)) + up((size_t)2 * n * d_emb * sizeof(float));
+}
+
+int stgn_predict_batch_static(stgn_ctx* ctx, uint32_t n, const uint32_t* src, const uint32_t* dst, const double* ts,
+                              int at_edge_time, float* scores) {
+  if (!ctx) return STGN_E_INVALID_ARG;
+  const stgn_config& c = ctx->cfg;
+  if (!ctx->have_predictor) return fail(ctx, STGN_E_INVALID_ARG, "stgn_set_predictor has not been called");
+  if (n > c.max_batch) return fail(ctx, STGN_E_BATCH_TOO_LARGE, "more edges than max_batch");
+  if (static_predict_bytes(n, c.d_emb) > kStaticScratchBytes) {
+    char buf[160];
+    snprintf(buf, sizeof buf, "%u edges of %u-wide rows need %zu bytes of static scratch, the array holds %zu",
+             n, c.d_emb, static_predict_bytes(n, c.d_emb), kStaticScratchBytes);
+    return fail(ctx, STGN_E_BATCH_TOO_LARGE, buf);
+  }
+  if (n == 0) return STGN_OK;
+  if (!src || !dst || !ts || !scores) return fail(ctx, STGN_E_INVALID_ARG, "NULL array");
+  if (!ctx->static_scratch) return fail(ctx, STGN_E_DEVICE, "static scratch was not resolved for this device");
+  // the same kernels as stgn_predict_batch, their scratch lists pointed at the static array
+  Dev d = ctx->d;
+  auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
+  unsigned char* p = ctx->static_scratch;
+  d.pred_rows = reinterpret_cast<uint32_t*>(p);
+  d.pred_tq = reinterpret_cast<double*>(p + up((size_t)2 * n * sizeof(uint32_t)));
+  d.pred_out = reinterpret_cast<float*>(p + up((size_t)2 * n * sizeof(uint32_t)) + up((size_t)2 * n * sizeof(double)));
+  hipStream_t s = ctx->stream;
+  ctx->idle = false;
+  if (at_edge_time) {
+    launch_predict_prep(d, s, n, src, dst, ts);
+    launch_layer_roots(d, s, 2 * n);
+  }
+  launch_predict_head(d, s, n, src, dst, at_edge_time, scores);
+  HIPCHK(ctx, hipGetLastError());
   return STGN_OK;
 }
 
