@@ -4,14 +4,20 @@
 A step is one batch of the synthetic edge stream through the whole hot path
 (stage + sort, message/GRU, apply, dirty-flag propagation, compaction, all attention
 layers for the affected set).  Inputs are resident in device memory before the timed
-region starts.  The stream is replayed from the empty graph:
+region starts.  The stream is replayed from the empty graph, and every pass sits at a
+FIXED position of the stream, whatever --warmup / --steps say:
 
-  warmup   W batches, untimed                              (default: first 70 % of the stream)
-  timed    K batches enqueued back to back, one sync      -> `value` (edges/s), ms_per_step
-  latency  next batches, one sync per batch                -> p50 / p95 batch latency
-  kernels  next batches with one HIP event pair per launch -> per-kernel average duration,
-                                                              roofline of the dominant kernel
-  cpu      the CPU oracle (full recompute per batch) on a bounded sample, 1 core
+  state    batches [0, P), P = 70 % of the stream, untimed: builds the graph state
+  warmup   W more untimed batches                              (--warmup, default 0)
+  timed    K batches enqueued back to back, one sync          -> `value` (edges/s), ms_per_step
+           (--steps, default: all of [P + W, Q), Q = 85 % of the stream; W + K must fit in there)
+  filler   untimed up to batch Q
+  latency  from batch Q on, one sync per batch                 -> p50 / p95 batch latency
+  host     next batches fed from host memory                   -> PCIe-inclusive rate
+  stages   next batches with the library's per-stage events
+  kernels  next batches with one HIP event pair per launch     -> per-kernel average duration,
+                                                                  roofline of the dominant kernel
+  cpu      the CPU oracle on a bounded sample of the same workload, 1 core
 
 Prints ONE JSON line.
 """
@@ -89,12 +95,99 @@ def stored_traffic(workload, batches):
     return float(m.group(1))
 
 
+def cpu_sample_plan(w, st, Q, n_s=40_000):
+    """Large graphs: the nodes whose rows the CPU oracle will evaluate (uniform over all nodes) and the
+    edges their recent-neighbour lists hold after batch Q (ascending edge ids).  Bookkeeping on the raw
+    edge list only."""
+    hi = Q * w.batch
+    rng = np.random.default_rng(7)
+    n_s = min(n_s, w.num_nodes)
+    S = np.sort(rng.choice(w.num_nodes, size=n_s, replace=False)).astype(np.int64)
+    src, dst = st.src[:hi].astype(np.int64), st.dst[:hi].astype(np.int64)
+    inS = np.zeros(w.num_nodes, dtype=bool)
+    inS[S] = True
+    eids = np.nonzero(inS[src] | inS[dst])[0]
+    node = np.concatenate([src[eids], dst[eids]])
+    eid2 = np.concatenate([eids, eids])
+    keep = inS[node]
+    node, eid2 = node[keep], eid2[keep]
+    order = np.lexsort((eid2, node))
+    node, eid2 = node[order], eid2[order]
+    # rank of every entry from the end of its node's list: the last k are the recent-neighbour list
+    n_ent = len(node)
+    last = np.r_[node[1:] != node[:-1], True] if n_ent else np.zeros(0, bool)
+    end_of = np.zeros(n_ent, dtype=np.int64)
+    if n_ent:
+        ends = np.nonzero(last)[0]
+        end_of = ends[np.searchsorted(ends, np.arange(n_ent), side="left")]
+    in_ring = (end_of - np.arange(n_ent)) < w.k
+    return {"S": S, "ring_e": np.unique(eid2[in_ring]), "entries": int(in_ring.sum()), "Q": Q}
+
+
+def cpu_baseline(w, st, weights, nf, Q, cpu_steps, note, plan=None, plan_rows=None):
+    """The CPU oracle (full recompute of every node after every batch, one core) at the stream position
+    the GPU passes are taken at (batch Q).
+
+    Small graphs: the oracle replays the stream up to batch Q, then `cpu_steps` batches are timed, each
+    = ingest + full recompute of all rows.  Large graphs (a full recompute alone would take minutes to
+    hours): the cost of one row is measured on a uniform sample of nodes -- a fresh oracle is fed exactly
+    the edges the sampled nodes' recent-neighbour lists hold after batch Q (`plan`, their feature rows in
+    `plan_rows`) and evaluates their first-layer rows (a row's cost depends on how many entries it
+    attends to and on the widths, equal for all layers here, not on the values) -- and multiplied out to
+    all N nodes and all layers; one real batch is ingested on the same oracle for the message / GRU /
+    append part.  Labelled "extrapolated"."""
+    from oracle import oracle as orc
+    if plan is None:
+        o = orc.Oracle.from_workload(w, weights, nf)
+        for ob in range(Q):
+            o.ingest(*st.batch(ob))
+        note("cpu baseline: oracle state built", force=True)
+        c0 = time.perf_counter()
+        ce = 0
+        for i in range(cpu_steps):
+            s_, d_, t_, e_ = st.batch(Q + i)
+            o.ingest(s_, d_, t_, e_)
+            o.embed_all()                                  # the oracle has no cache: full recompute
+            ce += len(s_)
+        cw = time.perf_counter() - c0
+        return {"value": ce / cw, "unit": "edges/s", "cores": 1, "kind": "oracle",
+                "sample": f"{cpu_steps} batches of {w.batch} edges after {Q} untimed state-building batches (the "
+                          f"position of the GPU passes); each = ingest + full recompute of all {w.num_nodes} nodes, "
+                          f"{w.layers} layers; host has {os.cpu_count()} logical cores, oracle uses 1",
+                "seconds_per_batch": cw / cpu_steps, "extrapolated": False}
+    S, ring_e, entries = plan["S"], plan["ring_e"], plan["entries"]
+    o = orc.Oracle.from_workload(w, weights, nf)
+    for lo in range(0, len(ring_e), w.batch):
+        e = ring_e[lo:lo + w.batch]
+        rc, _, _ = o.ingest(st.src[e], st.dst[e], st.ts[e], plan_rows[lo:lo + w.batch])
+        assert rc == 0
+    note("cpu baseline: sampled neighbourhoods loaded", force=True)
+    c0 = time.perf_counter()
+    o.embed_nodes(S.astype(np.uint32), layer=1)
+    row_s = (time.perf_counter() - c0) / len(S)
+    # one real batch for the message / GRU / append / affected-set part (on a graph far smaller than the real one)
+    s_, d_, t_, e_ = st.batch(Q)
+    if len(ring_e):
+        t_ = t_ - t_[0] + st.ts[ring_e[-1]] + 1.0
+    c0 = time.perf_counter()
+    o.ingest(s_, d_, t_, e_)
+    ing_s = time.perf_counter() - c0
+    per_batch = w.num_nodes * w.layers * row_s + ing_s
+    return {"value": w.batch / per_batch, "unit": "edges/s", "cores": 1, "kind": "oracle",
+            "sample": f"extrapolated: first-layer rows of {len(S)} nodes drawn uniformly from all {w.num_nodes} "
+                      f"({entries} recent-neighbour entries, as held after batch {Q}) evaluated by the oracle in "
+                      f"{row_s * len(S):.1f} s, times N x layers = {w.num_nodes} x {w.layers} rows of a full recompute "
+                      f"per batch, plus one batch ingested ({ing_s:.2f} s); host has {os.cpu_count()} logical "
+                      f"cores, oracle uses 1",
+            "seconds_per_batch": per_batch, "seconds_per_row": row_s, "extrapolated": True}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", default="C2")
+    ap.add_argument("--workload", default="C5")
     ap.add_argument("--predict-reps", type=int, default=20, help="timed repetitions of the root-inference call per mode")
     ap.add_argument("--batch", type=int, default=None, help="override the workload's batch size (ablation sweeps)")
     ap.add_argument("--k", type=int, default=None, help="override the workload's recent-neighbour count (ablation sweeps)")
@@ -122,15 +215,21 @@ def main():
         w = w.scaled(name=f"{w.name}(B={args.batch or w.batch},k={args.k or w.k})", batch=args.batch or w.batch,
                      k=args.k or w.k)
     nb = w.num_batches
-    W = int(0.70 * nb) if args.warmup is None else args.warmup
-    K = int(0.15 * nb) if args.steps is None else args.steps
-    rest = max(nb - W - K, 0)
+    P = int(0.70 * nb)                     # state-building prefix: the same for every invocation
+    Q = int(0.85 * nb)                     # the diagnostic passes start here: the same for every invocation
+    W = 0 if args.warmup is None else args.warmup
+    K = (Q - P - W) if args.steps is None else args.steps
+    rest = nb - Q
     LAT = min(rest * 6 // 15, 160) if args.latency_steps is None else args.latency_steps
     HOST = min(rest * 4 // 15, 48) if args.host_steps is None else args.host_steps
     KER = min(rest - LAT - HOST, 100) if args.kernel_steps is None else args.kernel_steps
-    if W + K + LAT + HOST + KER > nb or K <= 0:
-        print(f"bench.py: warmup {W} + steps {K} + latency {LAT} + host {HOST} + kernel {KER} exceed the stream "
-              f"of {nb} batches", file=sys.stderr)
+    if K <= 0 or W < 0 or P + W + K > Q:
+        print(f"bench.py: warmup {W} + steps {K} do not fit the timed span of {Q - P} batches "
+              f"(batches [{P}, {Q}) of the {nb}-batch stream)", file=sys.stderr)
+        sys.exit(2)
+    if Q + LAT + HOST + KER > nb:
+        print(f"bench.py: latency {LAT} + host {HOST} + kernel {KER} batches exceed the last {rest} batches of the stream",
+              file=sys.stderr)
         sys.exit(2)
 
     last_note = [time.perf_counter()]
@@ -150,17 +249,28 @@ def main():
     g = binding.StreamTGN.from_workload(w, weights, nf)
 
     # the whole stream segment that will be used, resident on the device
-    used = (W + K + LAT + HOST + KER) * w.batch
-    used = min(used, w.num_edges)
+    used = min((Q + LAT + HOST + KER) * w.batch, w.num_edges)
     d_src = torch.from_numpy(st.src[:used].astype(np.int32)).to(dev)
     d_dst = torch.from_numpy(st.dst[:used].astype(np.int32)).to(dev)
     d_ts = torch.from_numpy(st.ts[:used]).to(dev)
     d_ef = torch.empty((used, w.d_edge), dtype=torch.float32, device=dev)
+    # large graphs: which edges the CPU baseline's sampled rows need (their feature rows are picked up below)
+    plan, plan_rows = None, None
+    if not args.no_cpu and args.cpu_steps > 0 and w.num_nodes > 20_000:
+        plan = cpu_sample_plan(w, st, Q)
+        plan_rows = np.zeros((len(plan["ring_e"]), w.d_edge), dtype=np.float32)
     CH = 1 << 18
-    for lo in range(0, used, CH):
-        hi = min(lo + CH, used)
-        d_ef[lo:hi] = torch.from_numpy(st.edge_features(lo, hi)).to(dev)
-        note(f"edge features resident: {hi}/{used}")
+    if w.d_edge:
+        # the feature rows are drawn chunk by chunk from independently keyed generators: several host threads
+        import concurrent.futures as cf
+        with cf.ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as pool:
+            spans = [(lo, min(lo + CH, used)) for lo in range(0, used, CH)]
+            for (lo, hi), rows in zip(spans, pool.map(lambda sp: st.edge_features(*sp), spans)):
+                d_ef[lo:hi] = torch.from_numpy(rows).to(dev)
+                if plan is not None:
+                    i0, i1 = np.searchsorted(plan["ring_e"], [lo, hi])
+                    plan_rows[i0:i1] = rows[plan["ring_e"][i0:i1] - lo]
+                note(f"edge features resident: {hi}/{used}")
     torch.cuda.synchronize()
     note("warm-up", force=True)
 
@@ -169,12 +279,17 @@ def main():
         return g.ingest_batch(d_src[lo:hi], d_dst[lo:hi], d_ts[lo:hi], d_ef[lo:hi], stats=stats)
 
     b = 0
-    for _ in range(W):
-        feed(b); b += 1
-        if b % 256 == 0:
-            g.sync()
-            note(f"warm-up batch {b}/{W}")
-    g.sync()
+
+    def run_untimed(upto, what):
+        nonlocal b
+        while b < upto:
+            feed(b); b += 1
+            if b % 256 == 0:
+                g.sync()
+                note(f"{what}: batch {b}/{upto}")
+        g.sync()
+
+    run_untimed(P + W, "state building")
     tot0 = g.totals()
     note("timed region", force=True)
 
@@ -191,6 +306,7 @@ def main():
     aff = tot1["affected"] - tot0["affected"]
     direct = tot1["direct"] - tot0["direct"]
 
+    run_untimed(Q, "filler up to the diagnostic passes")
     note("latency / host-input / kernel passes", force=True)
     # per-batch latency: enqueue + wait, one batch at a time
     lat = []
@@ -317,24 +433,7 @@ def main():
 
     cpu = None
     if not args.no_cpu and args.cpu_steps > 0:
-        from oracle import oracle as orc
-        o = orc.Oracle.from_workload(w, weights, nf)
-        ob = 0
-        for _ in range(min(W, nb - args.cpu_steps)):      # state building, untimed
-            o.ingest(*st.batch(ob)); ob += 1
-        c0 = time.perf_counter()
-        ce = 0
-        for _ in range(args.cpu_steps):
-            s_, d_, t_, e_ = st.batch(ob); ob += 1
-            o.ingest(s_, d_, t_, e_)
-            o.embed_all()                                  # the oracle has no cache: full recompute
-            ce += len(s_)
-        cw = time.perf_counter() - c0
-        cpu = {"value": ce / cw, "unit": "edges/s", "cores": 1, "kind": "oracle",
-               "sample": f"{args.cpu_steps} batches of {w.batch} edges after {ob - args.cpu_steps} untimed "
-                         f"state-building batches; each = ingest + full recompute of all {w.num_nodes} nodes, "
-                         f"{w.layers} layers; host has {os.cpu_count()} logical cores, oracle uses 1",
-               "seconds_per_batch": cw / args.cpu_steps}
+        cpu = cpu_baseline(w, st, weights, nf, Q, args.cpu_steps, note, plan, plan_rows)
 
     lat_ms = np.array(lat) * 1e3 if lat else np.array([float("nan")])
     out = {
@@ -353,7 +452,8 @@ def main():
         "config": {"workload": f"{w.name}: {w.num_nodes} nodes, {w.num_edges} edges, Zipf s={w.zipf_s}, "
                                f"d_edge={w.d_edge}, d={w.d_emb}, k={w.k}, heads={w.heads}, layers={w.layers}, "
                                f"batch={w.batch}, {'TGN' if w.d_mem else 'TGAT (memoryless)'}",
-                   "batch": w.batch, "layers": w.layers, "k": w.k, "timed_batches": [W, W + K]},
+                   "batch": w.batch, "layers": w.layers, "k": w.k, "timed_batches": [P + W, P + W + K],
+                   "state_building_batches": P, "diagnostic_passes_from_batch": Q},
         "p50_batch_latency_ms": float(np.percentile(lat_ms, 50)),
         "p95_batch_latency_ms": float(np.percentile(lat_ms, 95)),
         "affected_embeddings_per_s": aff / wall,

@@ -64,8 +64,9 @@ def rings_matrix(src, dst, n_edges, num_nodes, k):
     node = np.concatenate([s, d])
     other = np.concatenate([d, s])
     eid = np.concatenate([e, e])
-    side = np.concatenate([np.zeros(n_edges, np.int64), np.ones(n_edges, np.int64)])
-    order = np.lexsort((side, eid, node))            # by node, then arrival (source side first)
+    # by node, then arrival: an edge appears once per node (no self loops), so (node, edge id) is a total
+    # order and one 64-bit key sorts it
+    order = np.argsort(node * np.int64(max(n_edges, 1)) + eid, kind="stable")
     node, other, eid = node[order], other[order], eid[order]
     deg = np.bincount(node, minlength=num_nodes)
     end = np.cumsum(deg)                              # one past the last entry of each node

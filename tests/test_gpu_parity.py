@@ -42,9 +42,11 @@ def check_neighbours(g, o, nodes):
 
 
 def run_stream(binding, w, *, batches=None, check_every=1, full_check_at=(), nodes_for_rings=None, node_feat=None,
-               device_inputs=False, weights=None):
+               device_inputs=False, weights=None, ts_shift=0.0):
     import torch
     st = synth.EdgeStream(w)
+    if ts_shift:
+        st.ts = st.ts + ts_shift                 # the whole stream moved along the time axis (both sides read st)
     W = synth.make_weights(w) if weights is None else weights
     o = orc.Oracle.from_workload(w, W, node_feat)
     g = binding.StreamTGN.from_workload(w, W, node_feat)
@@ -112,6 +114,22 @@ def test_small_graphs_all_shapes(binding, kw):
     w = tiny_workload(num_nodes=150, num_edges=1500, batch=50, zipf_s=1.0, **kw)
     nf = synth.node_features(w)
     g, o, st = run_stream(binding, w, node_feat=nf, full_check_at=set(range(0, 30, 5)))
+    g.close()
+
+
+@pytest.mark.parametrize("shift", [1e7, 1e9])
+@pytest.mark.parametrize("kw", [
+    dict(layers=2, d_mem=16, d_edge=6, d_time=16, d_emb=16, d_msg=16, heads=2, k=4),
+    dict(layers=2, d_mem=100, d_edge=172, d_time=100, d_emb=100, d_msg=100, heads=2, k=10),   # the paper's widths
+])
+def test_timestamps_of_large_magnitude(binding, kw, shift):
+    """Every timestamp moved by 1e7 and by 1e9 (the paper's largest streams reach such values).  A node's
+    first message then encodes a gap of that size (its last-interaction time starts at 0), where the
+    argument omega * dt + phase only makes sense reduced in fp64; attention gaps stay differences of
+    fp64 times.  Memory and both layers against the oracle, which evaluates cos of the fp64 argument."""
+    w = tiny_workload(num_nodes=150, num_edges=1500, batch=50, zipf_s=1.0, **kw)
+    g, o, st = run_stream(binding, w, full_check_at=set(range(0, 30, 5)), ts_shift=shift)
+    assert st.ts[0] > 0.99 * shift
     g.close()
 
 
@@ -731,9 +749,10 @@ def test_edge_capacity_is_enforced(binding):
 
 
 def test_c2_stream_sampled(binding):
-    """Config 2 (the benchmark workload), first 300 batches with device-resident inputs as the
-    benchmark feeds them: exact affected set every batch; memory and sampled embeddings at
-    checkpoints; one full comparison of all rows at the end."""
+    """Config 2, the WHOLE stream of 1,000 batches with device-resident inputs as the benchmark feeds
+    them: exact affected set on every batch; memory of the batch's endpoints and sampled embeddings
+    (inside and outside the affected set) at checkpoints that include the span the benchmark times
+    (batches 700-850) and the end of the stream; all rows of both layers at the end."""
     import torch
     w = synth.WORKLOADS["C2"]
     st = synth.EdgeStream(w)
@@ -742,15 +761,19 @@ def test_c2_stream_sampled(binding):
     g = binding.StreamTGN.from_workload(w, W)
     rng = np.random.default_rng(5)
     allnodes = np.arange(w.num_nodes, dtype=np.uint32)
-    nb = 300
+    nb = w.num_batches
+    d_src = torch.from_numpy(st.src.astype(np.int32)).cuda()
+    d_dst = torch.from_numpy(st.dst.astype(np.int32)).cuda()
+    d_ts = torch.from_numpy(st.ts).cuda()
+    d_ef = torch.from_numpy(st.edge_features(0, w.num_edges)).cuda()
+    checkpoints = {59, 299, 499, 700, 775, 850, 925, 999}
     for b in range(nb):
         s, d, t, ef = st.batch(b)
         rc, D, A = o.ingest(s, d, t, ef)
-        dev = (torch.from_numpy(s.astype(np.int32)).cuda(), torch.from_numpy(d.astype(np.int32)).cuda(),
-               torch.from_numpy(t).cuda(), torch.from_numpy(ef).cuda())
-        g.ingest_batch(*dev)
+        lo, hi = b * w.batch, (b + 1) * w.batch
+        g.ingest_batch(d_src[lo:hi], d_dst[lo:hi], d_ts[lo:hi], d_ef[lo:hi])
         assert np.array_equal(g.get_affected(), A), f"batch {b}"
-        if b % 60 == 59:
+        if b in checkpoints:
             gm, gt = g.get_memory(D)
             om, ot = o.memory(D)
             assert np.array_equal(gt, ot)
@@ -758,9 +781,14 @@ def test_c2_stream_sampled(binding):
             inA = rng.choice(A, size=60, replace=False)
             out = rng.choice(np.setdiff1d(allnodes, A), size=20, replace=False)
             S = np.concatenate([inA, out]).astype(np.uint32)
-            check_rows(g.get_embeddings(S), o.embed_nodes(S), f"batch {b}: sampled embeddings")
+            for l in (1, 2):
+                check_rows(g.get_embeddings(S, layer=l), o.embed_nodes(S, layer=l), f"batch {b}: sampled rows of layer {l}")
             check_neighbours(g, o, S[:20])
     ref = o.embed_all()
     for l in (1, 2):
         check_rows(g.get_embeddings(allnodes, layer=l), ref[l - 1], f"final layer {l}")
+    gm, gt = g.get_memory(allnodes)
+    om, ot = o.memory(allnodes)
+    assert np.array_equal(gt, ot)
+    check_rows(gm, om, "final memory")
     g.close()

@@ -360,3 +360,20 @@ def test_mean_and_sum_aggregators_against_vectorised_torch(agg):
         assert np.abs(got.astype(np.float64) - mem).max() <= 5e-7
         mem = got.copy()                                             # follow the oracle's rounding
     assert multi > 50, "the stream has no node with several messages in one batch: the case tests nothing"
+
+
+def test_vectorised_ring_table_matches_the_brute_force_lists():
+    """`rings_matrix` (used by the full-size GPU tests) against the per-node Python lists."""
+    from tests.helpers import affected_from_rings, rings_matrix
+    w = tiny_workload(num_nodes=30, num_edges=500, k=4, zipf_s=1.2)
+    st = synth.EdgeStream(w)
+    for hi in (0, 1, 37, 500):
+        nbr_m, eid_m, deg = rings_matrix(st.src, st.dst, hi, w.num_nodes, w.k)
+        rings = brute_rings(st.src, st.dst, hi, w.num_nodes, w.k)
+        for v in range(w.num_nodes):
+            c = min(int(deg[v]), w.k)
+            assert [(int(a), int(e)) for a, e in zip(nbr_m[v, :c], eid_m[v, :c])] == rings[v]
+            assert (nbr_m[v, c:] == -1).all()
+        D = np.unique(np.concatenate([st.src[max(hi - 20, 0):hi], st.dst[max(hi - 20, 0):hi]])).astype(np.uint32)
+        if len(D):
+            assert np.array_equal(affected_from_rings(nbr_m, D, 2), brute_affected(rings, D, 2))
