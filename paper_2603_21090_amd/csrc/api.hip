@@ -14,7 +14,7 @@ using namespace stgn;
 namespace {
 
 const char* const kClassNames[KC_COUNT] = {"stage_sort", "memory_update", "apply", "plan", "expand", "compact",
-                                           "layer", "gather_rows", "noop", "project", "predict"};
+                                           "layer", "gather_rows", "noop", "project", "predict", "bucket_rows"};
 
 std::string g_create_error;
 
@@ -229,6 +229,13 @@ size_t layout(const stgn_config& c, char* base, Dev* d) {
     if (d->thr[l] >= c.layers + 1) { d->R[l] = d->A; d->thr[l] = 0xFFu; }
     else { d->R[l] = b.take<uint32_t>(N); ++d->n_lists; }
   }
+  // row lists regrouped by entry count: worth a launch once a layer has thousands of tiles
+  d->bucketed = N >= 32768u ? 1u : 0u;
+  for (uint32_t l = 0; l < c.layers; ++l) {
+    if (!d->bucketed) d->RS[l] = nullptr;
+    else if (l && d->thr[l] == 0xFFu && d->thr[l - 1] == 0xFFu) d->RS[l] = d->RS[l - 1];   // both walk A (pointers are null while measuring)
+    else d->RS[l] = b.take<uint32_t>(N);
+  }
   for (uint32_t l = 0; l < c.layers; ++l) d->L[l].d_in = l == 0 ? d->d0 : c.d_emb;
   d->pred_rows = b.take<uint32_t>(B2);
   d->pred_tq = b.take<double>(B2);
@@ -414,10 +421,11 @@ void drain_timing(stgn_ctx* ctx) {
 // every layer over all rows (initial state, full rebuild) or over the per-layer lists of the last batch
 void run_layers(stgn_ctx* ctx, const Dev& d, bool all_rows) {
   if (all_rows) { Scope s(ctx, KC_PROJECT); launch_project_nodes(d, ctx->stream); }   // cached keys|values of the layer-0 rows
+  if (d.bucketed) { Scope s(ctx, KC_BUCKET); launch_bucket_rows(d, ctx->stream, all_rows); }
   for (uint32_t l = 0; l < d.layers; ++l) {
     Scope s(ctx, KC_LAYER);
-    if (all_rows) launch_layer(d, ctx->stream, l, nullptr, nullptr, d.N);
-    else launch_layer(d, ctx->stream, l, d.R[l], &d.bc->nR[l], d.N);
+    if (all_rows) launch_layer(d, ctx->stream, l, d.bucketed ? d.RS[0] : nullptr, nullptr, d.N);
+    else launch_layer(d, ctx->stream, l, d.bucketed ? d.RS[l] : d.R[l], &d.bc->nR[l], d.N);
   }
 }
 

@@ -247,6 +247,59 @@ __global__ __launch_bounds__(256) void compact_write_kernel(Dev d) {
   if (blockIdx.x == gridDim.x - 1 && t == 0) finish_batch(d, total);
 }
 
+// Orders a layer's row list so that rows with equally many recent-neighbour entries sit together.  The
+// attention kernel serves four rows per wave in lockstep and sixteen per workgroup, so a tile costs what
+// its LONGEST row costs: on skewed graphs a tile of sixteen consecutive ids runs to nearly k entries while
+// the mean row holds a few.  Within every window of 4,096 list positions the rows are regrouped by
+// descending entry count min(deg, k) (a counting sort, stable: ids stay ascending inside a group, and the
+// order is the same on every run); tiles cut from the regrouped list are homogeneous.  A row's result does
+// not depend on which rows share its tile, so only the cost changes.  grid.y = list.
+constexpr uint32_t kBucketWindow = 4096;
+constexpr uint32_t kMaxBins = 65;                            // entry counts 0 .. k, k <= 64
+struct BucketJob { const uint32_t* in; const uint32_t* count; uint32_t* out; uint32_t count_max; };
+struct BucketJobs { BucketJob j[STGN_MAX_LAYERS]; };
+__global__ __launch_bounds__(256) void bucket_rows_kernel(Dev d, BucketJobs jobs) {
+  __shared__ uint32_t s[4];
+  __shared__ uint32_t s_hist[kMaxBins], s_base[kMaxBins];
+  const BucketJob job = jobs.j[blockIdx.y];
+  uint32_t n = job.count_max;
+  if (job.count) { const uint32_t c = *job.count; n = c < n ? c : n; }
+  const uint32_t w0 = blockIdx.x * kBucketWindow;
+  if (w0 >= n) return;
+  const uint32_t t = threadIdx.x, p0 = w0 + t * 16u;
+  const uint32_t nb = d.k + 1u;
+  if (t < nb) s_hist[t] = 0u;
+  __syncthreads();
+  uint32_t id[16], bin[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const uint32_t p = p0 + i;
+    id[i] = p < n ? (job.in ? job.in[p] : p) : 0xFFFFFFFFu;
+    uint32_t b = 0xFFu;                                      // no row
+    if (p < n) { const uint32_t dg = d.deg[id[i]]; b = d.k - (dg < d.k ? dg : d.k); }   // bin 0 = full rings: longest rows first
+    bin[i] = b;
+    if (b != 0xFFu) atomicAdd(&s_hist[b], 1u);
+  }
+  __syncthreads();
+  if (t == 0) {
+    uint32_t run = 0;
+    for (uint32_t b = 0; b < nb; ++b) { s_base[b] = run; run += s_hist[b]; }
+  }
+  __syncthreads();
+  for (uint32_t b = 0; b < nb; ++b) {
+    if (s_hist[b] == 0u) continue;                           // the same for every thread
+    uint32_t mine = 0;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) mine += bin[i] == b ? 1u : 0u;
+    uint32_t excl;
+    block_scan_256(mine, s, &excl);
+    uint32_t o = w0 + s_base[b] + excl;
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+      if (bin[i] == b) job.out[o++] = id[i];
+  }
+}
+
 __global__ __launch_bounds__(256) void compact_small_kernel(Dev d, uint32_t last_value) {
   __shared__ uint32_t s[256];
   compact_small_block(d, last_value, blockIdx.x, gridDim.x, s);
@@ -273,6 +326,22 @@ void launch_expand(const Dev& d, hipStream_t s, uint32_t hop, bool planned, hipE
   uint64_t want = ((uint64_t)d.N + 63) / 64;
   uint32_t blocks = want > 4096 ? 4096u : (uint32_t)(want ? want : 1);
   launch_done(expand_kernel, dim3(blocks), dim3(256), 0, s, done, d, hop, planned ? 1u : 0u);
+}
+
+// the lists the layers of a batch (all_rows = false) or of a rebuild (true) walk, regrouped by entry count
+void launch_bucket_rows(const Dev& d, hipStream_t s, bool all_rows) {
+  BucketJobs jobs{};
+  uint32_t nj = 0;
+  if (all_rows) {
+    jobs.j[nj++] = BucketJob{nullptr, nullptr, d.RS[0], d.N};
+  } else {
+    for (uint32_t l = 0; l < d.layers; ++l) {
+      if (l && d.R[l] == d.R[l - 1]) continue;               // the same list: ordered once (its copy is shared)
+      jobs.j[nj++] = BucketJob{d.R[l], &d.bc->nR[l], d.RS[l], d.N};
+    }
+  }
+  const uint32_t blocks = (d.N + kBucketWindow - 1) / kBucketWindow;
+  hipLaunchKernelGGL(bucket_rows_kernel, dim3(blocks, nj), dim3(256), 0, s, d, jobs);
 }
 
 bool compact_in_one(const Dev& d) { return (d.N + kFlagsPerBlock - 1) / kFlagsPerBlock <= kSmallBlocks; }

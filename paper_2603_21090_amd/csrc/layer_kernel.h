@@ -267,7 +267,15 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
   };
   if (pf_ok) stage_b(); else stage_none();
 
-  for (uint32_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+  // Round i gives workgroup b the tile i G + (b + 37 i) mod G (G workgroups): every round is a permutation of
+  // its G tiles, and a workgroup's position inside the round moves from round to round.  The row list may
+  // be regrouped by entry count in windows of 256 tiles (long rows first), so a fixed position would hand
+  // the same workgroups every long tile.
+  const uint32_t G = gridDim.x;
+  auto tile_of = [&](uint32_t i) { return i * G + (blockIdx.x + 37u * i) % G; };
+  for (uint32_t round = 0;; ++round) {
+    const uint32_t tile = tile_of(round);
+    if (tile >= ntiles) break;                                // wave-uniform; only in a workgroup's last round
     derive_lane();
     // ================================================================ phase 0: stage the tile
     Ops16<2> oq;                                              // first weight chunk of this wave's first unit
@@ -325,7 +333,7 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
       }
       __syncthreads();
     }
-    stage_a(tile + gridDim.x);                               // row ids of this workgroup's next tile
+    stage_a(tile_of(round + 1u));                            // row ids of this workgroup's next tile
     // ---- this lane group's row: entry count, query time, ring records; the first chunk of cached
     // rows is requested now and arrives while the projections below run
     const uint32_t local = wave * 4u + grp;

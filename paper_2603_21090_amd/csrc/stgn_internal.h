@@ -158,6 +158,10 @@ struct Dev {
   // the first l hops with a memory, one hop less without one, where layer-0 inputs never change).
   // R[l] is that ascending sub-list of A (A itself where the threshold covers every flag).
   uint32_t* R[STGN_MAX_LAYERS];
+  // RS[l]: R[l] regrouped by recent-neighbour entry count (bucket_rows_kernel), what the layer launches walk on
+  // graphs large enough for it to pay (bucketed); layers that share a list share the copy
+  uint32_t* RS[STGN_MAX_LAYERS];
+  uint32_t bucketed;
   uint32_t thr[STGN_MAX_LAYERS];
   uint32_t n_lists;                  // separate lists (layers whose threshold does not cover every flag)
   // root-node inference (stgn_predict_batch): the 2n roots (source, destination of edge i at 2i, 2i+1),
@@ -212,7 +216,7 @@ __device__ inline unsigned long long stripes_sum_thread(const Dev& d, uint32_t c
 
 // Kernel classes for the optional event timing
 enum KernelClass { KC_SORT = 0, KC_MEMORY, KC_APPLY, KC_PLAN, KC_EXPAND, KC_COMPACT, KC_LAYER,
-                   KC_GATHER, KC_NOOP, KC_PROJECT, KC_PREDICT, KC_COUNT };
+                   KC_GATHER, KC_NOOP, KC_PROJECT, KC_PREDICT, KC_BUCKET, KC_COUNT };
 
 // A launch whose completion is an event (`done`, may be null): the event rides on the kernel's own
 // completion signal instead of a marker of its own behind it, which costs the stream a microsecond or
@@ -236,6 +240,7 @@ void launch_apply(const Dev& d, hipStream_t s, const uint32_t* src, const uint32
 void launch_plan(const Dev& d, hipStream_t s, uint32_t hop);
 void launch_expand(const Dev& d, hipStream_t s, uint32_t hop, bool planned, hipEvent_t done = nullptr);
 void launch_compact(const Dev& d, hipStream_t s, int phase);
+void launch_bucket_rows(const Dev& d, hipStream_t s, bool all_rows);   // regroups the layers' row lists by entry count (Dev::RS)
 bool compact_in_one(const Dev& d);   // the compaction is a single launch (phase 0) for this node count
 void launch_layer(const Dev& d, hipStream_t s, uint32_t layer, const uint32_t* rows, const uint32_t* count_ptr,
                   uint32_t count_max);
