@@ -60,6 +60,15 @@ def lib():
         _lib.orc_degree.argtypes = [C.c_void_p, C.c_uint32]
         _lib.orc_memory.argtypes = [C.c_void_p, C.c_uint32, _u32p, _f32p, _f64p]
         _lib.orc_set_memory.argtypes = [C.c_void_p, C.c_uint32, _u32p, _f32p, _f64p]
+        _lib.orc_delta_enable.argtypes = [C.c_void_p, C.c_double]
+        _lib.orc_delta_rows.argtypes = [C.c_void_p, C.c_uint32, C.c_uint32, _u32p, _f32p]
+        _lib.orc_delta_attn.restype = C.c_uint32
+        _lib.orc_delta_attn.argtypes = [C.c_void_p, C.c_uint32, C.c_uint32, _f64p, _f64p]
+        _lib.orc_delta_last_fractions.argtypes = [C.c_void_p, _f32p]
+        _lib.orc_drift_status.argtypes = [C.c_void_p, _f64p, _u32p, _f64p]
+        _lib.orc_maintain.restype = C.c_int
+        _lib.orc_maintain.argtypes = [C.c_void_p, C.c_double, C.c_double, _u32p]
+        _lib.orc_delta_full_rebuild.argtypes = [C.c_void_p]
         _lib.orc_time_encode.argtypes = [C.c_uint32, _f32p, _f32p, C.c_double, _f64p]
         _lib.orc_message.argtypes = [C.c_void_p, _f32p, _f32p, _f32p, C.c_double, _f64p]
         _lib.orc_gru.argtypes = [C.c_uint32, C.c_uint32] + [_f32p] * 9 + [_f64p] * 3
@@ -153,6 +162,49 @@ class Oracle:
         lib().orc_predict(self._h, len(src), _p(src, _u32p), _p(dst, _u32p), _p(ts, _f64p), int(at_edge_time),
                           _p(w, _f32p), float(b), _p(out, _f64p))
         return out
+
+    # ---- delta mode and drift-aware rebuild scheduling (approximate mode of the method)
+    def delta_enable(self, gamma=0.9):
+        """Switches the delta mode on: every later ingest refreshes the cached rows, exactly where a row's own
+        input or query time changed, by the delta update elsewhere.  Rebuilds every cache exactly first."""
+        lib().orc_delta_enable(self._h, float(gamma))
+
+    def delta_rows(self, nodes, layer=None) -> np.ndarray:
+        nodes = np.ascontiguousarray(nodes, dtype=np.uint32)
+        layer = self.layers if layer is None else layer
+        out = np.empty((len(nodes), self.d_emb), dtype=np.float32)
+        lib().orc_delta_rows(self._h, layer, len(nodes), _p(nodes, _u32p), _p(out, _f32p))
+        return out
+
+    def delta_attn(self, node, layer=None):
+        """(weights in effect, scores) of a row's attention cache, each [entries x heads]."""
+        layer = self.layers if layer is None else layer
+        H = self.cfg.heads
+        a = np.zeros(self.k * H, dtype=np.float64)
+        s = np.zeros(self.k * H, dtype=np.float64)
+        n = lib().orc_delta_attn(self._h, layer, int(node), _p(a, _f64p), _p(s, _f64p))
+        return a[:n * H].reshape(n, H).copy(), s[:n * H].reshape(n, H).copy()
+
+    def delta_last_fractions(self) -> np.ndarray:
+        out = np.empty(self.N, dtype=np.float32)
+        lib().orc_delta_last_fractions(self._h, _p(out, _f32p))
+        return out
+
+    def drift_status(self):
+        """(global drift metric, size of the cumulative affected set, per-node estimates)."""
+        g, c = C.c_double(0.0), C.c_uint32(0)
+        per = np.empty(self.N, dtype=np.float64)
+        lib().orc_drift_status(self._h, C.byref(g), C.byref(c), _p(per, _f64p))
+        return g.value, c.value, per
+
+    def maintain(self, delta_max, alpha):
+        """Adaptive rebuild policy; returns (action, drifted nodes): 0 nothing, 1 partial, 2 full rebuild."""
+        n = C.c_uint32(0)
+        act = lib().orc_maintain(self._h, float(delta_max), float(alpha), C.byref(n))
+        return act, n.value
+
+    def delta_full_rebuild(self):
+        lib().orc_delta_full_rebuild(self._h)
 
     def neighbors(self, node):
         nbr = np.empty(self.k, dtype=np.uint32)

@@ -23,6 +23,11 @@
 //   batching ................. Sec. 3.6.2 (pre-batch memory for all reads, one GRU
 //                              transition per node per batch)
 //   root inference + score ... Algorithm 1 (embed, predict, then update), Eq. (parallel_embed)
+//   delta mode ............... Sec. 3.3 "Stage 4: Incremental Embedding Generation" (Eq. delta_embedding, the
+//                              attention cache), Sec. 3.4 "Correctness of Incremental Computation" (delta mode);
+//                              an approximation: the algorithm's steps in the paper's order
+//   drift estimator, rebuild . Sec. 3.5 (Definition "Drift Estimator", Eq. global_drift, Eq. rebuild_trigger,
+//                              partial / full rebuild)
 //
 // Pins (tests/test_oracle_*.py): closed forms for the time encoding and the GRU,
 // library GRU cell and library scaled-dot-product attention as cross-checks,
@@ -47,7 +52,35 @@ struct Layer {
   std::vector<float> WQ, WK, WV, WO, bO;
 };
 
+// ---- delta mode (approximate; Sec. 3.3 Stage 4, "Delta embedding" and "Attention score caching")
+// AttnCache of one (layer, node): per recent-neighbour entry the score, the weight currently in effect in
+// the cached sums, and the part of the value that depends on the neighbour and the edge; per row the sums
+// themselves.  The value of entry j is V_j = Vc_j + phi_j W_V[time rows]; the head output is kept as
+// o_h = S_h + pb_h W_V,h[time rows] with S = sum_j a_j Vc_j and pb_h = sum_j a_{h,j} phi_j.
+struct AttnRow {
+  bool valid = false;
+  std::vector<uint32_t> eid;            // the entries the row was built on, most recent first
+  std::vector<double> s, a;             // [n x heads] scores, weights in effect
+  std::vector<double> vc;               // [n x d_emb]
+  std::vector<double> S, pb, Z, m;      // [d_emb], [heads x d_time], [heads], [heads] (softmax denominator and its reference score)
+};
+struct Delta {
+  bool on = false;
+  double gamma = 0.9;
+  std::vector<std::vector<float>> H;            // [layers][N x d_emb] cached rows (fp32, as the method stores them)
+  std::vector<std::vector<AttnRow>> ac;         // [layers][N]
+  // drift estimator (Sec. 3.5): per node a running sum with lazy decay, globally their sum and the
+  // size of the cumulative affected set since the last rebuild
+  std::vector<double> dsum;
+  std::vector<uint32_t> dlast;
+  std::vector<char> seen;
+  double G = 0.0;
+  uint32_t count = 0, tau = 0;
+  std::vector<float> last_frac;                 // per node: changed fraction in the last batch (final layer); -1 exact, -2 untouched
+};
+
 struct Oracle {
+  Delta dl;
   double window = 0.0;               // T_w; <= 0: no expiry
   uint32_t aggregator = 0;           // 0 Last, 1 Mean, 2 Sum
   uint32_t N, d_mem, d_node, d_edge, d_time, d_emb, d_msg, k, heads, layers;
@@ -200,6 +233,188 @@ void embed_row(const Oracle& o, uint32_t l, uint32_t v, PrevRow prev, float* out
   embed_row_at(o, l, v, o.t_last[v], prev, out_row);
 }
 
+// ---------------------------------------------------------------------------------------------------
+// Delta mode.  Layer l (1-based) reads the CACHED rows of layer l - 1 (layer 0: memory | features).
+
+void delta_prev_row(const Oracle& o, uint32_t l, uint32_t u, float* row) {
+  if (l == 1) { h0_row(o, u, row); return; }
+  std::memcpy(row, &o.dl.H[l - 2][(size_t)u * o.d_emb], o.d_emb * sizeof(float));
+}
+
+// q of row v at layer l (Eq. attn_detail, query side [h_v || phi(0)] W_Q)
+void delta_query(const Oracle& o, uint32_t l, uint32_t v, double* q) {
+  const Layer& Ly = o.L[l - 1];
+  std::vector<double> qin(Ly.d_in + o.d_time);
+  std::vector<float> hrow(Ly.d_in);
+  delta_prev_row(o, l, v, hrow.data());
+  for (uint32_t i = 0; i < Ly.d_in; ++i) qin[i] = hrow[i];
+  time_encode(o.d_time, o.omega.data(), o.phase.data(), 0.0, qin.data() + Ly.d_in);
+  vecmat(qin.data(), Ly.WQ.data(), nullptr, Ly.d_in + o.d_time, o.d_emb, q);
+}
+
+// One entry (neighbour u, edge e) of row v at layer l, query time tq: per-head score, the neighbour|edge
+// part of the value, and the time encoding of the gap.
+void delta_entry(const Oracle& o, uint32_t l, const double* q, const Entry& en, double tq,
+                 double* score, double* vc, double* phi) {
+  const Layer& Ly = o.L[l - 1];
+  const uint32_t din = Ly.d_in, d = o.d_emb, dt = o.d_time, de = o.d_edge, dk = d / o.heads;
+  std::vector<double> z(din + de + dt), K(d);
+  std::vector<float> hrow(din);
+  delta_prev_row(o, l, en.nbr, hrow.data());
+  for (uint32_t i = 0; i < din; ++i) z[i] = hrow[i];
+  for (uint32_t i = 0; i < de; ++i) z[din + i] = o.efeat[(size_t)en.eid * de + i];
+  time_encode(dt, o.omega.data(), o.phase.data(), tq - o.ts[en.eid], phi);
+  for (uint32_t i = 0; i < dt; ++i) z[din + de + i] = phi[i];
+  vecmat(z.data(), Ly.WK.data(), nullptr, din + de + dt, d, K.data());
+  for (uint32_t h = 0; h < o.heads; ++h) {
+    double acc = 0.0;
+    for (uint32_t c = 0; c < dk; ++c) acc += q[h * dk + c] * K[h * dk + c];
+    score[h] = acc / std::sqrt((double)dk);
+  }
+  vecmat(z.data(), Ly.WV.data(), nullptr, din + de, d, vc);       // node and edge rows of W_V only
+}
+
+// the cached row from the cached sums: o_h = S_h + pb_h W_V,h[time rows]; row = o W_O + b_O
+void delta_emit(Oracle& o, uint32_t l, uint32_t v) {
+  const Layer& Ly = o.L[l - 1];
+  const AttnRow& r = o.dl.ac[l - 1][v];
+  const uint32_t d = o.d_emb, dt = o.d_time, dk = d / o.heads, t0 = Ly.d_in + o.d_edge;
+  std::vector<double> oh(r.S), res(d);
+  for (uint32_t h = 0; h < o.heads; ++h)
+    for (uint32_t c = 0; c < dk; ++c) {
+      double acc = 0.0;
+      for (uint32_t i = 0; i < dt; ++i) acc += r.pb[h * dt + i] * (double)Ly.WV[(size_t)(t0 + i) * d + h * dk + c];
+      oh[h * dk + c] += acc;
+    }
+  vecmat(oh.data(), Ly.WO.data(), Ly.bO.data(), d, d, res.data());
+  float* out = &o.dl.H[l - 1][(size_t)v * d];
+  for (uint32_t i = 0; i < d; ++i) out[i] = (float)res[i];
+}
+
+// Exact recomputation of row v at layer l; refreshes its attention cache.
+void delta_exact_row(Oracle& o, uint32_t l, uint32_t v) {
+  const uint32_t d = o.d_emb, dt = o.d_time, H = o.heads, dk = d / H;
+  const double tq = o.t_last[v];
+  std::vector<Entry> nb = recent(o, v);
+  if (o.window > 0.0)
+    nb.erase(std::remove_if(nb.begin(), nb.end(), [&](const Entry& e) { return tq - o.ts[e.eid] > o.window; }), nb.end());
+  const uint32_t n = (uint32_t)nb.size();
+  AttnRow& r = o.dl.ac[l - 1][v];
+  r.valid = true;
+  r.eid.resize(n);
+  r.s.assign((size_t)n * H, 0.0); r.a.assign((size_t)n * H, 0.0); r.vc.assign((size_t)n * d, 0.0);
+  r.S.assign(d, 0.0); r.pb.assign((size_t)H * dt, 0.0); r.Z.assign(H, 0.0); r.m.assign(H, 0.0);
+  std::vector<double> q(d), phi((size_t)n * dt);
+  delta_query(o, l, v, q.data());
+  for (uint32_t j = 0; j < n; ++j) {
+    r.eid[j] = nb[j].eid;
+    delta_entry(o, l, q.data(), nb[j], tq, &r.s[(size_t)j * H], &r.vc[(size_t)j * d], &phi[(size_t)j * dt]);
+  }
+  for (uint32_t h = 0; h < H && n; ++h) {
+    double mx = -INFINITY;
+    for (uint32_t j = 0; j < n; ++j) mx = std::max(mx, r.s[(size_t)j * H + h]);
+    double den = 0.0;
+    for (uint32_t j = 0; j < n; ++j) den += std::exp(r.s[(size_t)j * H + h] - mx);
+    r.m[h] = mx; r.Z[h] = den;
+    for (uint32_t j = 0; j < n; ++j) {
+      const double a = std::exp(r.s[(size_t)j * H + h] - mx) / den;
+      r.a[(size_t)j * H + h] = a;
+      for (uint32_t c = 0; c < dk; ++c) r.S[h * dk + c] += a * r.vc[(size_t)j * d + h * dk + c];
+      for (uint32_t i = 0; i < dt; ++i) r.pb[h * dt + i] += a * phi[(size_t)j * dt + i];
+    }
+  }
+  delta_emit(o, l, v);
+}
+
+// Delta update of row v at layer l (Eq. delta_embedding, "updated neighbours"): the row itself, its query
+// time and its entries are unchanged; entries whose neighbour's input row changed get a new score, a new
+// weight from the updated denominator and a new value part, the other entries keep the weight they have.
+// Returns the number of changed entries.
+template <class Changed>
+uint32_t delta_update_row(Oracle& o, uint32_t l, uint32_t v, Changed changed) {
+  const uint32_t d = o.d_emb, dt = o.d_time, H = o.heads, dk = d / H;
+  AttnRow& r = o.dl.ac[l - 1][v];
+  const uint32_t n = (uint32_t)r.eid.size();
+  const double tq = o.t_last[v];
+  std::vector<double> q(d), sc(H), vc(d), phi(dt);
+  delta_query(o, l, v, q.data());
+  uint32_t nch = 0;
+  for (uint32_t j = 0; j < n; ++j) {
+    const uint32_t e = r.eid[j];
+    const Entry en{o.src[e] == v ? o.dst[e] : o.src[e], e};
+    if (!changed(en.nbr)) continue;
+    ++nch;
+    delta_entry(o, l, q.data(), en, tq, sc.data(), vc.data(), phi.data());
+    for (uint32_t h = 0; h < H; ++h) {
+      const double e_old = std::exp(r.s[(size_t)j * H + h] - r.m[h]), e_new = std::exp(sc[h] - r.m[h]);
+      const double Zn = r.Z[h] - e_old + e_new;
+      const double a_old = r.a[(size_t)j * H + h], a_new = e_new / Zn;
+      for (uint32_t c = 0; c < dk; ++c)
+        r.S[h * dk + c] += a_new * vc[h * dk + c] - a_old * r.vc[(size_t)j * d + h * dk + c];
+      for (uint32_t i = 0; i < dt; ++i) r.pb[h * dt + i] += (a_new - a_old) * phi[i];
+      r.s[(size_t)j * H + h] = sc[h];
+      r.a[(size_t)j * H + h] = a_new;
+      r.Z[h] = Zn;
+    }
+    for (uint32_t c = 0; c < d; ++c) r.vc[(size_t)j * d + c] = vc[c];
+  }
+  delta_emit(o, l, v);
+  return nch;
+}
+
+double drift_now(const Delta& dl, uint32_t v) {
+  return dl.seen[v] ? dl.dsum[v] * std::pow(dl.gamma, (double)(dl.tau - dl.dlast[v])) : 0.0;
+}
+void drift_set(Delta& dl, uint32_t v, double value) {
+  const double old = drift_now(dl, v);
+  if (!dl.seen[v]) { dl.seen[v] = 1; dl.count += 1; }
+  dl.dsum[v] = value; dl.dlast[v] = dl.tau;
+  dl.G += value - old;
+}
+void drift_reset_all(Delta& dl) {
+  std::fill(dl.dsum.begin(), dl.dsum.end(), 0.0);
+  std::fill(dl.seen.begin(), dl.seen.end(), 0);
+  dl.G = 0.0; dl.count = 0;
+}
+
+// Refresh of the caches after a batch.  flag[v]: 0 untouched, 1 endpoint of the batch, h + 2 first reached
+// by hop h.  Layer l recomputes the rows whose inputs changed (flags up to thr_l); of those, a row whose
+// own input row or query time changed is recomputed exactly, the others take the delta update.
+void delta_refresh(Oracle& o, const std::vector<uint32_t>& flag) {
+  Delta& dl = o.dl;
+  dl.tau += 1;
+  dl.G *= dl.gamma;
+  std::fill(dl.last_frac.begin(), dl.last_frac.end(), -2.0f);
+  auto thr = [&](uint32_t l) { return o.d_mem ? l + 1 : l; };         // rows layer l (1-based) recomputes: flags 1 .. thr(l)
+  for (uint32_t l = 1; l <= o.layers; ++l) {
+    auto input_changed = [&](uint32_t u) {                             // u's layer-(l-1) row changed in this batch
+      if (flag[u] == 0) return false;
+      return l == 1 ? (o.d_mem != 0 && flag[u] == 1) : flag[u] <= thr(l - 1);
+    };
+    for (uint32_t v = 0; v < o.N; ++v) {
+      if (flag[v] == 0 || flag[v] > thr(l)) continue;
+      const bool exact = flag[v] == 1 || input_changed(v) || !dl.ac[l - 1][v].valid;
+      if (exact) {
+        delta_exact_row(o, l, v);
+        if (l == o.layers) { drift_set(dl, v, 0.0); dl.last_frac[v] = -1.0f; }
+      } else {
+        const uint32_t n = (uint32_t)dl.ac[l - 1][v].eid.size();
+        const uint32_t nch = delta_update_row(o, l, v, input_changed);
+        if (l == o.layers) {
+          const double frac = n ? (double)nch / (double)n : 0.0;
+          drift_set(dl, v, drift_now(dl, v) + frac);
+          dl.last_frac[v] = (float)frac;
+        }
+      }
+    }
+  }
+}
+
+void delta_rebuild_rows(Oracle& o, uint32_t n, const uint32_t* nodes) {
+  for (uint32_t l = 1; l <= o.layers; ++l)
+    for (uint32_t i = 0; i < n; ++i) delta_exact_row(o, l, nodes ? nodes[i] : i);
+}
+
 void copyf(std::vector<float>& dst, const float* src, size_t n) {
   dst.assign(n, 0.0f);
   if (src && n) std::memcpy(dst.data(), src, n * sizeof(float));
@@ -342,19 +557,21 @@ int orc_ingest(void* h, uint32_t n, const uint32_t* src, const uint32_t* dst, co
   // 4. affected set from the post-batch logs.  w depends on u iff an edge between them is
   //    still among w's most recent k entries; a changed u therefore dirties exactly those w.
   std::vector<char> inA(o.N, 0);
+  std::vector<uint32_t> flag(o.N, 0);                 // 1: endpoint, h + 2: first reached by hop h
   std::vector<uint32_t> frontier = D;
-  for (uint32_t v : D) inA[v] = 1;
+  for (uint32_t v : D) { inA[v] = 1; flag[v] = 1; }
   for (uint32_t hop = 0; hop < o.layers; ++hop) {
     std::vector<uint32_t> next;
     for (uint32_t u : frontier) {
       for (const Entry& en : o.log[u]) {
         const uint32_t w = en.nbr;
         if (inA[w]) continue;
-        if (held_by(o, w, en.eid)) { inA[w] = 1; next.push_back(w); }
+        if (held_by(o, w, en.eid)) { inA[w] = 1; flag[w] = hop + 2; next.push_back(w); }
       }
     }
     frontier.swap(next);
   }
+  if (o.dl.on) delta_refresh(o, flag);
   uint32_t na = 0;
   for (uint32_t v = 0; v < o.N; ++v) if (inA[v]) { if (affected_out) affected_out[na] = v; ++na; }
   if (n_affected) *n_affected = na;
@@ -464,6 +681,75 @@ void orc_gru(uint32_t d_msg, uint32_t d_mem,
 void orc_attention(uint32_t d, uint32_t heads, uint32_t n, const double* q, const double* K, const double* V,
                    const float* WO, const float* bO, double* out) {
   attention(d, heads, n, q, K, V, WO, bO, out);
+}
+
+// ---- delta mode and drift-aware rebuild scheduling (approximate; see the header) ----
+
+// Switches the delta mode on (gamma: decay of the drift estimator) and rebuilds every cache exactly.
+void orc_delta_enable(void* h, double gamma) {
+  Oracle& o = *(Oracle*)h;
+  Delta& dl = o.dl;
+  dl.on = true; dl.gamma = gamma;
+  dl.H.assign(o.layers, std::vector<float>((size_t)o.N * o.d_emb, 0.0f));
+  dl.ac.assign(o.layers, std::vector<AttnRow>(o.N));
+  dl.dsum.assign(o.N, 0.0); dl.dlast.assign(o.N, 0); dl.seen.assign(o.N, 0); dl.last_frac.assign(o.N, -2.0f);
+  dl.G = 0.0; dl.count = 0; dl.tau = 0;
+  delta_rebuild_rows(o, o.N, nullptr);
+}
+
+// cached rows of the given nodes at a layer (1-based)
+void orc_delta_rows(void* h, uint32_t layer, uint32_t n, const uint32_t* nodes, float* out) {
+  Oracle& o = *(Oracle*)h;
+  for (uint32_t i = 0; i < n; ++i)
+    std::memcpy(out + (size_t)i * o.d_emb, &o.dl.H[layer - 1][(size_t)nodes[i] * o.d_emb], o.d_emb * sizeof(float));
+}
+
+// attention cache of one row: entry count; weights in effect [n x heads]; scores [n x heads] (nullable)
+uint32_t orc_delta_attn(void* h, uint32_t layer, uint32_t v, double* a, double* s) {
+  Oracle& o = *(Oracle*)h;
+  const AttnRow& r = o.dl.ac[layer - 1][v];
+  if (a) std::copy(r.a.begin(), r.a.end(), a);
+  if (s) std::copy(r.s.begin(), r.s.end(), s);
+  return (uint32_t)r.eid.size();
+}
+
+// per node: fraction of changed entries in the last batch at the final layer (-1: recomputed exactly, -2: untouched)
+void orc_delta_last_fractions(void* h, float* out) {
+  Oracle& o = *(Oracle*)h;
+  std::copy(o.dl.last_frac.begin(), o.dl.last_frac.end(), out);
+}
+
+// drift estimator: the global metric (Eq. global_drift), the size of the cumulative affected set, and per node (nullable, [N])
+void orc_drift_status(void* h, double* global, uint32_t* count, double* per_node) {
+  Oracle& o = *(Oracle*)h;
+  if (global) *global = o.dl.count ? o.dl.G / (double)o.dl.count : 0.0;
+  if (count) *count = o.dl.count;
+  if (per_node) for (uint32_t v = 0; v < o.N; ++v) per_node[v] = drift_now(o.dl, v);
+}
+
+// Adaptive rebuild policy (Eq. rebuild_trigger): nothing (0) while the global metric is at most delta_max;
+// otherwise the nodes whose own estimate exceeds delta_max are recomputed exactly (1, partial rebuild) when
+// they are fewer than alpha * N, else every row is (2, full rebuild); either way all estimators restart.
+int orc_maintain(void* h, double delta_max, double alpha, uint32_t* n_drift) {
+  Oracle& o = *(Oracle*)h;
+  Delta& dl = o.dl;
+  if (n_drift) *n_drift = 0;
+  const double global = dl.count ? dl.G / (double)dl.count : 0.0;
+  if (!(global > delta_max)) return 0;
+  std::vector<uint32_t> drifted;
+  for (uint32_t v = 0; v < o.N; ++v) if (drift_now(dl, v) > delta_max) drifted.push_back(v);
+  if (n_drift) *n_drift = (uint32_t)drifted.size();
+  int action;
+  if ((double)drifted.size() < alpha * (double)o.N) { delta_rebuild_rows(o, (uint32_t)drifted.size(), drifted.data()); action = 1; }
+  else { delta_rebuild_rows(o, o.N, nullptr); action = 2; }
+  drift_reset_all(dl);
+  return action;
+}
+
+void orc_delta_full_rebuild(void* h) {
+  Oracle& o = *(Oracle*)h;
+  delta_rebuild_rows(o, o.N, nullptr);
+  drift_reset_all(o.dl);
 }
 
 }  // extern "C"
