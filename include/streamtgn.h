@@ -75,7 +75,9 @@ typedef struct {
                         <= 0: no expiry.  The affected set does not depend on it (a sound superset). */
   uint32_t aggregator; /* Eq. agg_functions, how a node's messages of one batch become one: STGN_AGG_LAST
                         (the latest), STGN_AGG_MEAN, STGN_AGG_SUM (added in batch order).  Ignored when d_mem = 0. */
-  uint32_t reserved;   /* 0 */
+  uint32_t delta_mode; /* 0: every affected row is recomputed exactly (results identical to a full recomputation).
+                        1: the approximate mode of Sec. 3.3 "Stage 4" / Eq. delta_embedding (see stgn_maintain). */
+  double   drift_gamma; /* delta mode: decay of the drift estimator per batch (Sec. 3.5), in (0, 1]; else ignored */
 } stgn_config;
 
 /* Parameters, host pointers, copied (and re-packed) by stgn_create.
@@ -153,8 +155,43 @@ int stgn_ingest_batch(stgn_ctx *ctx, uint32_t n, const uint32_t *src, const uint
 int stgn_get_embeddings(stgn_ctx *ctx, uint32_t layer, uint32_t n, const uint32_t *nodes,
                         float *out, int on_device);
 
-/* Recompute every layer for every node from the current state (Sec. 3.5, full rebuild). */
+/* Recompute every layer for every node from the current state (Sec. 3.5, full rebuild); in delta mode every
+ * attention cache is refreshed and the drift estimators restart. */
 int stgn_full_rebuild(stgn_ctx *ctx);
+
+/* ---- Delta mode (Sec. 3.3 "Stage 4", Eq. delta_embedding; Sec. 3.5, drift-aware rebuild scheduling) ----
+ * With delta_mode = 1 the library keeps, per layer and node, an attention cache: per recent-neighbour entry the
+ * score, the attention weight in effect and the neighbour|edge part of the value, and per row the weighted sums,
+ * the softmax denominator and its reference score.  After a batch a listed row whose own input row and query
+ * time are unchanged (it is in the affected set only because neighbours changed) is not recomputed: each entry j
+ * whose neighbour's input row changed gets its new score s', the denominator becomes Z' = Z - e^(s_j) + e^(s'),
+ * the entry's weight e^(s') / Z', and the sums are corrected by (new weight x new value) - (old weight x old
+ * value); the other entries keep the weight they have, so the weights no longer sum to one exactly.  The
+ * row's deviation from the exact row is at most
+ *     (attention mass of the unchanged entries) x max |V_unchanged| x |1 - Z / Z'| x ||W_O||_2
+ * per update.  Endpoints of the batch, rows whose own input changed, and every row touched by a rebuild are
+ * recomputed exactly and refresh their cache.  stgn_predict_batch(at_edge_time = 1) always computes exactly.
+ * Costs layers x num_nodes x k x (64 ks + 2 heads) floats of workspace on top of the exact mode
+ * (ks = heads x ceil(d_emb / heads / 64)).
+ *
+ * Drift estimator: per node the decayed sum, over the batches since the node's final-layer row was last
+ * exact, of (changed entries / entries) of its delta updates: est_v <- gamma est_v per batch.  The global metric
+ * is the mean estimate over the nodes updated since the last rebuild (Eq. global_drift).
+ *
+ * stgn_drift_status: synchronises; global_drift, n_tracked (size of that node set) and per_node (host
+ * [num_nodes], the decayed estimates) are each nullable. */
+int stgn_drift_status(stgn_ctx *ctx, double *global_drift, uint32_t *n_tracked, float *per_node);
+
+/* Adaptive rebuild policy (Eq. rebuild_trigger).  Synchronises.  While the global metric is at most delta_max:
+ * nothing (STGN_MAINTAIN_NONE).  Otherwise V_drift = nodes whose own estimate exceeds delta_max; if
+ * |V_drift| < alpha * num_nodes their rows are recomputed exactly at every layer (STGN_MAINTAIN_PARTIAL; rows
+ * outside V_drift keep what they hold), else every row is (STGN_MAINTAIN_FULL, = stgn_full_rebuild); either way
+ * all estimators restart at zero.  action, n_drift (|V_drift|): host, nullable.  The rebuild itself is
+ * enqueued, not awaited. */
+#define STGN_MAINTAIN_NONE 0
+#define STGN_MAINTAIN_PARTIAL 1
+#define STGN_MAINTAIN_FULL 2
+int stgn_maintain(stgn_ctx *ctx, double delta_max, double alpha, int *action, uint32_t *n_drift);
 
 /* Link-prediction head (Algorithm 1, "Link prediction").  The paper's error analysis (Sec. 3.6.3)
  * takes the score as a linear function of the concatenated source and destination embeddings:

@@ -27,7 +27,8 @@ class Config(C.Structure):
     _fields_ = [("num_nodes", C.c_uint32), ("max_edges", C.c_uint64), ("max_batch", C.c_uint32),
                 ("d_mem", C.c_uint32), ("d_node", C.c_uint32), ("d_edge", C.c_uint32), ("d_time", C.c_uint32),
                 ("d_emb", C.c_uint32), ("d_msg", C.c_uint32), ("k", C.c_uint32), ("heads", C.c_uint32),
-                ("layers", C.c_uint32), ("window", C.c_double), ("aggregator", C.c_uint32), ("reserved", C.c_uint32)]
+                ("layers", C.c_uint32), ("window", C.c_double), ("aggregator", C.c_uint32), ("delta_mode", C.c_uint32),
+                ("drift_gamma", C.c_double)]
 
 
 class Weights(C.Structure):
@@ -58,7 +59,8 @@ _lib = None
 EXPORTS = ("stgn_query_workspace", "stgn_create", "stgn_destroy", "stgn_ingest_batch", "stgn_get_embeddings",
            "stgn_full_rebuild", "stgn_sync", "stgn_get_affected", "stgn_get_neighbors", "stgn_get_history",
            "stgn_get_memory", "stgn_get_totals", "stgn_kernel_times", "stgn_last_error", "stgn_version",
-           "stgn_set_predictor", "stgn_predict_batch", "stgn_predict_batch_static")
+           "stgn_set_predictor", "stgn_predict_batch", "stgn_predict_batch_static", "stgn_drift_status",
+           "stgn_maintain")
 
 
 def load_library():
@@ -89,6 +91,8 @@ def load_library():
     L.stgn_set_predictor.argtypes = [vp, vp, C.c_float]
     L.stgn_predict_batch.argtypes = [vp, C.c_uint32, vp, vp, vp, C.c_int, C.c_int, vp]
     L.stgn_predict_batch_static.argtypes = [vp, C.c_uint32, vp, vp, vp, C.c_int, vp]
+    L.stgn_drift_status.argtypes = [vp, C.POINTER(C.c_double), _u32p, vp]
+    L.stgn_maintain.argtypes = [vp, C.c_double, C.c_double, C.POINTER(C.c_int), _u32p]
     L.stgn_last_error.argtypes = [vp]
     L.stgn_last_error.restype = C.c_char_p
     L.stgn_version.restype = C.c_char_p
@@ -105,9 +109,9 @@ def _ptr(a):
 
 
 def make_config(*, num_nodes, max_edges, max_batch, d_mem, d_node, d_edge, d_time, d_emb, d_msg, k, heads, layers,
-                window=0.0, aggregator=0):
+                window=0.0, aggregator=0, delta_mode=0, drift_gamma=0.0):
     return Config(num_nodes, max_edges, max_batch, d_mem, d_node, d_edge, d_time, d_emb, d_msg, k, heads, layers,
-                  float(window), int(aggregator), 0)
+                  float(window), int(aggregator), int(delta_mode), float(drift_gamma))
 
 
 def query_workspace(cfg: Config) -> int:
@@ -164,11 +168,11 @@ class StreamTGN:
         self._h = h
 
     @classmethod
-    def from_workload(cls, w, weights, node_feat=None, max_edges=None, max_batch=None, **kw):
+    def from_workload(cls, w, weights, node_feat=None, max_edges=None, max_batch=None, delta_mode=0, drift_gamma=0.0, **kw):
         cfg = make_config(num_nodes=w.num_nodes, max_edges=max_edges or w.num_edges, max_batch=max_batch or w.batch,
                           d_mem=w.d_mem, d_node=w.d_node, d_edge=w.d_edge, d_time=w.d_time, d_emb=w.d_emb,
                           d_msg=w.d_msg, k=w.k, heads=w.heads, layers=w.layers, window=getattr(w, "window", 0.0),
-                          aggregator=getattr(w, "aggregator", 0))
+                          aggregator=getattr(w, "aggregator", 0), delta_mode=delta_mode, drift_gamma=drift_gamma)
         return cls(cfg, weights, node_feat, **kw)
 
     def close(self):
@@ -267,6 +271,19 @@ class StreamTGN:
 
     def full_rebuild(self):
         self._check(self._L.stgn_full_rebuild(self._h))
+
+    def drift_status(self, per_node=False):
+        """(global drift metric, size of the cumulative affected set[, per-node estimates]) -- delta mode."""
+        g, n = C.c_double(0.0), C.c_uint32(0)
+        out = np.empty(self.cfg.num_nodes, dtype=np.float32) if per_node else None
+        self._check(self._L.stgn_drift_status(self._h, C.byref(g), C.byref(n), _ptr(out)))
+        return (g.value, n.value, out) if per_node else (g.value, n.value)
+
+    def maintain(self, delta_max, alpha):
+        """Adaptive rebuild policy; returns (action 0 none / 1 partial / 2 full, |V_drift|) -- delta mode."""
+        act, nd = C.c_int(0), C.c_uint32(0)
+        self._check(self._L.stgn_maintain(self._h, C.c_double(delta_max), C.c_double(alpha), C.byref(act), C.byref(nd)))
+        return act.value, nd.value
 
     def sync(self, check=True):
         rc = self._L.stgn_sync(self._h)

@@ -133,6 +133,8 @@ int check_config(const stgn_config* c, std::string* why) {
   if (c->d_mem && (c->d_msg == 0 || c->d_msg > 512)) return bad("d_msg out of range");
   if (c->heads == 0 || c->d_emb % c->heads != 0) return bad("heads must divide d_emb");
   if (c->aggregator > STGN_AGG_SUM) return bad("aggregator must be STGN_AGG_LAST, STGN_AGG_MEAN or STGN_AGG_SUM");
+  if (c->delta_mode > 1) return bad("delta_mode must be 0 or 1");
+  if (c->delta_mode && !(c->drift_gamma > 0.0 && c->drift_gamma <= 1.0)) return bad("drift_gamma must lie in (0, 1]");
   if (!attn_supported(c->d_emb, c->d_time, c->heads))
     return bad("unsupported attention shape: heads in {1,2,4}, d_time <= 128, and heads * ceil(d_emb / heads / 64) <= 4 "
                "(every head takes whole 64-float slots of a cached key row)");
@@ -236,6 +238,23 @@ size_t layout(const stgn_config& c, char* base, Dev* d) {
     else if (l && d->thr[l] == 0xFFu && d->thr[l - 1] == 0xFFu) d->RS[l] = d->RS[l - 1];   // both walk A (pointers are null while measuring)
     else d->RS[l] = b.take<uint32_t>(N);
   }
+  // delta mode: attention cache per layer, the kept flags, the drift estimator
+  d->delta = c.delta_mode;
+  d->gamma = (float)c.drift_gamma;
+  for (uint32_t l = 0; l < STGN_MAX_LAYERS; ++l) {
+    const bool on = c.delta_mode && l < c.layers;
+    d->ac_S[l] = on ? b.take<float>((size_t)N * kSlot * d->ks) : nullptr;
+    d->ac_P[l] = on ? b.take<float>((size_t)N * kSlot * d->nt * c.heads) : nullptr;
+    d->ac_ZM[l] = on ? b.take<float>((size_t)N * 2 * c.heads) : nullptr;
+    d->ac_W[l] = on ? b.take<float>((size_t)N * c.k * 2 * c.heads) : nullptr;
+    d->ac_V[l] = on ? b.take<float>((size_t)N * c.k * kSlot * d->ks) : nullptr;
+  }
+  d->flags_kept = c.delta_mode ? b.take<uint8_t>(mark_bytes(N)) : nullptr;
+  d->drift = c.delta_mode ? b.take<DriftCtl>(1) : nullptr;
+  d->dsum = c.delta_mode ? b.take<float>(N) : nullptr;
+  d->dlast = c.delta_mode ? b.take<uint32_t>(N) : nullptr;
+  d->dseen = c.delta_mode ? b.take<uint8_t>(N) : nullptr;
+  d->dlist = c.delta_mode ? b.take<uint32_t>(N) : nullptr;
   for (uint32_t l = 0; l < c.layers; ++l) d->L[l].d_in = l == 0 ? d->d0 : c.d_emb;
   d->pred_rows = b.take<uint32_t>(B2);
   d->pred_tq = b.take<double>(B2);
@@ -425,7 +444,7 @@ void run_layers(stgn_ctx* ctx, const Dev& d, bool all_rows) {
   for (uint32_t l = 0; l < d.layers; ++l) {
     Scope s(ctx, KC_LAYER);
     if (all_rows) launch_layer(d, ctx->stream, l, d.bucketed ? d.RS[0] : nullptr, nullptr, d.N);
-    else launch_layer(d, ctx->stream, l, d.bucketed ? d.RS[l] : d.R[l], &d.bc->nR[l], d.N);
+    else launch_layer(d, ctx->stream, l, d.bucketed ? d.RS[l] : d.R[l], &d.bc->nR[l], d.N, /*force_exact=*/false);
   }
 }
 
@@ -563,7 +582,13 @@ int stgn_create(const stgn_config* cfg, const stgn_weights* w, const float* node
   }
   // ring places past a row's entry count read edge 0: its rows must be finite before the first edge arrives
   for (uint32_t l = 0; l < cfg->layers; ++l) launch_zero(ctx->d.KVE[l].base, ctx->d.ld_kv, ctx->stream);
+  if (cfg->delta_mode) {            // no flag set, estimator at rest
+    launch_zero(reinterpret_cast<float*>(ctx->d.flags_kept), mark_bytes(cfg->num_nodes) / sizeof(float), ctx->stream);
+    launch_zero(reinterpret_cast<float*>(ctx->d.drift), sizeof(DriftCtl) / sizeof(float), ctx->stream);
+    launch_drift_reset(ctx->d, ctx->stream);
+  }
   run_layers(ctx, ctx->d, true);    // every cache row = empty-neighbourhood embedding
+  if (cfg->delta_mode) launch_drift_reset(ctx->d, ctx->stream);
   hipError_t e = hipStreamSynchronize(ctx->stream);
   if (e == hipSuccess) e = hipGetLastError();
   if (e != hipSuccess) { ctx->err = std::string("initial rebuild: ") + hipGetErrorString(e); return bail(STGN_E_DEVICE); }
@@ -751,6 +776,58 @@ int stgn_full_rebuild(stgn_ctx* ctx) {
   if (!ctx) return STGN_E_INVALID_ARG;
   ctx->idle = false;
   run_layers(ctx, ctx->d, true);
+  if (ctx->cfg.delta_mode) launch_drift_reset(ctx->d, ctx->stream);   // every row is exact again
+  HIPCHK(ctx, hipGetLastError());
+  return STGN_OK;
+}
+
+int stgn_drift_status(stgn_ctx* ctx, double* global_drift, uint32_t* n_tracked, float* per_node) {
+  if (!ctx) return STGN_E_INVALID_ARG;
+  if (!ctx->cfg.delta_mode) return fail(ctx, STGN_E_INVALID_ARG, "the context was not created in delta mode");
+  const Dev& d = ctx->d;
+  if (per_node) launch_drift_values(d, ctx->stream, reinterpret_cast<float*>(d.dlist));
+  DriftCtl h{};
+  HIPCHK(ctx, hipMemcpyAsync(&h, d.drift, sizeof h, hipMemcpyDeviceToHost, ctx->stream));
+  if (per_node)
+    HIPCHK(ctx, hipMemcpyAsync(per_node, d.dlist, (size_t)d.N * sizeof(float), hipMemcpyDeviceToHost, ctx->stream));
+  int rc = sync_and_poll(ctx);
+  if (global_drift) *global_drift = h.count ? h.G / (double)h.count : 0.0;
+  if (n_tracked) *n_tracked = h.count;
+  return rc;
+}
+
+int stgn_maintain(stgn_ctx* ctx, double delta_max, double alpha, int* action, uint32_t* n_drift) {
+  if (!ctx) return STGN_E_INVALID_ARG;
+  if (!ctx->cfg.delta_mode) return fail(ctx, STGN_E_INVALID_ARG, "the context was not created in delta mode");
+  const Dev& d = ctx->d;
+  if (action) *action = STGN_MAINTAIN_NONE;
+  if (n_drift) *n_drift = 0;
+  DriftCtl h{};
+  HIPCHK(ctx, hipMemcpyAsync(&h, d.drift, sizeof h, hipMemcpyDeviceToHost, ctx->stream));
+  int rc = sync_and_poll(ctx);
+  if (rc) return rc;
+  const double global = h.count ? h.G / (double)h.count : 0.0;
+  if (!(global > delta_max)) return STGN_OK;
+  ctx->idle = false;
+  const uint32_t zero = 0;
+  HIPCHK(ctx, hipMemcpyAsync(&d.drift->n_list, &zero, sizeof zero, hipMemcpyHostToDevice, ctx->stream));
+  launch_drift_list(d, ctx->stream, (float)delta_max);
+  uint32_t n_list = 0;
+  HIPCHK(ctx, hipMemcpyAsync(&n_list, &d.drift->n_list, sizeof n_list, hipMemcpyDeviceToHost, ctx->stream));
+  HIPCHK(ctx, hipStreamSynchronize(ctx->stream));
+  if (n_drift) *n_drift = n_list;
+  if ((double)n_list < alpha * (double)d.N) {
+    // partial rebuild: the drifted rows, layer by layer, exactly (the other rows keep what they hold)
+    for (uint32_t l = 0; l < d.layers; ++l) {
+      Scope s(ctx, KC_LAYER);
+      launch_layer(d, ctx->stream, l, d.dlist, &d.drift->n_list, d.N);
+    }
+    if (action) *action = STGN_MAINTAIN_PARTIAL;
+  } else {
+    run_layers(ctx, d, true);
+    if (action) *action = STGN_MAINTAIN_FULL;
+  }
+  launch_drift_reset(d, ctx->stream);
   HIPCHK(ctx, hipGetLastError());
   return STGN_OK;
 }

@@ -81,6 +81,8 @@ __device__ inline void finish_batch(const Dev& d, const uint32_t (&total)[STGN_M
   c->tot_direct += bc->nD;
   bc->scanned = stripes_sum_thread(d, kScannedCounter);
   c->tot_scanned += bc->scanned;
+  // delta mode: one more batch for the drift estimator (every per-node estimate, hence their sum, decays by gamma)
+  if (d.delta && !bc->skip) { d.drift->tau += 1u; d.drift->G *= (double)d.gamma; }
 }
 
 // Count and write in one launch, for flag arrays of at most kSmallBlocks blocks: a workgroup counts
@@ -118,6 +120,7 @@ __device__ inline void compact_small_block(const Dev& d, uint32_t last_value, ui
   }
   uint4 m = make_uint4(0u, 0u, 0u, 0u);
   if (v0 < d.N) m = *reinterpret_cast<const uint4*>(d.mark + v0);     // the flag array is padded to whole blocks
+  if (d.flags_kept && v0 < d.N) *reinterpret_cast<uint4*>(d.flags_kept + v0) = m;   // delta mode reads the batch's flags in the layer launches
   uint32_t excl;
 #pragma unroll
   for (uint32_t list = 0; list <= STGN_MAX_LAYERS; ++list) {

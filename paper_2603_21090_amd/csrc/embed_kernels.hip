@@ -82,6 +82,15 @@ LaunchArgs make_args(const Dev& d, uint32_t layer) {
   k.ld_in = d.H[layer].ld; k.ld_out = d.H[layer + 1].ld; k.ld_kv = d.ld_kv; k.ld_kve = d.KVE[layer].ld;
   k.window = d.window;
   k.k = d.k; k.d_in = L.d_in; k.d_emb = d.d_emb; k.dk = d.dk; k.d_time = d.d_time;
+  if (d.delta) {
+    k.flags = d.flags_kept;
+    k.thr_in = d.d_mem ? layer + 1u : layer;                  // flags at or below: the owner's input row of this layer changed
+    k.force_exact = 1u; k.is_final = layer + 1 == d.layers ? 1u : 0u;
+    k.gamma = d.gamma;
+    k.ac_S = d.ac_S[layer]; k.ac_P = d.ac_P[layer]; k.ac_ZM = d.ac_ZM[layer]; k.ac_W = d.ac_W[layer]; k.ac_V = d.ac_V[layer];
+    k.drift = d.drift; k.dsum = d.dsum; k.dlast = d.dlast; k.dseen = d.dseen;
+  }
+  a.delta = d.delta != 0;
   a.ks = d.ks; a.nt = d.nt; a.heads = d.heads;
   a.num_cu = d.num_cu;
   a.lds = (size_t)layer_impl::layer_lds(L.d_in, d.heads, d.ks, d.nt, d.k).total * sizeof(float);
@@ -108,8 +117,10 @@ int attn_supported(uint32_t d_emb, uint32_t d_time, uint32_t heads) {
   return d_time >= 1 && d_time <= kMaxTimeSlots * kSlot && heads * sh <= kMaxKeySlots;
 }
 
-void launch_layer(const Dev& d, hipStream_t s, uint32_t layer, const uint32_t* rows, const uint32_t* cp, uint32_t cm) {
+void launch_layer(const Dev& d, hipStream_t s, uint32_t layer, const uint32_t* rows, const uint32_t* cp, uint32_t cm,
+                  bool force_exact) {
   LaunchArgs a = make_args(d, layer);
+  a.k.force_exact = force_exact ? 1u : 0u;
   a.s = s; a.rows = rows; a.cp = cp; a.cm = cm; a.set_attr = false;
   go_heads(a);
 }
@@ -121,6 +132,7 @@ void launch_predict_prep(const Dev& d, hipStream_t s, uint32_t n, const uint32_t
 // the final layer for the roots listed in pred_rows, at the times in pred_tq, into pred_out
 void launch_layer_roots(const Dev& d, hipStream_t s, uint32_t nroots) {
   LaunchArgs a = make_args(d, d.layers - 1);
+  a.delta = false;                                            // root rows are computed at their own times, from nothing cached
   a.k.tq_rows = d.pred_tq;
   a.k.out_rows = d.pred_out;
   a.s = s; a.rows = d.pred_rows; a.cp = nullptr; a.cm = nroots; a.set_attr = false;
@@ -147,6 +159,50 @@ void launch_gather_times(const Dev& d, hipStream_t s, uint32_t n, const uint32_t
   hipLaunchKernelGGL(gather_times_kernel, dim3(blocks), dim3(256), 0, s, d.t_last, d.N, n, nodes, out);
 }
 
+// ---- drift estimator (Sec. 3.5)
+__global__ __launch_bounds__(256) void drift_reset_kernel(Dev d) {
+  const uint32_t nth = gridDim.x * blockDim.x, tid = blockIdx.x * blockDim.x + threadIdx.x;
+  for (uint32_t v = tid; v < d.N; v += nth) { d.dsum[v] = 0.0f; d.dlast[v] = 0u; d.dseen[v] = 0; }
+  if (tid == 0) { d.drift->G = 0.0; d.drift->count = 0u; d.drift->n_list = 0u; }
+}
+
+// nodes whose decayed estimate exceeds the threshold, in no particular order
+__global__ __launch_bounds__(256) void drift_list_kernel(Dev d, float threshold) {
+  const uint32_t nth = gridDim.x * blockDim.x, tid = blockIdx.x * blockDim.x + threadIdx.x;
+  const uint32_t tau = d.drift->tau;
+  for (uint32_t v = tid; v < d.N; v += nth) {
+    if (!d.dseen[v]) continue;
+    const float now = d.dsum[v] * __powf(d.gamma, (float)(tau - d.dlast[v]));
+    if (now > threshold) d.dlist[atomicAdd(&d.drift->n_list, 1u)] = v;
+  }
+}
+
+// every node's decayed estimate (0 for nodes outside the cumulative affected set)
+__global__ __launch_bounds__(256) void drift_values_kernel(Dev d, float* out) {
+  const uint32_t nth = gridDim.x * blockDim.x, tid = blockIdx.x * blockDim.x + threadIdx.x;
+  const uint32_t tau = d.drift->tau;
+  for (uint32_t v = tid; v < d.N; v += nth)
+    out[v] = d.dseen[v] ? d.dsum[v] * __powf(d.gamma, (float)(tau - d.dlast[v])) : 0.0f;
+}
+
+void launch_drift_values(const Dev& d, hipStream_t s, float* out) {
+  uint32_t blocks = (d.N + 255) / 256;
+  if (blocks > 2048) blocks = 2048;
+  hipLaunchKernelGGL(drift_values_kernel, dim3(blocks ? blocks : 1), dim3(256), 0, s, d, out);
+}
+
+void launch_drift_reset(const Dev& d, hipStream_t s) {
+  uint32_t blocks = (d.N + 255) / 256;
+  if (blocks > 2048) blocks = 2048;
+  hipLaunchKernelGGL(drift_reset_kernel, dim3(blocks ? blocks : 1), dim3(256), 0, s, d);
+}
+
+void launch_drift_list(const Dev& d, hipStream_t s, float threshold) {
+  uint32_t blocks = (d.N + 255) / 256;
+  if (blocks > 2048) blocks = 2048;
+  hipLaunchKernelGGL(drift_list_kernel, dim3(blocks ? blocks : 1), dim3(256), 0, s, d, threshold);
+}
+
 int setup_embed_attributes(const Dev& d) {
   for (uint32_t l = 0; l < d.layers; ++l) {
     LaunchArgs a = make_args(d, l);
@@ -158,6 +214,11 @@ int setup_embed_attributes(const Dev& d) {
     a.set_attr = true;
     go_heads(a);
     if (a.err != hipSuccess) return -1;
+    if (a.delta) {                                                // the exact variant serves the root rows
+      a.delta = false;
+      go_heads(a);
+      if (a.err != hipSuccess) return -1;
+    }
   }
   return 0;
 }

@@ -243,6 +243,7 @@ __global__ __launch_bounds__(256) void compact_write_kernel(Dev d) {
     }
     total[list] = before + block_total;
   }
+  if (d.flags_kept && v0 < d.N) *reinterpret_cast<uint4*>(d.flags_kept + v0) = m;   // delta mode reads the batch's flags in the layer launches
   if (m.x | m.y | m.z | m.w) *reinterpret_cast<uint4*>(d.mark + v0) = make_uint4(0u, 0u, 0u, 0u);   // ready for the next batch
   if (blockIdx.x == gridDim.x - 1 && t == 0) finish_batch(d, total);
 }

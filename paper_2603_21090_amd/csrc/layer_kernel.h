@@ -57,7 +57,7 @@ __device__ inline float dot4(const float4 a, const float4 b, float acc) {
 
 struct LayerLds {
   uint32_t ldx, ldq, ldz;        // strides (floats) of the X / O tile, the Q / H' tile and the qt / pb tile
-  uint32_t off_q, off_z, off_r, total;
+  uint32_t off_q, off_z, off_r, off_sc, total;
 };
 
 // Every stride is 4 (mod 8) floats: rows stay 16-byte aligned and the 16 rows of an operand read
@@ -71,7 +71,8 @@ __host__ __device__ inline LayerLds layer_lds(uint32_t d_in, uint32_t heads, uin
   l.off_q = kTM * l.ldx;
   l.off_z = l.off_q + kTM * l.ldq;
   l.off_r = l.off_z + kTM * l.ldz + 4 * kGrpK;    // operand reads may run one chunk past the last row
-  l.total = l.off_r + kTM * k * 4;                // the ring records of the tile's rows, 16 bytes each
+  l.off_sc = l.off_r + kTM * k * 4;               // the ring records of the tile's rows, 16 bytes each
+  l.total = l.off_sc + kTM * k * heads;           // delta mode: the scores of a row's entries until its weights are known
   return l;
 }
 
@@ -91,6 +92,14 @@ struct LayerArgs {
   const float *WQ, *cQ, *WKT, *WV, *WO, *bO, *WKVnext;   // matrices group-major (mfma16.h)
   uint32_t ld_in, ld_out, ld_kv, ld_kve;           // ld_kve = 0 without edge features (every edge reads one zero row)
   uint32_t k, d_in, d_emb, dk, d_time;
+  // delta mode (read by the delta variant only): the batch's dirty flags and the highest flag whose owner's
+  // input row of this layer changed (a row at or below it, or an endpoint, is recomputed exactly; an entry whose
+  // neighbour is at or below it is a changed entry); the attention cache of this layer; the drift estimator
+  const uint8_t* flags;
+  uint32_t thr_in, force_exact, is_final;
+  float gamma;
+  float *ac_S, *ac_P, *ac_ZM, *ac_W, *ac_V;
+  DriftCtl* drift; float* dsum; uint32_t* dlast; uint8_t* dseen;
 };
 
 // cached rows (node and edge, keys and values) of one chunk of JC ring entries, one float4 per lane and slot
@@ -101,11 +110,12 @@ struct GatherBuf {
 };
 
 // KS key slots in total (heads x slots per head), NT time slots; JC ring entries fetched together.
-template <int KS, int NT, int H, int JC, int WGS>
+// DELTA: the approximate mode of Sec. 3.3 "Stage 4" (attention cache, delta update of changed entries).
+template <int KS, int NT, int H, int JC, int WGS, bool DELTA>
 __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint32_t* __restrict__ rows,
                                                          const uint32_t* count_ptr, uint32_t count_max) {
   extern __shared__ __align__(16) float lds[];
-  __shared__ uint32_t s_node[kTM], s_cnt[kTM], s_next[kTM];
+  __shared__ uint32_t s_node[kTM], s_cnt[kTM], s_next[kTM], s_ex[kTM];
   __shared__ double s_tq[kTM], s_tqn[kTM];
   __shared__ __align__(16) double s_om[NT * kSlot], s_ph[NT * kSlot];
   static_assert(KS % H == 0, "whole slots per head");
@@ -282,7 +292,16 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
     const uint32_t w1 = wave < ntd ? wave : 0u;              // loads are unconditional (clamped), products are not
     load_b16(a.WQ + (size_t)w1 * g_in * kGrpFloats, 0, oq.b[0]);
     load_b16(a.WQ + (size_t)(w1 + 4 < ntd ? w1 + 4 : w1) * g_in * kGrpFloats, 0, oq.b[1]);
-    if (tid < kTM) s_node[tid] = s_next[tid];
+    if (tid < kTM) {
+      s_node[tid] = s_next[tid];
+      if constexpr (DELTA) {
+        // exact recomputation for endpoints of the batch (query time and entries moved), for rows whose own
+        // input row changed (every score moves), and whenever the caller asks for it
+        const uint32_t node = s_next[tid];
+        const uint32_t fl = node != 0xFFFFFFFFu ? a.flags[node] : 0u;
+        s_ex[tid] = (a.force_exact || fl == 1u || (fl != 0u && fl <= a.thr_in)) ? 1u : 0u;
+      }
+    }
     if (pf_ok) {
       // everything was fetched a tile ago: registers -> LDS
 #pragma unroll
@@ -361,7 +380,7 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
       }
     };
     ZBuf z0;
-    gather(0, z0);
+    if constexpr (!DELTA) gather(0, z0);
     // ================================================================ phase 1: q = x W_Q + c_Q
     for (uint32_t nt = wave; nt < ntd; nt += 8) {
       const bool two = nt + 4 < ntd;
@@ -418,6 +437,177 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
     }
     __syncthreads();
     // ================================================================ phase 3: gather + attention
+    if constexpr (DELTA) {
+      // ---- delta mode.  An exact row runs the same online softmax as the exact mode and leaves its attention
+      // cache behind: per entry score, weight and the neighbour|edge part of the value, per row the sums S and
+      // pb, the denominator and its reference score.  A delta row starts from its cached sums and visits only
+      // the entries whose neighbour's input row changed: new score, denominator Z' = Z - e_old + e_new, new
+      // weight e_new / Z', sums corrected by (new weight x new value) - (old weight x old value); the
+      // other entries keep the weight they have (Eq. delta_embedding, "updated neighbours").  Plain loop,
+      // no prefetch: the mode trades exactness for touching fewer rows, not for a tuned pipeline.
+      float* Sc = lds + ll.off_sc;
+      const uint32_t node = s_node[local];
+      const bool live = node != 0xFFFFFFFFu;
+      const uint32_t nn = live ? node : 0u;
+      const bool ex = s_ex[local] != 0u;
+      float* acS = a.ac_S + (size_t)nn * (kSlot * KS) + 4u * sub;
+      float* acP = a.ac_P + (size_t)nn * (kSlot * NT * H) + 4u * sub;
+      float* acZM = a.ac_ZM + (size_t)nn * (2 * H);
+      float4 accv[KS], accp[H][NT];
+      float mref[H], lrun[H];                                 // exact row: running reference and denominator; delta row: m and Z
+#pragma unroll
+      for (int s = 0; s < KS; ++s) accv[s] = ex ? make_float4(0.f, 0.f, 0.f, 0.f) : *reinterpret_cast<const float4*>(acS + s * kSlot);
+#pragma unroll
+      for (int h = 0; h < H; ++h) {
+#pragma unroll
+        for (int t = 0; t < NT; ++t)
+          accp[h][t] = ex ? make_float4(0.f, 0.f, 0.f, 0.f) : *reinterpret_cast<const float4*>(acP + (h * NT + t) * kSlot);
+        mref[h] = ex ? -INFINITY : acZM[2 * h + 1];
+        lrun[h] = ex ? 0.0f : acZM[2 * h];
+      }
+      float4 qk[KS];
+#pragma unroll
+      for (int s = 0; s < KS; ++s) qk[s] = *reinterpret_cast<const float4*>(Qs + local * ll.ldq + s * kSlot + 4u * sub);
+      const float* zq = Zs + local * ll.ldz + 4u * sub;
+      for (uint32_t j = sub; j < cnt; j += 16)
+#pragma unroll
+        for (int h = 0; h < H; ++h) Sc[(local * k + j) * H + h] = -INFINITY;
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      uint32_t nch = 0, nvalid = 0;
+      for (uint32_t j = 0; j < cmax; ++j) {
+        const RingEntry e = rrow[j < k ? j : k - 1u];
+        const bool have = j < cnt;
+        const uint32_t fl = have ? a.flags[e.nbr] : 0u;
+        const bool chg = fl != 0u && fl <= a.thr_in;
+        const double dt = tq - e.t;
+        const bool vj = have && dt <= a.window;
+        const bool act = vj && (ex || chg);
+        nvalid += vj ? 1u : 0u;
+        if (!__any(act)) continue;                            // no row of this wave needs the entry
+        const float* nrow = a.KVn + (size_t)(act ? e.nbr : 0u) * a.ld_kv + 4u * sub;
+        const float* erow = a.KVe + (size_t)(act ? e.eid : 0u) * a.ld_kve + 4u * sub;
+        float4 kk[KS], vv[KS];
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+          const float4 kn = *reinterpret_cast<const float4*>(nrow + s * kSlot), ke = *reinterpret_cast<const float4*>(erow + s * kSlot);
+          const float4 vn = *reinterpret_cast<const float4*>(nrow + (KS + s) * kSlot), ve = *reinterpret_cast<const float4*>(erow + (KS + s) * kSlot);
+          kk[s] = make_float4(kn.x + ke.x, kn.y + ke.y, kn.z + ke.z, kn.w + ke.w);
+          vv[s] = make_float4(vn.x + ve.x, vn.y + ve.y, vn.z + ve.z, vn.w + ve.w);
+        }
+        float4 zt[NT];
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+          const double2 oa = *reinterpret_cast<const double2*>(s_om + t * kSlot + 4u * sub), ob = *reinterpret_cast<const double2*>(s_om + t * kSlot + 4u * sub + 2);
+          const double2 pa = *reinterpret_cast<const double2*>(s_ph + t * kSlot + 4u * sub), pb = *reinterpret_cast<const double2*>(s_ph + t * kSlot + 4u * sub + 2);
+          const float c0 = cos_rev(oa.x * dt + pa.x), c1 = cos_rev(oa.y * dt + pa.y);
+          const float c2 = cos_rev(ob.x * dt + pb.x), c3 = cos_rev(ob.y * dt + pb.y);
+          zt[t] = make_float4(tok[t][0] ? c0 : 0.0f, tok[t][1] ? c1 : 0.0f, tok[t][2] ? c2 : 0.0f, tok[t][3] ? c3 : 0.0f);
+        }
+        float sc[H];
+#pragma unroll
+        for (int h = 0; h < H; ++h) {
+          float p = 0.0f;
+#pragma unroll
+          for (int s = h * SH; s < (h + 1) * SH; ++s) p = dot4(qk[s], kk[s], p);
+#pragma unroll
+          for (int t = 0; t < NT; ++t) p = dot4(*reinterpret_cast<const float4*>(zq + h * Ztp + t * kSlot), zt[t], p);
+          sc[h] = row16_sum(p);
+        }
+        if (act && live) {
+          float* w = a.ac_W + ((size_t)nn * k + j) * (2 * H);
+          float* vc = a.ac_V + ((size_t)nn * k + j) * (kSlot * KS) + 4u * sub;
+          if (ex) {
+#pragma unroll
+            for (int h = 0; h < H; ++h) {
+              const bool mv = sc[h] > mref[h] + 30.0f;
+              const float mnew = mv ? sc[h] : mref[h];
+              const float scale = mv ? __expf(mref[h] - mnew) : 1.0f;     // exp(-inf) = 0 on the first move
+              mref[h] = mnew;
+              const float p = __expf(sc[h] - mnew);
+              lrun[h] = fmaf(lrun[h], scale, p);
+#pragma unroll
+              for (int s = h * SH; s < (h + 1) * SH; ++s) {
+                accv[s].x = fmaf(accv[s].x, scale, p * vv[s].x); accv[s].y = fmaf(accv[s].y, scale, p * vv[s].y);
+                accv[s].z = fmaf(accv[s].z, scale, p * vv[s].z); accv[s].w = fmaf(accv[s].w, scale, p * vv[s].w);
+              }
+#pragma unroll
+              for (int t = 0; t < NT; ++t) {
+                accp[h][t].x = fmaf(accp[h][t].x, scale, p * zt[t].x); accp[h][t].y = fmaf(accp[h][t].y, scale, p * zt[t].y);
+                accp[h][t].z = fmaf(accp[h][t].z, scale, p * zt[t].z); accp[h][t].w = fmaf(accp[h][t].w, scale, p * zt[t].w);
+              }
+              if (sub == 0) Sc[(local * k + j) * H + h] = sc[h];
+            }
+          } else {
+            nch += 1u;
+#pragma unroll
+            for (int h = 0; h < H; ++h) {
+              const float s_old = w[2 * h], a_old = w[2 * h + 1];
+              const float e_old = __expf(s_old - mref[h]), e_new = __expf(sc[h] - mref[h]);
+              const float Zn = lrun[h] - e_old + e_new;
+              const float a_new = e_new / Zn;
+              lrun[h] = Zn;
+#pragma unroll
+              for (int s = h * SH; s < (h + 1) * SH; ++s) {
+                const float4 vo = *reinterpret_cast<const float4*>(vc + s * kSlot);
+                accv[s].x += a_new * vv[s].x - a_old * vo.x; accv[s].y += a_new * vv[s].y - a_old * vo.y;
+                accv[s].z += a_new * vv[s].z - a_old * vo.z; accv[s].w += a_new * vv[s].w - a_old * vo.w;
+              }
+              const float da = a_new - a_old;
+#pragma unroll
+              for (int t = 0; t < NT; ++t) {
+                accp[h][t].x = fmaf(da, zt[t].x, accp[h][t].x); accp[h][t].y = fmaf(da, zt[t].y, accp[h][t].y);
+                accp[h][t].z = fmaf(da, zt[t].z, accp[h][t].z); accp[h][t].w = fmaf(da, zt[t].w, accp[h][t].w);
+              }
+              if (sub == 0) { w[2 * h] = sc[h]; w[2 * h + 1] = a_new; }
+            }
+          }
+#pragma unroll
+          for (int s = 0; s < KS; ++s) *reinterpret_cast<float4*>(vc + s * kSlot) = vv[s];
+        }
+      }
+      // ---- the row's sums: normalised by the denominator after an exact recomputation, as they stand after a delta update
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+      for (int h = 0; h < H; ++h) {
+        const float inv = ex ? (lrun[h] > 0.0f ? 1.0f / lrun[h] : 0.0f) : 1.0f;
+#pragma unroll
+        for (int s = h * SH; s < (h + 1) * SH; ++s) {
+          float4 o = accv[s];
+          o.x *= inv; o.y *= inv; o.z *= inv; o.w *= inv;
+          *reinterpret_cast<float4*>(Xs + local * ll.ldx + s * kSlot + 4u * sub) = o;
+          if (live) *reinterpret_cast<float4*>(acS + s * kSlot) = o;
+        }
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+          float4 o = accp[h][t];
+          o.x *= inv; o.y *= inv; o.z *= inv; o.w *= inv;
+          *reinterpret_cast<float4*>(Zs + local * ll.ldz + h * Ztp + t * kSlot + 4u * sub) = o;
+          if (live) *reinterpret_cast<float4*>(acP + (h * NT + t) * kSlot) = o;
+        }
+        if (live && sub == 0) { acZM[2 * h] = lrun[h]; acZM[2 * h + 1] = mref[h]; }
+        if (ex && live)
+          for (uint32_t j = sub; j < cnt; j += 16) {          // the weights in effect after the exact recomputation
+            const float sj = Sc[(local * k + j) * H + h];
+            float* w = a.ac_W + ((size_t)nn * k + j) * (2 * H);
+            w[2 * h] = sj;
+            w[2 * h + 1] = lrun[h] > 0.0f ? __expf(sj - mref[h]) * inv : 0.0f;
+          }
+      }
+      // ---- drift estimator (Sec. 3.5), final layer: an exact recomputation restarts the node's estimate, a
+      // delta update adds the changed fraction of its entries to the decayed estimate
+      if (a.is_final && live && sub == 0 && !a.out_rows) {
+        const uint32_t tau = a.drift->tau;
+        const float old = a.dseen[nn] ? a.dsum[nn] * __powf(a.gamma, (float)(tau - a.dlast[nn])) : 0.0f;
+        const float nw = ex ? 0.0f : old + (nvalid ? (float)nch / (float)nvalid : 0.0f);
+        if (!a.dseen[nn]) { a.dseen[nn] = 1; atomicAdd(&a.drift->count, 1u); }
+        a.dsum[nn] = nw; a.dlast[nn] = tau;
+        if (nw != old) atomicAdd(&a.drift->G, (double)nw - (double)old);
+      }
+    } else
     {
       float4 accv[KS], accp[H][NT];
 #pragma unroll
@@ -691,14 +881,15 @@ struct LaunchArgs {
   LayerArgs k;
   hipStream_t s; const uint32_t* rows; const uint32_t* cp; uint32_t cm;
   uint32_t ks, nt, heads;
+  bool delta;                       // the delta-mode variant of the kernel
   uint32_t num_cu;                  // compute units of the device
   bool set_attr; size_t lds; hipError_t err;
   int query_wgs; uint32_t wgs;      // query_wgs: only report the workgroups per CU of the variant in `wgs`
 };
 
-template <int KS, int NT, int H, int JC, int WGS>
-void go(LaunchArgs& a) {
-  auto kern = layer_kernel<KS, NT, H, JC, WGS>;
+template <int KS, int NT, int H, int JC, int WGS, bool DELTA>
+void go_k(LaunchArgs& a) {
+  auto kern = layer_kernel<KS, NT, H, JC, WGS, DELTA>;
   if (a.query_wgs) { a.wgs = WGS; return; }
   if (a.set_attr) {
     a.err = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)a.lds);
@@ -710,6 +901,12 @@ void go(LaunchArgs& a) {
   if (blocks > cap) blocks = cap;
   if (blocks < 1) blocks = 1;
   hipLaunchKernelGGL(kern, dim3((uint32_t)blocks), dim3(256), a.lds, a.s, a.k, a.rows, a.cp, a.cm);
+}
+
+template <int KS, int NT, int H, int JC, int WGS>
+void go(LaunchArgs& a) {
+  if (a.delta) { go_k<KS, NT, H, 1, WGS, true>(a); return; }
+  go_k<KS, NT, H, JC, WGS, false>(a);
 }
 
 // Ring entries per chunk and workgroups per CU are bounded by registers: two chunks of JC * 4 KS

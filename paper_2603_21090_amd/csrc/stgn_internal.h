@@ -69,6 +69,14 @@ struct Ctrl {
   BatchCtl b[kSets];
 };
 
+// Drift estimator of the delta mode (Sec. 3.5, Definition "Drift Estimator", Eq. global_drift): the sum of the
+// per-node estimates, the size of the cumulative affected set since the last rebuild, the batch counter the
+// per-node values decay against, and the length of the list of drifted nodes (stgn_maintain).
+struct DriftCtl {
+  double   G;
+  uint32_t count, tau, n_list, pad;
+};
+
 // Row-table descriptor: row v starts at base + v * ld (floats)
 struct Table {
   float*   base;
@@ -164,6 +172,24 @@ struct Dev {
   uint32_t bucketed;
   uint32_t thr[STGN_MAX_LAYERS];
   uint32_t n_lists;                  // separate lists (layers whose threshold does not cover every flag)
+  // delta mode (Sec. 3.3 "Stage 4", Eq. delta_embedding; null / 0 when it is off): the attention cache per layer
+  // and node -- the sums in effect S (head outputs before the time part, a row of the head-output tile) and
+  // pb (a row of the time tile), the softmax denominator and its reference score per head, and per
+  // recent-neighbour entry (index = recency at the row's last exact recomputation) score and weight in effect per
+  // head and the neighbour|edge part of the value -- the flags of the last batch where the compaction clears
+  // them, and the drift estimator (per node: running sum with lazy decay, batch of the last update, member of
+  // the cumulative affected set)
+  uint32_t delta;
+  float    gamma;
+  float*   ac_S[STGN_MAX_LAYERS];    // [N x 64 ks]
+  float*   ac_P[STGN_MAX_LAYERS];    // [N x 64 nt heads]
+  float*   ac_ZM[STGN_MAX_LAYERS];   // [N x 2 heads]     Z_h at 2h, m_h at 2h + 1
+  float*   ac_W[STGN_MAX_LAYERS];    // [N x k x 2 heads] s_h at 2h, a_h at 2h + 1
+  float*   ac_V[STGN_MAX_LAYERS];    // [N x k x 64 ks]
+  uint8_t* flags_kept;               // [mark_bytes(N)]
+  DriftCtl* drift;
+  float*   dsum; uint32_t* dlast; uint8_t* dseen;   // [N] each
+  uint32_t* dlist;                   // [N] nodes whose estimate exceeds the threshold (stgn_maintain)
   // root-node inference (stgn_predict_batch): the 2n roots (source, destination of edge i at 2i, 2i+1),
   // their query times, their final-layer rows, staging for host inputs / outputs, and the head [w | b]
   uint32_t* pred_rows; double* pred_tq; float* pred_out;
@@ -242,8 +268,14 @@ void launch_expand(const Dev& d, hipStream_t s, uint32_t hop, bool planned, hipE
 void launch_compact(const Dev& d, hipStream_t s, int phase);
 void launch_bucket_rows(const Dev& d, hipStream_t s, bool all_rows);   // regroups the layers' row lists by entry count (Dev::RS)
 bool compact_in_one(const Dev& d);   // the compaction is a single launch (phase 0) for this node count
+// force_exact: recompute every listed row exactly (initial state, rebuilds); otherwise, in delta mode, a row
+// whose own input row and query time are unchanged takes the delta update
 void launch_layer(const Dev& d, hipStream_t s, uint32_t layer, const uint32_t* rows, const uint32_t* count_ptr,
-                  uint32_t count_max);
+                  uint32_t count_max, bool force_exact = true);
+// drift estimator: clear it; list the nodes whose estimate exceeds `threshold` (Dev::dlist, DriftCtl::n_list)
+void launch_drift_reset(const Dev& d, hipStream_t s);
+void launch_drift_list(const Dev& d, hipStream_t s, float threshold);
+void launch_drift_values(const Dev& d, hipStream_t s, float* out);   // every node's decayed estimate, [N]
 void launch_gather_rows(const Dev& d, hipStream_t s, uint32_t layer, uint32_t n, const uint32_t* nodes, float* out);
 void launch_gather_times(const Dev& d, hipStream_t s, uint32_t n, const uint32_t* nodes, double* out);   // last-interaction times
 // root-node inference: roots and query times of n edges; the final layer for the 2n roots; the linear head
