@@ -213,8 +213,10 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
   }
   __syncthreads();
 
-  // ---- staging of a tile, one tile ahead.  Stage A reads the tile's row ids into s_next; stage B
-  // (issued while the previous tile's last products run) fetches, into registers, this thread's
+  // ---- staging of a tile, one tile ahead.  Stage A requests the tile's row ids (ahead of phase 1) and
+  // puts them into s_next once they are there (end of phase 2); stage B (issued with the first gathers of
+  // phase 3, whose waits cover it: a later wait for a weight chunk would stall on it, loads return in
+  // order) fetches, into registers, this thread's
   // share of the rows' ring slots, degrees, query times and own input rows; the tile's phase 0 then
   // only moves registers into LDS.  A workgroup strides over many tiles, so all but its first tile
   // start without waiting for memory.  Shapes whose share does not fit two items per thread stage
@@ -225,12 +227,17 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
   uint32_t p_deg[2];
   double p_tl[2];
   float4 p_x[2];
-  auto stage_a = [&](uint32_t t) {
+  uint32_t p_row = 0xFFFFFFFFu;
+  double p_tqn = 0.0;
+  auto stage_a = [&](uint32_t t) {                            // requests only: nothing waits for the values here
     if (tid < kTM) {
       const uint32_t r = t * kTM + tid;
-      s_next[tid] = (t < ntiles && r < n) ? (rows ? rows[r] : r) : 0xFFFFFFFFu;
-      s_tqn[tid] = (a.tq_rows && t < ntiles && r < n) ? a.tq_rows[r] : 0.0;
+      p_row = (t < ntiles && r < n) ? (rows ? rows[r] : r) : 0xFFFFFFFFu;
+      p_tqn = (a.tq_rows && t < ntiles && r < n) ? a.tq_rows[r] : 0.0;
     }
+  };
+  auto stage_a_commit = [&]() {
+    if (tid < kTM) { s_next[tid] = p_row; s_tqn[tid] = p_tqn; }
   };
   auto stage_b = [&]() {
 #pragma unroll
@@ -267,6 +274,7 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
     if (sl == 0) { s_cnt[r] = cnt; s_tq[r] = a.tq_rows ? s_tqn[r] : tl; }
   };
   stage_a(blockIdx.x);
+  stage_a_commit();
   __syncthreads();
   auto stage_none = [&]() {                                   // keeps the registers defined on every path
 #pragma unroll
@@ -435,7 +443,11 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
         }
       }
     }
+    stage_a_commit();                                         // requested before phase 1: here by now
     __syncthreads();
+    // next tile's rows, in flight among the gathers of phase 3 (four-slot shapes have no registers to
+    // spare in phase 3: theirs are requested behind it)
+    if constexpr (KS <= 2) { if (pf_ok) stage_b(); else stage_none(); }
     // ================================================================ phase 3: gather + attention
     if constexpr (DELTA) {
       // ---- delta mode.  An exact row runs the same online softmax as the exact mode and leaves its attention
@@ -766,7 +778,7 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
       load_b16(wv(h4, n0), 0, ov[0].b[0]);
       load_b16(wv(h4, n1), 0, ov[0].b[1]);
       __syncthreads();
-      if (pf_ok) stage_b(); else stage_none();                // next tile's rows, in flight during phases 4 to 6
+      if constexpr (KS > 2) { if (pf_ok) stage_b(); else stage_none(); }
       for (; x < nunits4; x += 4) {
         if (x != wave) {
           decode4(x);
