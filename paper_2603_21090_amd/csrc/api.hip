@@ -232,11 +232,17 @@ size_t layout(const stgn_config& c, char* base, Dev* d) {
     else { d->R[l] = b.take<uint32_t>(N); ++d->n_lists; }
   }
   // row lists regrouped by entry count: worth a launch once a layer has thousands of tiles
-  d->bucketed = N >= 32768u ? 1u : 0u;
-  for (uint32_t l = 0; l < c.layers; ++l) {
-    if (!d->bucketed) d->RS[l] = nullptr;
-    else if (l && d->thr[l] == 0xFFu && d->thr[l - 1] == 0xFFu) d->RS[l] = d->RS[l - 1];   // both walk A (pointers are null while measuring)
+  d->bucketed = N >= 32768u && c.k <= 64u ? 1u : 0u;          // (the regrouping kernel has bins for up to 64 entries)
+  // query cache: shapes whose tiles are staged a tile ahead (layer_kernel.h: two staged items per thread)
+  d->qcache = d->bucketed && !c.delta_mode && 16u * c.k <= 512u && 4u * round_up(std::max(d->d0, c.d_emb), 16u) <= 512u ? 1u : 0u;
+  d->ld_qc = kSlot * (d->ks + c.heads * d->nt);
+  for (uint32_t l = 0; l < STGN_MAX_LAYERS; ++l) {
+    if (l >= c.layers || !d->bucketed) d->RS[l] = nullptr;
+    else if (l && !d->qcache && d->thr[l] == 0xFFu && d->thr[l - 1] == 0xFFu) d->RS[l] = d->RS[l - 1];   // both walk A (pointers are null while measuring)
     else d->RS[l] = b.take<uint32_t>(N);
+    const bool qc = d->qcache && l < c.layers;
+    d->QC[l] = qc ? b.take<float>((size_t)N * d->ld_qc) : nullptr;
+    d->tile_clean[l] = qc ? b.take<uint8_t>(round_up(N / 16u + 1u, 256u)) : nullptr;
   }
   // delta mode: attention cache per layer, the kept flags, the drift estimator
   d->delta = c.delta_mode;
@@ -249,7 +255,7 @@ size_t layout(const stgn_config& c, char* base, Dev* d) {
     d->ac_W[l] = on ? b.take<float>((size_t)N * c.k * 2 * c.heads) : nullptr;
     d->ac_V[l] = on ? b.take<float>((size_t)N * c.k * kSlot * d->ks) : nullptr;
   }
-  d->flags_kept = c.delta_mode ? b.take<uint8_t>(mark_bytes(N)) : nullptr;
+  d->flags_kept = c.delta_mode || d->qcache ? b.take<uint8_t>(mark_bytes(N)) : nullptr;
   d->drift = c.delta_mode ? b.take<DriftCtl>(1) : nullptr;
   d->dsum = c.delta_mode ? b.take<float>(N) : nullptr;
   d->dlast = c.delta_mode ? b.take<uint32_t>(N) : nullptr;
@@ -582,8 +588,8 @@ int stgn_create(const stgn_config* cfg, const stgn_weights* w, const float* node
   }
   // ring places past a row's entry count read edge 0: its rows must be finite before the first edge arrives
   for (uint32_t l = 0; l < cfg->layers; ++l) launch_zero(ctx->d.KVE[l].base, ctx->d.ld_kv, ctx->stream);
+  if (ctx->d.flags_kept) launch_zero(reinterpret_cast<float*>(ctx->d.flags_kept), mark_bytes(cfg->num_nodes) / sizeof(float), ctx->stream);
   if (cfg->delta_mode) {            // no flag set, estimator at rest
-    launch_zero(reinterpret_cast<float*>(ctx->d.flags_kept), mark_bytes(cfg->num_nodes) / sizeof(float), ctx->stream);
     launch_zero(reinterpret_cast<float*>(ctx->d.drift), sizeof(DriftCtl) / sizeof(float), ctx->stream);
     launch_drift_reset(ctx->d, ctx->stream);
   }

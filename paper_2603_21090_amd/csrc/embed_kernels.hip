@@ -90,10 +90,12 @@ LaunchArgs make_args(const Dev& d, uint32_t layer) {
     k.ac_S = d.ac_S[layer]; k.ac_P = d.ac_P[layer]; k.ac_ZM = d.ac_ZM[layer]; k.ac_W = d.ac_W[layer]; k.ac_V = d.ac_V[layer];
     k.drift = d.drift; k.dsum = d.dsum; k.dlast = d.dlast; k.dseen = d.dseen;
   }
+  k.QC = d.qcache ? d.QC[layer] : nullptr;
+  k.tile_clean = d.qcache ? d.tile_clean[layer] : nullptr;
   a.delta = d.delta != 0;
   a.ks = d.ks; a.nt = d.nt; a.heads = d.heads;
   a.num_cu = d.num_cu;
-  a.lds = (size_t)layer_impl::layer_lds(L.d_in, d.heads, d.ks, d.nt, d.k).total * sizeof(float);
+  a.lds = (size_t)layer_impl::layer_lds(L.d_in, d.heads, d.ks, d.nt, d.k, d.delta != 0).total * sizeof(float);
   a.err = hipSuccess;
   return a;
 }
@@ -121,6 +123,7 @@ void launch_layer(const Dev& d, hipStream_t s, uint32_t layer, const uint32_t* r
                   bool force_exact) {
   LaunchArgs a = make_args(d, layer);
   a.k.force_exact = force_exact ? 1u : 0u;
+  if (force_exact) a.k.tile_clean = nullptr;                   // every row projects its query again (and refreshes the cache)
   a.s = s; a.rows = rows; a.cp = cp; a.cm = cm; a.set_attr = false;
   go_heads(a);
 }
@@ -133,6 +136,8 @@ void launch_predict_prep(const Dev& d, hipStream_t s, uint32_t n, const uint32_t
 void launch_layer_roots(const Dev& d, hipStream_t s, uint32_t nroots) {
   LaunchArgs a = make_args(d, d.layers - 1);
   a.delta = false;                                            // root rows are computed at their own times, from nothing cached
+  a.k.tile_clean = nullptr;                                   // the cached rows are current, hence every root's q and qt
+  a.k.all_clean = a.k.QC ? 1u : 0u;
   a.k.tq_rows = d.pred_tq;
   a.k.out_rows = d.pred_out;
   a.s = s; a.rows = d.pred_rows; a.cp = nullptr; a.cm = nroots; a.set_attr = false;

@@ -253,33 +253,41 @@ __global__ __launch_bounds__(256) void compact_write_kernel(Dev d) {
 // its LONGEST row costs: on skewed graphs a tile of sixteen consecutive ids runs to nearly k entries while
 // the mean row holds a few.  Within every window of 4,096 list positions the rows are regrouped by
 // descending entry count min(deg, k) (a counting sort, stable: ids stay ascending inside a group, and the
-// order is the same on every run); tiles cut from the regrouped list are homogeneous.  A row's result does
-// not depend on which rows share its tile, so only the cost changes.  grid.y = list.
+// order is the same on every run); tiles cut from the regrouped list are homogeneous.  With the query cache
+// the rows whose own input row changed in the batch (flag at most thr_in) come first, grouped the same way,
+// then the others, and every tile of the window is marked: 1 when none of its rows changed.  A row's result
+// does not depend on which rows share its tile, so only the cost changes.  grid.y = list.
 constexpr uint32_t kBucketWindow = 4096;
-constexpr uint32_t kMaxBins = 65;                            // entry counts 0 .. k, k <= 64
-struct BucketJob { const uint32_t* in; const uint32_t* count; uint32_t* out; uint32_t count_max; };
+constexpr uint32_t kMaxBins = 2 * 65;                        // entry counts 0 .. k, k <= 64; changed | unchanged input
+struct BucketJob { const uint32_t* in; const uint32_t* count; uint32_t* out; uint32_t count_max; uint8_t* tile_clean; uint32_t thr_in; };
 struct BucketJobs { BucketJob j[STGN_MAX_LAYERS]; };
 __global__ __launch_bounds__(256) void bucket_rows_kernel(Dev d, BucketJobs jobs) {
   __shared__ uint32_t s[4];
   __shared__ uint32_t s_hist[kMaxBins], s_base[kMaxBins];
+  __shared__ uint32_t s_changed[kBucketWindow / 16];
   const BucketJob job = jobs.j[blockIdx.y];
   uint32_t n = job.count_max;
   if (job.count) { const uint32_t c = *job.count; n = c < n ? c : n; }
   const uint32_t w0 = blockIdx.x * kBucketWindow;
   if (w0 >= n) return;
   const uint32_t t = threadIdx.x, p0 = w0 + t * 16u;
-  const uint32_t nb = d.k + 1u;
+  const uint32_t nbk = d.k + 1u, nb = job.tile_clean ? 2u * nbk : nbk;
   if (t < nb) s_hist[t] = 0u;
+  s_changed[t] = 0u;
   __syncthreads();
   uint32_t id[16], bin[16];
 #pragma unroll
   for (int i = 0; i < 16; ++i) {
     const uint32_t p = p0 + i;
     id[i] = p < n ? (job.in ? job.in[p] : p) : 0xFFFFFFFFu;
-    uint32_t b = 0xFFu;                                      // no row
-    if (p < n) { const uint32_t dg = d.deg[id[i]]; b = d.k - (dg < d.k ? dg : d.k); }   // bin 0 = full rings: longest rows first
+    uint32_t b = 0xFFFFu;                                    // no row
+    if (p < n) {
+      const uint32_t dg = d.deg[id[i]];
+      b = d.k - (dg < d.k ? dg : d.k);                       // bin 0 = full rings: longest rows first
+      if (job.tile_clean && d.flags_kept[id[i]] > job.thr_in) b += nbk;
+    }
     bin[i] = b;
-    if (b != 0xFFu) atomicAdd(&s_hist[b], 1u);
+    if (b != 0xFFFFu) atomicAdd(&s_hist[b], 1u);
   }
   __syncthreads();
   if (t == 0) {
@@ -297,7 +305,14 @@ __global__ __launch_bounds__(256) void bucket_rows_kernel(Dev d, BucketJobs jobs
     uint32_t o = w0 + s_base[b] + excl;
 #pragma unroll
     for (int i = 0; i < 16; ++i)
-      if (bin[i] == b) job.out[o++] = id[i];
+      if (bin[i] == b) {
+        if (b < nbk) s_changed[(o - w0) >> 4] = 1u;          // (every writer stores the same value)
+        job.out[o++] = id[i];
+      }
+  }
+  if (job.tile_clean) {
+    __syncthreads();
+    if (p0 < n) job.tile_clean[p0 >> 4] = s_changed[t] ? 0 : 1;
   }
 }
 
@@ -334,11 +349,12 @@ void launch_bucket_rows(const Dev& d, hipStream_t s, bool all_rows) {
   BucketJobs jobs{};
   uint32_t nj = 0;
   if (all_rows) {
-    jobs.j[nj++] = BucketJob{nullptr, nullptr, d.RS[0], d.N};
+    jobs.j[nj++] = BucketJob{nullptr, nullptr, d.RS[0], d.N, nullptr, 0u};
   } else {
     for (uint32_t l = 0; l < d.layers; ++l) {
-      if (l && d.R[l] == d.R[l - 1]) continue;               // the same list: ordered once (its copy is shared)
-      jobs.j[nj++] = BucketJob{d.R[l], &d.bc->nR[l], d.RS[l], d.N};
+      if (l && d.RS[l] == d.RS[l - 1]) continue;             // the same list: ordered once (its copy is shared)
+      // flags at or below thr_in: the owner's input row of this layer changed in the batch
+      jobs.j[nj++] = BucketJob{d.R[l], &d.bc->nR[l], d.RS[l], d.N, d.tile_clean[l], d.d_mem ? l + 1u : l};
     }
   }
   const uint32_t blocks = (d.N + kBucketWindow - 1) / kBucketWindow;

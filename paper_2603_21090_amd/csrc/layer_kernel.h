@@ -19,6 +19,7 @@
 // Weights stream from L2 (group-major packing, see mfma16.h); several workgroups per CU overlap one's
 // gather with another's products.
 #pragma once
+#include <type_traits>
 #include "stgn_internal.h"
 #include "mfma16.h"
 
@@ -55,6 +56,15 @@ __device__ inline float dot4(const float4 a, const float4 b, float acc) {
   return fmaf(a.w, b.w, acc);
 }
 
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>): register arrays indexed by constants
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (N > 0) {
+    static_for<N - 1>(f);
+    f(std::integral_constant<int, N - 1>{});
+  }
+}
+
 struct LayerLds {
   uint32_t ldx, ldq, ldz;        // strides (floats) of the X / O tile, the Q / H' tile and the qt / pb tile
   uint32_t off_q, off_z, off_r, off_sc, total;
@@ -62,7 +72,7 @@ struct LayerLds {
 
 // Every stride is 4 (mod 8) floats: rows stay 16-byte aligned and the 16 rows of an operand read
 // fall into distinct banks.  ks = key slots (heads * slots per head), nt = time slots.
-__host__ __device__ inline LayerLds layer_lds(uint32_t d_in, uint32_t heads, uint32_t ks, uint32_t nt, uint32_t k) {
+__host__ __device__ inline LayerLds layer_lds(uint32_t d_in, uint32_t heads, uint32_t ks, uint32_t nt, uint32_t k, bool delta) {
   LayerLds l;
   const uint32_t wx = round_up(d_in, kGrpK), wo = kSlot * ks;
   l.ldx = (wx > wo ? wx : wo) + 4;                // the input tile and the head-output tile share storage
@@ -72,7 +82,7 @@ __host__ __device__ inline LayerLds layer_lds(uint32_t d_in, uint32_t heads, uin
   l.off_z = l.off_q + kTM * l.ldq;
   l.off_r = l.off_z + kTM * l.ldz + 4 * kGrpK;    // operand reads may run one chunk past the last row
   l.off_sc = l.off_r + kTM * k * 4;               // the ring records of the tile's rows, 16 bytes each
-  l.total = l.off_sc + kTM * k * heads;           // delta mode: the scores of a row's entries until its weights are known
+  l.total = l.off_sc + (delta ? kTM * k * heads : 0u);       // delta mode: the scores of a row's entries until its weights are known
   return l;
 }
 
@@ -92,6 +102,11 @@ struct LayerArgs {
   const float *WQ, *cQ, *WKT, *WV, *WO, *bO, *WKVnext;   // matrices group-major (mfma16.h)
   uint32_t ld_in, ld_out, ld_kv, ld_kve;           // ld_kve = 0 without edge features (every edge reads one zero row)
   uint32_t k, d_in, d_emb, dk, d_time;
+  // query cache (both null: off): this layer's cached q | qt rows, [node][64 (KS + H NT)], and per tile of the
+  // row list whether every row's input row is unchanged (then q and qt are read back, not projected); a
+  // launch that must recompute everything passes tile_clean = null and still refreshes QC
+  float* QC; const uint8_t* tile_clean;
+  uint32_t all_clean;                              // every listed row reads q | qt back (root-node inference: nothing changed)
   // delta mode (read by the delta variant only): the batch's dirty flags and the highest flag whose owner's
   // input row of this layer changed (a row at or below it, or an endpoint, is recomputed exactly; an entry whose
   // neighbour is at or below it is a changed entry); the attention cache of this layer; the drift estimator
@@ -115,7 +130,7 @@ template <int KS, int NT, int H, int JC, int WGS, bool DELTA>
 __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint32_t* __restrict__ rows,
                                                          const uint32_t* count_ptr, uint32_t count_max) {
   extern __shared__ __align__(16) float lds[];
-  __shared__ uint32_t s_node[kTM], s_cnt[kTM], s_next[kTM], s_ex[kTM];
+  __shared__ uint32_t s_node[kTM], s_cnt[kTM], s_next[kTM], s_ex[kTM], s_cleann;
   __shared__ double s_tq[kTM], s_tqn[kTM];
   __shared__ __align__(16) double s_om[NT * kSlot], s_ph[NT * kSlot];
   static_assert(KS % H == 0, "whole slots per head");
@@ -138,7 +153,7 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
   const uint32_t ntd = round_up(a.d_emb, 16) >> 4, ntk = round_up(dk, 16) >> 4;                           // column tiles
   constexpr uint32_t ntz = Ztp >> 4;                                                                       // tiles of a qt vector
   const uint32_t nzt = (a.d_time + 15u) >> 4;                                                              // ... that hold valid columns
-  const LayerLds ll = layer_lds(a.d_in, H, KS, NT, k);
+  const LayerLds ll = layer_lds(a.d_in, H, KS, NT, k, DELTA);
   float* Xs = lds;                            // input rows (phases 0-1), then head outputs (phases 3-5)
   float* Qs = lds + ll.off_q;                 // q (phases 1-3), then the output rows (phases 5-6)
   float* Zs = lds + ll.off_z;                 // qt (phases 2-3), then pb (phases 3-4)
@@ -226,20 +241,25 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
   RingEntry p_ring[2];
   uint32_t p_deg[2];
   double p_tl[2];
-  float4 p_x[2];
-  uint32_t p_row = 0xFFFFFFFFu;
+  float4 p_x[2];                                              // own input rows (not fetched for a tile that reads q | qt back)
+  constexpr int NQ = KS + H * NT;                             // quads per thread of a tile's cached q | qt rows
+  constexpr uint32_t QW4 = 16u * NQ;                          // quads per cached row
+  uint32_t p_row = 0xFFFFFFFFu, p_clean = 0u;
   double p_tqn = 0.0;
   auto stage_a = [&](uint32_t t) {                            // requests only: nothing waits for the values here
     if (tid < kTM) {
       const uint32_t r = t * kTM + tid;
       p_row = (t < ntiles && r < n) ? (rows ? rows[r] : r) : 0xFFFFFFFFu;
       p_tqn = (a.tq_rows && t < ntiles && r < n) ? a.tq_rows[r] : 0.0;
+      if (tid == 0) p_clean = t < ntiles ? (a.all_clean ? 1u : a.tile_clean ? a.tile_clean[t] : 0u) : 0u;
     }
   };
   auto stage_a_commit = [&]() {
     if (tid < kTM) { s_next[tid] = p_row; s_tqn[tid] = p_tqn; }
+    if (tid == 0) s_cleann = p_clean;
   };
   auto stage_b = [&]() {
+    const bool cl = __builtin_amdgcn_readfirstlane((int)s_cleann) != 0;
 #pragma unroll
     for (int e = 0; e < 2; ++e) {
       const uint32_t x = tid + 256u * e;
@@ -252,12 +272,14 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
         p_deg[e] = a.deg[nn];
         p_tl[e] = a.t_last[nn];
       }
-      {
+      if (!cl) {
         const uint32_t xc = x < kTM * qpr ? x : 0u;
         const uint32_t r = xc / qpr, q = xc - r * qpr;
         const uint32_t node = s_next[r];
         // columns past d_in are row padding of the table (zero)
         p_x[e] = *reinterpret_cast<const float4*>(a.Hin + (size_t)(node != 0xFFFFFFFFu ? node : 0u) * a.ld_in + 4u * q);
+      } else {
+        p_x[e] = make_float4(0.f, 0.f, 0.f, 0.f);
       }
     }
   };
@@ -280,8 +302,8 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
 #pragma unroll
     for (int e = 0; e < 2; ++e) {
       p_ring[e].nbr = 0u; p_ring[e].eid = 0u; p_ring[e].t = 0.0; p_deg[e] = 0u; p_tl[e] = 0.0;
-      p_x[e] = make_float4(0.f, 0.f, 0.f, 0.f);
     }
+    p_x[0] = p_x[1] = make_float4(0.f, 0.f, 0.f, 0.f);
   };
   if (pf_ok) stage_b(); else stage_none();
 
@@ -295,11 +317,15 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
     const uint32_t tile = tile_of(round);
     if (tile >= ntiles) break;                                // wave-uniform; only in a workgroup's last round
     derive_lane();
+    // every row of the tile has its q and qt in the query cache (set by the staging of a tile ago; uniform)
+    const bool clean = __builtin_amdgcn_readfirstlane((int)s_cleann) != 0;
     // ================================================================ phase 0: stage the tile
     Ops16<2> oq;                                              // first weight chunk of this wave's first unit
     const uint32_t w1 = wave < ntd ? wave : 0u;              // loads are unconditional (clamped), products are not
-    load_b16(a.WQ + (size_t)w1 * g_in * kGrpFloats, 0, oq.b[0]);
-    load_b16(a.WQ + (size_t)(w1 + 4 < ntd ? w1 + 4 : w1) * g_in * kGrpFloats, 0, oq.b[1]);
+    if (!clean) {
+      load_b16(a.WQ + (size_t)w1 * g_in * kGrpFloats, 0, oq.b[0]);
+      load_b16(a.WQ + (size_t)(w1 + 4 < ntd ? w1 + 4 : w1) * g_in * kGrpFloats, 0, oq.b[1]);
+    }
     if (tid < kTM) {
       s_node[tid] = s_next[tid];
       if constexpr (DELTA) {
@@ -319,7 +345,7 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
           const uint32_t r = x / k, sl = x - r * k;
           place_ring(r, sl, s_next[r] != 0xFFFFFFFFu, p_ring[e], p_deg[e], p_tl[e]);
         }
-        if (x < kTM * qpr) {
+        if (!clean && x < kTM * qpr) {
           const uint32_t r = x / qpr, q = x - r * qpr;
           const float4 v = s_next[r] != 0xFFFFFFFFu ? p_x[e] : make_float4(0.f, 0.f, 0.f, 0.f);
           *reinterpret_cast<float4*>(Xs + r * ll.ldx + 4u * q) = v;
@@ -388,6 +414,25 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
       }
     };
     ZBuf z0;
+    if (clean) {
+      // the rows' q and qt from the query cache, requested together with the first gather (whose wait at
+      // the start of phase 3 is there in any case), then into their tiles
+      float4 qv[NQ];
+      static_for<NQ>([&](auto E) {
+        constexpr int e = decltype(E)::value;
+        const uint32_t x = tid + 256u * e, r = x / QW4, q4 = x - r * QW4;
+        const uint32_t node = s_node[r];
+        qv[e] = *reinterpret_cast<const float4*>(a.QC + (size_t)(node != 0xFFFFFFFFu ? node : 0u) * (4u * QW4) + 4u * q4);
+      });
+      if constexpr (!DELTA) gather(0, z0);
+      static_for<NQ>([&](auto E) {
+        constexpr int e = decltype(E)::value;
+        const uint32_t x = tid + 256u * e, r = x / QW4, q4 = x - r * QW4;
+        const float4 v = s_node[r] != 0xFFFFFFFFu ? qv[e] : make_float4(0.f, 0.f, 0.f, 0.f);
+        float* dst = q4 < 16u * KS ? Qs + r * ll.ldq + 4u * q4 : Zs + r * ll.ldz + 4u * (q4 - 16u * KS);
+        *reinterpret_cast<float4*>(dst) = v;
+      });
+    } else {
     if constexpr (!DELTA) gather(0, z0);
     // ================================================================ phase 1: q = x W_Q + c_Q
     for (uint32_t nt = wave; nt < ntd; nt += 8) {
@@ -443,11 +488,22 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
         }
       }
     }
-    stage_a_commit();                                         // requested before phase 1: here by now
+    }  // q and qt: read back, or projected
+    stage_a_commit();                                         // requested ahead of the loads waited for above: here by now
     __syncthreads();
     // next tile's rows, in flight among the gathers of phase 3 (four-slot shapes have no registers to
     // spare in phase 3: theirs are requested behind it)
     if constexpr (KS <= 2) { if (pf_ok) stage_b(); else stage_none(); }
+    if (!clean && a.QC && !a.out_rows) {                      // the rows' q | qt for later batches
+      static_for<NQ>([&](auto E) {
+        constexpr int e = decltype(E)::value;
+        const uint32_t x = tid + 256u * e, r = x / QW4, q4 = x - r * QW4;
+        const uint32_t node = s_node[r];
+        const float* src = q4 < 16u * KS ? Qs + r * ll.ldq + 4u * q4 : Zs + r * ll.ldz + 4u * (q4 - 16u * KS);
+        if (node != 0xFFFFFFFFu) *reinterpret_cast<float4*>(a.QC + (size_t)node * (4u * QW4) + 4u * q4) = *reinterpret_cast<const float4*>(src);
+      });
+      __syncthreads();                                        // phase 3 puts pb where qt is: not before every thread has read its share
+    }
     // ================================================================ phase 3: gather + attention
     if constexpr (DELTA) {
       // ---- delta mode.  An exact row runs the same online softmax as the exact mode and leaves its attention

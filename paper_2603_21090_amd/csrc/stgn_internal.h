@@ -170,6 +170,15 @@ struct Dev {
   // graphs large enough for it to pay (bucketed); layers that share a list share the copy
   uint32_t* RS[STGN_MAX_LAYERS];
   uint32_t bucketed;
+  // Query cache (with the regrouped lists, exact mode): per layer and node the query vector q and its time part
+  // qt (Eq. attn_detail: q = [h_v | phi(0)] W_Q; qt_h = q_h W_K,h[time rows]^T), which depend on the node's own
+  // input row only, in the layout of the layer kernel's q and qt tiles.  A listed row whose input row did not
+  // change in the batch reads them back instead of projecting again; the regrouping puts such rows together
+  // and says per tile of 16 list positions whether all of its rows are of that kind (tile_clean).
+  uint32_t qcache;
+  uint32_t ld_qc;                    // floats per cached row: 64 (ks + heads nt)
+  float*   QC[STGN_MAX_LAYERS];      // [N x ld_qc]
+  uint8_t* tile_clean[STGN_MAX_LAYERS];   // [ceil(N / 16)]
   uint32_t thr[STGN_MAX_LAYERS];
   uint32_t n_lists;                  // separate lists (layers whose threshold does not cover every flag)
   // delta mode (Sec. 3.3 "Stage 4", Eq. delta_embedding; null / 0 when it is off): the attention cache per layer
@@ -186,7 +195,7 @@ struct Dev {
   float*   ac_ZM[STGN_MAX_LAYERS];   // [N x 2 heads]     Z_h at 2h, m_h at 2h + 1
   float*   ac_W[STGN_MAX_LAYERS];    // [N x k x 2 heads] s_h at 2h, a_h at 2h + 1
   float*   ac_V[STGN_MAX_LAYERS];    // [N x k x 64 ks]
-  uint8_t* flags_kept;               // [mark_bytes(N)]
+  uint8_t* flags_kept;               // [mark_bytes(N)] (also kept for the query cache)
   DriftCtl* drift;
   float*   dsum; uint32_t* dlast; uint8_t* dseen;   // [N] each
   uint32_t* dlist;                   // [N] nodes whose estimate exceeds the threshold (stgn_maintain)

@@ -35,10 +35,13 @@ def score_bound(o, w, wp, s, d):
     dict(layers=2, d_mem=16, d_edge=12, d_time=16, d_emb=16, d_msg=16, heads=2, k=4),
     dict(layers=2, d_mem=0, d_node=12, d_edge=6, d_time=8, d_emb=16, heads=1, k=5),            # memoryless
     dict(layers=2, d_mem=100, d_edge=172, d_time=100, d_emb=100, d_msg=100, heads=2, k=10),    # the paper's widths
+    # enough nodes for the regrouped row lists and the query cache (the roots read their q back)
+    dict(layers=2, d_mem=16, d_edge=12, d_time=16, d_emb=16, d_msg=16, heads=2, k=4, num_nodes=40000, num_edges=2000, zipf_s=0.7),
+    dict(layers=2, d_mem=0, d_node=12, d_edge=6, d_time=8, d_emb=16, heads=1, k=5, num_nodes=40000, num_edges=2000, zipf_s=0.7),
 ])
 def test_scores_match_the_oracle_before_every_batch(binding, kw):
     import torch
-    w = tiny_workload(num_nodes=300, num_edges=3000, batch=100, zipf_s=1.0, **kw)
+    w = tiny_workload(**{**dict(num_nodes=300, num_edges=3000, batch=100, zipf_s=1.0), **kw})
     nf = synth.node_features(w)
     st = synth.EdgeStream(w)
     W = synth.make_weights(w)
@@ -66,10 +69,12 @@ def test_scores_match_the_oracle_before_every_batch(binding, kw):
     g.close()
 
 
-def test_edge_time_mode_at_a_nodes_own_last_time_reproduces_the_cached_row_bit_for_bit(binding):
+@pytest.mark.parametrize("num_nodes", [200, 40000])
+def test_edge_time_mode_at_a_nodes_own_last_time_reproduces_the_cached_row_bit_for_bit(binding, num_nodes):
     """The roots go through the same layer kernel as the cache refresh, only with the query time taken
-    from the edge: asked at the node's own last-interaction time it must give the cached row's bits."""
-    w = tiny_workload(num_nodes=200, num_edges=2000, batch=100, layers=2, k=4, d_mem=16, d_edge=12, d_time=16,
+    from the edge: asked at the node's own last-interaction time it must give the cached row's bits
+    (with 40,000 nodes the roots read their query vectors back from the query cache)."""
+    w = tiny_workload(num_nodes=num_nodes, num_edges=2000, batch=100, layers=2, k=4, d_mem=16, d_edge=12, d_time=16,
                       d_emb=16, d_msg=16, heads=2)
     st = synth.EdgeStream(w)
     W = synth.make_weights(w)
@@ -83,7 +88,7 @@ def test_edge_time_mode_at_a_nodes_own_last_time_reproduces_the_cached_row_bit_f
         e = np.zeros(2 * w.d_emb, np.float32); e[c] = 1.0           # score = coordinate c of the source row
         g.set_predictor(e, 0.0)
         n = 100                                                      # max_batch
-        for lo in range(0, w.num_nodes, n):
+        for lo in range(0, min(w.num_nodes, 2000), n):
             u = nodes[lo:lo + n]
             got = g.predict_batch(u, np.roll(u, 1), t_last[lo:lo + n], at_edge_time=True)
             assert np.array_equal(got, H[u, c])

@@ -43,7 +43,13 @@ def test_workspace_sizes_scale_with_the_configuration():
     # one cached key|value row per edge and layer (two heads of 50: 2 x 2 x 64 floats) must be inside;
     # the raw edge-feature rows are not kept
     w = synth.WORKLOADS["C4"]
-    assert w.num_edges * (w.layers * 256 * 4) < sizes["C4"] < w.num_edges * (w.layers * 256 * 4 + 128 * 4)
+    # ... and per node and layer the cached query row (q and its time part: 64 x (2 + 2 x 2) floats)
+    per_node = w.layers * 64 * 6 * 4
+    assert w.num_edges * (w.layers * 256 * 4) + w.num_nodes * per_node < sizes["C4"] \
+        < w.num_edges * (w.layers * 256 * 4 + 128 * 4) + w.num_nodes * per_node
+    # delta mode adds the attention cache: per node, layer and recent-neighbour entry the value part and two floats per head
+    d4 = binding.query_workspace(cfg_of(w, delta_mode=1, drift_gamma=0.9))
+    assert d4 - sizes["C4"] > w.num_nodes * w.layers * w.k * (128 + 4) * 4 - w.num_nodes * per_node
 
 
 @pytest.mark.parametrize("ok", [dict(d_emb=256, heads=4), dict(d_emb=256, heads=1), dict(d_emb=130, heads=1),
@@ -57,7 +63,8 @@ def test_widest_supported_attention_shapes(lib, ok):
                                  dict(layers=0), dict(layers=5), dict(k=0), dict(heads=3), dict(heads=0),
                                  dict(d_emb=0), dict(d_time=0), dict(d_mem=0, d_node=0), dict(max_edges=2**31),
                                  dict(d_emb=300, heads=4),      # 75-wide heads: 8 key slots, more than a cached row has
-                                 dict(d_emb=260, heads=1), dict(d_time=129), dict(aggregator=3)])
+                                 dict(d_emb=260, heads=1), dict(d_time=129), dict(aggregator=3), dict(delta_mode=2),
+                                 dict(delta_mode=1, drift_gamma=0.0), dict(delta_mode=1, drift_gamma=1.5)])
 def test_bad_configurations_are_rejected(lib, bad):
     w = synth.WORKLOADS["C1"]
     n = C.c_size_t(0)
