@@ -126,7 +126,8 @@ struct GatherBuf {
 
 // KS key slots in total (heads x slots per head), NT time slots; JC ring entries fetched together.
 // DELTA: the approximate mode of Sec. 3.3 "Stage 4" (attention cache, delta update of changed entries).
-template <int KS, int NT, int H, int JC, int WGS, bool DELTA>
+// QCACHE: the query cache is in use (rows may read q and qt back, rows that project store theirs).
+template <int KS, int NT, int H, int JC, int WGS, bool DELTA, bool QCACHE>
 __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint32_t* __restrict__ rows,
                                                          const uint32_t* count_ptr, uint32_t count_max) {
   extern __shared__ __align__(16) float lds[];
@@ -251,15 +252,15 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
       const uint32_t r = t * kTM + tid;
       p_row = (t < ntiles && r < n) ? (rows ? rows[r] : r) : 0xFFFFFFFFu;
       p_tqn = (a.tq_rows && t < ntiles && r < n) ? a.tq_rows[r] : 0.0;
-      if (tid == 0) p_clean = t < ntiles ? (a.all_clean ? 1u : a.tile_clean ? a.tile_clean[t] : 0u) : 0u;
+      if constexpr (QCACHE) { if (tid == 0) p_clean = t < ntiles ? (a.all_clean ? 1u : a.tile_clean ? a.tile_clean[t] : 0u) : 0u; }
     }
   };
   auto stage_a_commit = [&]() {
     if (tid < kTM) { s_next[tid] = p_row; s_tqn[tid] = p_tqn; }
-    if (tid == 0) s_cleann = p_clean;
+    if constexpr (QCACHE) { if (tid == 0) s_cleann = p_clean; }
   };
   auto stage_b = [&]() {
-    const bool cl = __builtin_amdgcn_readfirstlane((int)s_cleann) != 0;
+    const bool cl = QCACHE && __builtin_amdgcn_readfirstlane((int)s_cleann) != 0;
 #pragma unroll
     for (int e = 0; e < 2; ++e) {
       const uint32_t x = tid + 256u * e;
@@ -318,7 +319,7 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
     if (tile >= ntiles) break;                                // wave-uniform; only in a workgroup's last round
     derive_lane();
     // every row of the tile has its q and qt in the query cache (set by the staging of a tile ago; uniform)
-    const bool clean = __builtin_amdgcn_readfirstlane((int)s_cleann) != 0;
+    const bool clean = QCACHE && __builtin_amdgcn_readfirstlane((int)s_cleann) != 0;
     // ================================================================ phase 0: stage the tile
     Ops16<2> oq;                                              // first weight chunk of this wave's first unit
     const uint32_t w1 = wave < ntd ? wave : 0u;              // loads are unconditional (clamped), products are not
@@ -494,7 +495,7 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
     // next tile's rows, in flight among the gathers of phase 3 (four-slot shapes have no registers to
     // spare in phase 3: theirs are requested behind it)
     if constexpr (KS <= 2) { if (pf_ok) stage_b(); else stage_none(); }
-    if (!clean && a.QC && !a.out_rows) {                      // the rows' q | qt for later batches
+    if (QCACHE && !clean && !a.out_rows) {                    // the rows' q | qt for later batches
       static_for<NQ>([&](auto E) {
         constexpr int e = decltype(E)::value;
         const uint32_t x = tid + 256u * e, r = x / QW4, q4 = x - r * QW4;
@@ -955,9 +956,9 @@ struct LaunchArgs {
   int query_wgs; uint32_t wgs;      // query_wgs: only report the workgroups per CU of the variant in `wgs`
 };
 
-template <int KS, int NT, int H, int JC, int WGS, bool DELTA>
+template <int KS, int NT, int H, int JC, int WGS, bool DELTA, bool QCACHE>
 void go_k(LaunchArgs& a) {
-  auto kern = layer_kernel<KS, NT, H, JC, WGS, DELTA>;
+  auto kern = layer_kernel<KS, NT, H, JC, WGS, DELTA, QCACHE>;
   if (a.query_wgs) { a.wgs = WGS; return; }
   if (a.set_attr) {
     a.err = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)a.lds);
@@ -973,8 +974,9 @@ void go_k(LaunchArgs& a) {
 
 template <int KS, int NT, int H, int JC, int WGS>
 void go(LaunchArgs& a) {
-  if (a.delta) { go_k<KS, NT, H, 1, WGS, true>(a); return; }
-  go_k<KS, NT, H, JC, WGS, false>(a);
+  if (a.delta) { go_k<KS, NT, H, 1, WGS, true, false>(a); return; }
+  if (a.k.QC) { go_k<KS, NT, H, JC, WGS, false, true>(a); return; }
+  go_k<KS, NT, H, JC, WGS, false, false>(a);
 }
 
 // Ring entries per chunk and workgroups per CU are bounded by registers: two chunks of JC * 4 KS

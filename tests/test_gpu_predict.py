@@ -69,20 +69,23 @@ def test_scores_match_the_oracle_before_every_batch(binding, kw):
     g.close()
 
 
-@pytest.mark.parametrize("num_nodes", [200, 40000])
-def test_edge_time_mode_at_a_nodes_own_last_time_reproduces_the_cached_row_bit_for_bit(binding, num_nodes):
+@pytest.mark.parametrize("num_nodes,d_mem,d_node", [(200, 16, 0), (40000, 0, 12)])
+def test_edge_time_mode_at_a_nodes_own_last_time_reproduces_the_cached_row_bit_for_bit(binding, num_nodes, d_mem, d_node):
     """The roots go through the same layer kernel as the cache refresh, only with the query time taken
     from the edge: asked at the node's own last-interaction time it must give the cached row's bits
-    (with 40,000 nodes the roots read their query vectors back from the query cache)."""
-    w = tiny_workload(num_nodes=num_nodes, num_edges=2000, batch=100, layers=2, k=4, d_mem=16, d_edge=12, d_time=16,
-                      d_emb=16, d_msg=16, heads=2)
+    (the memoryless model of 40,000 nodes keeps a query cache, which its roots read)."""
+    w = tiny_workload(num_nodes=num_nodes, num_edges=2000, batch=100, layers=2, k=4, d_mem=d_mem, d_node=d_node, d_edge=12,
+                      d_time=16, d_emb=16, d_msg=16, heads=2)
     st = synth.EdgeStream(w)
     W = synth.make_weights(w)
-    g = binding.StreamTGN.from_workload(w, W)
+    g = binding.StreamTGN.from_workload(w, W, synth.node_features(w))
+    t_last = np.zeros(w.num_nodes)
     for b in range(10):
-        g.ingest_batch(*st.batch(b))
+        s, d, t, ef = st.batch(b)
+        g.ingest_batch(s, d, t, ef)
+        np.maximum.at(t_last, s, t)
+        np.maximum.at(t_last, d, t)
     nodes = np.arange(w.num_nodes, dtype=np.uint32)
-    _, t_last = g.get_memory(nodes)
     H = g.get_embeddings(nodes)
     for c in (0, 7, w.d_emb - 1):
         e = np.zeros(2 * w.d_emb, np.float32); e[c] = 1.0           # score = coordinate c of the source row

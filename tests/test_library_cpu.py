@@ -43,10 +43,13 @@ def test_workspace_sizes_scale_with_the_configuration():
     # one cached key|value row per edge and layer (two heads of 50: 2 x 2 x 64 floats) must be inside;
     # the raw edge-feature rows are not kept
     w = synth.WORKLOADS["C4"]
-    # ... and per node and layer the cached query row (q and its time part: 64 x (2 + 2 x 2) floats)
-    per_node = w.layers * 64 * 6 * 4
-    assert w.num_edges * (w.layers * 256 * 4) + w.num_nodes * per_node < sizes["C4"] \
-        < w.num_edges * (w.layers * 256 * 4 + 128 * 4) + w.num_nodes * per_node
+    assert w.num_edges * (w.layers * 256 * 4) < sizes["C4"] < w.num_edges * (w.layers * 256 * 4 + 128 * 4)
+    # a memoryless model also keeps, per node and layer, the query row (q and its time part: 64 x (2 + 2 x 2) floats)
+    w5 = synth.WORKLOADS["C5"]
+    per_node = w5.layers * 64 * 6 * 4
+    assert w5.num_edges * (w5.layers * 256 * 4) + w5.num_nodes * per_node < sizes["C5"] \
+        < w5.num_edges * (w5.layers * 256 * 4 + 128 * 4) + w5.num_nodes * (per_node + 2048)
+    per_node = 0
     # delta mode adds the attention cache: per node, layer and recent-neighbour entry the value part and two floats per head
     d4 = binding.query_workspace(cfg_of(w, delta_mode=1, drift_gamma=0.9))
     assert d4 - sizes["C4"] > w.num_nodes * w.layers * w.k * (128 + 4) * 4 - w.num_nodes * per_node
