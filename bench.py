@@ -198,6 +198,13 @@ def main():
     ap.add_argument("--rebuilds", type=int, default=3, help="timed full_rebuild() calls at the end")
     ap.add_argument("--cpu-steps", type=int, default=2)
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--delta-mode", action="store_true",
+                    help="run the approximate delta-embedding mode instead of the exact one (a diagnostic: the line's "
+                         "`mode` says so); reports the drift metric and the deviation from an exact rebuild at the end")
+    ap.add_argument("--drift-gamma", type=float, default=0.95)
+    ap.add_argument("--maintain-every", type=int, default=0, help="delta mode: call the rebuild policy every this many batches")
+    ap.add_argument("--delta-max", type=float, default=0.5)
+    ap.add_argument("--alpha", type=float, default=0.1)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (5 times) so that hardware byte counters "
                          "collected around this command can be scaled against a kernel of known traffic")
@@ -246,7 +253,9 @@ def main():
     st = synth.EdgeStream(w)
     weights = synth.make_weights(w)
     nf = synth.node_features(w)
-    g = binding.StreamTGN.from_workload(w, weights, nf)
+    g = binding.StreamTGN.from_workload(w, weights, nf, delta_mode=1 if args.delta_mode else 0,
+                                        drift_gamma=args.drift_gamma if args.delta_mode else 0.0)
+    maintained = {0: 0, 1: 0, 2: 0}
 
     # the whole stream segment that will be used, resident on the device
     used = min((Q + LAT + HOST + KER) * w.batch, w.num_edges)
@@ -276,7 +285,10 @@ def main():
 
     def feed(b, stats=False):
         lo, hi = b * w.batch, min((b + 1) * w.batch, used)
-        return g.ingest_batch(d_src[lo:hi], d_dst[lo:hi], d_ts[lo:hi], d_ef[lo:hi], stats=stats)
+        r = g.ingest_batch(d_src[lo:hi], d_dst[lo:hi], d_ts[lo:hi], d_ef[lo:hi], stats=stats)
+        if args.delta_mode and args.maintain_every and b % args.maintain_every == args.maintain_every - 1:
+            maintained[g.maintain(args.delta_max, args.alpha)[0]] += 1      # (synchronises: part of this mode's cost)
+        return r
 
     b = 0
 
@@ -394,6 +406,25 @@ def main():
         roofline["batches"] = kernel_pass
         roofline["traffic"] = stored_traffic(w.name, kernel_pass)
 
+    # delta mode: how far the cached rows have moved from what an exact recomputation of the same state gives
+    delta = None
+    if args.delta_mode:
+        rng = np.random.default_rng(5)
+        probe = rng.choice(w.num_nodes, size=min(w.num_nodes, 200_000), replace=False).astype(np.uint32)
+        gdrift, tracked = g.drift_status()
+        approx = g.get_embeddings(probe).astype(np.float64)
+        g.full_rebuild()
+        exact = g.get_embeddings(probe).astype(np.float64)
+        dev_ = np.linalg.norm(approx - exact, axis=1) / (np.linalg.norm(exact, axis=1) + 1e-30)
+        moved = dev_ > 0
+        delta = {"drift_gamma": args.drift_gamma, "global_drift": gdrift, "tracked_nodes": tracked,
+                 "maintain_every": args.maintain_every, "delta_max": args.delta_max, "alpha": args.alpha,
+                 "maintain_actions": {"none": maintained[0], "partial": maintained[1], "full": maintained[2]},
+                 "probe_rows": int(len(probe)), "rows_off_exact": int(moved.sum()),
+                 "rel_deviation_p50": float(np.percentile(dev_[moved], 50)) if moved.any() else 0.0,
+                 "rel_deviation_p99": float(np.percentile(dev_[moved], 99)) if moved.any() else 0.0,
+                 "rel_deviation_max": float(dev_.max())}
+
     # full_rebuild(): every layer over all N rows, the largest launches this path has
     rebuild = None
     if args.rebuilds > 0:
@@ -449,6 +480,8 @@ def main():
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
+        "mode": "delta (approximate embeddings; not the headline configuration)" if args.delta_mode else "exact",
+        "delta_mode": delta,
         "config": {"workload": f"{w.name}: {w.num_nodes} nodes, {w.num_edges} edges, Zipf s={w.zipf_s}, "
                                f"d_edge={w.d_edge}, d={w.d_emb}, k={w.k}, heads={w.heads}, layers={w.layers}, "
                                f"batch={w.batch}, {'TGN' if w.d_mem else 'TGAT (memoryless)'}",

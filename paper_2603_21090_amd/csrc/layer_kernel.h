@@ -545,11 +545,25 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
       __builtin_amdgcn_wave_barrier();
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
       uint32_t nch = 0, nvalid = 0;
+      const bool any_delta = __any(!ex);                      // (exact rows take every entry: no flags needed)
+      uint32_t chmask = 0;                                    // entries j0 .. j0 + 31 whose neighbour's input row changed
       for (uint32_t j = 0; j < cmax; ++j) {
+        if ((j & 31u) == 0u && any_delta) {
+          // the flags of 32 entries at once (lane s of a row: entries j + s and j + 16 + s), not one dependent
+          // read per entry
+          chmask = 0;
+#pragma unroll
+          for (uint32_t half = 0; half < 2; ++half) {
+            const uint32_t jj = j + 16u * half + sub;
+            bool c = false;
+            if (jj < cnt) { const uint32_t fl = a.flags[rrow[jj].nbr]; c = fl != 0u && fl <= a.thr_in; }
+            const uint64_t bal = __ballot(c);
+            chmask |= ((uint32_t)(bal >> (16u * grp)) & 0xFFFFu) << (16u * half);
+          }
+        }
         const RingEntry e = rrow[j < k ? j : k - 1u];
         const bool have = j < cnt;
-        const uint32_t fl = have ? a.flags[e.nbr] : 0u;
-        const bool chg = fl != 0u && fl <= a.thr_in;
+        const bool chg = (chmask >> (j & 31u)) & 1u;
         const double dt = tq - e.t;
         const bool vj = have && dt <= a.window;
         const bool act = vj && (ex || chg);
