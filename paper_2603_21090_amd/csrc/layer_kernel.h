@@ -846,31 +846,38 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
         n1 = two4 ? n0 + 1u : n0;
       };
       decode4(x < nunits4 ? x : nunits4 - 1u);
-      load_b16(wv(h4, n0), 0, ov[0].b[0]);
-      load_b16(wv(h4, n1), 0, ov[0].b[1]);
+      // every weight chunk of the wave's first unit is requested ahead of the barrier: one memory latency
+      // for the unit, most of it spent waiting for the slowest wave of phase 3 anyway
+      Upfront16<2, NT> u4;
+      {
+        const float* const B4[2] = {wv(h4, n0), wv(h4, n1)};
+        u4.request(B4, NT);
+      }
       __syncthreads();
       if constexpr (KS > 2) { if (pf_ok) stage_b(); else stage_none(); }
       for (; x < nunits4; x += 4) {
-        if (x != wave) {
+        floatx4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+        if (x == wave) {
+          u4.multiply(Zs + h4 * Ztp + a_z, NT, acc);
+        } else {
           decode4(x);
           load_b16(wv(h4, n0), 0, ov[0].b[0]);
           load_b16(wv(h4, n1), 0, ov[0].b[1]);
-        }
-        const float* Ap = Zs + h4 * Ztp + a_z;
-        const float* B0 = wv(h4, n0);
-        const float* B1 = wv(h4, n1);
-        load_a16(Ap, 0, ov[0].a);
-        floatx4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+          const float* Ap = Zs + h4 * Ztp + a_z;
+          const float* B0 = wv(h4, n0);
+          const float* B1 = wv(h4, n1);
+          load_a16(Ap, 0, ov[0].a);
 #pragma unroll
-        for (int c = 0; c < NT; ++c) {
-          if (c + 1 < NT) {
-            load_a16(Ap, (c + 1) * kCG, ov[(c + 1) & 1].a);
-            load_b16(B0, (c + 1) * kCG, ov[(c + 1) & 1].b[0]);
-            load_b16(B1, (c + 1) * kCG, ov[(c + 1) & 1].b[1]);
+          for (int c = 0; c < NT; ++c) {
+            if (c + 1 < NT) {
+              load_a16(Ap, (c + 1) * kCG, ov[(c + 1) & 1].a);
+              load_b16(B0, (c + 1) * kCG, ov[(c + 1) & 1].b[0]);
+              load_b16(B1, (c + 1) * kCG, ov[(c + 1) & 1].b[1]);
+            }
+            __builtin_amdgcn_sched_barrier(0);      // requests stay ahead of the products they overlap
+            mfma16_chunk<2>(ov[c & 1], acc);
+            __builtin_amdgcn_sched_barrier(0);
           }
-          __builtin_amdgcn_sched_barrier(0);      // requests stay ahead of the products they overlap
-          mfma16_chunk<2>(ov[c & 1], acc);
-          __builtin_amdgcn_sched_barrier(0);
         }
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
@@ -886,15 +893,24 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
     // ================================================================ phase 5: h' = o W_O + b_O
     {
       Ops16<2> oo;
-      load_b16(a.WO + (size_t)w1 * g_o * kGrpFloats, 0, oo.b[0]);
-      load_b16(a.WO + (size_t)(w1 + 4 < ntd ? w1 + 4 : w1) * g_o * kGrpFloats, 0, oo.b[1]);
+      constexpr int U5 = KS <= 2 ? KS : 1;                    // weight chunks of the first unit requested up front
+      Upfront16<2, U5> u5;
+      {
+        const float* const B5[2] = {a.WO + (size_t)w1 * g_o * kGrpFloats, a.WO + (size_t)(w1 + 4 < ntd ? w1 + 4 : w1) * g_o * kGrpFloats};
+        if constexpr (KS <= 2) u5.request(B5, KS);
+        else { load_b16(B5[0], 0, oo.b[0]); load_b16(B5[1], 0, oo.b[1]); }
+      }
       __syncthreads();
       for (uint32_t nt = wave; nt < ntd; nt += 8) {
         const bool two = nt + 4 < ntd;
         const float* const Bt[2] = {a.WO + (size_t)nt * g_o * kGrpFloats, a.WO + (size_t)(two ? nt + 4 : nt) * g_o * kGrpFloats};
         floatx4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
-        if (nt != wave) { load_b16(Bt[0], 0, oo.b[0]); load_b16(Bt[1], 0, oo.b[1]); }
-        mfma16_gemm_pre<2>(Xs + a_x, KS, Bt, acc, oo);
+        if (KS <= 2 && nt == wave) {
+          u5.multiply(Xs + a_x, KS, acc);
+        } else {
+          if (nt != wave) { load_b16(Bt[0], 0, oo.b[0]); load_b16(Bt[1], 0, oo.b[1]); }
+          mfma16_gemm_pre<2>(Xs + a_x, KS, Bt, acc, oo);
+        }
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
           const uint32_t col = (nt + 4 * t) * 16 + m16_col(lane);
