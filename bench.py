@@ -438,8 +438,14 @@ def main():
         tr1 = g.totals()
         ent = (tr1["gathered"] - tr0["gathered"]) / args.rebuilds          # ring records over all layers
         rb_bytes = w.layers * algorithmic_bytes(w, w.num_nodes, ent / w.layers)        # every row, every layer
+        # a rebuild projects every row of every layer and gathers few entries per row (most nodes of a skewed
+        # graph hold short lists): at the published peaks its fp32 matrix work takes longer than its bytes
+        rb_flops = w.num_nodes * sum(sum(projection_flops_per_row(w, l)) for l in range(w.layers))
         rebuild = {"ms": rw * 1e3, "node_layers_per_s": w.num_nodes * w.layers / rw,
                    "algorithmic_GBs": rb_bytes / rw / 1e9, "frac_hbm": rb_bytes / rw / 1e9 / HBM_PEAK_GBS,
+                   "projection_TFLOPs": rb_flops / rw / 1e12,
+                   "frac_mfma_f32": rb_flops / rw / 1e12 / MFMA_F32_PEAK_TFLOPS,
+                   "bound": "mfma" if rb_flops / (MFMA_F32_PEAK_TFLOPS * 1e12) > rb_bytes / (HBM_PEAK_GBS * 1e9) else "hbm",
                    "ring_entries": ent / w.layers}
 
     # per-batch root-node inference (Algorithm 1: embed and score the batch's endpoints BEFORE the batch is

@@ -53,7 +53,8 @@ def trace(dirname, bench_json):
     rows.sort(key=lambda r: int(r["Start_Timestamp"]))
     lay = [r for r in rows if "layer_kernel" in r["Kernel_Name"]]
     dur = [int(r["End_Timestamp"]) - int(r["Start_Timestamp"]) for r in lay]
-    sel = dur[b0 * layers:b1 * layers]
+    # the first `layers` launches are the rebuild at creation; batch b's launches follow those of batch b - 1
+    sel = dur[(b0 + 1) * layers:(b1 + 1) * layers]
     print()
     print(f"layer kernel, launches of batches [{b0}, {b1}) ({len(sel)} launches): average "
           f"{sum(sel) / max(len(sel), 1) / 1e3:.2f} us")
@@ -90,7 +91,7 @@ def traffic(fetch_dir, write_dir, bench_json):
     total = 0.0
     for counter, dirname in (("FETCH_SIZE", fetch_dir), ("WRITE_SIZE", write_dir)):
         disp = _counter(dirname, counter)
-        lay = [v for n, v in disp if "layer_kernel" in n][b0 * layers:b1 * layers]
+        lay = [v for n, v in disp if "layer_kernel" in n][(b0 + 1) * layers:(b1 + 1) * layers]   # (creation launches first)
         cal = [v for n, v in disp if "elementwise" in n][-4:]      # the first copy also pages memory in
         cal_mean = sum(cal) / len(cal)
         factor = GIB_KIB / cal_mean
