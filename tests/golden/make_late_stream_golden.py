@@ -14,7 +14,7 @@ after every checkpoint, so an interrupted replay keeps what it reached).  Only `
 input generators are imported: no value in the file comes from the HIP path.
 
     python tests/golden/make_late_stream_golden.py C3 850 999
-    python tests/golden/make_late_stream_golden.py C4 1000 2000 3000 3500 4250
+    python tests/golden/make_late_stream_golden.py C4 3500 4250
 
 One core; C3 takes minutes, C4 hours (the oracle scans whole adjacency logs per batch).
 """
