@@ -234,18 +234,19 @@ size_t layout(const stgn_config& c, char* base, Dev* d) {
   // row lists regrouped by entry count: worth a launch once a layer has thousands of tiles
   d->bucketed = N >= 32768u && c.k <= 64u ? 1u : 0u;          // (the regrouping kernel has bins for up to 64 entries)
   // query cache: shapes whose tiles are staged a tile ahead (layer_kernel.h: two staged items per thread)
-  // Memoryless models only: there the first layer's inputs never change and layer l's only within l - 1 hops of
-  // an endpoint, so nearly every listed row reads its query back (config 5: layer launch 9 % shorter).  With a
-  // memory, endpoints and their first hop project again at the last layer, and storing their queries costs
-  // what the others save (measured: config 3 4 % slower, config 4 3 % faster, rebuilds 12 % slower).
-  d->qcache = d->bucketed && !c.delta_mode && c.d_mem == 0 && 16u * c.k <= 512u &&
+  // Memoryless models: every layer (the first layer's inputs never change and layer l's only within l - 1 hops
+  // of an endpoint, so nearly every listed row reads its query back; config 5: layer launch 9 % shorter).  With
+  // a memory only the first layer, whose inputs change for the batch's endpoints alone: at the later layers the
+  // endpoints' first hop projects again, most of the affected set on graphs with hubs, and storing those
+  // queries costs what the other rows save (measured with every layer cached: config 3 4 % slower).
+  d->qcache = d->bucketed && !c.delta_mode && 16u * c.k <= 512u &&
               4u * round_up(std::max(d->d0, c.d_emb), 16u) <= 512u ? 1u : 0u;
   d->ld_qc = kSlot * (d->ks + c.heads * d->nt);
   for (uint32_t l = 0; l < STGN_MAX_LAYERS; ++l) {
     if (l >= c.layers || !d->bucketed) d->RS[l] = nullptr;
     else if (l && !d->qcache && d->thr[l] == 0xFFu && d->thr[l - 1] == 0xFFu) d->RS[l] = d->RS[l - 1];   // both walk A (pointers are null while measuring)
     else d->RS[l] = b.take<uint32_t>(N);
-    const bool qc = d->qcache && l < c.layers;
+    const bool qc = d->qcache && l < c.layers && (c.d_mem == 0 || l == 0);
     d->QC[l] = qc ? b.take<float>((size_t)N * d->ld_qc) : nullptr;
     d->tile_clean[l] = qc ? b.take<uint8_t>(round_up(N / 16u + 1u, 256u)) : nullptr;
   }

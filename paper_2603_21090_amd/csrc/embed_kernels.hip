@@ -90,7 +90,7 @@ LaunchArgs make_args(const Dev& d, uint32_t layer) {
     k.ac_S = d.ac_S[layer]; k.ac_P = d.ac_P[layer]; k.ac_ZM = d.ac_ZM[layer]; k.ac_W = d.ac_W[layer]; k.ac_V = d.ac_V[layer];
     k.drift = d.drift; k.dsum = d.dsum; k.dlast = d.dlast; k.dseen = d.dseen;
   }
-  k.QC = d.qcache ? d.QC[layer] : nullptr;
+  k.QC = d.qcache ? d.QC[layer] : nullptr;                     // (null for the layers that keep none)
   k.tile_clean = d.qcache ? d.tile_clean[layer] : nullptr;
   a.delta = d.delta != 0;
   a.ks = d.ks; a.nt = d.nt; a.heads = d.heads;

@@ -42,11 +42,14 @@ def test_workspace_sizes_scale_with_the_configuration():
     assert sizes["C5"] < 200 * 2**30          # the largest workload fits one MI355X (288 GB)
     # one cached key|value row per edge and layer (two heads of 50: 2 x 2 x 64 floats) must be inside;
     # the raw edge-feature rows are not kept
+    # ... and the query row (q and its time part: 64 x (2 + 2 x 2) floats) per node: of the first layer
+    # with a memory, of every layer without
     w = synth.WORKLOADS["C4"]
-    assert w.num_edges * (w.layers * 256 * 4) < sizes["C4"] < w.num_edges * (w.layers * 256 * 4 + 128 * 4)
-    # a memoryless model also keeps, per node and layer, the query row (q and its time part: 64 x (2 + 2 x 2) floats)
+    qrow = 64 * 6 * 4
+    assert w.num_edges * (w.layers * 256 * 4) + w.num_nodes * qrow < sizes["C4"] \
+        < w.num_edges * (w.layers * 256 * 4 + 128 * 4) + w.num_nodes * qrow
     w5 = synth.WORKLOADS["C5"]
-    per_node = w5.layers * 64 * 6 * 4
+    per_node = w5.layers * qrow
     assert w5.num_edges * (w5.layers * 256 * 4) + w5.num_nodes * per_node < sizes["C5"] \
         < w5.num_edges * (w5.layers * 256 * 4 + 128 * 4) + w5.num_nodes * (per_node + 2048)
     per_node = 0
