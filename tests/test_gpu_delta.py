@@ -111,6 +111,15 @@ def test_policy_takes_each_of_its_three_branches(binding):
     assert seen[0] and seen[1] and seen[2], seen
 
 
+def test_delta_mode_with_lists_longer_than_one_flag_fetch(binding):
+    """k = 40: the kernel fetches the flags of 32 entries at a time, a hub's list takes two fetches."""
+    w = tiny_workload(num_nodes=300, num_edges=3000, batch=40, zipf_s=1.2, layers=2, k=40, d_mem=8, d_edge=6, d_time=8,
+                      d_emb=16, d_msg=8, heads=2)
+    g, o, _, n_delta_rows = run(binding, w, delta_max=0.3, alpha=0.2, every=3)
+    assert n_delta_rows > 50
+    g.close()
+
+
 def test_delta_mode_with_a_temporal_window(binding):
     w = tiny_workload(num_nodes=300, num_edges=3000, batch=40, layers=2, k=5, d_mem=16, d_edge=6, d_time=16, d_emb=16,
                       d_msg=16, heads=2, zipf_s=0.8, window=15.0)

@@ -133,6 +133,32 @@ def test_timestamps_of_large_magnitude(binding, kw, shift):
     g.close()
 
 
+@pytest.mark.parametrize("kw", [
+    dict(num_nodes=300, k=40),                                  # more ring slots than a tile stages ahead: staged inside the tile
+    dict(num_nodes=300, k=70, d_mem=0, d_node=12),
+    dict(num_nodes=40000, k=40),                                # regrouped row lists; no query cache at this k
+    dict(num_nodes=40000, k=70),                                # more entries than the regrouping has bins for: plain lists
+    dict(num_nodes=40000, k=70, d_mem=0, d_node=12),
+    dict(num_nodes=40000, k=30, d_mem=0, d_node=12),            # regrouped lists and query cache with nearly full staging
+])
+def test_long_recent_neighbour_lists(binding, kw):
+    """Recent-neighbour lists of 30 to 70 entries, filled by the hubs of a skewed stream, on both sides of
+    the node count from which the row lists are regrouped."""
+    w = tiny_workload(**{**dict(num_edges=3000, batch=100, zipf_s=1.2, layers=2, d_mem=8, d_edge=6, d_time=8, d_emb=16,
+                                d_msg=8, heads=2), **kw})
+    rng = np.random.default_rng(4)
+    some = np.sort(rng.choice(w.num_nodes, 300, replace=False)).astype(np.uint32)
+    g, o, st = run_stream(binding, w, node_feat=synth.node_features(w), full_check_at={3, 11, 19}, nodes_for_rings=some)
+    deg = np.bincount(np.concatenate([st.src, st.dst]), minlength=w.num_nodes)
+    assert (deg >= w.k).sum() >= 3, "no list was filled"
+    g.full_rebuild()
+    ref = o.embed_all()
+    allnodes = np.arange(w.num_nodes, dtype=np.uint32)
+    for l in range(1, w.layers + 1):
+        check_rows(g.get_embeddings(allnodes, layer=l), ref[l - 1], f"after a rebuild: layer {l}")
+    g.close()
+
+
 @pytest.mark.parametrize("d_mem,d_node", [(16, 0), (0, 12)])
 def test_layers_recompute_only_rows_whose_inputs_changed(binding, d_mem, d_node):
     """Layer l of a batch recomputes the endpoints plus the first l hops (one hop less without a
