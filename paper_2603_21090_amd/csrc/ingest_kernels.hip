@@ -172,7 +172,10 @@ __device__ void project_rows(const Dev& d, const float* __restrict__ ef, uint32_
   const uint32_t nE = (all_nodes || !d.d_edge) ? 0u : c->n_edges;
   const uint64_t E0 = c->E_base;
   const uint32_t tD = (nD + kProjRows - 1) / kProjRows, tE = (nE + kProjRows - 1) / kProjRows;
-  const uint32_t ntiles = (tD + d.layers * tE) * d.ks;       // (row tile, column group)
+  // work items: (row tile, column group); for all nodes one item per row tile, which takes every column group
+  // in turn (the rows are staged once, with 16-byte loads)
+  const uint32_t groups_per_item = all_nodes ? d.ks : 1u;
+  const uint32_t ntiles = (tD + d.layers * tE) * (all_nodes ? 1u : d.ks);
   const uint32_t kmax = d.d0 > d.d_edge ? d.d0 : d.d_edge;
   const uint32_t lda = round_up(kmax, kGrpK) + 4;
   const uint32_t lane = threadIdx.x & 63u;
@@ -182,7 +185,8 @@ __device__ void project_rows(const Dev& d, const float* __restrict__ ef, uint32_
   for (uint32_t x = threadIdx.x; x < kProjRows * lda + 4 * kGrpK; x += 256) lds[x] = 0.0f;
   __syncthreads();
   for (uint32_t item = bid; item < ntiles; item += nblk) {
-    const uint32_t tile = item / d.ks, nt = wave + 8u * (item - tile * d.ks);
+    const uint32_t tile = all_nodes ? item : item / d.ks;
+    uint32_t nt = all_nodes ? wave : wave + 8u * (item - tile * d.ks);
     const bool node_job = tile < tD;
     const uint32_t layer = node_job ? 0u : (tile - tD) / tE;
     const uint32_t r0 = (node_job ? tile : (tile - tD) - layer * tE) * kProjRows;
@@ -191,13 +195,22 @@ __device__ void project_rows(const Dev& d, const float* __restrict__ ef, uint32_
     const float* W = node_job ? d.L[0].WKVn : d.L[layer].WKVe;
     float* out = node_job ? d.KV[0].base : d.KVE[layer].base;
     const uint32_t ck = chunks_of(K), gk = kCG * ck;
-    const float* const Bt[2] = {W + (size_t)nt * gk * kGrpFloats, W + (size_t)(nt + 4) * gk * kGrpFloats};
     Ops16<2> P;                                               // first weight chunk, requested ahead of the staging
-    load_b16(Bt[0], 0, P.b[0]);
-    load_b16(Bt[1], 0, P.b[1]);
+    load_b16(W + (size_t)nt * gk * kGrpFloats, 0, P.b[0]);
+    load_b16(W + (size_t)(nt + 4) * gk * kGrpFloats, 0, P.b[1]);
     // stage the rows (columns K .. lda keep zeros or finite leftovers of a wider job: they meet zero weights).
     // A batch endpoint's new memory is read from the batch's scratch rows: the write-back into the
     // memory table runs in the same launch.
+    if (all_nodes) {
+      // whole table rows (stride and row padding are multiples of four floats; padding columns are zero)
+      const uint32_t q4 = round_up(K, 4u) >> 2;
+      for (uint32_t x = threadIdx.x; x < kProjRows * q4; x += 256) {
+        const uint32_t r = x / q4, q = x - r * q4;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (r0 + r < nrows) v = *reinterpret_cast<const float4*>(d.H[0].base + (size_t)(r0 + r) * d.H[0].ld + 4u * q);
+        *reinterpret_cast<float4*>(lds + r * lda + 4u * q) = v;
+      }
+    } else
     for (uint32_t x = threadIdx.x; x < kProjRows * K; x += 256) {
       const uint32_t r = x / K, col = x - r * K;
       float v = 0.0f;
@@ -210,7 +223,9 @@ __device__ void project_rows(const Dev& d, const float* __restrict__ ef, uint32_
       lds[r * lda + col] = v;
     }
     __syncthreads();
-    {
+    for (uint32_t cg = 0; cg < groups_per_item; ++cg, nt += 8u) {
+      const float* const Bt[2] = {W + (size_t)nt * gk * kGrpFloats, W + (size_t)(nt + 4) * gk * kGrpFloats};
+      if (cg) { load_b16(Bt[0], 0, P.b[0]); load_b16(Bt[1], 0, P.b[1]); }
       floatx4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
       mfma16_gemm_pre<2>(lds + a_off, ck, Bt, acc, P);
 #pragma unroll
@@ -367,7 +382,7 @@ void launch_apply(const Dev& d, hipStream_t s, const uint32_t* src, const uint32
 }
 
 void launch_project_nodes(const Dev& d, hipStream_t s) {
-  uint64_t blocks = (uint64_t)((d.N + kProjRows - 1) / kProjRows) * d.ks;
+  uint64_t blocks = (uint64_t)((d.N + kProjRows - 1) / kProjRows);
   const uint32_t cap = 8u * (d.num_cu ? d.num_cu : 256u);
   if (blocks > cap) blocks = cap;
   hipLaunchKernelGGL(project_nodes_kernel, dim3((uint32_t)blocks), dim3(256), project_lds(d), s, d);
