@@ -95,7 +95,7 @@ def stored_traffic(workload, batches):
     return float(m.group(1))
 
 
-def cpu_sample_plan(w, st, Q, n_s=40_000):
+def cpu_sample_plan(w, st, Q, n_s=120_000):
     """Large graphs: the nodes whose rows the CPU oracle will evaluate (uniform over all nodes) and the
     edges their recent-neighbour lists hold after batch Q (ascending edge ids).  Bookkeeping on the raw
     edge list only."""
