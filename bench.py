@@ -496,6 +496,8 @@ def main():
         "p50_batch_latency_ms": float(np.percentile(lat_ms, 50)),
         "p95_batch_latency_ms": float(np.percentile(lat_ms, 95)),
         "affected_embeddings_per_s": aff / wall,
+        # the same count over the time of the layer launches alone (per-stage pass, serial path)
+        "affected_embeddings_per_s_of_embed_stage": (aff / K) / (stage_us[4] / max(n_stage, 1) * 1e-6) if n_stage and stage_us[4] > 0 else None,
         "mean_affected": aff / K,
         "mean_rows_recomputed_per_layer": (tot1["rows"] - tot0["rows"]) / K / w.layers,
         "mean_direct": direct / K,
