@@ -113,7 +113,11 @@ typedef struct {
 } stgn_batch_stats;
 
 /* Device bytes stgn_create needs for this configuration (host computation only): the whole
- * device-resident state, dominated by the per-edge tables (adjacency, features, cached rows). */
+ * device-resident state, dominated by the per-edge tables (adjacency, cached key|value rows of
+ * every edge and layer).  From 32,768 nodes (k <= 32) the library also keeps, per node, the query
+ * vectors of the first layer (of every layer for a model without memory), 64 * (ks + heads * nt)
+ * floats each (ks = heads * ceil(d_emb / heads / 64), nt = ceil(d_time / 64)); delta_mode adds the
+ * attention cache described at stgn_maintain. */
 int stgn_query_workspace(const stgn_config *cfg, size_t *device_bytes);
 
 /* Builds the state on the current device: zero memory (Sec. 2.2.4), empty adjacency, every
