@@ -171,6 +171,8 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
   for (uint32_t x = threadIdx.x; x < ll.off_r; x += 256) lds[x] = 0.0f;
   bool tok[NT][4];
   uint32_t gathered = 0;
+  double drift_sum = 0.0;                     // delta mode: this wave's share of the drift estimator's sum and member count
+  uint32_t drift_new = 0;
   uint32_t a_x, a_q, a_z, c_off_x, c_off_q, c_off_z;
   auto derive_lane = [&]() {
     asm volatile("" : "+v"(tid));
@@ -546,38 +548,61 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
       uint32_t nch = 0, nvalid = 0;
       const bool any_delta = __any(!ex);                      // (exact rows take every entry: no flags needed)
-      uint32_t chmask = 0;                                    // entries j0 .. j0 + 31 whose neighbour's input row changed
-      for (uint32_t j = 0; j < cmax; ++j) {
-        if ((j & 31u) == 0u && any_delta) {
-          // the flags of 32 entries at once (lane s of a row: entries j + s and j + 16 + s), not one dependent
-          // read per entry
-          chmask = 0;
+      struct DBuf { float4 n[2 * KS], e[2 * KS]; uint32_t j; };
+      for (uint32_t jb = 0; jb < cmax; jb += 32u) {
+        // Which of the entries jb .. jb + 31 each row takes, worked out at once (lane s of a row looks at entries
+        // jb + s and jb + 16 + s: their window test and the flag of their neighbour), instead of one dependent
+        // flag read per entry: an exact row takes its valid entries, a delta row the valid ones whose
+        // neighbour's input row changed.
+        uint32_t vmask = 0, cmask = 0;
 #pragma unroll
-          for (uint32_t half = 0; half < 2; ++half) {
-            const uint32_t jj = j + 16u * half + sub;
-            bool c = false;
-            if (jj < cnt) { const uint32_t fl = a.flags[rrow[jj].nbr]; c = fl != 0u && fl <= a.thr_in; }
-            const uint64_t bal = __ballot(c);
-            chmask |= ((uint32_t)(bal >> (16u * grp)) & 0xFFFFu) << (16u * half);
+        for (uint32_t half = 0; half < 2; ++half) {
+          const uint32_t jj = jb + 16u * half + sub;
+          bool v = false, c = false;
+          if (jj < cnt) {
+            const RingEntry e = rrow[jj];
+            v = tq - e.t <= a.window;
+            if (any_delta) { const uint32_t fl = a.flags[e.nbr]; c = fl != 0u && fl <= a.thr_in; }
           }
+          const uint64_t bv = __ballot(v), bc = __ballot(c);
+          vmask |= ((uint32_t)(bv >> (16u * grp)) & 0xFFFFu) << (16u * half);
+          cmask |= ((uint32_t)(bc >> (16u * grp)) & 0xFFFFu) << (16u * half);
         }
-        const RingEntry e = rrow[j < k ? j : k - 1u];
-        const bool have = j < cnt;
-        const bool chg = (chmask >> (j & 31u)) & 1u;
+        const uint32_t amask = ex ? vmask : (vmask & cmask);
+        nvalid += (uint32_t)__popc(vmask);
+        if (!ex) nch += (uint32_t)__popc(amask);
+        // entries some row of the wave takes, in entry order; the cached rows of the next one are in flight
+        // while the current one is worked on
+        const uint32_t wmask = (uint32_t)__builtin_amdgcn_readlane((int)amask, 0) | (uint32_t)__builtin_amdgcn_readlane((int)amask, 16) |
+                               (uint32_t)__builtin_amdgcn_readlane((int)amask, 32) | (uint32_t)__builtin_amdgcn_readlane((int)amask, 48);
+        const uint32_t n_items = (uint32_t)__popc(wmask);
+        if (n_items == 0u) continue;
+        uint32_t cur_idx = 0, cur_mask = wmask;               // item c = the c-th set bit (requests come in ascending c)
+        auto fetch = [&](uint32_t c, DBuf& bf) {
+          while (cur_idx < c) { cur_mask &= cur_mask - 1u; ++cur_idx; }
+          const uint32_t j = jb + (uint32_t)__builtin_ctz(cur_mask);
+          bf.j = j;
+          const RingEntry e = rrow[j];
+          const bool act = (amask >> (j - jb)) & 1u;
+          const float* nrow = a.KVn + (size_t)(act ? e.nbr : 0u) * a.ld_kv + 4u * sub;
+          const float* erow = a.KVe + (size_t)(act ? e.eid : 0u) * a.ld_kve + 4u * sub;
+#pragma unroll
+          for (int s = 0; s < 2 * KS; ++s) {
+            bf.n[s] = *reinterpret_cast<const float4*>(nrow + s * kSlot);
+            bf.e[s] = *reinterpret_cast<const float4*>(erow + s * kSlot);
+          }
+        };
+        auto work = [&](uint32_t, const DBuf& bf) {
+        const uint32_t j = bf.j;
+        const RingEntry e = rrow[j];
+        const bool act = (amask >> (j - jb)) & 1u;
         const double dt = tq - e.t;
-        const bool vj = have && dt <= a.window;
-        const bool act = vj && (ex || chg);
-        nvalid += vj ? 1u : 0u;
-        if (!__any(act)) continue;                            // no row of this wave needs the entry
-        const float* nrow = a.KVn + (size_t)(act ? e.nbr : 0u) * a.ld_kv + 4u * sub;
-        const float* erow = a.KVe + (size_t)(act ? e.eid : 0u) * a.ld_kve + 4u * sub;
         float4 kk[KS], vv[KS];
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
-          const float4 kn = *reinterpret_cast<const float4*>(nrow + s * kSlot), ke = *reinterpret_cast<const float4*>(erow + s * kSlot);
-          const float4 vn = *reinterpret_cast<const float4*>(nrow + (KS + s) * kSlot), ve = *reinterpret_cast<const float4*>(erow + (KS + s) * kSlot);
-          kk[s] = make_float4(kn.x + ke.x, kn.y + ke.y, kn.z + ke.z, kn.w + ke.w);
-          vv[s] = make_float4(vn.x + ve.x, vn.y + ve.y, vn.z + ve.z, vn.w + ve.w);
+          kk[s] = make_float4(bf.n[s].x + bf.e[s].x, bf.n[s].y + bf.e[s].y, bf.n[s].z + bf.e[s].z, bf.n[s].w + bf.e[s].w);
+          vv[s] = make_float4(bf.n[KS + s].x + bf.e[KS + s].x, bf.n[KS + s].y + bf.e[KS + s].y,
+                              bf.n[KS + s].z + bf.e[KS + s].z, bf.n[KS + s].w + bf.e[KS + s].w);
         }
         float4 zt[NT];
 #pragma unroll
@@ -623,7 +648,6 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
               if (sub == 0) Sc[(local * k + j) * H + h] = sc[h];
             }
           } else {
-            nch += 1u;
 #pragma unroll
             for (int h = 0; h < H; ++h) {
               const float s_old = w[2 * h], a_old = w[2 * h + 1];
@@ -649,6 +673,10 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
 #pragma unroll
           for (int s = 0; s < KS; ++s) *reinterpret_cast<float4*>(vc + s * kSlot) = vv[s];
         }
+        };
+        DBuf b0;
+        fetch(0u, b0);
+        pingpong_clamped<DBuf>(n_items, b0, fetch, work);
       }
       // ---- the row's sums: normalised by the denominator after an exact recomputation, as they stand after a delta update
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -682,14 +710,24 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
       }
       // ---- drift estimator (Sec. 3.5), final layer: an exact recomputation restarts the node's estimate, a
       // delta update adds the changed fraction of its entries to the decayed estimate
+      // (the changes of the sum and of the member count are collected per wave and added once, at the end of
+      // the launch: one update of the same word per row serialises -- 860 K of them took half of a launch)
+      float dg = 0.0f;
+      uint32_t dc = 0u;
       if (a.is_final && live && sub == 0 && !a.out_rows) {
         const uint32_t tau = a.drift->tau;
         const float old = a.dseen[nn] ? a.dsum[nn] * __powf(a.gamma, (float)(tau - a.dlast[nn])) : 0.0f;
         const float nw = ex ? 0.0f : old + (nvalid ? (float)nch / (float)nvalid : 0.0f);
-        if (!a.dseen[nn]) { a.dseen[nn] = 1; atomicAdd(&a.drift->count, 1u); }
+        if (!a.dseen[nn]) { a.dseen[nn] = 1; dc = 1u; }
         a.dsum[nn] = nw; a.dlast[nn] = tau;
-        if (nw != old) atomicAdd(&a.drift->G, (double)nw - (double)old);
+        dg = nw - old;
       }
+      drift_sum += (double)__int_as_float(__builtin_amdgcn_readlane(__float_as_int(dg), 0)) +
+                   (double)__int_as_float(__builtin_amdgcn_readlane(__float_as_int(dg), 16)) +
+                   (double)__int_as_float(__builtin_amdgcn_readlane(__float_as_int(dg), 32)) +
+                   (double)__int_as_float(__builtin_amdgcn_readlane(__float_as_int(dg), 48));
+      drift_new += (uint32_t)__builtin_amdgcn_readlane((int)dc, 0) + (uint32_t)__builtin_amdgcn_readlane((int)dc, 16) +
+                   (uint32_t)__builtin_amdgcn_readlane((int)dc, 32) + (uint32_t)__builtin_amdgcn_readlane((int)dc, 48);
     } else
     {
       float4 accv[KS], accp[H][NT];
@@ -956,6 +994,12 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
       }
     }
     __syncthreads();
+  }
+  if constexpr (DELTA) {
+    if (lane == 0 && a.is_final && !a.out_rows) {
+      if (drift_sum != 0.0) atomicAdd(&a.drift->G, drift_sum);
+      if (drift_new) atomicAdd(&a.drift->count, drift_new);
+    }
   }
   // statistics: the workgroup's count goes into the slot of its index with a plain update (launches
   // on one stream follow each other, and no other workgroup of a launch has this index); thousands of
