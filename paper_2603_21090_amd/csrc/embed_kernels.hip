@@ -175,10 +175,19 @@ __global__ __launch_bounds__(256) void drift_reset_kernel(Dev d) {
 __global__ __launch_bounds__(256) void drift_list_kernel(Dev d, float threshold) {
   const uint32_t nth = gridDim.x * blockDim.x, tid = blockIdx.x * blockDim.x + threadIdx.x;
   const uint32_t tau = d.drift->tau;
-  for (uint32_t v = tid; v < d.N; v += nth) {
-    if (!d.dseen[v]) continue;
-    const float now = d.dsum[v] * __powf(d.gamma, (float)(tau - d.dlast[v]));
-    if (now > threshold) d.dlist[atomicAdd(&d.drift->n_list, 1u)] = v;
+  // (grid-stride with a uniform trip count: every lane of a wave takes part in the ballots; one reservation
+  // of list places per wave and round)
+  const uint32_t lane = threadIdx.x & 63u;
+  for (uint32_t v0 = tid - lane; v0 < d.N; v0 += nth) {
+    const uint32_t v = v0 + lane;
+    bool hit = false;
+    if (v < d.N && d.dseen[v]) hit = d.dsum[v] * __powf(d.gamma, (float)(tau - d.dlast[v])) > threshold;
+    const uint64_t m = __ballot(hit);
+    if (m == 0ull) continue;
+    uint32_t base = 0;
+    if (lane == 0) base = atomicAdd(&d.drift->n_list, (uint32_t)__popcll(m));
+    base = (uint32_t)__builtin_amdgcn_readfirstlane((int)base);
+    if (hit) d.dlist[base + (uint32_t)__popcll(m & ((1ull << lane) - 1ull))] = v;
   }
 }
 
