@@ -514,8 +514,7 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
       // pb, the denominator and its reference score.  A delta row starts from its cached sums and visits only
       // the entries whose neighbour's input row changed: new score, denominator Z' = Z - e_old + e_new, new
       // weight e_new / Z', sums corrected by (new weight x new value) - (old weight x old value); the
-      // other entries keep the weight they have (Eq. delta_embedding, "updated neighbours").  Plain loop,
-      // no prefetch: the mode trades exactness for touching fewer rows, not for a tuned pipeline.
+      // other entries keep the weight they have (Eq. delta_embedding, "updated neighbours").
       float* Sc = lds + ll.off_sc;
       const uint32_t node = s_node[local];
       const bool live = node != 0xFFFFFFFFu;
@@ -524,6 +523,13 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
       float* acS = a.ac_S + (size_t)nn * (kSlot * KS) + 4u * sub;
       float* acP = a.ac_P + (size_t)nn * (kSlot * NT * H) + 4u * sub;
       float* acZM = a.ac_ZM + (size_t)nn * (2 * H);
+      // (first, and behind a fence of its own: a fence further down would wait for the cache reads below)
+      for (uint32_t j = sub; j < cnt; j += 16)
+#pragma unroll
+        for (int h = 0; h < H; ++h) Sc[(local * k + j) * H + h] = -INFINITY;
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
       float4 accv[KS], accp[H][NT];
       float mref[H], lrun[H];                                 // exact row: running reference and denominator; delta row: m and Z
 #pragma unroll
@@ -540,12 +546,6 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
 #pragma unroll
       for (int s = 0; s < KS; ++s) qk[s] = *reinterpret_cast<const float4*>(Qs + local * ll.ldq + s * kSlot + 4u * sub);
       const float* zq = Zs + local * ll.ldz + 4u * sub;
-      for (uint32_t j = sub; j < cnt; j += 16)
-#pragma unroll
-        for (int h = 0; h < H; ++h) Sc[(local * k + j) * H + h] = -INFINITY;
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-      __builtin_amdgcn_wave_barrier();
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
       uint32_t nch = 0, nvalid = 0;
       const bool any_delta = __any(!ex);                      // (exact rows take every entry: no flags needed)
       struct DBuf { float4 n[2 * KS], e[2 * KS]; uint32_t j; };
