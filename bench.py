@@ -10,7 +10,8 @@ FIXED position of the stream, whatever --warmup / --steps say:
   state    batches [0, P), P = 70 % of the stream, untimed: builds the graph state
   warmup   W more untimed batches                              (--warmup, default 0)
   timed    K batches enqueued back to back, one sync          -> `value` (edges/s), ms_per_step
-           (--steps, default: all of [P + W, Q), Q = 85 % of the stream; W + K must fit in there)
+           (--steps, default: all of [P + W, Q), Q = 85 % of the stream; a W + K longer than that moves P
+           back, down to 20 % of the stream)
   filler   untimed up to batch Q
   latency  from batch Q on, one sync per batch                 -> p50 / p95 batch latency
   host     next batches fed from host memory                   -> PCIe-inclusive rate
@@ -230,9 +231,12 @@ def main():
     LAT = min(rest * 6 // 15, 160) if args.latency_steps is None else args.latency_steps
     HOST = min(rest * 4 // 15, 48) if args.host_steps is None else args.host_steps
     KER = min(rest - LAT - HOST, 100) if args.kernel_steps is None else args.kernel_steps
+    if K > 0 and W >= 0 and P + W + K > Q and Q - W - K >= int(0.20 * nb):
+        P = Q - W - K                      # a longer timed span than 15 % of the stream: it starts earlier, and still ends at Q
     if K <= 0 or W < 0 or P + W + K > Q:
-        print(f"bench.py: warmup {W} + steps {K} do not fit the timed span of {Q - P} batches "
-              f"(batches [{P}, {Q}) of the {nb}-batch stream)", file=sys.stderr)
+        print(f"bench.py: warmup {W} + steps {K} do not fit batches [{int(0.20 * nb)}, {Q}) of the {nb}-batch stream "
+              f"(at least the first 20 % build the graph state, the passes from batch {Q} on have fixed positions)",
+              file=sys.stderr)
         sys.exit(2)
     if Q + LAT + HOST + KER > nb:
         print(f"bench.py: latency {LAT} + host {HOST} + kernel {KER} batches exceed the last {rest} batches of the stream",
