@@ -96,6 +96,21 @@ def stored_traffic(workload, batches):
     return float(m.group(1))
 
 
+def pass_positions(nb, latency_steps=None, host_steps=None, kernel_steps=None):
+    """Fixed positions of the passes in a stream of nb batches: (P, Q, LAT, HOST, KER, [first, last) of the
+    per-kernel pass) -- the state-building prefix, the start of the diagnostic passes, their lengths, and the
+    batches whose layer launches the roofline figures (and the stored counter traffic) refer to."""
+    P = int(0.70 * nb)
+    Q = int(0.85 * nb)
+    rest = nb - Q
+    LAT = min(rest * 6 // 15, 160) if latency_steps is None else latency_steps
+    HOST = min(rest * 4 // 15, 48) if host_steps is None else host_steps
+    KER = min(rest - LAT - HOST, 100) if kernel_steps is None else kernel_steps
+    n_stage = min(20, KER)
+    first = Q + LAT + HOST + n_stage
+    return P, Q, LAT, HOST, KER, [first, first + KER - n_stage]
+
+
 def cpu_sample_plan(w, st, Q, n_s=120_000):
     """Large graphs: the nodes whose rows the CPU oracle will evaluate (uniform over all nodes) and the
     edges their recent-neighbour lists hold after batch Q (ascending edge ids).  Bookkeeping on the raw
@@ -223,14 +238,11 @@ def main():
         w = w.scaled(name=f"{w.name}(B={args.batch or w.batch},k={args.k or w.k})", batch=args.batch or w.batch,
                      k=args.k or w.k)
     nb = w.num_batches
-    P = int(0.70 * nb)                     # state-building prefix: the same for every invocation
-    Q = int(0.85 * nb)                     # the diagnostic passes start here: the same for every invocation
+    # state-building prefix and start of the diagnostic passes: the same for every invocation
+    P, Q, LAT, HOST, KER, _ = pass_positions(nb, args.latency_steps, args.host_steps, args.kernel_steps)
     W = 0 if args.warmup is None else args.warmup
     K = (Q - P - W) if args.steps is None else args.steps
     rest = nb - Q
-    LAT = min(rest * 6 // 15, 160) if args.latency_steps is None else args.latency_steps
-    HOST = min(rest * 4 // 15, 48) if args.host_steps is None else args.host_steps
-    KER = min(rest - LAT - HOST, 100) if args.kernel_steps is None else args.kernel_steps
     if K > 0 and W >= 0 and P + W + K > Q and Q - W - K >= int(0.20 * nb):
         P = Q - W - K                      # a longer timed span than 15 % of the stream: it starts earlier, and still ends at Q
     if K <= 0 or W < 0 or P + W + K > Q:

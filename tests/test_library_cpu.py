@@ -96,3 +96,14 @@ def test_create_without_workspace_or_device_fails_cleanly(lib):
     assert rc == -8 and not h.value
     rc = lib.stgn_create(C.byref(cfg_of(w)), None, None, None, 0, None, C.byref(h))
     assert rc == -1
+
+
+@pytest.mark.parametrize("name", ["C2", "C4", "C5"])
+def test_stored_counter_traffic_belongs_to_the_batches_the_benchmark_profiles(name):
+    """bench.py reports `roofline.traffic` from the counter summaries under profiles/, which are keyed to a
+    batch range: it must be the range of the benchmark's per-kernel pass, or the figure silently turns null."""
+    import bench
+    w = synth.WORKLOADS[name]
+    window = bench.pass_positions(w.num_batches)[5]
+    got = bench.stored_traffic(name, window)
+    assert got is not None and got > 0, f"profiles/layer_kernel_{name}_hbm_traffic.txt does not cover batches {window}"
