@@ -191,10 +191,17 @@ size_t layout(const stgn_config& c, char* base, Dev* d) {
   if (d->sh == 3) d->sh = 4;                                  // kernel variants exist for 1, 2 and 4 slots per head
   d->ks = c.heads * d->sh;
   d->nt = (c.d_time + kSlot - 1) / kSlot;
+  // edge features of at most one slot stay raw rows (stgn_internal.h); the delta mode caches per-entry values
+  // that hold the edge part, and keeps the projected edge rows
+  d->es = c.d_edge && c.d_edge <= kSlot && !c.delta_mode ? 1u : 0u;
+  if (d->es && !layer_tiles_fit(*d, d->nt + 1)) d->es = 0;   // (shapes whose tiles fill the LDS as they are)
+  d->nz = d->nt + d->es;
   d->ld_kv = 2 * kSlot * d->ks;
+  float* raw_rows = d->es ? b.take<float>((size_t)c.max_edges * kSlot) : nullptr;
   for (uint32_t l = 0; l < c.layers; ++l) {
     d->KV[l].ld = d->ld_kv;
     d->KV[l].base = b.take<float>((size_t)N * d->ld_kv);
+    if (d->es) { d->KVE[l].ld = kSlot; d->KVE[l].base = raw_rows; continue; }
     d->KVE[l].ld = c.d_edge ? d->ld_kv : 0;                   // without edge features every edge reads one zero row
     d->KVE[l].base = b.take<float>((size_t)(c.d_edge ? c.max_edges : 1) * d->ld_kv);
   }
@@ -241,7 +248,7 @@ size_t layout(const stgn_config& c, char* base, Dev* d) {
   // queries costs what the other rows save (measured with every layer cached: config 3 4 % slower).
   d->qcache = d->bucketed && !c.delta_mode && 16u * c.k <= 512u &&
               4u * round_up(std::max(d->d0, c.d_emb), 16u) <= 512u ? 1u : 0u;
-  d->ld_qc = kSlot * (d->ks + c.heads * d->nt);
+  d->ld_qc = kSlot * (d->ks + c.heads * d->nz);
   for (uint32_t l = 0; l < STGN_MAX_LAYERS; ++l) {
     if (l >= c.layers || !d->bucketed) d->RS[l] = nullptr;
     else if (l && !d->qcache && d->thr[l] == 0xFFu && d->thr[l - 1] == 0xFFu) d->RS[l] = d->RS[l - 1];   // both walk A (pointers are null while measuring)
@@ -301,12 +308,12 @@ size_t layout(const stgn_config& c, char* base, Dev* d) {
     LayerDev& L = d->L[l];
     L.WQn = b.take<float>(tiled_size(L.d_in, c.d_emb));
     L.cQ = b.take<float>(c.d_emb);
-    L.WKT = b.take<float>(tiled_size(kSlot * d->sh, c.heads * kSlot * d->nt));
-    L.WV = b.take<float>(tiled_size(kSlot * d->nt, c.heads * round_up(d->dk, 16)));
+    L.WKT = b.take<float>(tiled_size(kSlot * d->sh, c.heads * kSlot * d->nz));
+    L.WV = b.take<float>(tiled_size(kSlot * d->nz, c.heads * round_up(d->dk, 16)));
     L.WO = b.take<float>(tiled_size(kSlot * d->ks, c.d_emb));
     L.bO = b.take<float>(c.d_emb);
     L.WKVn = b.take<float>(tiled_size(L.d_in, d->ld_kv));
-    L.WKVe = c.d_edge ? b.take<float>(tiled_size(c.d_edge, d->ld_kv)) : nullptr;
+    L.WKVe = c.d_edge && !d->es ? b.take<float>(tiled_size(c.d_edge, d->ld_kv)) : nullptr;
   }
   return (b.off + 255) & ~(size_t)255;
 }
@@ -362,7 +369,7 @@ int pack_parameters(stgn_ctx* ctx, const stgn_weights* w) {
   // Row z of W_K / W_V belongs to the node block (z < d_in), the edge block or the time block of the
   // attention input; column h dk + cc to head h.  In a cached row and in the head-output tile head h
   // starts at float 64 sh h (padded-head layout).
-  const uint32_t dk = d.dk, npk = round_up(dk, 16), hp = kSlot * d.sh, Ztp = kSlot * d.nt;
+  const uint32_t dk = d.dk, npk = round_up(dk, 16), hp = kSlot * d.sh, Ztp = kSlot * d.nz;
   const double inv_sqrt_dk = 1.0 / std::sqrt((double)dk);
   for (uint32_t l = 0; l < c.layers; ++l) {
     const LayerDev& L = d.L[l];
@@ -380,16 +387,22 @@ int pack_parameters(stgn_ctx* ctx, const stgn_weights* w) {
         acc += tscale * std::cos((double)w->phase[i]) * (double)WQ[(size_t)(L.d_in + i) * c.d_emb + col];
       cQ[col] = (float)(acc * inv_sqrt_dk);
     }
-    // time rows of W_K, head blocks transposed: K = column inside the head, columns = (head, time index);
-    // time rows of W_V, head blocks: K = time index, columns = (head, column inside the head padded to 16)
+    // time rows of W_K, head blocks transposed: K = column inside the head, columns = (head, index in z);
+    // time rows of W_V, head blocks: K = index in z, columns = (head, column inside the head padded to 16).
+    // z = [phi | f]: time index i at i, and with raw edge rows feature i at 64 nt + i.
     std::vector<float> WKT(tiled_size(hp, c.heads * Ztp), 0.0f);
     std::vector<float> WVp(tiled_size(Ztp, c.heads * npk), 0.0f);
     for (uint32_t h = 0; h < c.heads; ++h)
-      for (uint32_t i = 0; i < c.d_time; ++i)
-        for (uint32_t cc = 0; cc < dk; ++cc) {
+      for (uint32_t cc = 0; cc < dk; ++cc) {
+        for (uint32_t i = 0; i < c.d_time; ++i) {
           put_tiled(WKT, hp, cc, h * Ztp + i, (double)WK[(size_t)(t0 + i) * c.d_emb + h * dk + cc] * tscale);
           put_tiled(WVp, Ztp, i, h * npk + cc, (double)WV[(size_t)(t0 + i) * c.d_emb + h * dk + cc] * tscale);
         }
+        for (uint32_t i = 0; i < (d.es ? c.d_edge : 0u); ++i) {
+          put_tiled(WKT, hp, cc, h * Ztp + kSlot * d.nt + i, WK[(size_t)(e0 + i) * c.d_emb + h * dk + cc]);
+          put_tiled(WVp, Ztp, kSlot * d.nt + i, h * npk + cc, WV[(size_t)(e0 + i) * c.d_emb + h * dk + cc]);
+        }
+      }
     // W_O with its rows moved to the padded-head layout of the head outputs
     std::vector<float> WO(tiled_size(kSlot * d.ks, c.d_emb), 0.0f);
     for (uint32_t h = 0; h < c.heads; ++h)
@@ -398,7 +411,7 @@ int pack_parameters(stgn_ctx* ctx, const stgn_weights* w) {
           put_tiled(WO, kSlot * d.ks, h * hp + cc, col, WOs[(size_t)(h * dk + cc) * c.d_emb + col]);
     // node and edge rows of [W_K | W_V] in the cached-row layout: keys in floats [0, 64 ks), values behind
     std::vector<float> WKVn(tiled_size(L.d_in, d.ld_kv), 0.0f);
-    std::vector<float> WKVe(c.d_edge ? tiled_size(c.d_edge, d.ld_kv) : 0, 0.0f);
+    std::vector<float> WKVe(c.d_edge && !d.es ? tiled_size(c.d_edge, d.ld_kv) : 0, 0.0f);
     for (uint32_t h = 0; h < c.heads; ++h)
       for (uint32_t cc = 0; cc < dk; ++cc) {
         const uint32_t kc = h * hp + cc, vc = kSlot * d.ks + h * hp + cc;
@@ -407,7 +420,7 @@ int pack_parameters(stgn_ctx* ctx, const stgn_weights* w) {
           put_tiled(WKVn, L.d_in, i, kc, WK[(size_t)i * c.d_emb + wc]);
           put_tiled(WKVn, L.d_in, i, vc, WV[(size_t)i * c.d_emb + wc]);
         }
-        for (uint32_t i = 0; i < c.d_edge; ++i) {
+        for (uint32_t i = 0; i < (d.es ? 0u : c.d_edge); ++i) {
           put_tiled(WKVe, c.d_edge, i, kc, WK[(size_t)(e0 + i) * c.d_emb + wc]);
           put_tiled(WKVe, c.d_edge, i, vc, WV[(size_t)(e0 + i) * c.d_emb + wc]);
         }
@@ -593,7 +606,7 @@ int stgn_create(const stgn_config* cfg, const stgn_weights* w, const float* node
     if (e != hipSuccess) { ctx->err = std::string("node feature upload: ") + hipGetErrorString(e); return bail(STGN_E_DEVICE); }
   }
   // ring places past a row's entry count read edge 0: its rows must be finite before the first edge arrives
-  for (uint32_t l = 0; l < cfg->layers; ++l) launch_zero(ctx->d.KVE[l].base, ctx->d.ld_kv, ctx->stream);
+  for (uint32_t l = 0; l < cfg->layers; ++l) launch_zero(ctx->d.KVE[l].base, ctx->d.es ? kSlot : ctx->d.ld_kv, ctx->stream);
   if (ctx->d.flags_kept) launch_zero(reinterpret_cast<float*>(ctx->d.flags_kept), mark_bytes(cfg->num_nodes) / sizeof(float), ctx->stream);
   if (cfg->delta_mode) {            // no flag set, estimator at rest
     launch_zero(reinterpret_cast<float*>(ctx->d.drift), sizeof(DriftCtl) / sizeof(float), ctx->stream);

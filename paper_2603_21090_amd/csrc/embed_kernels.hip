@@ -81,7 +81,7 @@ LaunchArgs make_args(const Dev& d, uint32_t layer) {
   k.WQ = L.WQn; k.cQ = L.cQ; k.WKT = L.WKT; k.WV = L.WV; k.WO = L.WO; k.bO = L.bO;
   k.ld_in = d.H[layer].ld; k.ld_out = d.H[layer + 1].ld; k.ld_kv = d.ld_kv; k.ld_kve = d.KVE[layer].ld;
   k.window = d.window;
-  k.k = d.k; k.d_in = L.d_in; k.d_emb = d.d_emb; k.dk = d.dk; k.d_time = d.d_time;
+  k.k = d.k; k.d_in = L.d_in; k.d_emb = d.d_emb; k.dk = d.dk; k.d_time = d.d_time; k.d_edge = d.d_edge;
   if (d.delta) {
     k.flags = d.flags_kept;
     k.thr_in = d.d_mem ? layer + 1u : layer;                  // flags at or below: the owner's input row of this layer changed
@@ -93,9 +93,10 @@ LaunchArgs make_args(const Dev& d, uint32_t layer) {
   k.QC = d.qcache ? d.QC[layer] : nullptr;                     // (null for the layers that keep none)
   k.tile_clean = d.qcache ? d.tile_clean[layer] : nullptr;
   a.delta = d.delta != 0;
+  a.es = d.es != 0;
   a.ks = d.ks; a.nt = d.nt; a.heads = d.heads;
   a.num_cu = d.num_cu;
-  a.lds = (size_t)layer_impl::layer_lds(L.d_in, d.heads, d.ks, d.nt, d.k, d.delta != 0).total * sizeof(float);
+  a.lds = (size_t)layer_impl::layer_lds(L.d_in, d.heads, d.ks, d.nz, d.k, d.delta != 0).total * sizeof(float);
   a.err = hipSuccess;
   return a;
 }
@@ -215,6 +216,20 @@ void launch_drift_list(const Dev& d, hipStream_t s, float threshold) {
   uint32_t blocks = (d.N + 255) / 256;
   if (blocks > 2048) blocks = 2048;
   hipLaunchKernelGGL(drift_list_kernel, dim3(blocks ? blocks : 1), dim3(256), 0, s, d, threshold);
+}
+
+// Whether the layer kernel's tiles fit its share of the LDS at every layer with nz slots of z (d: the
+// configuration fields and ks, nt).
+int layer_tiles_fit(const Dev& d, uint32_t nz) {
+  LaunchArgs a{};
+  a.ks = d.ks; a.nt = d.nt; a.heads = d.heads; a.query_wgs = 1;
+  go_heads(a);
+  if (a.wgs == 0) return 0;
+  for (uint32_t l = 0; l < d.layers; ++l) {
+    const size_t lds = (size_t)layer_impl::layer_lds(l ? d.d_emb : d.d0, d.heads, d.ks, nz, d.k, false).total * sizeof(float);
+    if (lds + 3072 > kMaxLds / a.wgs) return 0;
+  }
+  return 1;
 }
 
 int setup_embed_attributes(const Dev& d) {

@@ -158,7 +158,8 @@ __device__ inline uint64_t log_addr(const Dev& d, uint32_t node, uint32_t pos) {
 // Cached key|value rows that do not come out of a layer kernel (see LayerDev):
 //   per batch:  KV[0][v] = [memory'(v) | features(v)] [W_K | W_V](node rows of layer 0) for the batch's
 //       endpoints v (their memory just changed; skipped without a memory), and for every layer l
-//       KVE[l][e] = feat_e [W_K | W_V](edge rows of layer l) for the batch's edges e;
+//       KVE[l][e] = feat_e [W_K | W_V](edge rows of layer l) for the batch's edges e (not with raw edge rows:
+//       those are copied by the appending workgroups of the launch);
 //   all_nodes (initial state, full rebuild):  KV[0][v] for every node.
 // One workgroup (four waves) per 16 rows and 128 of the 128 ks output columns: the rows go through
 // LDS as the A operand, wave w computes the column tiles w and w + 4 of the workgroup's column group
@@ -169,7 +170,7 @@ __device__ void project_rows(const Dev& d, const float* __restrict__ ef, uint32_
                              float* lds) {
   const BatchCtl* c = d.bc;
   const uint32_t nD = all_nodes ? d.N : (d.d_mem ? c->nD : 0u);
-  const uint32_t nE = (all_nodes || !d.d_edge) ? 0u : c->n_edges;
+  const uint32_t nE = (all_nodes || !d.d_edge || d.es) ? 0u : c->n_edges;
   const uint64_t E0 = c->E_base;
   const uint32_t tD = (nD + kProjRows - 1) / kProjRows, tE = (nE + kProjRows - 1) / kProjRows;
   // work items: (row tile, column group); for all nodes one item per row tile, which takes every column group
@@ -320,8 +321,15 @@ __global__ __launch_bounds__(256) void apply_kernel(Dev d, const uint32_t* __res
       d.H[0].base[(size_t)d.D[dd] * d.H[0].ld + col] = d.mem_new[(size_t)dd * d.d_mem + col];
     }
   }
-  // (the raw edge-feature rows and timestamps are not kept: an edge's features live on in its cached
-  // key|value rows, written by the projecting workgroups of this launch, and its time in the ring records)
+  // An edge's features live on in its cached key|value rows, written by the projecting workgroups of this
+  // launch, or (narrow features) as the raw row padded with zeros to one slot; its time in the ring records.
+  if (d.es) {
+    float* rows = d.KVE[0].base + (size_t)E0 * kSlot;
+    for (uint32_t x = tid; x < n * kSlot; x += nth) {
+      const uint32_t i = x / kSlot, col = x - i * kSlot;
+      rows[x] = col < d.d_edge ? ef[(size_t)i * d.d_edge + col] : 0.0f;
+    }
+  }
 }
 
 __global__ void zero_kernel(float* p, size_t n) {
@@ -374,7 +382,7 @@ void launch_apply(const Dev& d, hipStream_t s, const uint32_t* src, const uint32
   if (blocks < 1) blocks = 1;
   // workgroups that project: one per 16-row tile of the largest batch (endpoints, and edges per layer)
   const uint32_t per = (d.max_batch + kProjRows - 1) / kProjRows;
-  uint32_t pblocks = ((d.d_mem ? 2 * per : 0) + (d.d_edge ? d.layers * per : 0)) * d.ks;
+  uint32_t pblocks = ((d.d_mem ? 2 * per : 0) + (d.d_edge && !d.es ? d.layers * per : 0)) * d.ks;
   if (pblocks > 2048) pblocks = 2048;
   const uint32_t cblocks = with_compaction ? compact_blocks_of(d.N) : 0u;
   launch_done(apply_kernel, dim3(blocks + pblocks + cblocks), dim3(256), pblocks ? project_lds(d) : 0, s, done, d, src, dst,

@@ -71,13 +71,13 @@ struct LayerLds {
 };
 
 // Every stride is 4 (mod 8) floats: rows stay 16-byte aligned and the 16 rows of an operand read
-// fall into distinct banks.  ks = key slots (heads * slots per head), nt = time slots.
-__host__ __device__ inline LayerLds layer_lds(uint32_t d_in, uint32_t heads, uint32_t ks, uint32_t nt, uint32_t k, bool delta) {
+// fall into distinct banks.  ks = key slots (heads * slots per head), nz = slots of z = [phi | raw edge row].
+__host__ __device__ inline LayerLds layer_lds(uint32_t d_in, uint32_t heads, uint32_t ks, uint32_t nz, uint32_t k, bool delta) {
   LayerLds l;
   const uint32_t wx = round_up(d_in, kGrpK), wo = kSlot * ks;
   l.ldx = (wx > wo ? wx : wo) + 4;                // the input tile and the head-output tile share storage
   l.ldq = wo + 4;                                 // q in the padded-head layout, later the output rows h'
-  l.ldz = heads * kSlot * nt + 4;
+  l.ldz = heads * kSlot * nz + 4;
   l.off_q = kTM * l.ldx;
   l.off_z = l.off_q + kTM * l.ldq;
   l.off_r = l.off_z + kTM * l.ldz + 4 * kGrpK;    // operand reads may run one chunk past the last row
@@ -90,6 +90,7 @@ __host__ __device__ inline LayerLds layer_lds(uint32_t d_in, uint32_t heads, uin
 struct LayerArgs {
   const float* Hin; float* Hout;
   const float* KVn; const float* KVe;              // cached key|value rows of the input table's nodes / of the edges
+                                                   // (ES variants: KVe holds the raw feature rows, one slot each)
   float* KVout;                                    // the next layer's node table (null for the last layer)
   // root-node inference: query time per list row instead of the node's last-interaction time, and the
   // output rows go to out_rows[list position] instead of the layer cache (both null otherwise)
@@ -101,8 +102,8 @@ struct LayerArgs {
   uint64_t* gathered_slots;                        // statistic: ring entries gathered, one plain counter per workgroup index
   const float *WQ, *cQ, *WKT, *WV, *WO, *bO, *WKVnext;   // matrices group-major (mfma16.h)
   uint32_t ld_in, ld_out, ld_kv, ld_kve;           // ld_kve = 0 without edge features (every edge reads one zero row)
-  uint32_t k, d_in, d_emb, dk, d_time;
-  // query cache (both null: off): this layer's cached q | qt rows, [node][64 (KS + H NT)], and per tile of the
+  uint32_t k, d_in, d_emb, dk, d_time, d_edge;
+  // query cache (both null: off): this layer's cached q | qt rows, [node][64 (KS + H NZ)], and per tile of the
   // row list whether every row's input row is unchanged (then q and qt are read back, not projected); a
   // launch that must recompute everything passes tile_clean = null and still refreshes QC
   float* QC; const uint8_t* tile_clean;
@@ -117,17 +118,21 @@ struct LayerArgs {
   DriftCtl* drift; float* dsum; uint32_t* dlast; uint8_t* dseen;
 };
 
-// cached rows (node and edge, keys and values) of one chunk of JC ring entries, one float4 per lane and slot
-template <int JC, int KS>
+// cached rows (node and edge, keys and values) of one chunk of JC ring entries, one float4 per lane and slot;
+// ES: the edge's raw feature row (one slot) instead of its cached row
+template <int JC, int KS, int ES>
 struct GatherBuf {
   float4 n[JC][2 * KS];
-  float4 e[JC][2 * KS];
+  float4 e[JC][ES ? 1 : 2 * KS];
 };
 
 // KS key slots in total (heads x slots per head), NT time slots; JC ring entries fetched together.
+// ES = 1: raw edge rows.  The vector z_j = [phi(dt_j) | f_j] of NZ = NT + 1 slots takes the place of phi(dt_j)
+// in the re-associated time products (scores: (W_K,h[time | edge] q_h) . z_j; values: (sum_j a_j z_j)
+// W_V,h[time | edge]), and the cached rows hold the node parts alone.
 // DELTA: the approximate mode of Sec. 3.3 "Stage 4" (attention cache, delta update of changed entries).
 // QCACHE: the query cache is in use (rows may read q and qt back, rows that project store theirs).
-template <int KS, int NT, int H, int JC, int WGS, bool DELTA, bool QCACHE>
+template <int KS, int NT, int ES, int H, int JC, int WGS, bool DELTA, bool QCACHE>
 __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint32_t* __restrict__ rows,
                                                          const uint32_t* count_ptr, uint32_t count_max) {
   extern __shared__ __align__(16) float lds[];
@@ -135,8 +140,10 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
   __shared__ double s_tq[kTM], s_tqn[kTM];
   __shared__ __align__(16) double s_om[NT * kSlot], s_ph[NT * kSlot];
   static_assert(KS % H == 0, "whole slots per head");
+  static_assert(!(DELTA && ES), "the delta mode keeps projected edge rows");
   constexpr int SH = KS / H;                  // slots per head
-  constexpr uint32_t Ztp = NT * kSlot;        // floats of one head's qt / pb vector
+  constexpr int NZ = NT + ES;                 // slots of z
+  constexpr uint32_t Ztp = NZ * kSlot;        // floats of one head's qt / pb vector
   // (a batch that failed validation leaves every per-layer count at zero: nothing to test here, and the
   // control block's batch fields may already belong to the next batch, whose front part runs concurrently)
   uint32_t n = count_max;
@@ -150,16 +157,16 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
   const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
   const uint32_t k = a.k, dk = a.dk;
   const uint32_t c_in = chunks_of(a.d_in), c_de = chunks_of(a.d_emb);                                     // chunks of K
-  const uint32_t g_in = kCG * c_in, g_de = kCG * c_de, g_dk = kCG * SH, g_zt = kCG * NT, g_o = kCG * KS;  // groups of K
+  const uint32_t g_in = kCG * c_in, g_de = kCG * c_de, g_dk = kCG * SH, g_zt = kCG * NZ, g_o = kCG * KS;  // groups of K
   const uint32_t ntd = round_up(a.d_emb, 16) >> 4, ntk = round_up(dk, 16) >> 4;                           // column tiles
   constexpr uint32_t ntz = Ztp >> 4;                                                                       // tiles of a qt vector
-  const uint32_t nzt = (a.d_time + 15u) >> 4;                                                              // ... that hold valid columns
-  const LayerLds ll = layer_lds(a.d_in, H, KS, NT, k, DELTA);
+  const uint32_t nzt_t = (a.d_time + 15u) >> 4, nzt = nzt_t + (ES ? (a.d_edge + 15u) >> 4 : 0u);           // ... that hold valid columns
+  const LayerLds ll = layer_lds(a.d_in, H, KS, NZ, k, DELTA);
   float* Xs = lds;                            // input rows (phases 0-1), then head outputs (phases 3-5)
   float* Qs = lds + ll.off_q;                 // q (phases 1-3), then the output rows (phases 5-6)
   float* Zs = lds + ll.off_z;                 // qt (phases 2-3), then pb (phases 3-4)
   RingEntry* Rs = reinterpret_cast<RingEntry*>(lds + ll.off_r);   // [row][j], j = 0 the most recent entry
-  using ZBuf = GatherBuf<JC, KS>;
+  using ZBuf = GatherBuf<JC, KS, ES>;
 
   // ---- per-lane constants
   // time-encoding parameters (omega, phase in revolutions) live in LDS, zero past d_time
@@ -198,14 +205,16 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
   struct Unit2 { uint32_t h, t0, t1; bool two; };
   uint32_t udesc = 0;
   if (lane < nu2) {
+    // the i-th valid tile: time tiles first, then (raw edge rows) the tiles of slot NT
+    auto vt = [&](uint32_t i) { return i < nzt_t ? i : 4u * NT + (i - nzt_t); };
     const uint32_t x = wave + 4u * lane, h = x / npr, i0 = 2u * (x - h * npr);
     const uint32_t two = i0 + 1u < nzt ? 1u : 0u;
-    udesc = h | (i0 << 8) | (two << 24);
+    udesc = h | (vt(i0) << 8) | (vt(i0 + two) << 16) | (two << 24);
   }
   auto decode2 = [&](uint32_t i) {
     const uint32_t dsc = (uint32_t)__builtin_amdgcn_readlane((int)udesc, (int)i);
     Unit2 u;
-    u.h = dsc & 0xFFu; u.t0 = (dsc >> 8) & 0xFFu; u.two = (dsc >> 24) != 0u; u.t1 = u.t0 + (u.two ? 1u : 0u);
+    u.h = dsc & 0xFFu; u.t0 = (dsc >> 8) & 0xFFu; u.t1 = (dsc >> 16) & 0xFFu; u.two = (dsc >> 24) != 0u;
     return u;
   };
   auto wkt = [&](uint32_t h, uint32_t t) { return a.WKT + (size_t)(h * ntz + t) * g_dk * kGrpFloats; };
@@ -245,7 +254,7 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
   uint32_t p_deg[2];
   double p_tl[2];
   float4 p_x[2];                                              // own input rows (not fetched for a tile that reads q | qt back)
-  constexpr int NQ = KS + H * NT;                             // quads per thread of a tile's cached q | qt rows
+  constexpr int NQ = KS + H * NZ;                             // quads per thread of a tile's cached q | qt rows
   constexpr uint32_t QW4 = 16u * NQ;                          // quads per cached row
   uint32_t p_row = 0xFFFFFFFFu, p_clean = 0u;
   double p_tqn = 0.0;
@@ -412,8 +421,9 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
 #pragma unroll
         for (int s = 0; s < 2 * KS; ++s) {
           zb.n[jc][s] = *reinterpret_cast<const float4*>(nrow + s * kSlot);
-          zb.e[jc][s] = *reinterpret_cast<const float4*>(erow + s * kSlot);
+          if constexpr (!ES) zb.e[jc][s] = *reinterpret_cast<const float4*>(erow + s * kSlot);
         }
+        if constexpr (ES) zb.e[jc][0] = *reinterpret_cast<const float4*>(erow);
       }
     };
     ZBuf z0;
@@ -730,13 +740,13 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
                    (uint32_t)__builtin_amdgcn_readlane((int)dc, 32) + (uint32_t)__builtin_amdgcn_readlane((int)dc, 48);
     } else
     {
-      float4 accv[KS], accp[H][NT];
+      float4 accv[KS], accp[H][NZ];
 #pragma unroll
       for (int s = 0; s < KS; ++s) accv[s] = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
       for (int h = 0; h < H; ++h)
 #pragma unroll
-        for (int t = 0; t < NT; ++t) accp[h][t] = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int t = 0; t < NZ; ++t) accp[h][t] = make_float4(0.f, 0.f, 0.f, 0.f);
       float mref[H], lrun[H];
 #pragma unroll
       for (int h = 0; h < H; ++h) { mref[h] = -INFINITY; lrun[h] = 0.0f; }
@@ -747,7 +757,7 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
       const float* zq = Zs + local * ll.ldz + 4u * sub;       // qt of head h, time slot t: + h Ztp + 64 t (read per chunk)
       auto attend = [&](uint32_t c, const ZBuf& zb) {
         // time encodings of the chunk's entries (computed for every lane, then masked: no branches)
-        float4 zt[JC][NT];
+        float4 zt[JC][NZ];
         bool vj[JC];
         double2 om[NT][2], ph[NT][2];
 #pragma unroll
@@ -773,8 +783,9 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
             zz.w = tok[t][3] ? c3 : 0.0f;
             zt[jc][t] = zz;
           }
+          if constexpr (ES) zt[jc][NT] = zb.e[jc][0];
         }
-        // scores: q . (cached node keys + cached edge keys) + qt . phi
+        // scores: q . (cached node keys + cached edge keys) + qt . phi  (raw edge rows: q . node keys + qt . z)
         float sc[JC][H];
 #pragma unroll
         for (int h = 0; h < H; ++h) {
@@ -783,13 +794,14 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
             float p = 0.0f;
 #pragma unroll
             for (int s = h * SH; s < (h + 1) * SH; ++s) {
-              float4 kk;
-              kk.x = zb.n[jc][s].x + zb.e[jc][s].x; kk.y = zb.n[jc][s].y + zb.e[jc][s].y;
-              kk.z = zb.n[jc][s].z + zb.e[jc][s].z; kk.w = zb.n[jc][s].w + zb.e[jc][s].w;
+              float4 kk = zb.n[jc][s];
+              if constexpr (!ES) {
+                kk.x += zb.e[jc][s].x; kk.y += zb.e[jc][s].y; kk.z += zb.e[jc][s].z; kk.w += zb.e[jc][s].w;
+              }
               p = dot4(qk[s], kk, p);
             }
 #pragma unroll
-            for (int t = 0; t < NT; ++t) p = dot4(*reinterpret_cast<const float4*>(zq + h * Ztp + t * kSlot), zt[jc][t], p);
+            for (int t = 0; t < NZ; ++t) p = dot4(*reinterpret_cast<const float4*>(zq + h * Ztp + t * kSlot), zt[jc][t], p);
             const float tsum = row16_sum(p);
             sc[jc][h] = vj[jc] ? tsum : -INFINITY;
           }
@@ -817,7 +829,7 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
               accv[s].x *= scale; accv[s].y *= scale; accv[s].z *= scale; accv[s].w *= scale;
             }
 #pragma unroll
-            for (int t = 0; t < NT; ++t) {
+            for (int t = 0; t < NZ; ++t) {
               accp[h][t].x *= scale; accp[h][t].y *= scale; accp[h][t].z *= scale; accp[h][t].w *= scale;
             }
             mref[h] = mnew;
@@ -831,14 +843,18 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
             lrun[h] += p;
 #pragma unroll
             for (int s = h * SH; s < (h + 1) * SH; ++s) {
-              const float4 vn = zb.n[jc][KS + s], ve = zb.e[jc][KS + s];
-              accv[s].x = fmaf(p, vn.x + ve.x, accv[s].x);
-              accv[s].y = fmaf(p, vn.y + ve.y, accv[s].y);
-              accv[s].z = fmaf(p, vn.z + ve.z, accv[s].z);
-              accv[s].w = fmaf(p, vn.w + ve.w, accv[s].w);
+              float4 vv = zb.n[jc][KS + s];
+              if constexpr (!ES) {
+                const float4 ve = zb.e[jc][KS + s];
+                vv.x += ve.x; vv.y += ve.y; vv.z += ve.z; vv.w += ve.w;
+              }
+              accv[s].x = fmaf(p, vv.x, accv[s].x);
+              accv[s].y = fmaf(p, vv.y, accv[s].y);
+              accv[s].z = fmaf(p, vv.z, accv[s].z);
+              accv[s].w = fmaf(p, vv.w, accv[s].w);
             }
 #pragma unroll
-            for (int t = 0; t < NT; ++t) {
+            for (int t = 0; t < NZ; ++t) {
               const float4 zv = zt[jc][t];
               accp[h][t].x = fmaf(p, zv.x, accp[h][t].x);
               accp[h][t].y = fmaf(p, zv.y, accp[h][t].y);
@@ -861,16 +877,16 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
           *reinterpret_cast<float4*>(Xs + local * ll.ldx + s * kSlot + 4u * sub) = o;
         }
 #pragma unroll
-        for (int t = 0; t < NT; ++t) {
+        for (int t = 0; t < NZ; ++t) {
           float4 o = accp[h][t];
           o.x *= inv; o.y *= inv; o.z *= inv; o.w *= inv;
           *reinterpret_cast<float4*>(Zs + local * ll.ldz + h * Ztp + t * kSlot + 4u * sub) = o;
         }
       }
     }
-    // ================================================================ phase 4: o_h += pb_h W_V,h[time]
+    // ================================================================ phase 4: o_h += pb_h W_V,h[time | raw edge]
     {
-      // K runs over the time slots, one chunk per slot; the operands of the next slot are in flight
+      // K runs over the slots of z, one chunk per slot; the operands of the next slot are in flight
       // during the current one.  The weights of the first slot are requested ahead of the barrier.
       Ops16<2> ov[2];
       uint32_t x = wave;
@@ -886,17 +902,17 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
       decode4(x < nunits4 ? x : nunits4 - 1u);
       // every weight chunk of the wave's first unit is requested ahead of the barrier: one memory latency
       // for the unit, most of it spent waiting for the slowest wave of phase 3 anyway
-      Upfront16<2, NT> u4;
+      Upfront16<2, NZ> u4;
       {
         const float* const B4[2] = {wv(h4, n0), wv(h4, n1)};
-        u4.request(B4, NT);
+        u4.request(B4, NZ);
       }
       __syncthreads();
       if constexpr (KS > 2) { if (pf_ok) stage_b(); else stage_none(); }
       for (; x < nunits4; x += 4) {
         floatx4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
         if (x == wave) {
-          u4.multiply(Zs + h4 * Ztp + a_z, NT, acc);
+          u4.multiply(Zs + h4 * Ztp + a_z, NZ, acc);
         } else {
           decode4(x);
           load_b16(wv(h4, n0), 0, ov[0].b[0]);
@@ -906,8 +922,8 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
           const float* B1 = wv(h4, n1);
           load_a16(Ap, 0, ov[0].a);
 #pragma unroll
-          for (int c = 0; c < NT; ++c) {
-            if (c + 1 < NT) {
+          for (int c = 0; c < NZ; ++c) {
+            if (c + 1 < NZ) {
               load_a16(Ap, (c + 1) * kCG, ov[(c + 1) & 1].a);
               load_b16(B0, (c + 1) * kCG, ov[(c + 1) & 1].b[0]);
               load_b16(B1, (c + 1) * kCG, ov[(c + 1) & 1].b[1]);
@@ -1024,15 +1040,16 @@ struct LaunchArgs {
   LayerArgs k;
   hipStream_t s; const uint32_t* rows; const uint32_t* cp; uint32_t cm;
   uint32_t ks, nt, heads;
+  bool es;                          // raw edge rows (never together with delta)
   bool delta;                       // the delta-mode variant of the kernel
   uint32_t num_cu;                  // compute units of the device
   bool set_attr; size_t lds; hipError_t err;
   int query_wgs; uint32_t wgs;      // query_wgs: only report the workgroups per CU of the variant in `wgs`
 };
 
-template <int KS, int NT, int H, int JC, int WGS, bool DELTA, bool QCACHE>
+template <int KS, int NT, int ES, int H, int JC, int WGS, bool DELTA, bool QCACHE>
 void go_k(LaunchArgs& a) {
-  auto kern = layer_kernel<KS, NT, H, JC, WGS, DELTA, QCACHE>;
+  auto kern = layer_kernel<KS, NT, ES, H, JC, WGS, DELTA, QCACHE>;
   if (a.query_wgs) { a.wgs = WGS; return; }
   if (a.set_attr) {
     a.err = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)a.lds);
@@ -1048,9 +1065,13 @@ void go_k(LaunchArgs& a) {
 
 template <int KS, int NT, int H, int JC, int WGS>
 void go(LaunchArgs& a) {
-  if (a.delta) { go_k<KS, NT, H, 1, WGS, true, false>(a); return; }
-  if (a.k.QC) { go_k<KS, NT, H, JC, WGS, false, true>(a); return; }
-  go_k<KS, NT, H, JC, WGS, false, false>(a);
+  if (a.delta) { go_k<KS, NT, 0, H, 1, WGS, true, false>(a); return; }
+  if (a.es) {
+    if (a.k.QC) go_k<KS, NT, 1, H, JC, WGS, false, true>(a); else go_k<KS, NT, 1, H, JC, WGS, false, false>(a);
+    return;
+  }
+  if (a.k.QC) { go_k<KS, NT, 0, H, JC, WGS, false, true>(a); return; }
+  go_k<KS, NT, 0, H, JC, WGS, false, false>(a);
 }
 
 // Ring entries per chunk and workgroups per CU are bounded by registers: two chunks of JC * 4 KS

@@ -96,6 +96,12 @@ struct Table {
 //
 // A cached row holds [keys | values]; each head occupies whole slots of 64 floats (one slot = 16
 // lanes x float4), columns past dk are exact zeros: ld_kv = 2 * 64 * ks floats, ks = heads * ceil(dk / 64).
+//
+// Narrow edge features (d_edge <= 64, exact mode) are not projected at all: the raw feature row, padded to
+// one slot, is kept once per edge and rides through the layer kernel as one more slot of the time encoding,
+//   q_h . (f W_K,h[edge]) = (W_K,h[edge] q_h) . f   and   sum_j a_j (f_j W_V,h[edge]) = (sum_j a_j f_j) W_V,h[edge],
+// i.e. the vector z_j = [phi(dt_j) | f_j] takes the place of phi in the re-associated products above.  A
+// gathered entry then reads 256 bytes for its edge instead of a cached row per layer.
 constexpr uint32_t kSlot = 64;
 constexpr uint32_t kMaxKeySlots = 4;     // ks
 constexpr uint32_t kMaxTimeSlots = 2;    // ceil(d_time / 64)
@@ -103,12 +109,13 @@ struct LayerDev {
   uint32_t d_in;                 // input width
   const float* WQn;              // [d_in x d_emb]            node block of W_Q / sqrt(dk)
   const float* cQ;               // [d_emb]                   phi(0) * (time block of W_Q) / sqrt(dk)
-  const float* WKT;              // [dk x heads * 64 nt]      (time rows of W_K, head block)^T * sqrt(1/d_t)
-  const float* WV;               // [64 nt x heads * R16(dk)] time rows of W_V, head block, * sqrt(1/d_t)
+  const float* WKT;              // [dk x heads * 64 nz]      (time rows of W_K, head block)^T * sqrt(1/d_t), then, with raw
+                                 //                           edge rows, (edge rows of W_K, head block)^T in slot nt
+  const float* WV;               // [64 nz x heads * R16(dk)] time rows of W_V, head block, * sqrt(1/d_t); edge rows in slot nt
   const float* WO;               // [64 ks x d_emb]           rows in the padded-head layout of the head outputs
   const float* bO;               // [d_emb]
   const float* WKVn;             // [d_in x 128 ks]           node rows of [W_K | W_V] in the cached-row layout
-  const float* WKVe;             // [d_edge x 128 ks]         edge rows of [W_K | W_V] (null without edge features)
+  const float* WKVe;             // [d_edge x 128 ks]         edge rows of [W_K | W_V] (null without edge features or with raw edge rows)
 };
 
 struct Dev {
@@ -130,8 +137,10 @@ struct Dev {
   uint32_t* blk;                     // [N x maxb] block bases in units of kMinBlock entries
   // cached key|value rows (see LayerDev): KV[l] of the rows of H[l], KVE[l] of the edge features
   Table    KV[STGN_MAX_LAYERS];      // [N x ld_kv]
-  Table    KVE[STGN_MAX_LAYERS];     // [max_edges x ld_kv]; one zero row (ld 0) without edge features
+  Table    KVE[STGN_MAX_LAYERS];     // [max_edges x ld_kv]; one zero row (ld 0) without edge features; with raw edge
+                                     // rows every layer names the one table [max_edges x 64] of padded feature rows
   uint32_t sh, ks, nt, ld_kv;        // slots per head, key slots, time slots, floats per cached row
+  uint32_t es, nz;                   // es = 1: raw edge rows; nz = nt + es slots of the vector z = [phi | f]
   // per-batch scratch: two sets, the batches alternate (bind_batch points the plain fields at one of them)
   struct Scratch {
     uint32_t *D, *seg_start, *last_slot, *deg_new, *slot_pos, *slot_d, *slot_sorted;
@@ -176,7 +185,7 @@ struct Dev {
   // change in the batch reads them back instead of projecting again; the regrouping puts such rows together
   // and says per tile of 16 list positions whether all of its rows are of that kind (tile_clean).
   uint32_t qcache;
-  uint32_t ld_qc;                    // floats per cached row: 64 (ks + heads nt)
+  uint32_t ld_qc;                    // floats per cached row: 64 (ks + heads nz)
   float*   QC[STGN_MAX_LAYERS];      // [N x ld_qc]
   uint8_t* tile_clean[STGN_MAX_LAYERS];   // [ceil(N / 16)]
   uint32_t thr[STGN_MAX_LAYERS];
@@ -301,6 +310,7 @@ void launch_project_nodes(const Dev& d, hipStream_t s);
 constexpr size_t kMaxLds = 160 * 1024;   // LDS per workgroup on gfx950
 int  setup_ingest_attributes(const Dev& d);
 int  setup_embed_attributes(const Dev& d);
+int  layer_tiles_fit(const Dev& d, uint32_t nz);   // the layer kernel's LDS tiles with nz slots of z = [phi | raw edge row]
 int  setup_memory_attributes(const Dev& d);
 
 }  // namespace stgn

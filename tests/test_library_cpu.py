@@ -40,18 +40,24 @@ def test_workspace_sizes_scale_with_the_configuration():
     sizes = {name: binding.query_workspace(cfg_of(w)) for name, w in synth.WORKLOADS.items()}
     assert sizes["C1"] < sizes["C2"] < sizes["C3"] < sizes["C4"] < sizes["C5"]
     assert sizes["C5"] < 200 * 2**30          # the largest workload fits one MI355X (288 GB)
-    # one cached key|value row per edge and layer (two heads of 50: 2 x 2 x 64 floats) must be inside;
-    # the raw edge-feature rows are not kept
+    # wide edge features (172 floats): one cached key|value row per edge and layer (two heads of 50: 2 x 2 x 64
+    # floats) must be inside, the raw edge-feature rows are not kept
     # ... and the query row (q and its time part: 64 x (2 + 2 x 2) floats) per node: of the first layer
     # with a memory, of every layer without
     w = synth.WORKLOADS["C4"]
     qrow = 64 * 6 * 4
     assert w.num_edges * (w.layers * 256 * 4) + w.num_nodes * qrow < sizes["C4"] \
         < w.num_edges * (w.layers * 256 * 4 + 128 * 4) + w.num_nodes * qrow
+    # narrow edge features (64 floats): the raw row padded to 64 floats once per edge, no cached edge rows; per
+    # node and layer a cached key|value row and a query row of 64 x (2 + 2 x 3) floats (the edge slot rides
+    # with the time part)
     w5 = synth.WORKLOADS["C5"]
-    per_node = w5.layers * qrow
-    assert w5.num_edges * (w5.layers * 256 * 4) + w5.num_nodes * per_node < sizes["C5"] \
-        < w5.num_edges * (w5.layers * 256 * 4 + 128 * 4) + w5.num_nodes * (per_node + 2048)
+    per_node = w5.layers * (256 * 4 + 64 * 8 * 4)
+    assert w5.num_edges * 64 * 4 + w5.num_nodes * per_node < sizes["C5"] \
+        < w5.num_edges * (64 * 4 + 64) + w5.num_nodes * (per_node + 3072)
+    # ... the delta mode keeps the cached edge rows
+    d5 = binding.query_workspace(cfg_of(w5, delta_mode=1, drift_gamma=0.9))
+    assert d5 > w5.num_edges * w5.layers * 256 * 4
     per_node = 0
     # delta mode adds the attention cache: per node, layer and recent-neighbour entry the value part and two floats per head
     d4 = binding.query_workspace(cfg_of(w, delta_mode=1, drift_gamma=0.9))
