@@ -57,24 +57,34 @@ def cached_row_floats(w):
     return 2 * 64 * w.heads * sh
 
 
-def layout_bytes(w, rows, entries):
-    """Bytes the layer kernel's own data layout moves: per record the ring entry and two cached
-    key|value rows (the neighbour's and the edge's) instead of the raw rows; per target row its input
-    row, time, output row and, for every layer but the last, its own cached row for the next layer."""
+def raw_edge_rows(w, delta_mode=False):
+    """Whether the library keeps an edge's features as one raw 64-float row (narrow features, exact mode)
+    instead of a cached key|value row per layer."""
+    return 0 < w.d_edge <= 64 and not delta_mode
+
+
+def layout_bytes(w, rows, entries, delta_mode=False):
+    """Bytes the layer kernel's own data layout moves: per record the ring entry, the neighbour's cached
+    key|value row and the edge's (a cached row, or the raw feature row padded to 64 floats) instead of the
+    raw rows; per target row its input row, time, output row and, for every layer but the last, its own
+    cached row for the next layer."""
     d_in = np.mean([(w.d_mem + w.d_node) if l == 0 else w.d_emb for l in range(w.layers)])
     kv = 4 * cached_row_floats(w)
     per_row = 4 * d_in + 8 + 4 * w.d_emb + kv * (w.layers - 1) / w.layers
-    return rows * per_row + entries * (16 + kv * (2 if w.d_edge else 1))
+    edge = 256 if raw_edge_rows(w, delta_mode) else kv if w.d_edge else 0
+    return rows * per_row + entries * (16 + kv + edge)
 
 
-def projection_flops_per_row(w, layer):
+def projection_flops_per_row(w, layer, delta_mode=False):
     """FLOPs of the dense products the layer kernel executes for one (node, layer), padding not
-    counted: the query; the time parts of keys and values, re-associated; the output projection; and,
-    for every layer but the last, the row's cached keys and values for the next layer.  (The node and
-    edge parts of keys and values are cached rows: computed once per changed row / once per edge.)"""
+    counted: the query; the time parts of keys and values, re-associated (with raw edge rows the edge
+    parts ride along); the output projection; and, for every layer but the last, the row's cached keys
+    and values for the next layer.  (The node parts of keys and values, and the edge parts of wide edge
+    features, are cached rows: computed once per changed row / once per edge.)"""
     d_in = (w.d_mem + w.d_node) if layer == 0 else w.d_emb
-    q = 2 * (d_in * w.d_emb + w.d_emb * w.d_time)                 # q, then qt_h = W_K,h[time] q_h
-    o = 2 * (w.d_time * w.d_emb + w.d_emb * w.d_emb)              # pb_h W_V,h[time], then W_O
+    d_z = w.d_time + (w.d_edge if raw_edge_rows(w, delta_mode) else 0)
+    q = 2 * (d_in * w.d_emb + w.d_emb * d_z)                      # q, then qt_h = W_K,h[time | edge] q_h
+    o = 2 * (d_z * w.d_emb + w.d_emb * w.d_emb)                   # pb_h W_V,h[time | edge], then W_O
     if layer + 1 < w.layers:
         o += 2 * (w.d_emb * 2 * w.d_emb)                          # cached keys | values of the next layer
     return q, o
@@ -392,8 +402,8 @@ def main():
             kernels[name]["total_us"] = kernels[name]["avg_us"] * v["launches"]
     roofline = None
     if kernels:
-        qf = np.mean([projection_flops_per_row(w, l)[0] for l in range(w.layers)])
-        of = np.mean([projection_flops_per_row(w, l)[1] for l in range(w.layers)])
+        qf = np.mean([projection_flops_per_row(w, l, args.delta_mode)[0] for l in range(w.layers)])
+        of = np.mean([projection_flops_per_row(w, l, args.delta_mode)[1] for l in range(w.layers)])
         layer_bytes = algorithmic_bytes(w, rows_per_launch, entries_per_launch)
         if "layer" in kernels:
             # the fused layer kernel gathers (HBM) and projects (fp32 MFMA); per row the gather is the
@@ -411,7 +421,7 @@ def main():
             roofline["note"] = f"largest total time is in {dom}, which moves too little data for a roofline"
         # what the kernel's own data layout asks the memory system for (cached key|value rows): more
         # bytes than the plain definition needs, priced separately and never used for `achieved`
-        lay = layout_bytes(w, rows_per_launch, entries_per_launch)
+        lay = layout_bytes(w, rows_per_launch, entries_per_launch, args.delta_mode)
         roofline["layout_bytes_per_launch"] = lay
         roofline["layout_GBs"] = lay / (kernels["layer"]["avg_us"] * 1e-6) / 1e9
         roofline["layout_frac"] = roofline["layout_GBs"] / HBM_PEAK_GBS
@@ -456,7 +466,7 @@ def main():
         rb_bytes = w.layers * algorithmic_bytes(w, w.num_nodes, ent / w.layers)        # every row, every layer
         # a rebuild projects every row of every layer and gathers few entries per row (most nodes of a skewed
         # graph hold short lists): at the published peaks its fp32 matrix work takes longer than its bytes
-        rb_flops = w.num_nodes * sum(sum(projection_flops_per_row(w, l)) for l in range(w.layers))
+        rb_flops = w.num_nodes * sum(sum(projection_flops_per_row(w, l, args.delta_mode)) for l in range(w.layers))
         rebuild = {"ms": rw * 1e3, "node_layers_per_s": w.num_nodes * w.layers / rw,
                    "algorithmic_GBs": rb_bytes / rw / 1e9, "frac_hbm": rb_bytes / rw / 1e9 / HBM_PEAK_GBS,
                    "projection_TFLOPs": rb_flops / rw / 1e12,

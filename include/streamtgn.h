@@ -61,7 +61,9 @@ typedef struct stgn_ctx stgn_ctx;
  * max_batch <= STGN_MAX_BATCH; max_edges < 2^31.
  * Keys and values of Eq. attn_detail are linear in [h_u | e | phi(dt)]; their node and edge parts
  * are kept as cached rows (per node and layer, per edge and layer: 2 * 64 * heads * ceil(d_emb /
- * heads / 64) floats each), so the workspace grows by layers * max_edges such rows. */
+ * heads / 64) floats each), so the workspace grows by layers * max_edges such rows.  Edge features
+ * of at most 64 floats are kept as they are instead (exact mode: max_edges rows of 64 floats, no
+ * cached edge rows). */
 typedef struct {
   uint32_t num_nodes;
   uint64_t max_edges;
@@ -176,7 +178,7 @@ int stgn_full_rebuild(stgn_ctx *ctx);
  * per update.  Endpoints of the batch, rows whose own input changed, and every row touched by a rebuild are
  * recomputed exactly and refresh their cache.  stgn_predict_batch(at_edge_time = 1) always computes exactly.
  * Costs layers x num_nodes x k x (64 ks + 2 heads) floats of workspace on top of the exact mode
- * (ks = heads x ceil(d_emb / heads / 64)).
+ * (ks = heads x ceil(d_emb / heads / 64)), and always keeps the cached edge rows.
  *
  * Drift estimator: per node the decayed sum, over the batches since the node's final-layer row was last
  * exact, of (changed entries / entries) of its delta updates: est_v <- gamma est_v per batch.  The global metric

@@ -324,10 +324,16 @@ __global__ __launch_bounds__(256) void apply_kernel(Dev d, const uint32_t* __res
   // An edge's features live on in its cached key|value rows, written by the projecting workgroups of this
   // launch, or (narrow features) as the raw row padded with zeros to one slot; its time in the ring records.
   if (d.es) {
-    float* rows = d.KVE[0].base + (size_t)E0 * kSlot;
-    for (uint32_t x = tid; x < n * kSlot; x += nth) {
-      const uint32_t i = x / kSlot, col = x - i * kSlot;
-      rows[x] = col < d.d_edge ? ef[(size_t)i * d.d_edge + col] : 0.0f;
+    float4* rows = reinterpret_cast<float4*>(d.KVE[0].base + (size_t)E0 * kSlot);
+    for (uint32_t x = tid; x < n * (kSlot / 4); x += nth) {       // one 16-byte piece of a padded row per thread
+      const uint32_t i = x / (kSlot / 4), col = 4u * (x - i * (kSlot / 4));
+      const float* f = ef + (size_t)i * d.d_edge;
+      float4 v;
+      v.x = col < d.d_edge ? f[col] : 0.0f;
+      v.y = col + 1 < d.d_edge ? f[col + 1] : 0.0f;
+      v.z = col + 2 < d.d_edge ? f[col + 2] : 0.0f;
+      v.w = col + 3 < d.d_edge ? f[col + 3] : 0.0f;
+      rows[x] = v;
     }
   }
 }
@@ -376,7 +382,8 @@ void launch_place(const Dev& d, hipStream_t s, uint32_t n, hipEvent_t done) {
 void launch_apply(const Dev& d, hipStream_t s, const uint32_t* src, const uint32_t* dst, const double* ts,
                   const float* ef, bool with_compaction, hipEvent_t done) {
   // sized for the largest section (memory rows of a full batch's endpoints), grid-stride inside
-  const uint32_t work = 2 * d.max_batch * (d.d_mem > 1 ? d.d_mem : 1);
+  uint32_t work = 2 * d.max_batch * (d.d_mem > 1 ? d.d_mem : 1);
+  if (d.es && work < d.max_batch * (kSlot / 4)) work = d.max_batch * (kSlot / 4);
   uint32_t blocks = (work + 255) / 256;
   if (blocks > 2048) blocks = 2048;
   if (blocks < 1) blocks = 1;
