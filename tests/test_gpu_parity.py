@@ -109,6 +109,12 @@ def test_c1_full_stream(binding):
     dict(layers=2, d_mem=12, d_edge=9, d_time=70, d_emb=130, d_msg=16, heads=1, k=3),         # one wide head: three key slots rounded to four
     dict(layers=2, d_mem=0, d_node=20, d_edge=0, d_time=16, d_emb=140, heads=2, k=4),         # two slots per head, no edge features
     dict(layers=3, d_mem=16, d_edge=5, d_time=100, d_emb=100, d_msg=16, heads=1, k=3),        # one 100-wide head (two key slots), two time slots
+    # edge features on both sides of one 64-float slot (kept as raw rows up to it, projected past it)
+    dict(layers=2, d_mem=12, d_edge=64, d_time=20, d_emb=32, d_msg=12, heads=4, k=3),         # a full slot, four heads
+    dict(layers=2, d_mem=0, d_node=10, d_edge=63, d_time=70, d_emb=16, heads=2, k=4),         # one float short of a slot, two time slots
+    dict(layers=2, d_mem=0, d_node=10, d_edge=65, d_time=8, d_emb=16, heads=2, k=4),          # one float past a slot
+    dict(layers=1, d_mem=8, d_edge=1, d_time=8, d_emb=8, d_msg=8, heads=1, k=3),              # a single feature
+    dict(layers=2, d_mem=12, d_edge=40, d_time=100, d_emb=64, d_msg=12, heads=4, k=3),        # four heads and two time slots: no room for the edge slot in the LDS tiles
 ])
 def test_small_graphs_all_shapes(binding, kw):
     w = tiny_workload(num_nodes=150, num_edges=1500, batch=50, zipf_s=1.0, **kw)

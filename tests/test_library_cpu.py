@@ -64,6 +64,24 @@ def test_workspace_sizes_scale_with_the_configuration():
     assert d4 - sizes["C4"] > w.num_nodes * w.layers * w.k * (128 + 4) * 4 - w.num_nodes * per_node
 
 
+def test_edge_features_of_one_slot_are_kept_raw():
+    """Up to 64 edge features: one 64-float row per edge.  Past that, in the delta mode, and for shapes whose
+    layer-kernel tiles leave no room for the edge slot: a cached key|value row per edge and layer."""
+    w = synth.WORKLOADS["C5"]
+    kv = 2 * 64 * 2 * 4                       # two heads of 50: one slot each, keys and values, fp32
+    s64, s65 = (binding.query_workspace(cfg_of(w, d_edge=e)) for e in (64, 65))
+    # (with raw rows the cached query of a node is one slot per head longer)
+    assert s65 - s64 > w.num_edges * (w.layers * kv - 64 * 4) - w.num_nodes * w.layers * 2 * 64 * 4 - (1 << 24)
+    s1 = binding.query_workspace(cfg_of(w, d_edge=1))
+    assert abs(s64 - s1) < w.num_edges * 16 + 2 * 8192 * 64 * 4 * 4      # the same rows; staging differs by the batch's features
+    wide = dict(heads=4, d_emb=64, d_time=100)                              # four heads x (two time slots + the edge slot)
+    t0, t40 = (binding.query_workspace(cfg_of(w, d_edge=e, **wide)) for e in (0, 40))
+    assert t40 - t0 > w.num_edges * w.layers * (2 * 64 * 4 * 4) * 0.99
+    narrow = dict(heads=4, d_emb=64, d_time=20)                             # one time slot: the edge slot fits
+    u0, u40 = (binding.query_workspace(cfg_of(w, d_edge=e, **narrow)) for e in (0, 40))
+    assert u40 - u0 < w.num_edges * (64 * 4 + 16) + w.num_nodes * w.layers * 4 * 64 * 4 + (1 << 24)
+
+
 @pytest.mark.parametrize("ok", [dict(d_emb=256, heads=4), dict(d_emb=256, heads=1), dict(d_emb=130, heads=1),
                                 dict(d_emb=128, heads=2, d_time=128)])
 def test_widest_supported_attention_shapes(lib, ok):
