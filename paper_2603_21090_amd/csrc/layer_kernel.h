@@ -176,7 +176,6 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
   }
   // operand padding (columns nobody writes) must be finite: clear the tiles once
   for (uint32_t x = threadIdx.x; x < ll.off_r; x += 256) lds[x] = 0.0f;
-  bool tok[NT][4];
   uint32_t gathered = 0;
   double drift_sum = 0.0;                     // delta mode: this wave's share of the drift estimator's sum and member count
   uint32_t drift_new = 0;
@@ -184,10 +183,6 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
   auto derive_lane = [&]() {
     asm volatile("" : "+v"(tid));
     lane = tid & 63u; sub = lane & 15u; grp = lane >> 4;
-#pragma unroll
-    for (int t = 0; t < NT; ++t)
-#pragma unroll
-      for (int c = 0; c < 4; ++c) tok[t][c] = (uint32_t)t * kSlot + 4u * sub + c < a.d_time;
     a_x = (lane & 15u) * ll.ldx + 4u * (lane >> 4);
     a_q = (lane & 15u) * ll.ldq + 4u * (lane >> 4);
     a_z = (lane & 15u) * ll.ldz + 4u * (lane >> 4);
@@ -518,6 +513,17 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
       __syncthreads();                                        // phase 3 puts pb where qt is: not before every thread has read its share
     }
     // ================================================================ phase 3: gather + attention
+    // The time encodings are not masked per entry: a column past d_time has omega = phase = 0 and comes out as
+    // cos(0) = 1.  In the scores it meets an exact zero of qt (zero weight columns; tiles phase 2 does not
+    // write hold what the previous tile's pb left there, hence the zeros written here), and its share of pb
+    // is cleared once per row, when pb goes into its tile.
+    auto clear_past_d_time = [&](float4& o, int t) {
+      const uint32_t c0 = (uint32_t)t * kSlot + 4u * sub;
+      o.x = c0 < a.d_time ? o.x : 0.0f;
+      o.y = c0 + 1u < a.d_time ? o.y : 0.0f;
+      o.z = c0 + 2u < a.d_time ? o.z : 0.0f;
+      o.w = c0 + 3u < a.d_time ? o.w : 0.0f;
+    };
     if constexpr (DELTA) {
       // ---- delta mode.  An exact row runs the same online softmax as the exact mode and leaves its attention
       // cache behind: per entry score, weight and the neighbour|edge part of the value, per row the sums S and
@@ -621,7 +627,7 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
           const double2 pa = *reinterpret_cast<const double2*>(s_ph + t * kSlot + 4u * sub), pb = *reinterpret_cast<const double2*>(s_ph + t * kSlot + 4u * sub + 2);
           const float c0 = cos_rev(oa.x * dt + pa.x), c1 = cos_rev(oa.y * dt + pa.y);
           const float c2 = cos_rev(ob.x * dt + pb.x), c3 = cos_rev(ob.y * dt + pb.y);
-          zt[t] = make_float4(tok[t][0] ? c0 : 0.0f, tok[t][1] ? c1 : 0.0f, tok[t][2] ? c2 : 0.0f, tok[t][3] ? c3 : 0.0f);
+          zt[t] = make_float4(c0, c1, c2, c3);           // (columns past d_time: see the exact variant)
         }
         float sc[H];
 #pragma unroll
@@ -706,6 +712,7 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
         for (int t = 0; t < NT; ++t) {
           float4 o = accp[h][t];
           o.x *= inv; o.y *= inv; o.z *= inv; o.w *= inv;
+          clear_past_d_time(o, t);
           *reinterpret_cast<float4*>(Zs + local * ll.ldz + h * Ztp + t * kSlot + 4u * sub) = o;
           if (live) *reinterpret_cast<float4*>(acP + (h * NT + t) * kSlot) = o;
         }
@@ -776,12 +783,9 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
           for (int t = 0; t < NT; ++t) {
             const float c0 = cos_rev(om[t][0].x * dt + ph[t][0].x), c1 = cos_rev(om[t][0].y * dt + ph[t][0].y);
             const float c2 = cos_rev(om[t][1].x * dt + ph[t][1].x), c3 = cos_rev(om[t][1].y * dt + ph[t][1].y);
-            float4 zz;
-            zz.x = tok[t][0] ? c0 : 0.0f;
-            zz.y = tok[t][1] ? c1 : 0.0f;
-            zz.z = tok[t][2] ? c2 : 0.0f;
-            zz.w = tok[t][3] ? c3 : 0.0f;
-            zt[jc][t] = zz;
+            // columns past d_time come out as cos(0) = 1 and need no mask: qt is exactly zero there (zero
+            // weight columns), and what they add to pb meets zero weight rows in phase 4
+            zt[jc][t] = make_float4(c0, c1, c2, c3);
           }
           if constexpr (ES) zt[jc][NT] = zb.e[jc][0];
         }
@@ -880,6 +884,7 @@ __global__ __launch_bounds__(256, WGS) void layer_kernel(LayerArgs a, const uint
         for (int t = 0; t < NZ; ++t) {
           float4 o = accp[h][t];
           o.x *= inv; o.y *= inv; o.z *= inv; o.w *= inv;
+          if (t < NT) clear_past_d_time(o, t);                 // (a raw edge row's padding is zero, and so are its sums)
           *reinterpret_cast<float4*>(Zs + local * ll.ldz + h * Ztp + t * kSlot + 4u * sub) = o;
         }
       }
