@@ -19,6 +19,8 @@ FIXED position of the stream, whatever --warmup / --steps say:
   kernels  next batches with one HIP event pair per launch     -> per-kernel average duration,
                                                                   roofline of the dominant kernel
   cpu      the CPU oracle on a bounded sample of the same workload, 1 core
+  copy     a plain 1 GiB copy and a bare gather of the layer launch's own mix of rows, after the
+           library's context is gone                           -> roofline.measured_copy_GBs, roofline.bare_gather
 
 Prints ONE JSON line.
 """
@@ -554,7 +556,43 @@ def main():
     e1.record()
     torch.cuda.synchronize()
     copy_gbs = 4 * 2 * (1 << 30) / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del a_, b_
+    # a bare gather with the layer launch's own mix (rows recomputed, entries per row, a 1 KiB cached row and
+    # a 256-byte or 1 KiB edge row per entry, uniformly random rows of tables of the workload's sizes): what the
+    # memory system delivers to the kernel's access pattern when nothing else is asked of the chip
+    gather = None
+    if out["roofline"] is not None and w.num_nodes >= 32768:
+        rows_l = max(int(out["roofline"]["rows_per_launch"]), 1)
+        per = max(int(round(out["roofline"]["ring_entries_per_launch"] / rows_l)), 1)
+        rows_l = max(int(round(out["roofline"]["ring_entries_per_launch"] / per)), 1)     # groups: the launch's entry count
+        edge_floats = 64 if raw_edge_rows(w, args.delta_mode) else 256 if w.d_edge else 0
+        g_rows = min(w.num_edges, (8 << 30) // (4 * max(edge_floats, 1)))          # at most 8 GiB of edge rows
+        tn = torch.empty((w.num_nodes, 256), dtype=torch.float32, device=dev).normal_()
+        te = torch.empty((g_rows, edge_floats), dtype=torch.float32, device=dev).normal_() if edge_floats else None
+        gen = torch.Generator(device=dev).manual_seed(7)
+        i_n = torch.randint(0, w.num_nodes, (rows_l * per,), device=dev, generator=gen).to(torch.int32)
+        i_e = torch.randint(0, g_rows, (rows_l * per,), device=dev, generator=gen).to(torch.int32) if edge_floats else None
+        o_ = torch.empty(rows_l * 16, dtype=torch.float32, device=dev)
+        cs = torch.cuda.current_stream().cuda_stream
+        def one():
+            binding.probe_gather(tn, i_n, per, o_, cs)
+            if te is not None:
+                binding.probe_gather(te, i_e, per, o_, cs)
+        one()
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(4):
+            one()
+        e1.record()
+        torch.cuda.synchronize()
+        g_us = e0.elapsed_time(e1) * 1e3 / 4
+        g_bytes = rows_l * per * 4 * (256 + edge_floats)
+        gather = {"us": g_us, "GBs": g_bytes / g_us / 1e3, "groups": rows_l, "entries_per_group": per,
+                  "bytes_per_entry": 4 * (256 + edge_floats),
+                  "layer_launch_over_bare_gather": out["roofline"]["avg_launch_us"] / g_us}
+        del tn, te, i_n, i_e, o_
     if out["roofline"] is not None:
+        out["roofline"]["bare_gather"] = gather
         out["roofline"]["measured_copy_GBs"] = copy_gbs
         out["roofline"]["frac_of_measured_copy"] = out["roofline"]["achieved"] / copy_gbs
         if out["roofline"]["traffic"]:

@@ -271,6 +271,16 @@ int stgn_get_totals(stgn_ctx *ctx, uint64_t *edges, uint64_t *direct, uint64_t *
 int stgn_kernel_times(stgn_ctx *ctx, int enable, int reset, uint32_t cap,
                       const char **names, double *usec, uint64_t *launches);
 
+/* Diagnostic, no context: one launch of a bare gather on hip_stream, for pricing the layer kernel's
+ * gathers against what the memory system delivers to that access pattern alone.  table: device,
+ * n_rows rows of row_bytes (256 or 1024: a raw edge row, a cached key|value row of two slots per
+ * half) each, 256-byte aligned; idx: device, n_groups * per_group row numbers < n_rows (not
+ * checked: the caller's); every group of 16 lanes sums its per_group rows, one row in flight, and
+ * writes 16 floats to out (device, n_groups * 16 floats).  Asynchronous; the caller times it.
+ * STGN_E_INVALID_ARG for a NULL pointer, another row size or an empty launch. */
+int stgn_probe_gather(const float *table, uint64_t n_rows, uint32_t row_bytes, const uint32_t *idx,
+                      uint32_t n_groups, uint32_t per_group, float *out, void *hip_stream);
+
 const char *stgn_last_error(const stgn_ctx *ctx);   /* NULL ctx: message of the last failed create */
 const char *stgn_version(void);
 

@@ -60,7 +60,7 @@ EXPORTS = ("stgn_query_workspace", "stgn_create", "stgn_destroy", "stgn_ingest_b
            "stgn_full_rebuild", "stgn_sync", "stgn_get_affected", "stgn_get_neighbors", "stgn_get_history",
            "stgn_get_memory", "stgn_get_totals", "stgn_kernel_times", "stgn_last_error", "stgn_version",
            "stgn_set_predictor", "stgn_predict_batch", "stgn_predict_batch_static", "stgn_drift_status",
-           "stgn_maintain")
+           "stgn_maintain", "stgn_probe_gather")
 
 
 def load_library():
@@ -93,6 +93,7 @@ def load_library():
     L.stgn_predict_batch_static.argtypes = [vp, C.c_uint32, vp, vp, vp, C.c_int, vp]
     L.stgn_drift_status.argtypes = [vp, C.POINTER(C.c_double), _u32p, vp]
     L.stgn_maintain.argtypes = [vp, C.c_double, C.c_double, C.POINTER(C.c_int), _u32p]
+    L.stgn_probe_gather.argtypes = [vp, C.c_uint64, C.c_uint32, vp, C.c_uint32, C.c_uint32, vp, vp]
     L.stgn_last_error.argtypes = [vp]
     L.stgn_last_error.restype = C.c_char_p
     L.stgn_version.restype = C.c_char_p
@@ -120,6 +121,17 @@ def query_workspace(cfg: Config) -> int:
     if rc:
         raise StgnError(rc, load_library().stgn_last_error(None).decode())
     return n.value
+
+
+def probe_gather(table, idx, per_group, out, stream=0):
+    """One launch of the bare gather (stgn_probe_gather) on torch device tensors: table [rows, 64 or 256] fp32,
+    idx [groups * per_group] int32, out [groups * 16] fp32.  Asynchronous."""
+    row_bytes = table.shape[1] * 4
+    groups = idx.numel() // per_group
+    rc = load_library().stgn_probe_gather(table.data_ptr(), table.shape[0], row_bytes, idx.data_ptr(), groups, per_group,
+                                          out.data_ptr(), stream)
+    if rc:
+        raise StgnError(rc)
 
 
 def _marshal_weights(weights: dict, layers: int, has_memory: bool):

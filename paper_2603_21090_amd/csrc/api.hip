@@ -508,6 +508,14 @@ extern "C" {
 
 const char* stgn_version(void) { return "streamtgn-gfx950 0.1"; }
 
+int stgn_probe_gather(const float* table, uint64_t n_rows, uint32_t row_bytes, const uint32_t* idx, uint32_t n_groups,
+                      uint32_t per_group, float* out, void* hip_stream) {
+  if (!table || !idx || !out || !n_rows || !n_groups || !per_group || n_groups > (1u << 27)) return STGN_E_INVALID_ARG;
+  if (row_bytes != 256 && row_bytes != 1024) return STGN_E_INVALID_ARG;
+  launch_gather_probe((hipStream_t)hip_stream, table, row_bytes / 256, idx, n_groups, per_group, out);
+  return hipGetLastError() == hipSuccess ? STGN_OK : STGN_E_DEVICE;
+}
+
 const char* stgn_last_error(const stgn_ctx* ctx) { return ctx ? ctx->err.c_str() : g_create_error.c_str(); }
 
 int stgn_query_workspace(const stgn_config* cfg, size_t* device_bytes) {

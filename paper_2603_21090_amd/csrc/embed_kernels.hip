@@ -232,6 +232,33 @@ int layer_tiles_fit(const Dev& d, uint32_t nz) {
   return 1;
 }
 
+// ---- bare gather (diagnostic): 16 lanes per row piece of 256 B, as in the layer kernel's entry loop, and
+// nothing else -- few registers, full occupancy
+template <int SLOTS>
+__global__ __launch_bounds__(256) void gather_probe_kernel(const float* __restrict__ table, const uint32_t* __restrict__ idx,
+                                                           uint32_t n_groups, uint32_t per, float* __restrict__ out) {
+  const uint32_t g = (blockIdx.x * 256u + threadIdx.x) >> 4, sub = threadIdx.x & 15u;
+  if (g >= n_groups) return;
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  const uint32_t* ip = idx + (size_t)g * per;
+  for (uint32_t j = 0; j < per; ++j) {
+    const float* row = table + (size_t)ip[j] * (SLOTS * kSlot) + 4u * sub;
+#pragma unroll
+    for (int s = 0; s < SLOTS; ++s) {
+      const float4 v = *reinterpret_cast<const float4*>(row + s * kSlot);
+      acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    }
+  }
+  out[(size_t)g * 16u + sub] = acc.x + acc.y + acc.z + acc.w;
+}
+
+void launch_gather_probe(hipStream_t s, const float* table, uint32_t slots, const uint32_t* idx, uint32_t n_groups,
+                         uint32_t per, float* out) {
+  const dim3 grid((uint32_t)(((uint64_t)n_groups * 16u + 255u) / 256u)), blk(256);
+  if (slots == 1) hipLaunchKernelGGL(gather_probe_kernel<1>, grid, blk, 0, s, table, idx, n_groups, per, out);
+  else hipLaunchKernelGGL(gather_probe_kernel<4>, grid, blk, 0, s, table, idx, n_groups, per, out);
+}
+
 int setup_embed_attributes(const Dev& d) {
   for (uint32_t l = 0; l < d.layers; ++l) {
     LaunchArgs a = make_args(d, l);

@@ -309,6 +309,8 @@ int  attn_supported(uint32_t d_emb, uint32_t d_time, uint32_t heads);
 void launch_project_nodes(const Dev& d, hipStream_t s);
 constexpr size_t kMaxLds = 160 * 1024;   // LDS per workgroup on gfx950
 int  setup_ingest_attributes(const Dev& d);
+void launch_gather_probe(hipStream_t s, const float* table, uint32_t slots, const uint32_t* idx, uint32_t n_groups,
+                         uint32_t per, float* out);
 int  setup_embed_attributes(const Dev& d);
 int  layer_tiles_fit(const Dev& d, uint32_t nz);   // the layer kernel's LDS tiles with nz slots of z = [phi | raw edge row]
 int  setup_memory_attributes(const Dev& d);
