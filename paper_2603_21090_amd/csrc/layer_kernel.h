@@ -19,6 +19,7 @@
 // Weights stream from L2 (group-major packing, see mfma16.h); several workgroups per CU overlap one's
 // gather with another's products.
 #pragma once
+#include <mutex>
 #include <type_traits>
 #include "stgn_internal.h"
 #include "mfma16.h"
@@ -1057,7 +1058,15 @@ void go_k(LaunchArgs& a) {
   auto kern = layer_kernel<KS, NT, ES, H, JC, WGS, DELTA, QCACHE>;
   if (a.query_wgs) { a.wgs = WGS; return; }
   if (a.set_attr) {
-    a.err = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)a.lds);
+    // never lowered: other layers of this context and other contexts of the process may launch the same variant
+    static std::mutex mu;
+    static size_t granted = 0;
+    std::lock_guard<std::mutex> lock(mu);
+    a.err = hipSuccess;
+    if (a.lds > granted) {
+      a.err = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)a.lds);
+      if (a.err == hipSuccess) granted = a.lds;
+    }
     return;
   }
   uint64_t blocks = ((uint64_t)a.cm + kTM - 1) / kTM;

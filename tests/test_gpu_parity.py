@@ -115,6 +115,9 @@ def test_c1_full_stream(binding):
     dict(layers=2, d_mem=0, d_node=10, d_edge=65, d_time=8, d_emb=16, heads=2, k=4),          # one float past a slot
     dict(layers=1, d_mem=8, d_edge=1, d_time=8, d_emb=8, d_msg=8, heads=1, k=3),              # a single feature
     dict(layers=2, d_mem=12, d_edge=40, d_time=100, d_emb=64, d_msg=12, heads=4, k=3),        # four heads and two time slots: no room for the edge slot in the LDS tiles
+    # the first layer's tiles are much larger than the second's (74 KB against 50 KB of LDS per workgroup):
+    # both layers launch one kernel variant, which must be allowed the larger of the two
+    dict(layers=2, d_mem=0, d_node=512, d_edge=6, d_time=8, d_emb=100, heads=2, k=64),
 ])
 def test_small_graphs_all_shapes(binding, kw):
     w = tiny_workload(num_nodes=150, num_edges=1500, batch=50, zipf_s=1.0, **kw)
