@@ -7,6 +7,9 @@
 // that its dense products run over rows instead of (row, neighbour) pairs:
 //     score_{h,j} = q_h . (kn_{u_j} + ke_j)_h + qt_h . phi_j ,     qt_h = W_K,h[time] q_h      (q carries 1/sqrt(dk))
 //     o_h         = sum_j a_{h,j} (vn_{u_j} + ve_j)_h + pb_h W_V,h[time] ,   pb_h = sum_j a_{h,j} phi_j
+// Edge features of at most one 64-float slot are not cached at all (ES variants): the raw row rides with the
+// time encoding, z_j = [phi_j | e_j] in place of phi_j and W[time | edge] in place of W[time] above, and the
+// cached rows hold the node terms alone.
 // A workgroup of four waves owns 16 target rows and runs its phases without leaving the CU:
 //   1. q  = h_v W_Q(node block) + phi(0) W_Q(time block)                           (MFMA 16x16x4)
 //   2. qt_h = q_h W_K,h[time]^T, kept in LDS                                        (MFMA)
